@@ -1,0 +1,143 @@
+/*
+ * idkm.h -- C ABI of the MI355X (gfx950) implementation of implicit differentiable soft k-means
+ * (IDKM, arXiv 2312.07759): the soft-k-means fixed-point solve of one layer and its
+ * implicit-differentiation / Jacobian-free backward.
+ *
+ * Shapes, all row-major, all float32 in DEVICE memory unless a parameter says "host":
+ *   W [m,d]  the layer's m weight sub-vectors of dimension d   (Sec. 3, product-quantisation set-up)
+ *   C [k,d]  codebook of k codewords                           (Sec. 3)
+ *   A [m,k]  attention matrix, rows sum to one                 (Eq. "aterms", Eq. "arow")
+ *   Wq[m,d]  soft-quantised weights  Wq = A C                  (Eq. "softquant", "softquantmatrix")
+ *
+ * Ownership: every tensor pointer is caller-owned device memory; the library never frees or
+ * reallocates it.  A context owns only its scratch memory and O(k d) solver state.
+ * Threading: one context must not be used from two host threads at once.
+ * Errors: functions return an idkm_status; on any error nothing the caller can rely on has been
+ * written to the outputs.  Non-convergence and empty clusters are reported in idkm_info, not as
+ * errors.  Nothing is printed and the process is never terminated.
+ */
+#ifndef IDKM_H
+#define IDKM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct idkm_ctx idkm_ctx; /* opaque */
+
+typedef enum {
+    IDKM_OK = 0,
+    IDKM_ERR_INVALID_ARG = 1, /* bad shape / NULL / out-of-range parameter; see idkm_last_error */
+    IDKM_ERR_ALLOC = 2,       /* device or host allocation failed */
+    IDKM_ERR_DEVICE = 3,      /* a HIP call failed, or a device-side wait hit its time limit */
+    IDKM_ERR_NONFINITE = 4,   /* the solve produced a non-finite codebook (non-finite input) */
+    IDKM_ERR_NO_FORWARD = 5,  /* idkm_backward without a preceding successful idkm_forward */
+    IDKM_ERR_UNSUPPORTED = 6  /* shape outside the limits reported by idkm_limits */
+} idkm_status;
+
+/* Energy between a weight vector and a codeword inside the softmax of Eq. "aterms". */
+typedef enum {
+    IDKM_DIST_L2 = 0,  /* ||w - c||   : the paper's distance matrix (Alg. 1, distance step) */
+    IDKM_DIST_SQL2 = 1 /* ||w - c||^2 : squared variant (fixed-variance spherical mixture EM) */
+} idkm_dist;
+
+typedef enum {
+    IDKM_BWD_IMPLICIT = 0, /* solve the fixed point of Sec. 4.2 (Eq. "grad", "inv", "backiter") */
+    IDKM_BWD_JFB = 1       /* Jacobian-free: M* = I (Sec. 4.3, Eq. "jfbgrad") */
+} idkm_bwd_mode;
+
+/* How the device work is scheduled.  Results are identical up to rounding order. */
+typedef enum {
+    IDKM_PATH_AUTO = 0,      /* persistent when the problem fits on chip, else stream */
+    IDKM_PATH_STREAM = 1,    /* one kernel launch per pass over W */
+    IDKM_PATH_PERSISTENT = 2 /* one launch per solve, W held in registers, grid-wide exchange per pass */
+} idkm_path;
+
+typedef struct {
+    int32_t iters;          /* forward: evaluations of F; backward: passes of (dF/dC)^T, all attempts */
+    int32_t converged;      /* 1 if the stop rule was met before max_iter */
+    double residual;        /* forward: last ||C+ - C||_F; backward: last ||g+ - g||_F */
+    int32_t empty_clusters; /* clusters whose mass was exactly zero in the last evaluation */
+    int32_t path;           /* idkm_path actually used (never AUTO) */
+    double alpha;           /* backward: damping factor in use when the solve ended */
+} idkm_info;
+
+/* Largest shapes accepted: k <= max_k, d <= max_d, k*d <= max_kd. */
+typedef struct {
+    int32_t max_k, max_d, max_kd;
+} idkm_limits_t;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int32_t idkm_version(void);
+void idkm_limits(idkm_limits_t* out);
+const char* idkm_status_string(idkm_status s);
+
+/* Create / destroy a context bound to HIP device `device_id`.  Allocates the scratch buffers. */
+idkm_status idkm_create(idkm_ctx** out, int device_id);
+idkm_status idkm_destroy(idkm_ctx* ctx);
+/* Human-readable detail of the last error on this context (owned by the context; "" if none). */
+const char* idkm_last_error(const idkm_ctx* ctx);
+/* Select the scheduling path for subsequent calls (default IDKM_PATH_AUTO). */
+idkm_status idkm_set_path(idkm_ctx* ctx, idkm_path path);
+
+/*
+ * Algorithm 1 (soft k-means) followed by one evaluation at the solution.
+ *
+ *   C <- C0;  repeat  C+ = F(C, W)  until ||C+ - C||_F < tol  or max_iter evaluations   (Eq. "deepeqc")
+ *   F(C, W) = diag(A^T 1)^-1 A^T W,  A = rowsoftmax_tau(-D(W, C))                        (Eq. "centers")
+ * then, at the returned C* (the last C+):  A = A(W, C*), Wq = A C*, and the masses n* = A^T 1 and
+ * F* = F(C*, W) are kept in the context for idkm_backward ("plug it into F one time", Sec. 4.2).
+ *
+ *   W       device [m,d]; borrowed by the context until the next idkm_forward or idkm_destroy: it must
+ *           stay alive and unchanged through idkm_backward (Alg. 2: solve, loss, backward).
+ *   C0      device [k,d] initial codebook (Alg. 1 leaves it open; it is an input here).
+ *   tau>0   temperature; tol>=0 absolute Frobenius tolerance; max_iter>=1.
+ *   C_out   device [k,d], required.
+ *   A_out   device [m,k] or NULL (NULL: the attention matrix is never materialised).
+ *   Wq_out  device [m,d] or NULL.
+ *   assign_out device int32 [m] or NULL: index of the closest codeword q(w_i, C*) (Sec. 3), decided in
+ *           float32 on the key |w-c| (d==1) or sum_r (w_r-c_r)^2 with separately rounded multiply and add
+ *           in index order (d>1); ties go to the lowest index.
+ *   info    host pointer or NULL.  If non-NULL the call waits for the stream before returning.
+ *   hip_stream  a hipStream_t (NULL = default stream).  All work is enqueued on it.
+ * A cluster with zero mass keeps its previous centre.  Requires 1<=k<=m.
+ */
+idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, const float* C0, int32_t k,
+                         float tau, float tol, int32_t max_iter, idkm_dist dist, float* C_out, float* A_out,
+                         float* Wq_out, int32_t* assign_out, idkm_info* info, void* hip_stream);
+
+/*
+ * Backward of the layer W -> Wq = A(W, C*(W)) C*(W) for the last idkm_forward on this context
+ * (Alg. 2, per-layer backward steps): total derivative, including the direct dependence of A on W.
+ *
+ *   v = dL/dC* with W fixed;  g solves (I - dF/dC*)^T g = v  by the averaged iteration of Sec. 4.2
+ *       g <- alpha (v + (dF/dC*)^T g) + (1-alpha) g,  g_0 = v,
+ *   stopped when ||g+ - g||_F <= tol ||v||_F or after max_iter passes; a non-finite step or a step norm
+ *   that grows on 5 consecutive passes restarts from g = v with alpha halved (at most 6 times).
+ *   IDKM_BWD_JFB sets g = v (no pass).  dL/dW = (direct term through A) + (dF/dW)^T g.
+ * The attention weights are recomputed on the fly in every pass; nothing of size m*k is stored.
+ *
+ *   dWq     device [m,d], upstream gradient dL/dWq.
+ *   alpha   in (0,1]; 1 = undamped, 0.25 = the paper's setting.
+ *   dW_out  device [m,d], required.
+ *   info    host or NULL (as in idkm_forward).
+ */
+idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, float tol, int32_t max_iter,
+                          float alpha, float* dW_out, idkm_info* info, void* hip_stream);
+
+/*
+ * Single evaluations at a caller-supplied codebook C (device [k,d]), for testing one step in
+ * isolation.  They overwrite the forward state of the context with (W, C, n = A^T 1, F(C, W)).
+ *   idkm_step_F:   Cplus_out[k,d] = F(C, W)                         (Eq. "deepeqc"); n_out device [k] or NULL
+ *   idkm_step_JCT: out[k,d] = (dF/dC)^T g at the state left by idkm_step_F / idkm_forward, g device [k,d]
+ */
+idkm_status idkm_step_F(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, const float* C, int32_t k,
+                        float tau, idkm_dist dist, float* Cplus_out, float* n_out, void* hip_stream);
+idkm_status idkm_step_JCT(idkm_ctx* ctx, const float* g, float* out, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IDKM_H */

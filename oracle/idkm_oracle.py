@@ -270,10 +270,10 @@ def backward(W, C, tau, dist, G, mode, tol=1e-6, max_iter=1000, alpha=1.0):
     mode "implicit": g solves (I - dF/dC)^T g = v by the iteration of Sec. 4.2.
     mode "dense":    same system by Gaussian elimination (the definition, Eq. "grad"/"inv").
     mode "jfb":      g = v, the zeroth-order Neumann truncation M* = I (Sec. 4.3, Eq. "jfbgrad").
-    dL/dW = direct + (dF/dW)^T g.  Returns dict(dW, g, v, iters, converged, residual).
+    dL/dW = direct + (dF/dW)^T g.  Returns dict(dW, g, v, iters, converged, residual, alpha).
     """
     v, direct = loss_cotangents(W, C, tau, dist, G)
-    info = dict(iters=0, converged=True, residual=0.0)
+    info = dict(iters=0, converged=True, residual=0.0, alpha=alpha)
     if mode == "jfb":
         g = v
     elif mode == "dense":
@@ -281,7 +281,7 @@ def backward(W, C, tau, dist, G, mode, tol=1e-6, max_iter=1000, alpha=1.0):
     elif mode == "implicit":
         s = solve_iterative(C, W, tau, dist, v, tol, max_iter, alpha)
         g = s["g"]
-        info = dict(iters=s["iters"], converged=s["converged"], residual=s["residual"])
+        info = dict(iters=s["iters"], converged=s["converged"], residual=s["residual"], alpha=s["alpha"])
     else:
         raise ValueError(mode)
     dW = direct + vjp_F(C, W, tau, dist, g)[1]

@@ -1,0 +1,205 @@
+"""ctypes binding of libidkm.so: the same entry points as include/idkm.h, argument marshalling only.
+
+PyTorch supplies device memory and the current HIP stream; every step of the
+method runs inside the library's kernels.  There is no CPU fallback: if the
+shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libidkm.so")
+
+IDKM_OK = 0
+STATUS_NAMES = {0: "IDKM_OK", 1: "IDKM_ERR_INVALID_ARG", 2: "IDKM_ERR_ALLOC", 3: "IDKM_ERR_DEVICE",
+                4: "IDKM_ERR_NONFINITE", 5: "IDKM_ERR_NO_FORWARD", 6: "IDKM_ERR_UNSUPPORTED"}
+DIST_L2, DIST_SQL2 = 0, 1
+BWD_IMPLICIT, BWD_JFB = 0, 1
+PATH_AUTO, PATH_STREAM, PATH_PERSISTENT = 0, 1, 2
+
+EXPORTS = ["idkm_version", "idkm_limits", "idkm_status_string", "idkm_create", "idkm_destroy", "idkm_last_error",
+           "idkm_set_path", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT"]
+
+
+class IdkmInfo(C.Structure):
+    _fields_ = [("iters", C.c_int32), ("converged", C.c_int32), ("residual", C.c_double),
+                ("empty_clusters", C.c_int32), ("path", C.c_int32), ("alpha", C.c_double)]
+
+
+class IdkmLimits(C.Structure):
+    _fields_ = [("max_k", C.c_int32), ("max_d", C.c_int32), ("max_kd", C.c_int32)]
+
+
+class IdkmError(RuntimeError):
+    def __init__(self, status: int, detail: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {detail}")
+        self.status = status
+        self.detail = detail
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen libidkm.so (built in-tree by paper_2312_07759_amd.build).  Raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2312_07759_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, f32p, i32p = C.c_void_p, C.c_void_p, C.c_void_p
+    lib.idkm_version.restype = C.c_int32
+    lib.idkm_limits.argtypes = [C.POINTER(IdkmLimits)]
+    lib.idkm_limits.restype = None
+    lib.idkm_status_string.argtypes = [C.c_int]
+    lib.idkm_status_string.restype = C.c_char_p
+    lib.idkm_create.argtypes = [C.POINTER(vp), C.c_int]
+    lib.idkm_create.restype = C.c_int
+    lib.idkm_destroy.argtypes = [vp]
+    lib.idkm_destroy.restype = C.c_int
+    lib.idkm_last_error.argtypes = [vp]
+    lib.idkm_last_error.restype = C.c_char_p
+    lib.idkm_set_path.argtypes = [vp, C.c_int]
+    lib.idkm_set_path.restype = C.c_int
+    lib.idkm_forward.argtypes = [vp, f32p, C.c_int64, C.c_int32, f32p, C.c_int32, C.c_float, C.c_float, C.c_int32,
+                                 C.c_int, f32p, f32p, f32p, i32p, C.POINTER(IdkmInfo), vp]
+    lib.idkm_forward.restype = C.c_int
+    lib.idkm_backward.argtypes = [vp, f32p, C.c_int, C.c_float, C.c_int32, C.c_float, f32p, C.POINTER(IdkmInfo), vp]
+    lib.idkm_backward.restype = C.c_int
+    lib.idkm_step_F.argtypes = [vp, f32p, C.c_int64, C.c_int32, f32p, C.c_int32, C.c_float, C.c_int, f32p, f32p, vp]
+    lib.idkm_step_F.restype = C.c_int
+    lib.idkm_step_JCT.argtypes = [vp, f32p, f32p, vp]
+    lib.idkm_step_JCT.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+@dataclass
+class Info:
+    iters: int
+    converged: bool
+    residual: float
+    empty_clusters: int
+    path: int
+    alpha: float
+
+
+def _info(i: IdkmInfo) -> Info:
+    return Info(int(i.iters), bool(i.converged), float(i.residual), int(i.empty_clusters), int(i.path), float(i.alpha))
+
+
+def _ptr(t, dtype, shape, name):
+    """Device pointer of a contiguous torch tensor after checking dtype/shape/device."""
+    import torch
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a tensor in device memory")
+    if t.dtype != dtype or not t.is_contiguous() or tuple(t.shape) != tuple(shape):
+        raise TypeError(f"{name} must be contiguous {dtype} of shape {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Context:
+    """Owns an idkm_ctx.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, device: int = 0):
+        self._lib = load_library()
+        h = C.c_void_p()
+        st = self._lib.idkm_create(C.byref(h), int(device))
+        if st != IDKM_OK:
+            raise IdkmError(st, "idkm_create failed")
+        self._h = h
+        self.device = int(device)
+        self._keep = None
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.idkm_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st):
+        if st != IDKM_OK:
+            raise IdkmError(st, self._lib.idkm_last_error(self._h).decode())
+
+    def set_path(self, path: int):
+        self._check(self._lib.idkm_set_path(self._h, int(path)))
+
+    def forward(self, W, C0, tau, tol, max_iter, dist, want_A=False, want_Wq=True, want_assign=False):
+        """idkm_forward.  W [m,d], C0 [k,d] float32 device tensors.  Returns dict(C, A, Wq, assign, info)."""
+        import torch
+        m, d = W.shape
+        k = C0.shape[0]
+        dev = W.device
+        Cout = torch.empty((k, d), dtype=torch.float32, device=dev)
+        A = torch.empty((m, k), dtype=torch.float32, device=dev) if want_A else None
+        Wq = torch.empty((m, d), dtype=torch.float32, device=dev) if want_Wq else None
+        asg = torch.empty((m,), dtype=torch.int32, device=dev) if want_assign else None
+        info = IdkmInfo()
+        st = self._lib.idkm_forward(self._h, _ptr(W, torch.float32, (m, d), "W"), m, d,
+                                    _ptr(C0, torch.float32, (k, d), "C0"), k, float(tau), float(tol), int(max_iter),
+                                    int(dist), _ptr(Cout, torch.float32, (k, d), "C_out"),
+                                    _ptr(A, torch.float32, (m, k), "A_out"), _ptr(Wq, torch.float32, (m, d), "Wq_out"),
+                                    _ptr(asg, torch.int32, (m,), "assign_out"), C.byref(info), _stream())
+        self._check(st)
+        self._keep = W  # the library borrows W until backward
+        return dict(C=Cout, A=A, Wq=Wq, assign=asg, info=_info(info))
+
+    def backward(self, dWq, mode, tol=1e-6, max_iter=1000, alpha=1.0):
+        """idkm_backward.  dWq [m,d] float32 device tensor.  Returns dict(dW, info)."""
+        import torch
+        dW = torch.empty_like(dWq)
+        info = IdkmInfo()
+        st = self._lib.idkm_backward(self._h, _ptr(dWq, torch.float32, dWq.shape, "dWq"), int(mode), float(tol),
+                                     int(max_iter), float(alpha), _ptr(dW, torch.float32, dWq.shape, "dW_out"),
+                                     C.byref(info), _stream())
+        self._check(st)
+        return dict(dW=dW, info=_info(info))
+
+    def step_F(self, W, Cb, tau, dist):
+        """idkm_step_F: one evaluation of F at Cb.  Returns (C+ [k,d], n [k])."""
+        import torch
+        m, d = W.shape
+        k = Cb.shape[0]
+        Cp = torch.empty((k, d), dtype=torch.float32, device=W.device)
+        n = torch.empty((k,), dtype=torch.float32, device=W.device)
+        st = self._lib.idkm_step_F(self._h, _ptr(W, torch.float32, (m, d), "W"), m, d,
+                                   _ptr(Cb, torch.float32, (k, d), "C"), k, float(tau), int(dist),
+                                   _ptr(Cp, torch.float32, (k, d), "Cplus_out"), _ptr(n, torch.float32, (k,), "n_out"),
+                                   _stream())
+        self._check(st)
+        self._keep = W
+        return Cp, n
+
+    def step_JCT(self, g):
+        """idkm_step_JCT: (dF/dC)^T g at the state left by step_F / forward."""
+        import torch
+        out = torch.empty_like(g)
+        st = self._lib.idkm_step_JCT(self._h, _ptr(g, torch.float32, g.shape, "g"),
+                                     _ptr(out, torch.float32, g.shape, "out"), _stream())
+        self._check(st)
+        return out
+
+
+def limits():
+    lib = load_library()
+    lim = IdkmLimits()
+    lib.idkm_limits(C.byref(lim))
+    return dict(max_k=lim.max_k, max_d=lim.max_d, max_kd=lim.max_kd)

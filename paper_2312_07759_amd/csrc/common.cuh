@@ -1,0 +1,355 @@
+// Shared device-side definitions for the IDKM kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace idkm {
+
+// Passes over the m weight vectors.  Every pass recomputes the attention row
+// a_i. = softmax_tau(-e_i.) (Eq. "aterms") of each vector on the fly.
+constexpr int PASS_FWD = 0;  // one evaluation of F inside the forward loop (Alg. 1 body)
+constexpr int PASS_FIN = 1;  // evaluation at C*: Wq, A, assignments, and n*, F* kept for the backward
+constexpr int PASS_B1 = 2;   // v = dL/dC* with W fixed
+constexpr int PASS_B2 = 3;   // u = (dF/dC)^T g
+constexpr int PASS_B3 = 4;   // dW = direct + (dF/dW)^T g
+
+constexpr int DIST_L2 = 0;
+constexpr int DIST_SQL2 = 1;
+
+constexpr int BWD_IMPLICIT = 0;
+constexpr int BWD_JFB = 1;
+
+constexpr int WG = 256;  // threads per workgroup of the streaming kernels (4 wavefronts)
+
+// Device-resident control block of one context.
+struct Ctrl {
+    unsigned int ticket;  // workgroups that have stored their partials in the current launch
+    int abort_flag;       // a bounded device-side wait expired
+    // forward (Alg. 1)
+    int done, iters, converged, empty, nonfinite, max_iter;
+    double residual, tol;
+    // backward (Sec. 4.2 averaged iteration)
+    int b_done, b_iters, b_converged, b_attempt, b_grow, b_halvings, b_max_iter, b_mode;
+    double b_alpha, b_prev, b_vnorm, b_residual, b_tol;
+};
+
+// Kernel argument block.
+struct Args {
+    const float* W;  // [m,d]
+    const float* G;  // [m,d] upstream gradient dL/dWq (backward passes)
+    int64_t m;
+    int k, d;
+    float nscale;   // -log2(e)/tau: exp(-e/tau) = exp2(e*nscale)
+    float inv_tau;  // 1/tau
+    float tau;
+    int64_t vec_per_wg;  // vectors handled by one workgroup
+    Ctrl* ctrl;
+    // O(k d) solver state
+    double* Cd;  // [k,d] current codebook, float64 master copy
+    float* Cf;   // [k,d] float32 copy used by the E-step
+    double* nd;  // [k]   masses n = A^T 1 of the last evaluation
+    double* Fd;  // [k,d] F(C*, W)
+    float* Ff;   // [k,d]
+    double* gd;  // [k,d] current iterate of the backward solve
+    double* vd;  // [k,d] v = dL/dC*
+    double* ud;  // [k,d] last (dF/dC)^T g
+    float* Hs;   // [k,d] h/tau with h_j = g_j / n_j
+    double* partials;  // [gridDim.x][nacc]
+    double* stage;     // [<=256 + nacc] staging for the final reduction
+    double* tot;       // [nacc] reduced totals
+    // outputs
+    float* C_out;         // [k,d]
+    float* A_out;         // [m,k] or null
+    float* Wq_out;        // [m,d] or null
+    int32_t* assign_out;  // [m] or null
+    float* dW_out;        // [m,d]
+};
+
+// ---------------------------------------------------------------- wavefront (64-lane) reductions via DPP
+
+template <int CTRL, int ROWMASK>
+__device__ __forceinline__ float dpp_f(float identity, float x) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, identity), __builtin_bit_cast(int, x), CTRL,
+                                           ROWMASK, 0xf, false));
+}
+template <int CTRL, int ROWMASK>
+__device__ __forceinline__ int dpp_i(int identity, int x) {
+    return __builtin_amdgcn_update_dpp(identity, x, CTRL, ROWMASK, 0xf, false);
+}
+__device__ __forceinline__ float bcast_lane63(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
+// Fixed-order butterfly inside rows of 16 lanes, then row broadcasts; the total
+// ends in lane 63 and is returned to every lane.  The order of additions is the
+// same on every call, so results are reproducible bit for bit.
+__device__ __forceinline__ float wave_sum(float x) {
+    x += dpp_f<0xB1, 0xf>(0.f, x);   // quad_perm [1,0,3,2]
+    x += dpp_f<0x4E, 0xf>(0.f, x);   // quad_perm [2,3,0,1]
+    x += dpp_f<0x141, 0xf>(0.f, x);  // row_half_mirror
+    x += dpp_f<0x140, 0xf>(0.f, x);  // row_mirror
+    x += dpp_f<0x142, 0xa>(0.f, x);  // row_bcast15 into rows 1,3
+    x += dpp_f<0x143, 0xc>(0.f, x);  // row_bcast31 into rows 2,3
+    return bcast_lane63(x);
+}
+__device__ __forceinline__ float wave_max(float x) {
+    const float ninf = -__builtin_inff();
+    x = fmaxf(x, dpp_f<0xB1, 0xf>(ninf, x));
+    x = fmaxf(x, dpp_f<0x4E, 0xf>(ninf, x));
+    x = fmaxf(x, dpp_f<0x141, 0xf>(ninf, x));
+    x = fmaxf(x, dpp_f<0x140, 0xf>(ninf, x));
+    x = fmaxf(x, dpp_f<0x142, 0xa>(ninf, x));
+    x = fmaxf(x, dpp_f<0x143, 0xc>(ninf, x));
+    return bcast_lane63(x);
+}
+__device__ __forceinline__ float wave_min(float x) { return -wave_max(-x); }
+__device__ __forceinline__ int wave_min_i(int x) {
+    const int big = 0x7fffffff;
+    x = min(x, dpp_i<0xB1, 0xf>(big, x));
+    x = min(x, dpp_i<0x4E, 0xf>(big, x));
+    x = min(x, dpp_i<0x141, 0xf>(big, x));
+    x = min(x, dpp_i<0x140, 0xf>(big, x));
+    x = min(x, dpp_i<0x142, 0xa>(big, x));
+    x = min(x, dpp_i<0x143, 0xc>(big, x));
+    return __builtin_amdgcn_readlane(x, 63);
+}
+__device__ __forceinline__ double wave_sum_d(double x) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float fast_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
+__device__ __forceinline__ float fast_rsq(float x) { return __builtin_amdgcn_rsqf(x); }
+
+// ---------------------------------------------------------------- grid-level tail: last workgroup reduces
+
+// Called by all threads of a workgroup after its partials are stored.  Returns
+// true in every thread of the one workgroup that arrives last.
+__device__ __forceinline__ bool arrive_last(Ctrl* ctrl) {
+    __shared__ int s_last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned int t = atomicAdd(&ctrl->ticket, 1u);
+        s_last = (t == gridDim.x - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!s_last) return false;
+    __threadfence();
+    return true;
+}
+
+// Sum partials[wg][a] over wg in a fixed order into tot[a].  Two stages: P
+// interleaved slices, then the slices in order.
+__device__ __forceinline__ void reduce_partials(const Args& a, int nacc) {
+    const int nwg = gridDim.x;
+    int P = 1;
+    if (nacc < (int)blockDim.x) P = blockDim.x / nacc;
+    if (P > nwg) P = nwg;
+    const double* __restrict__ part = a.partials;
+    for (int idx = threadIdx.x; idx < nacc * P; idx += blockDim.x) {
+        int acc = idx % nacc, p = idx / nacc;
+        double s = 0.0;
+        for (int wg = p; wg < nwg; wg += P) s += part[(size_t)wg * nacc + acc];
+        a.stage[idx] = s;
+    }
+    __syncthreads();
+    for (int acc = threadIdx.x; acc < nacc; acc += blockDim.x) {
+        double s = 0.0;
+        for (int p = 0; p < P; ++p) s += a.stage[p * nacc + acc];
+        a.tot[acc] = s;
+    }
+    __syncthreads();
+}
+
+// Block-wide sum of one double per thread (fixed order); result to all threads.
+__device__ __forceinline__ double block_sum_d(double x) {
+    __shared__ double s_w[16];
+    __shared__ double s_r;
+    x = wave_sum_d(x);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = x;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double s = 0.0;
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) s += s_w[w];
+        s_r = s;
+    }
+    __syncthreads();
+    return s_r;
+}
+__device__ __forceinline__ int block_sum_i(int x) { return (int)(block_sum_d((double)x) + 0.5); }
+
+// Tail of a forward evaluation (Alg. 1: centre update and stop test).  tot holds
+// [k][d+1] = (n_j, s_j).  A cluster with zero mass keeps its centre.
+__device__ __forceinline__ void tail_forward(const Args& a) {
+    const int k = a.k, d = a.d, kd = k * d;
+    Ctrl* c = a.ctrl;
+    double r2 = 0.0;
+    int bad = 0, empty = 0;
+    for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
+        int j = idx / d, r = idx - j * d;
+        double n = a.tot[j * (d + 1)], s = a.tot[j * (d + 1) + 1 + r];
+        double cold = a.Cd[idx];
+        double cnew = (n > 0.0) ? s / n : cold;
+        if (!(n > 0.0) && r == 0) empty++;
+        if (!(fabs(cnew) <= 1.7e308)) bad = 1;
+        double df = cnew - cold;
+        r2 += df * df;
+        a.Cd[idx] = cnew;
+        a.Cf[idx] = (float)cnew;
+        if (r == 0) a.nd[j] = n;
+    }
+    r2 = block_sum_d(r2);
+    bad = block_sum_i(bad);
+    empty = block_sum_i(empty);
+    if (threadIdx.x == 0) {
+        double res = sqrt(r2);
+        c->iters += 1;
+        c->residual = res;
+        c->empty = empty;
+        if (bad) c->nonfinite = 1;
+        bool conv = res < c->tol;
+        c->converged = conv ? 1 : 0;
+        if (conv || bad || c->iters >= c->max_iter) c->done = 1;
+        c->ticket = 0;
+    }
+}
+
+// Tail of the evaluation at C* (Sec. 4.2 "plug it into F one time"): keeps n*, F*.
+__device__ __forceinline__ void tail_final(const Args& a) {
+    const int k = a.k, d = a.d, kd = k * d;
+    Ctrl* c = a.ctrl;
+    int empty = 0;
+    for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
+        int j = idx / d, r = idx - j * d;
+        double n = a.tot[j * (d + 1)], s = a.tot[j * (d + 1) + 1 + r];
+        double f = (n > 0.0) ? s / n : a.Cd[idx];
+        if (!(n > 0.0) && r == 0) empty++;
+        a.Fd[idx] = f;
+        a.Ff[idx] = (float)f;
+        if (r == 0) a.nd[j] = n;
+        if (a.C_out) a.C_out[idx] = a.Cf[idx];
+    }
+    empty = block_sum_i(empty);
+    if (threadIdx.x == 0) {
+        c->empty = empty;
+        c->ticket = 0;
+    }
+}
+
+// Hs_j = (g_j / n_j) / tau as float32; zero for an empty cluster.
+__device__ __forceinline__ void store_h(const Args& a, int idx, double g) {
+    int j = idx / a.d;
+    double n = a.nd[j];
+    a.Hs[idx] = (n > 0.0) ? (float)(g / n * (double)a.inv_tau) : 0.f;
+}
+
+// Tail of B1: tot = v.  Starts the backward solve at g = v.
+__device__ __forceinline__ void tail_b1(const Args& a) {
+    const int kd = a.k * a.d;
+    Ctrl* c = a.ctrl;
+    double v2 = 0.0;
+    for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
+        double v = a.tot[idx];
+        a.vd[idx] = v;
+        a.gd[idx] = v;
+        store_h(a, idx, v);
+        v2 += v * v;
+    }
+    v2 = block_sum_d(v2);
+    if (threadIdx.x == 0) {
+        c->b_vnorm = sqrt(v2);
+        c->b_iters = 0;
+        c->b_attempt = 0;
+        c->b_grow = 0;
+        c->b_halvings = 0;
+        c->b_prev = __builtin_inf();
+        c->b_residual = 0.0;
+        c->b_converged = (c->b_mode == BWD_JFB) ? 1 : 0;
+        c->b_done = (c->b_mode == BWD_JFB) ? 1 : 0;
+        if (!(v2 <= 1.7e308)) {  // non-finite cotangent: nothing to iterate on
+            c->nonfinite = 1;
+            c->b_done = 1;
+        }
+        c->ticket = 0;
+    }
+}
+
+// Tail of one pass of the averaged iteration (Sec. 4.2): tot = u = (dF/dC)^T g.
+//   g+ = alpha (v + u) + (1 - alpha) g ; stop when ||g+ - g|| <= tol ||v||.
+// A non-finite step or 5 consecutive growing steps restart from g = v with alpha/2.
+__device__ __forceinline__ void tail_b2(const Args& a) {
+    const int kd = a.k * a.d;
+    Ctrl* c = a.ctrl;
+    const double alpha = c->b_alpha;
+    double d2 = 0.0;
+    for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
+        double u = a.tot[idx];
+        a.ud[idx] = u;
+        double g = a.gd[idx];
+        double gn = alpha * (a.vd[idx] + u) + (1.0 - alpha) * g;
+        double df = gn - g;
+        d2 += df * df;
+        a.gd[idx] = gn;
+    }
+    d2 = block_sum_d(d2);
+    __shared__ int s_restart;
+    if (threadIdx.x == 0) {
+        double dn = sqrt(d2);
+        int restart = 0;
+        c->b_iters += 1;
+        c->b_attempt += 1;
+        c->b_residual = dn;
+        bool finite = (dn <= 1.7e308);
+        bool diverged = false;
+        if (!finite) {
+            diverged = true;
+        } else if (dn <= c->b_tol * c->b_vnorm) {
+            c->b_converged = 1;
+            c->b_done = 1;
+        } else {
+            c->b_grow = (dn > c->b_prev) ? c->b_grow + 1 : 0;
+            if (c->b_grow >= 5) diverged = true;
+            c->b_prev = dn;
+        }
+        if (!c->b_done && !diverged && c->b_attempt >= c->b_max_iter) c->b_done = 1;
+        if (diverged) {
+            if (c->b_halvings < 6) {
+                c->b_alpha = alpha * 0.5;
+                c->b_halvings += 1;
+                c->b_attempt = 0;
+                c->b_grow = 0;
+                c->b_prev = __builtin_inf();
+                restart = 1;
+            } else {
+                c->b_done = 1;
+            }
+        }
+        s_restart = restart;
+        c->ticket = 0;
+    }
+    __syncthreads();
+    const int restart = s_restart;
+    for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
+        double g = restart ? a.vd[idx] : a.gd[idx];
+        if (restart) a.gd[idx] = g;
+        store_h(a, idx, g);
+    }
+}
+
+template <int PASS>
+__device__ __forceinline__ void grid_tail(const Args& a, int nacc) {
+    if (!arrive_last(a.ctrl)) return;
+    reduce_partials(a, nacc);
+    if (PASS == PASS_FWD) tail_forward(a);
+    if (PASS == PASS_FIN) tail_final(a);
+    if (PASS == PASS_B1) tail_b1(a);
+    if (PASS == PASS_B2) tail_b2(a);
+}
+
+}  // namespace idkm

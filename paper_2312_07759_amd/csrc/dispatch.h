@@ -1,0 +1,14 @@
+// Host-side lookup of kernel instantiations.
+#pragma once
+#include "common.cuh"
+
+namespace idkm {
+
+typedef void (*KernelFn)(const Args);
+
+// Lane<->vector family: K in {2,4,8,16}, D in {1,2,4}.  nullptr if not instantiated.
+KernelFn small_kernel(int K, int D, int dist, int pass);
+// Lane<->codeword family: KPL = ceil(k/64) rounded up to {1,2,4,8,16}, D in {1,2,4,8}, KPL*(D+1) <= 80.
+KernelFn lane_kernel(int KPL, int D, int dist, int pass);
+
+}  // namespace idkm

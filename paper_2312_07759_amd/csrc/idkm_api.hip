@@ -1,0 +1,505 @@
+// C ABI of the IDKM library: argument validation, scratch management and the
+// scheduling of passes over W.  All arithmetic of the method runs in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "../../include/idkm.h"
+#include "common.cuh"
+#include "dispatch.h"
+
+namespace idkm {
+KernelFn small_kernel_0(int, int, int);
+KernelFn small_kernel_1(int, int, int);
+KernelFn lane_kernel_0(int, int, int);
+KernelFn lane_kernel_1(int, int, int);
+
+KernelFn small_kernel(int K, int D, int dist, int pass) {
+    return dist == DIST_L2 ? small_kernel_0(K, D, pass) : small_kernel_1(K, D, pass);
+}
+KernelFn lane_kernel(int KPL, int D, int dist, int pass) {
+    return dist == DIST_L2 ? lane_kernel_0(KPL, D, pass) : lane_kernel_1(KPL, D, pass);
+}
+
+constexpr int MAX_K = 1024, MAX_D = 8, MAX_KD = 4096;
+constexpr int MAX_NACC = MAX_K * 5 > MAX_KD + MAX_K ? MAX_K * 5 : MAX_KD + MAX_K;  // k (d+1) <= kd + k
+
+// ---------------------------------------------------------------- small utility kernels
+
+__global__ void k_init_forward(Args a, const float* C0, double tol, int max_iter) {
+    const int kd = a.k * a.d;
+    for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
+        float c = C0[idx];
+        a.Cd[idx] = (double)c;
+        a.Cf[idx] = c;
+    }
+    if (threadIdx.x == 0) {
+        Ctrl* c = a.ctrl;
+        c->ticket = 0;
+        c->abort_flag = 0;
+        c->done = 0;
+        c->iters = 0;
+        c->converged = 0;
+        c->empty = 0;
+        c->nonfinite = 0;
+        c->max_iter = max_iter;
+        c->residual = 0.0;
+        c->tol = tol;
+        c->b_done = 1;
+    }
+}
+
+__global__ void k_init_backward(Args a, int mode, double tol, int max_iter, double alpha) {
+    Ctrl* c = a.ctrl;
+    c->ticket = 0;
+    c->b_done = 0;
+    c->b_iters = 0;
+    c->b_converged = 0;
+    c->b_attempt = 0;
+    c->b_grow = 0;
+    c->b_halvings = 0;
+    c->b_max_iter = max_iter;
+    c->b_mode = mode;
+    c->b_alpha = alpha;
+    c->b_prev = __builtin_inf();
+    c->b_vnorm = 0.0;
+    c->b_residual = 0.0;
+    c->b_tol = tol;
+}
+
+// Hs = (g / n) / tau from a caller-supplied float32 cotangent; arms one raw (dF/dC)^T pass.
+__global__ void k_set_g(Args a, const float* g) {
+    const int kd = a.k * a.d;
+    for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
+        double gv = (double)g[idx];
+        a.gd[idx] = gv;
+        a.vd[idx] = 0.0;
+        store_h(a, idx, gv);
+    }
+    if (threadIdx.x == 0) {
+        Ctrl* c = a.ctrl;
+        c->ticket = 0;
+        c->b_done = 0;
+        c->b_iters = 0;
+        c->b_attempt = 0;
+        c->b_grow = 0;
+        c->b_halvings = 0;
+        c->b_max_iter = 1;
+        c->b_alpha = 1.0;
+        c->b_prev = __builtin_inf();
+        c->b_vnorm = 0.0;
+        c->b_tol = 0.0;
+    }
+}
+
+__global__ void k_f64_to_f32(const double* src, float* dst, int n) {
+    for (int i = threadIdx.x + blockIdx.x * blockDim.x; i < n; i += blockDim.x * gridDim.x) dst[i] = (float)src[i];
+}
+
+}  // namespace idkm
+
+using namespace idkm;
+
+struct idkm_ctx {
+    int device = 0;
+    std::string err;
+    idkm_path path = IDKM_PATH_AUTO;
+    // device scratch
+    Ctrl* ctrl = nullptr;
+    Ctrl* h_ctrl = nullptr;  // pinned host mirror
+    double *Cd = nullptr, *nd = nullptr, *Fd = nullptr, *gd = nullptr, *vd = nullptr, *ud = nullptr;
+    float *Cf = nullptr, *Ff = nullptr, *Hs = nullptr;
+    double *stage = nullptr, *tot = nullptr;
+    double* partials = nullptr;
+    size_t partials_cap = 0;  // in doubles
+    // forward state
+    bool has_forward = false;
+    const float* W = nullptr;
+    int64_t m = 0;
+    int d = 0, k = 0, dist = 0;
+    float tau = 0.f;
+};
+
+namespace {
+
+idkm_status fail(idkm_ctx* ctx, idkm_status s, const std::string& msg) {
+    if (ctx) ctx->err = msg;
+    return s;
+}
+
+#define HIP_TRY(ctx, expr)                                                                         \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess)                                                                      \
+            return fail(ctx, IDKM_ERR_DEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+struct Geometry {
+    bool small;    // lane<->vector family
+    int kpl;       // lane<->codeword family: codewords per lane
+    int nwg;       // workgroups per pass
+    int64_t vec_per_wg;
+};
+
+bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// Which kernel family serves (k, d), and how a pass is cut into workgroups.
+idkm_status plan(idkm_ctx* ctx, int64_t m, int k, int d, Geometry* g) {
+    if (k > MAX_K || d > MAX_D || (int64_t)k * d > MAX_KD)
+        return fail(ctx, IDKM_ERR_UNSUPPORTED, "shape exceeds idkm_limits (k<=1024, d<=8, k*d<=4096)");
+    if (!(d == 1 || d == 2 || d == 4 || d == 8)) return fail(ctx, IDKM_ERR_UNSUPPORTED, "d must be 1, 2, 4 or 8");
+    g->small = (k >= 2 && k <= 16 && pow2(k) && d <= 4);
+    if (g->small) {
+        int64_t vpt = (m + (int64_t)WG * 2048 - 1) / ((int64_t)WG * 2048);
+        if (vpt < 1) vpt = 1;
+        if (vpt > 32) vpt = 32;
+        g->vec_per_wg = (int64_t)WG * vpt;
+        g->kpl = 0;
+    } else {
+        int kpl = (k + 63) / 64, p = 1;
+        while (p < kpl) p <<= 1;
+        g->kpl = p;
+        if (p * (d + 1) > 80) return fail(ctx, IDKM_ERR_UNSUPPORTED, "ceil(k/64)*(d+1) must be <= 80");
+        int64_t vpw = (m + 4095) / 4096;
+        if (vpw < 1) vpw = 1;
+        if (vpw > 512) vpw = 512;
+        g->vec_per_wg = vpw * (WG / 64);
+    }
+    int64_t nwg = (m + g->vec_per_wg - 1) / g->vec_per_wg;
+    if (nwg > 0x3fffffff) return fail(ctx, IDKM_ERR_UNSUPPORTED, "m too large");
+    g->nwg = (int)nwg;
+    return IDKM_OK;
+}
+
+idkm_status ensure_partials(idkm_ctx* ctx, size_t need) {
+    if (need <= ctx->partials_cap) return IDKM_OK;
+    if (ctx->partials) {
+        (void)hipFree(ctx->partials);
+        ctx->partials = nullptr;
+        ctx->partials_cap = 0;
+    }
+    if (hipMalloc(&ctx->partials, need * sizeof(double)) != hipSuccess)
+        return fail(ctx, IDKM_ERR_ALLOC, "hipMalloc of the partial-sum buffer failed");
+    ctx->partials_cap = need;
+    return IDKM_OK;
+}
+
+Args base_args(idkm_ctx* ctx) {
+    Args a;
+    std::memset(&a, 0, sizeof(a));
+    a.W = ctx->W;
+    a.m = ctx->m;
+    a.k = ctx->k;
+    a.d = ctx->d;
+    a.tau = ctx->tau;
+    a.inv_tau = 1.0f / ctx->tau;
+    a.nscale = (float)(-1.4426950408889634 / (double)ctx->tau);
+    a.ctrl = ctx->ctrl;
+    a.Cd = ctx->Cd;
+    a.Cf = ctx->Cf;
+    a.nd = ctx->nd;
+    a.Fd = ctx->Fd;
+    a.Ff = ctx->Ff;
+    a.gd = ctx->gd;
+    a.vd = ctx->vd;
+    a.ud = ctx->ud;
+    a.Hs = ctx->Hs;
+    a.partials = ctx->partials;
+    a.stage = ctx->stage;
+    a.tot = ctx->tot;
+    return a;
+}
+
+idkm_status launch_pass(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, hipStream_t s) {
+    KernelFn fn = g.small ? small_kernel(ctx->k, ctx->d, ctx->dist, pass) : lane_kernel(g.kpl, ctx->d, ctx->dist, pass);
+    if (!fn) return fail(ctx, IDKM_ERR_UNSUPPORTED, "no kernel for this (k, d)");
+    a.vec_per_wg = g.vec_per_wg;
+    hipLaunchKernelGGL(fn, dim3(g.nwg), dim3(WG), 0, s, a);
+    HIP_TRY(ctx, hipGetLastError());
+    return IDKM_OK;
+}
+
+idkm_status read_ctrl(idkm_ctx* ctx, hipStream_t s) {
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->h_ctrl, ctx->ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipStreamSynchronize(s));
+    return IDKM_OK;
+}
+
+idkm_status check_common(idkm_ctx* ctx) {
+    if (!ctx) return IDKM_ERR_INVALID_ARG;
+    ctx->err.clear();
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    return IDKM_OK;
+}
+
+idkm_status validate_problem(idkm_ctx* ctx, const float* W, int64_t m, int d, const float* C, int k, float tau) {
+    if (!W || !C) return fail(ctx, IDKM_ERR_INVALID_ARG, "W and the codebook must be non-NULL");
+    if (m < 1 || d < 1 || k < 1) return fail(ctx, IDKM_ERR_INVALID_ARG, "m, d, k must be >= 1");
+    if ((int64_t)k > m) return fail(ctx, IDKM_ERR_INVALID_ARG, "k must be <= m");
+    if (!(tau > 0.f) || !std::isfinite(tau)) return fail(ctx, IDKM_ERR_INVALID_ARG, "tau must be finite and > 0");
+    return IDKM_OK;
+}
+
+// Runs `pass` repeatedly in growing chunks until the device-side flag says the solve is over.
+template <class DoneFn>
+idkm_status run_until_done(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, hipStream_t s, int64_t budget,
+                           DoneFn done) {
+    int chunk = 8;
+    int64_t launched = 0;
+    while (launched < budget) {
+        int n = (int)((budget - launched < chunk) ? (budget - launched) : chunk);
+        for (int t = 0; t < n; ++t) {
+            idkm_status st = launch_pass(ctx, g, pass, a, s);
+            if (st != IDKM_OK) return st;
+        }
+        launched += n;
+        idkm_status st = read_ctrl(ctx, s);
+        if (st != IDKM_OK) return st;
+        if (done(*ctx->h_ctrl)) break;
+        if (chunk < 64) chunk *= 2;
+    }
+    return IDKM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t idkm_version(void) { return 100; }
+
+void idkm_limits(idkm_limits_t* out) {
+    if (!out) return;
+    out->max_k = MAX_K;
+    out->max_d = MAX_D;
+    out->max_kd = MAX_KD;
+}
+
+const char* idkm_status_string(idkm_status s) {
+    switch (s) {
+        case IDKM_OK: return "ok";
+        case IDKM_ERR_INVALID_ARG: return "invalid argument";
+        case IDKM_ERR_ALLOC: return "allocation failed";
+        case IDKM_ERR_DEVICE: return "device error";
+        case IDKM_ERR_NONFINITE: return "non-finite result";
+        case IDKM_ERR_NO_FORWARD: return "no forward state";
+        case IDKM_ERR_UNSUPPORTED: return "unsupported shape";
+    }
+    return "unknown";
+}
+
+idkm_status idkm_create(idkm_ctx** out, int device_id) {
+    if (!out) return IDKM_ERR_INVALID_ARG;
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return IDKM_ERR_DEVICE;
+    if (device_id < 0 || device_id >= ndev) return IDKM_ERR_INVALID_ARG;
+    if (hipSetDevice(device_id) != hipSuccess) return IDKM_ERR_DEVICE;
+    idkm_ctx* c = new (std::nothrow) idkm_ctx();
+    if (!c) return IDKM_ERR_ALLOC;
+    c->device = device_id;
+    bool ok = true;
+    ok &= hipMalloc(&c->ctrl, sizeof(Ctrl)) == hipSuccess;
+    ok &= hipHostMalloc(&c->h_ctrl, sizeof(Ctrl)) == hipSuccess;
+    ok &= hipMalloc(&c->Cd, MAX_KD * sizeof(double)) == hipSuccess;
+    ok &= hipMalloc(&c->Fd, MAX_KD * sizeof(double)) == hipSuccess;
+    ok &= hipMalloc(&c->gd, MAX_KD * sizeof(double)) == hipSuccess;
+    ok &= hipMalloc(&c->vd, MAX_KD * sizeof(double)) == hipSuccess;
+    ok &= hipMalloc(&c->ud, MAX_KD * sizeof(double)) == hipSuccess;
+    ok &= hipMalloc(&c->nd, MAX_K * sizeof(double)) == hipSuccess;
+    ok &= hipMalloc(&c->Cf, MAX_KD * sizeof(float)) == hipSuccess;
+    ok &= hipMalloc(&c->Ff, MAX_KD * sizeof(float)) == hipSuccess;
+    ok &= hipMalloc(&c->Hs, MAX_KD * sizeof(float)) == hipSuccess;
+    ok &= hipMalloc(&c->stage, (MAX_NACC + 2 * WG) * sizeof(double)) == hipSuccess;
+    ok &= hipMalloc(&c->tot, MAX_NACC * sizeof(double)) == hipSuccess;
+    if (!ok) {
+        idkm_destroy(c);
+        return IDKM_ERR_ALLOC;
+    }
+    *out = c;
+    return IDKM_OK;
+}
+
+idkm_status idkm_destroy(idkm_ctx* c) {
+    if (!c) return IDKM_ERR_INVALID_ARG;
+    (void)hipSetDevice(c->device);
+    (void)hipDeviceSynchronize();
+    void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials};
+    for (void* p : dev)
+        if (p) (void)hipFree(p);
+    if (c->h_ctrl) (void)hipHostFree(c->h_ctrl);
+    delete c;
+    return IDKM_OK;
+}
+
+const char* idkm_last_error(const idkm_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+idkm_status idkm_set_path(idkm_ctx* ctx, idkm_path path) {
+    if (!ctx) return IDKM_ERR_INVALID_ARG;
+    if (path != IDKM_PATH_AUTO && path != IDKM_PATH_STREAM && path != IDKM_PATH_PERSISTENT)
+        return fail(ctx, IDKM_ERR_INVALID_ARG, "unknown path");
+    ctx->path = path;
+    return IDKM_OK;
+}
+
+idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, const float* C0, int32_t k, float tau,
+                         float tol, int32_t max_iter, idkm_dist dist, float* C_out, float* A_out, float* Wq_out,
+                         int32_t* assign_out, idkm_info* info, void* hip_stream) {
+    idkm_status st = check_common(ctx);
+    if (st != IDKM_OK) return st;
+    ctx->has_forward = false;
+    st = validate_problem(ctx, W, m, d, C0, k, tau);
+    if (st != IDKM_OK) return st;
+    if (!C_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "C_out must be non-NULL");
+    if (!(tol >= 0.f)) return fail(ctx, IDKM_ERR_INVALID_ARG, "tol must be >= 0");
+    if (max_iter < 1) return fail(ctx, IDKM_ERR_INVALID_ARG, "max_iter must be >= 1");
+    if (dist != IDKM_DIST_L2 && dist != IDKM_DIST_SQL2) return fail(ctx, IDKM_ERR_INVALID_ARG, "unknown dist");
+    Geometry g;
+    st = plan(ctx, m, k, d, &g);
+    if (st != IDKM_OK) return st;
+    st = ensure_partials(ctx, (size_t)g.nwg * (size_t)k * (d + 1));
+    if (st != IDKM_OK) return st;
+    hipStream_t s = (hipStream_t)hip_stream;
+
+    ctx->W = W;
+    ctx->m = m;
+    ctx->d = d;
+    ctx->k = k;
+    ctx->dist = (int)dist;
+    ctx->tau = tau;
+    Args a = base_args(ctx);
+
+    hipLaunchKernelGGL(k_init_forward, dim3(1), dim3(WG), 0, s, a, C0, (double)tol, (int)max_iter);
+    HIP_TRY(ctx, hipGetLastError());
+    st = run_until_done(ctx, g, PASS_FWD, a, s, max_iter, [](const Ctrl& c) { return c.done != 0; });
+    if (st != IDKM_OK) return st;
+    if (ctx->h_ctrl->nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "the codebook became non-finite");
+
+    a.C_out = C_out;
+    a.A_out = A_out;
+    a.Wq_out = Wq_out;
+    a.assign_out = assign_out;
+    st = launch_pass(ctx, g, PASS_FIN, a, s);
+    if (st != IDKM_OK) return st;
+    ctx->has_forward = true;
+    if (info) {
+        int iters = ctx->h_ctrl->iters, conv = ctx->h_ctrl->converged;
+        double res = ctx->h_ctrl->residual;
+        st = read_ctrl(ctx, s);
+        if (st != IDKM_OK) return st;
+        info->iters = iters;
+        info->converged = conv;
+        info->residual = res;
+        info->empty_clusters = ctx->h_ctrl->empty;
+        info->path = IDKM_PATH_STREAM;
+        info->alpha = 0.0;
+    }
+    return IDKM_OK;
+}
+
+idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, float tol, int32_t max_iter,
+                          float alpha, float* dW_out, idkm_info* info, void* hip_stream) {
+    idkm_status st = check_common(ctx);
+    if (st != IDKM_OK) return st;
+    if (!ctx->has_forward) return fail(ctx, IDKM_ERR_NO_FORWARD, "idkm_backward needs a successful idkm_forward first");
+    if (!dWq || !dW_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "dWq and dW_out must be non-NULL");
+    if (mode != IDKM_BWD_IMPLICIT && mode != IDKM_BWD_JFB) return fail(ctx, IDKM_ERR_INVALID_ARG, "unknown mode");
+    if (!(tol >= 0.f)) return fail(ctx, IDKM_ERR_INVALID_ARG, "tol must be >= 0");
+    if (max_iter < 1) return fail(ctx, IDKM_ERR_INVALID_ARG, "max_iter must be >= 1");
+    if (!(alpha > 0.f && alpha <= 1.f)) return fail(ctx, IDKM_ERR_INVALID_ARG, "alpha must be in (0,1]");
+    Geometry g;
+    st = plan(ctx, ctx->m, ctx->k, ctx->d, &g);
+    if (st != IDKM_OK) return st;
+    st = ensure_partials(ctx, (size_t)g.nwg * (size_t)ctx->k * (ctx->d + 1));
+    if (st != IDKM_OK) return st;
+    hipStream_t s = (hipStream_t)hip_stream;
+    Args a = base_args(ctx);
+    a.G = dWq;
+    a.dW_out = dW_out;
+
+    hipLaunchKernelGGL(k_init_backward, dim3(1), dim3(1), 0, s, a, (int)mode, (double)tol, (int)max_iter, (double)alpha);
+    HIP_TRY(ctx, hipGetLastError());
+    st = launch_pass(ctx, g, PASS_B1, a, s);
+    if (st != IDKM_OK) return st;
+    if (mode == IDKM_BWD_IMPLICIT) {
+        // every attempt (alpha, alpha/2, ...) may use max_iter passes; at most 7 attempts
+        st = run_until_done(ctx, g, PASS_B2, a, s, (int64_t)max_iter * 7, [](const Ctrl& c) { return c.b_done != 0; });
+        if (st != IDKM_OK) return st;
+    }
+    st = launch_pass(ctx, g, PASS_B3, a, s);
+    if (st != IDKM_OK) return st;
+    if (info) {
+        st = read_ctrl(ctx, s);
+        if (st != IDKM_OK) return st;
+        const Ctrl& c = *ctx->h_ctrl;
+        info->iters = c.b_iters;
+        info->converged = c.b_converged;
+        info->residual = c.b_residual;
+        info->empty_clusters = c.empty;
+        info->path = IDKM_PATH_STREAM;
+        info->alpha = c.b_alpha;
+        if (c.nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "the cotangent became non-finite");
+    }
+    return IDKM_OK;
+}
+
+idkm_status idkm_step_F(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, const float* C, int32_t k, float tau,
+                        idkm_dist dist, float* Cplus_out, float* n_out, void* hip_stream) {
+    idkm_status st = check_common(ctx);
+    if (st != IDKM_OK) return st;
+    ctx->has_forward = false;
+    st = validate_problem(ctx, W, m, d, C, k, tau);
+    if (st != IDKM_OK) return st;
+    if (!Cplus_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "Cplus_out must be non-NULL");
+    if (dist != IDKM_DIST_L2 && dist != IDKM_DIST_SQL2) return fail(ctx, IDKM_ERR_INVALID_ARG, "unknown dist");
+    Geometry g;
+    st = plan(ctx, m, k, d, &g);
+    if (st != IDKM_OK) return st;
+    st = ensure_partials(ctx, (size_t)g.nwg * (size_t)k * (d + 1));
+    if (st != IDKM_OK) return st;
+    hipStream_t s = (hipStream_t)hip_stream;
+    ctx->W = W;
+    ctx->m = m;
+    ctx->d = d;
+    ctx->k = k;
+    ctx->dist = (int)dist;
+    ctx->tau = tau;
+    Args a = base_args(ctx);
+    hipLaunchKernelGGL(k_init_forward, dim3(1), dim3(WG), 0, s, a, C, 0.0, 1);
+    HIP_TRY(ctx, hipGetLastError());
+    st = launch_pass(ctx, g, PASS_FIN, a, s);
+    if (st != IDKM_OK) return st;
+    HIP_TRY(ctx, hipMemcpyAsync(Cplus_out, ctx->Ff, sizeof(float) * k * d, hipMemcpyDeviceToDevice, s));
+    if (n_out) {
+        hipLaunchKernelGGL(k_f64_to_f32, dim3(1), dim3(WG), 0, s, ctx->nd, n_out, (int)k);
+        HIP_TRY(ctx, hipGetLastError());
+    }
+    ctx->has_forward = true;
+    return IDKM_OK;
+}
+
+idkm_status idkm_step_JCT(idkm_ctx* ctx, const float* gvec, float* out, void* hip_stream) {
+    idkm_status st = check_common(ctx);
+    if (st != IDKM_OK) return st;
+    if (!ctx->has_forward) return fail(ctx, IDKM_ERR_NO_FORWARD, "idkm_step_JCT needs idkm_step_F or idkm_forward first");
+    if (!gvec || !out) return fail(ctx, IDKM_ERR_INVALID_ARG, "g and out must be non-NULL");
+    Geometry g;
+    st = plan(ctx, ctx->m, ctx->k, ctx->d, &g);
+    if (st != IDKM_OK) return st;
+    st = ensure_partials(ctx, (size_t)g.nwg * (size_t)ctx->k * (ctx->d + 1));
+    if (st != IDKM_OK) return st;
+    hipStream_t s = (hipStream_t)hip_stream;
+    Args a = base_args(ctx);
+    hipLaunchKernelGGL(k_set_g, dim3(1), dim3(WG), 0, s, a, gvec);
+    HIP_TRY(ctx, hipGetLastError());
+    st = launch_pass(ctx, g, PASS_B2, a, s);
+    if (st != IDKM_OK) return st;
+    hipLaunchKernelGGL(k_f64_to_f32, dim3(1), dim3(WG), 0, s, ctx->ud, out, ctx->k * ctx->d);
+    HIP_TRY(ctx, hipGetLastError());
+    return IDKM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,43 @@
+// Instantiations of the lane<->codeword kernels for energy variant 1.
+#include "dispatch.h"
+#include "lane_k.cuh"
+
+namespace idkm {
+
+template <int KPL, int D>
+static KernelFn pick(int pass) {
+    if (KPL * (D + 1) > 80) return nullptr;
+    switch (pass) {
+        case PASS_FWD: return lane_pass<KPL, D, 1, PASS_FWD>;
+        case PASS_FIN: return lane_pass<KPL, D, 1, PASS_FIN>;
+        case PASS_B1: return lane_pass<KPL, D, 1, PASS_B1>;
+        case PASS_B2: return lane_pass<KPL, D, 1, PASS_B2>;
+        case PASS_B3: return lane_pass<KPL, D, 1, PASS_B3>;
+    }
+    return nullptr;
+}
+
+template <int KPL>
+static KernelFn pick_d(int D, int pass) {
+    switch (D) {
+        case 1: return pick<KPL, 1>(pass);
+        case 2: return pick<KPL, 2>(pass);
+        case 4: return pick<KPL, 4>(pass);
+        case 8: return pick<(KPL > 8 ? 8 : KPL), 8>(pass);
+    }
+    return nullptr;
+}
+
+KernelFn lane_kernel_1(int KPL, int D, int pass) {
+    if (D == 8 && KPL > 8) return nullptr;
+    switch (KPL) {
+        case 1: return pick_d<1>(D, pass);
+        case 2: return pick_d<2>(D, pass);
+        case 4: return pick_d<4>(D, pass);
+        case 8: return pick_d<8>(D, pass);
+        case 16: return pick_d<16>(D, pass);
+    }
+    return nullptr;
+}
+
+}  // namespace idkm

@@ -1,0 +1,39 @@
+// Instantiations of the lane<->vector kernels for energy variant 0.
+#include "dispatch.h"
+#include "small_k.cuh"
+
+namespace idkm {
+
+template <int K, int D>
+static KernelFn pick(int pass) {
+    switch (pass) {
+        case PASS_FWD: return small_pass<K, D, 0, PASS_FWD>;
+        case PASS_FIN: return small_pass<K, D, 0, PASS_FIN>;
+        case PASS_B1: return small_pass<K, D, 0, PASS_B1>;
+        case PASS_B2: return small_pass<K, D, 0, PASS_B2>;
+        case PASS_B3: return small_pass<K, D, 0, PASS_B3>;
+    }
+    return nullptr;
+}
+
+template <int K>
+static KernelFn pick_d(int D, int pass) {
+    switch (D) {
+        case 1: return pick<K, 1>(pass);
+        case 2: return pick<K, 2>(pass);
+        case 4: return pick<K, 4>(pass);
+    }
+    return nullptr;
+}
+
+KernelFn small_kernel_0(int K, int D, int pass) {
+    switch (K) {
+        case 2: return pick_d<2>(D, pass);
+        case 4: return pick_d<4>(D, pass);
+        case 8: return pick_d<8>(D, pass);
+        case 16: return pick_d<16>(D, pass);
+    }
+    return nullptr;
+}
+
+}  // namespace idkm

@@ -1,0 +1,257 @@
+// Lane <-> codeword kernels for large (or odd-sized) codebooks: lane l of a
+// wavefront owns codewords l, l+64, ... (KPL per lane), a wavefront walks over
+// weight vectors one at a time (broadcast from a lane with v_readlane), the row
+// softmax is a wavefront reduction, and the M-step sums stay in lane registers.
+#pragma once
+#include "common.cuh"
+#include "small_k.cuh"
+
+namespace idkm {
+
+__device__ __forceinline__ float lane_bcast(float x, int l) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), l));
+}
+
+template <int KPL, int D, int DIST, int PASS>
+__global__ __launch_bounds__(WG) void lane_pass(const Args a) {
+    constexpr bool STATS = (PASS == PASS_FWD || PASS == PASS_FIN);
+    constexpr bool BACK = (PASS == PASS_B1 || PASS == PASS_B2 || PASS == PASS_B3);
+    constexpr bool USE_G = (PASS == PASS_B1 || PASS == PASS_B3);
+    constexpr bool USE_H = (PASS == PASS_B2 || PASS == PASS_B3);
+    constexpr int ACCW = STATS ? (D + 1) : D;
+    constexpr int NA = (PASS == PASS_B3) ? 1 : KPL * ACCW;  // accumulators per lane
+
+    if (PASS == PASS_FWD && a.ctrl->done) return;
+    if (PASS == PASS_B2 && a.ctrl->b_done) return;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k = a.k;
+    const float inf = __builtin_inff();
+
+    float c[KPL][D], hs[KPL][D], ff[KPL][D];
+    bool valid[KPL];
+#pragma unroll
+    for (int q = 0; q < KPL; ++q) {
+        const int j = lane + 64 * q;
+        valid[q] = j < k;
+#pragma unroll
+        for (int r = 0; r < D; ++r) {
+            c[q][r] = valid[q] ? a.Cf[j * D + r] : 0.f;
+            hs[q][r] = (USE_H && valid[q]) ? a.Hs[j * D + r] : 0.f;
+            ff[q][r] = (USE_H && valid[q]) ? a.Ff[j * D + r] : 0.f;
+        }
+    }
+    float acc[NA];
+#pragma unroll
+    for (int q = 0; q < NA; ++q) acc[q] = 0.f;
+
+    const int64_t vpw = a.vec_per_wg / (WG / 64);
+    const int64_t wbase = (int64_t)blockIdx.x * a.vec_per_wg + (int64_t)wave * vpw;
+    int64_t wend = wbase + vpw;
+    if (wend > a.m) wend = a.m;
+    const float nscale = a.nscale;
+
+    for (int64_t b = wbase; b < wend; b += 64) {
+        const int64_t i = b + lane;
+        const bool in = i < wend;
+        float wv[D], gv[D], ov[D];
+        int oa = 0;
+#pragma unroll
+        for (int r = 0; r < D; ++r) wv[r] = gv[r] = ov[r] = 0.f;
+        if (in) {
+            VecLoad<D>::load(a.W, i, wv);
+            if (USE_G) VecLoad<D>::load(a.G, i, gv);
+        }
+        const int cnt = (wend - b < 64) ? (int)(wend - b) : 64;
+        for (int l = 0; l < cnt; ++l) {
+            float w[D], g[D], gs[D];
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                w[r] = lane_bcast(wv[r], l);
+                if (USE_G) {
+                    g[r] = lane_bcast(gv[r], l);
+                    gs[r] = g[r] * a.inv_tau;
+                }
+            }
+            // E-step: energies of this lane's codewords, wavefront softmax (Eq. "aterms")
+            float df[KPL][D], ri[KPL], u[KPL], at[KPL];
+            float umax = -inf;
+#pragma unroll
+            for (int q = 0; q < KPL; ++q) {
+#pragma unroll
+                for (int r = 0; r < D; ++r) df[q][r] = w[r] - c[q][r];
+                float e;
+                ri[q] = 0.f;
+                if (D == 1) {
+                    e = (DIST == DIST_SQL2) ? df[q][0] * df[q][0] : fabsf(df[q][0]);
+                } else {
+                    float e2 = df[q][0] * df[q][0];
+#pragma unroll
+                    for (int r = 1; r < D; ++r) e2 = fmaf(df[q][r], df[q][r], e2);
+                    if (DIST == DIST_SQL2) {
+                        e = e2;
+                    } else if (BACK) {
+                        float rs = (e2 > 0.f) ? fast_rsq(e2) : 0.f;
+                        ri[q] = rs;
+                        e = e2 * rs;
+                    } else {
+                        e = fast_sqrt(e2);
+                    }
+                }
+                u[q] = valid[q] ? e * nscale : -inf;
+                umax = fmaxf(umax, u[q]);
+            }
+            umax = wave_max(umax);
+            float S = 0.f;
+#pragma unroll
+            for (int q = 0; q < KPL; ++q) {
+                at[q] = fast_exp2(u[q] - umax);
+                S += at[q];
+            }
+            S = wave_sum(S);
+            const float rS = fast_rcp(S);
+#pragma unroll
+            for (int q = 0; q < KPL; ++q) at[q] *= rS;
+
+            if (STATS) {
+#pragma unroll
+                for (int q = 0; q < KPL; ++q) {
+                    acc[q * ACCW] += at[q];
+#pragma unroll
+                    for (int r = 0; r < D; ++r) acc[q * ACCW + 1 + r] = fmaf(at[q], w[r], acc[q * ACCW + 1 + r]);
+                }
+            }
+            if (PASS == PASS_FIN) {
+                if (a.Wq_out) {
+#pragma unroll
+                    for (int r = 0; r < D; ++r) {
+                        float s = 0.f;
+#pragma unroll
+                        for (int q = 0; q < KPL; ++q) s = fmaf(at[q], c[q][r], s);
+                        s = wave_sum(s);
+                        if (lane == l) ov[r] = s;
+                    }
+                }
+                if (a.A_out) {
+#pragma unroll
+                    for (int q = 0; q < KPL; ++q)
+                        if (valid[q]) a.A_out[(b + l) * (int64_t)k + lane + 64 * q] = at[q];
+                }
+                if (a.assign_out) {
+                    float bk = inf;
+                    int bj = 0x7fffffff;
+#pragma unroll
+                    for (int q = 0; q < KPL; ++q) {
+                        float key;
+                        if (D == 1) {
+                            key = fabsf(df[q][0]);
+                        } else {
+                            key = __fmul_rn(df[q][0], df[q][0]);
+#pragma unroll
+                            for (int r = 1; r < D; ++r) key = __fadd_rn(key, __fmul_rn(df[q][r], df[q][r]));
+                        }
+                        if (valid[q] && key < bk) {  // ascending j within the lane: strict < keeps the lowest
+                            bk = key;
+                            bj = lane + 64 * q;
+                        }
+                    }
+                    const float kmin = wave_min(bk);
+                    // lowest index among all codewords attaining the minimum key
+                    int cand = 0x7fffffff;
+#pragma unroll
+                    for (int q = 0; q < KPL; ++q) {
+                        float key;
+                        if (D == 1) {
+                            key = fabsf(df[q][0]);
+                        } else {
+                            key = __fmul_rn(df[q][0], df[q][0]);
+#pragma unroll
+                            for (int r = 1; r < D; ++r) key = __fadd_rn(key, __fmul_rn(df[q][r], df[q][r]));
+                        }
+                        if (valid[q] && key == kmin && lane + 64 * q < cand) cand = lane + 64 * q;
+                    }
+                    (void)bj;
+                    const int jmin = wave_min_i(cand);
+                    if (lane == l) oa = jmin;
+                }
+            }
+            if (BACK) {
+                float qv[KPL], qb = 0.f;
+#pragma unroll
+                for (int q = 0; q < KPL; ++q) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int r = 0; r < D; ++r) {
+                        if (USE_G) s = fmaf(gs[r], c[q][r], s);
+                        if (USE_H) s = fmaf(hs[q][r], w[r] - ff[q][r], s);
+                    }
+                    qv[q] = s;
+                    qb = fmaf(at[q], s, qb);
+                }
+                qb = wave_sum(qb);
+                float out[D];
+#pragma unroll
+                for (int r = 0; r < D; ++r) out[r] = 0.f;
+#pragma unroll
+                for (int q = 0; q < KPL; ++q) {
+                    const float th = at[q] * (qv[q] - qb);
+#pragma unroll
+                    for (int r = 0; r < D; ++r) {
+                        float dl;
+                        if (DIST == DIST_SQL2)
+                            dl = 2.f * df[q][r];
+                        else if (D == 1)
+                            dl = (df[q][0] > 0.f) ? 1.f : ((df[q][0] < 0.f) ? -1.f : 0.f);
+                        else
+                            dl = df[q][r] * ri[q];
+                        if (PASS == PASS_B3) {
+                            out[r] = fmaf(at[q], hs[q][r] * a.tau, out[r]);
+                            out[r] = fmaf(-th, dl, out[r]);
+                        } else {
+                            float t = acc[q * ACCW + r];
+                            if (PASS == PASS_B1) t = fmaf(at[q], g[r], t);
+                            acc[q * ACCW + r] = fmaf(th, dl, t);
+                        }
+                    }
+                }
+                if (PASS == PASS_B3) {
+#pragma unroll
+                    for (int r = 0; r < D; ++r) {
+                        const float s = wave_sum(out[r]);
+                        if (lane == l) ov[r] = s;
+                    }
+                }
+            }
+        }
+        if (in) {
+            if (PASS == PASS_FIN && a.Wq_out) VecLoad<D>::store(a.Wq_out, i, ov);
+            if (PASS == PASS_FIN && a.assign_out) a.assign_out[i] = oa;
+            if (PASS == PASS_B3) VecLoad<D>::store(a.dW_out, i, ov);
+        }
+    }
+
+    if (PASS == PASS_B3) return;
+
+    // workgroup partial: wavefronts add into LDS one after the other (fixed order), float64
+    __shared__ double s_acc[64][NA];
+    for (int wv = 0; wv < WG / 64; ++wv) {
+        if (wave == wv) {
+#pragma unroll
+            for (int q = 0; q < NA; ++q) {
+                if (wv == 0)
+                    s_acc[lane][q] = (double)acc[q];
+                else
+                    s_acc[lane][q] += (double)acc[q];
+            }
+        }
+        __syncthreads();
+    }
+    const int nacc = k * ACCW;
+    for (int idx = threadIdx.x; idx < nacc; idx += WG) {
+        const int j = idx / ACCW, comp = idx - j * ACCW;
+        a.partials[(size_t)blockIdx.x * nacc + idx] = s_acc[j & 63][(j >> 6) * ACCW + comp];
+    }
+    grid_tail<PASS>(a, nacc);
+}
+
+}  // namespace idkm

@@ -1,0 +1,242 @@
+// Lane <-> weight-vector kernels for small codebooks (K <= 16): each lane owns
+// whole vectors, the K codewords are wave-uniform, and the K (D+1) partial sums
+// of the M-step live in the lane's registers.
+#pragma once
+#include "common.cuh"
+
+namespace idkm {
+
+template <int D>
+struct VecLoad {
+    static __device__ __forceinline__ void load(const float* __restrict__ p, int64_t i, float (&w)[D]) {
+#pragma unroll
+        for (int r = 0; r < D; ++r) w[r] = p[i * D + r];
+    }
+    static __device__ __forceinline__ void store(float* __restrict__ p, int64_t i, const float (&w)[D]) {
+#pragma unroll
+        for (int r = 0; r < D; ++r) p[i * D + r] = w[r];
+    }
+};
+template <>
+struct VecLoad<2> {
+    static __device__ __forceinline__ void load(const float* __restrict__ p, int64_t i, float (&w)[2]) {
+        float2 v = reinterpret_cast<const float2*>(p)[i];
+        w[0] = v.x, w[1] = v.y;
+    }
+    static __device__ __forceinline__ void store(float* __restrict__ p, int64_t i, const float (&w)[2]) {
+        reinterpret_cast<float2*>(p)[i] = make_float2(w[0], w[1]);
+    }
+};
+template <>
+struct VecLoad<4> {
+    static __device__ __forceinline__ void load(const float* __restrict__ p, int64_t i, float (&w)[4]) {
+        float4 v = reinterpret_cast<const float4*>(p)[i];
+        w[0] = v.x, w[1] = v.y, w[2] = v.z, w[3] = v.w;
+    }
+    static __device__ __forceinline__ void store(float* __restrict__ p, int64_t i, const float (&w)[4]) {
+        reinterpret_cast<float4*>(p)[i] = make_float4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+// E-step for one vector against K uniform codewords (Eq. "aterms"): fills the
+// attention row a[K], the differences df = w - c and, for the plain norm with
+// D > 1 when derivatives are needed, ri = 1/||w - c|| (0 at coincidence).
+template <int K, int D, int DIST, bool DERIV>
+__device__ __forceinline__ void estep_small(const float (&w)[D], const float (&c)[K][D], float nscale, float (&a)[K],
+                                            float (&df)[K][D], float (&ri)[K]) {
+    float u[K];
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+#pragma unroll
+        for (int r = 0; r < D; ++r) df[j][r] = w[r] - c[j][r];
+        float e;
+        if (D == 1) {
+            e = (DIST == DIST_SQL2) ? df[j][0] * df[j][0] : fabsf(df[j][0]);
+            ri[j] = 0.f;
+        } else {
+            float e2 = df[j][0] * df[j][0];
+#pragma unroll
+            for (int r = 1; r < D; ++r) e2 = fmaf(df[j][r], df[j][r], e2);
+            if (DIST == DIST_SQL2) {
+                e = e2;
+                ri[j] = 0.f;
+            } else if (DERIV) {
+                float rs = (e2 > 0.f) ? fast_rsq(e2) : 0.f;
+                ri[j] = rs;
+                e = e2 * rs;
+            } else {
+                e = fast_sqrt(e2);
+                ri[j] = 0.f;
+            }
+        }
+        u[j] = e * nscale;
+    }
+    float umax = u[0];
+#pragma unroll
+    for (int j = 1; j < K; ++j) umax = fmaxf(umax, u[j]);
+    float S = 0.f;
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+        a[j] = fast_exp2(u[j] - umax);
+        S += a[j];
+    }
+    const float rS = fast_rcp(S);
+#pragma unroll
+    for (int j = 0; j < K; ++j) a[j] *= rS;
+}
+
+// delta_jr = d e_j / d w_r
+template <int K, int D, int DIST>
+__device__ __forceinline__ float delta_small(const float (&df)[K][D], const float (&ri)[K], int j, int r) {
+    if (DIST == DIST_SQL2) return 2.f * df[j][r];
+    if (D == 1) return (df[j][0] > 0.f) ? 1.f : ((df[j][0] < 0.f) ? -1.f : 0.f);
+    return df[j][r] * ri[j];
+}
+
+template <int K, int D, int DIST, int PASS>
+__global__ __launch_bounds__(WG) void small_pass(const Args a) {
+    constexpr bool STATS = (PASS == PASS_FWD || PASS == PASS_FIN);
+    constexpr bool BACK = (PASS == PASS_B1 || PASS == PASS_B2 || PASS == PASS_B3);
+    constexpr bool USE_G = (PASS == PASS_B1 || PASS == PASS_B3);
+    constexpr bool USE_H = (PASS == PASS_B2 || PASS == PASS_B3);
+    constexpr int ACCW = STATS ? (D + 1) : D;
+    constexpr int NACC = (PASS == PASS_B3) ? 1 : K * ACCW;
+
+    if (PASS == PASS_FWD && a.ctrl->done) return;
+    if (PASS == PASS_B2 && a.ctrl->b_done) return;
+
+    float c[K][D], hs[K][D], ff[K][D];
+#pragma unroll
+    for (int j = 0; j < K; ++j)
+#pragma unroll
+        for (int r = 0; r < D; ++r) {
+            c[j][r] = a.Cf[j * D + r];
+            hs[j][r] = USE_H ? a.Hs[j * D + r] : 0.f;
+            ff[j][r] = USE_H ? a.Ff[j * D + r] : 0.f;
+        }
+
+    float acc[NACC];
+#pragma unroll
+    for (int q = 0; q < NACC; ++q) acc[q] = 0.f;
+
+    const int64_t base = (int64_t)blockIdx.x * a.vec_per_wg;
+    int64_t end = base + a.vec_per_wg;
+    if (end > a.m) end = a.m;
+    const float nscale = a.nscale;
+
+    for (int64_t i = base + threadIdx.x; i < end; i += WG) {
+        float w[D], g[D], gs[D];
+        VecLoad<D>::load(a.W, i, w);
+        if (USE_G) {
+            VecLoad<D>::load(a.G, i, g);
+#pragma unroll
+            for (int r = 0; r < D; ++r) gs[r] = g[r] * a.inv_tau;
+        }
+        float at[K], df[K][D], ri[K];
+        estep_small<K, D, DIST, BACK>(w, c, nscale, at, df, ri);
+
+        if (STATS) {
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                acc[j * ACCW] += at[j];
+#pragma unroll
+                for (int r = 0; r < D; ++r) acc[j * ACCW + 1 + r] = fmaf(at[j], w[r], acc[j * ACCW + 1 + r]);
+            }
+        }
+        if (PASS == PASS_FIN) {
+            if (a.Wq_out) {
+                float wq[D];
+#pragma unroll
+                for (int r = 0; r < D; ++r) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int j = 0; j < K; ++j) s = fmaf(at[j], c[j][r], s);
+                    wq[r] = s;
+                }
+                VecLoad<D>::store(a.Wq_out, i, wq);
+            }
+            if (a.A_out) {
+#pragma unroll
+                for (int j = 0; j < K; ++j) a.A_out[i * K + j] = at[j];
+            }
+            if (a.assign_out) {
+                // closest codeword decided on a float32 key with separately rounded operations
+                int best = 0;
+                float bk = 0.f;
+#pragma unroll
+                for (int j = 0; j < K; ++j) {
+                    float key;
+                    if (D == 1) {
+                        key = fabsf(df[j][0]);
+                    } else {
+                        key = __fmul_rn(df[j][0], df[j][0]);
+#pragma unroll
+                        for (int r = 1; r < D; ++r) key = __fadd_rn(key, __fmul_rn(df[j][r], df[j][r]));
+                    }
+                    if (j == 0 || key < bk) {
+                        bk = key;
+                        best = j;
+                    }
+                }
+                a.assign_out[i] = best;
+            }
+        }
+        if (BACK) {
+            // q_j = (G_i . c_j)/tau [loss through A C]  +  (h_j/tau) . (w_i - F_j) [through F]
+            float q[K], qbar = 0.f;
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                float s = 0.f;
+#pragma unroll
+                for (int r = 0; r < D; ++r) {
+                    if (USE_G) s = fmaf(gs[r], c[j][r], s);
+                    if (USE_H) s = fmaf(hs[j][r], w[r] - ff[j][r], s);
+                }
+                q[j] = s;
+                qbar = fmaf(at[j], s, qbar);
+            }
+            float out[D];
+#pragma unroll
+            for (int r = 0; r < D; ++r) out[r] = 0.f;
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                const float th = at[j] * (q[j] - qbar);
+#pragma unroll
+                for (int r = 0; r < D; ++r) {
+                    const float dl = delta_small<K, D, DIST>(df, ri, j, r);
+                    if (PASS == PASS_B3) {
+                        // sum_j a_j h_j  -  (1/tau) sum_j theta_j delta_j   (theta already carries 1/tau)
+                        out[r] = fmaf(at[j], hs[j][r] * a.tau, out[r]);
+                        out[r] = fmaf(-th, dl, out[r]);
+                    } else {
+                        float t = acc[j * ACCW + r];
+                        if (PASS == PASS_B1) t = fmaf(at[j], g[r], t);
+                        acc[j * ACCW + r] = fmaf(th, dl, t);
+                    }
+                }
+            }
+            if (PASS == PASS_B3) VecLoad<D>::store(a.dW_out, i, out);
+        }
+    }
+
+    if (PASS == PASS_B3) return;
+
+    // workgroup partial in float64, fixed order: lanes (butterfly), then wavefronts 0..3
+    __shared__ double s_part[WG / 64][NACC];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int q = 0; q < NACC; ++q) {
+        double v = wave_sum_d((double)acc[q]);
+        if (lane == 0) s_part[wave][q] = v;
+    }
+    __syncthreads();
+    for (int q = threadIdx.x; q < NACC; q += WG) {
+        double s = 0.0;
+#pragma unroll
+        for (int wv = 0; wv < WG / 64; ++wv) s += s_part[wv][q];
+        a.partials[(size_t)blockIdx.x * NACC + q] = s;
+    }
+    grid_tail<PASS>(a, NACC);
+}
+
+}  // namespace idkm
