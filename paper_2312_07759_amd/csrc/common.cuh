@@ -197,7 +197,7 @@ __device__ __forceinline__ void tail_forward(const Args& a) {
         double cold = a.Cd[idx];
         double cnew = (n > 0.0) ? s / n : cold;
         if (!(n > 0.0) && r == 0) empty++;
-        if (!(fabs(cnew) <= 1.7e308)) bad = 1;
+        if (!(n >= 0.0) || !(fabs(s) <= 1.7e308) || !(fabs(cnew) <= 1.7e308)) bad = 1;  // NaN or Inf anywhere
         double df = cnew - cold;
         r2 += df * df;
         a.Cd[idx] = cnew;
@@ -224,20 +224,23 @@ __device__ __forceinline__ void tail_forward(const Args& a) {
 __device__ __forceinline__ void tail_final(const Args& a) {
     const int k = a.k, d = a.d, kd = k * d;
     Ctrl* c = a.ctrl;
-    int empty = 0;
+    int empty = 0, bad = 0;
     for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
         int j = idx / d, r = idx - j * d;
         double n = a.tot[j * (d + 1)], s = a.tot[j * (d + 1) + 1 + r];
         double f = (n > 0.0) ? s / n : a.Cd[idx];
         if (!(n > 0.0) && r == 0) empty++;
+        if (!(n >= 0.0) || !(fabs(s) <= 1.7e308)) bad = 1;
         a.Fd[idx] = f;
         a.Ff[idx] = (float)f;
         if (r == 0) a.nd[j] = n;
         if (a.C_out) a.C_out[idx] = a.Cf[idx];
     }
     empty = block_sum_i(empty);
+    bad = block_sum_i(bad);
     if (threadIdx.x == 0) {
         c->empty = empty;
+        if (bad) c->nonfinite = 1;
         c->ticket = 0;
     }
 }

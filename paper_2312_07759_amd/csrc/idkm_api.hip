@@ -396,6 +396,10 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
         info->empty_clusters = ctx->h_ctrl->empty;
         info->path = IDKM_PATH_STREAM;
         info->alpha = 0.0;
+        if (ctx->h_ctrl->nonfinite) {
+            ctx->has_forward = false;
+            return fail(ctx, IDKM_ERR_NONFINITE, "non-finite masses in the evaluation at C*");
+        }
     }
     return IDKM_OK;
 }
