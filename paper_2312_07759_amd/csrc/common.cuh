@@ -153,9 +153,18 @@ __device__ __forceinline__ void reduce_partials(const Args& a, int nacc) {
     const double* __restrict__ part = a.partials;
     for (int idx = threadIdx.x; idx < nacc * P; idx += blockDim.x) {
         int acc = idx % nacc, p = idx / nacc;
-        double s = 0.0;
-        for (int wg = p; wg < nwg; wg += P) s += part[(size_t)wg * nacc + acc];
-        a.stage[idx] = s;
+        // eight independent chains keep eight loads in flight; the order is still fixed
+        double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        int wg = p;
+        for (; wg + 7 * P < nwg; wg += 8 * P) {
+            double x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = part[(size_t)(wg + u * P) * nacc + acc];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s[u] += x[u];
+        }
+        for (; wg < nwg; wg += P) s[0] += part[(size_t)wg * nacc + acc];
+        a.stage[idx] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
     }
     __syncthreads();
     for (int acc = threadIdx.x; acc < nacc; acc += blockDim.x) {

@@ -11,4 +11,9 @@ KernelFn small_kernel(int K, int D, int dist, int pass);
 // Lane<->codeword family: KPL = ceil(k/64) rounded up to {1,2,4,8,16}, D in {1,2,4,8}, KPL*(D+1) <= 80.
 KernelFn lane_kernel(int KPL, int D, int dist, int pass);
 
+struct PArgs;
+typedef void (*PersistFn)(const Args, const PArgs);
+// Persistent forward / backward solve for the lane<->vector family; nullptr if K (D+1) > 32.
+PersistFn persist_kernel(int K, int D, int dist, bool bwd);
+
 }  // namespace idkm

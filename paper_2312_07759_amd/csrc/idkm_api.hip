@@ -11,6 +11,7 @@
 #include "../../include/idkm.h"
 #include "common.cuh"
 #include "dispatch.h"
+#include "persist_small.cuh"
 
 namespace idkm {
 KernelFn small_kernel_0(int, int, int);
@@ -56,6 +57,7 @@ __global__ void k_init_forward(Args a, const float* C0, double tol, int max_iter
 __global__ void k_init_backward(Args a, int mode, double tol, int max_iter, double alpha) {
     Ctrl* c = a.ctrl;
     c->ticket = 0;
+    c->abort_flag = 0;
     c->b_done = 0;
     c->b_iters = 0;
     c->b_converged = 0;
@@ -96,6 +98,10 @@ __global__ void k_set_g(Args a, const float* g) {
     }
 }
 
+__global__ void k_fill_u64(unsigned long long* p, size_t n, unsigned long long v) {
+    for (size_t i = threadIdx.x + (size_t)blockIdx.x * blockDim.x; i < n; i += (size_t)blockDim.x * gridDim.x) p[i] = v;
+}
+
 __global__ void k_f64_to_f32(const double* src, float* dst, int n) {
     for (int i = threadIdx.x + blockIdx.x * blockDim.x; i < n; i += blockDim.x * gridDim.x) dst[i] = (float)src[i];
 }
@@ -116,6 +122,13 @@ struct idkm_ctx {
     double *stage = nullptr, *tot = nullptr;
     double* partials = nullptr;
     size_t partials_cap = 0;  // in doubles
+    // persistent path
+    int num_cu = 0;
+    bool coop = false;
+    unsigned long long* xbuf = nullptr;  // [2][XROWS][num_cu] stamped exchange words
+    size_t xbuf_words = 0;
+    unsigned int seq_base = 0;
+    unsigned int spin_limit = 1u << 20;
     // forward state
     bool has_forward = false;
     const float* W = nullptr;
@@ -154,7 +167,7 @@ idkm_status plan(idkm_ctx* ctx, int64_t m, int k, int d, Geometry* g) {
     if (!(d == 1 || d == 2 || d == 4 || d == 8)) return fail(ctx, IDKM_ERR_UNSUPPORTED, "d must be 1, 2, 4 or 8");
     g->small = (k >= 2 && k <= 16 && pow2(k) && d <= 4);
     if (g->small) {
-        int64_t vpt = (m + (int64_t)WG * 2048 - 1) / ((int64_t)WG * 2048);
+        int64_t vpt = (m + (int64_t)WG * 1024 - 1) / ((int64_t)WG * 1024);
         if (vpt < 1) vpt = 1;
         if (vpt > 32) vpt = 32;
         g->vec_per_wg = (int64_t)WG * vpt;
@@ -220,6 +233,59 @@ idkm_status launch_pass(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, hip
     a.vec_per_wg = g.vec_per_wg;
     hipLaunchKernelGGL(fn, dim3(g.nwg), dim3(WG), 0, s, a);
     HIP_TRY(ctx, hipGetLastError());
+    return IDKM_OK;
+}
+
+constexpr int XROWS = 32;                 // widest exchange row count: K (D+1) <= 32
+constexpr size_t LDS_TILE_MAX = 144 * 1024;  // bytes of LDS a persistent workgroup may use for its tile
+
+struct PersistPlan {
+    PersistFn fn;
+    int grid, per;
+    size_t lds;
+};
+
+// Can (m, k, d) run as one persistent launch with `tiles` resident tensors (1: W; 2: W and dL/dWq)?
+bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
+    if (!ctx->coop || ctx->num_cu < 1) return false;
+    const int k = ctx->k, d = ctx->d;
+    if (!(k >= 2 && k <= 16 && pow2(k) && d <= 4) || k * (d + 1) > XROWS) return false;
+    pp->fn = persist_kernel(k, d, ctx->dist, bwd);
+    if (!pp->fn) return false;
+    const int64_t m = ctx->m;
+    int64_t g = (m + 4 * PT - 1) / (4 * PT);  // at least ~4 vectors per thread before adding workgroups
+    if (g < 1) g = 1;
+    if (g > ctx->num_cu) g = ctx->num_cu;
+    int64_t per = (m + g - 1) / g;
+    per = (per + 3) / 4 * 4;
+    const size_t lds = (size_t)per * d * sizeof(float) * (bwd ? 2 : 1);
+    if (lds > LDS_TILE_MAX) return false;
+    pp->grid = (int)((m + per - 1) / per);
+    pp->per = (int)per;
+    pp->lds = lds;
+    return true;
+}
+
+idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, unsigned int exchanges, hipStream_t s) {
+    if ((size_t)2 * XROWS * pp.grid > ctx->xbuf_words) return fail(ctx, IDKM_ERR_DEVICE, "exchange buffer too small");
+    if (ctx->seq_base > 0xffffffffu - exchanges - 2u) {  // stamps would wrap: start over from a clean buffer
+        hipLaunchKernelGGL(k_fill_u64, dim3(64), dim3(256), 0, s, ctx->xbuf, ctx->xbuf_words, 0ull);
+        HIP_TRY(ctx, hipGetLastError());
+        ctx->seq_base = 0;
+    }
+    PArgs pa;
+    pa.xbuf = ctx->xbuf;
+    pa.seq_base = ctx->seq_base;
+    pa.spin_limit = ctx->spin_limit;
+    pa.per = pp.per;
+    HIP_TRY(ctx, hipFuncSetAttribute((const void*)pp.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pp.lds));
+    int nb = 0;
+    HIP_TRY(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)pp.fn, PT, pp.lds));
+    if (nb < 1 || (int64_t)nb * ctx->num_cu < pp.grid)
+        return fail(ctx, IDKM_ERR_DEVICE, "persistent grid would not be co-resident");
+    void* args[] = {(void*)&a, (void*)&pa};
+    HIP_TRY(ctx, hipLaunchCooperativeKernel((const void*)pp.fn, dim3(pp.grid), dim3(PT), args, pp.lds, s));
+    ctx->seq_base += exchanges;
     return IDKM_OK;
 }
 
@@ -315,6 +381,15 @@ idkm_status idkm_create(idkm_ctx** out, int device_id) {
     ok &= hipMalloc(&c->Hs, MAX_KD * sizeof(float)) == hipSuccess;
     ok &= hipMalloc(&c->stage, (MAX_NACC + 2 * WG) * sizeof(double)) == hipSuccess;
     ok &= hipMalloc(&c->tot, MAX_NACC * sizeof(double)) == hipSuccess;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device_id) == hipSuccess) {
+        c->num_cu = prop.multiProcessorCount;
+        c->coop = prop.cooperativeLaunch != 0;
+    }
+    c->xbuf_words = (size_t)2 * XROWS * (c->num_cu > 0 ? c->num_cu : 1);
+    ok &= hipMalloc(&c->xbuf, c->xbuf_words * sizeof(unsigned long long)) == hipSuccess;
+    if (ok) ok &= hipMemset(c->xbuf, 0, c->xbuf_words * sizeof(unsigned long long)) == hipSuccess;
+    if (ok) ok &= hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
         idkm_destroy(c);
         return IDKM_ERR_ALLOC;
@@ -327,7 +402,7 @@ idkm_status idkm_destroy(idkm_ctx* c) {
     if (!c) return IDKM_ERR_INVALID_ARG;
     (void)hipSetDevice(c->device);
     (void)hipDeviceSynchronize();
-    void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials};
+    void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials, c->xbuf};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     if (c->h_ctrl) (void)hipHostFree(c->h_ctrl);
@@ -374,6 +449,35 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
 
     hipLaunchKernelGGL(k_init_forward, dim3(1), dim3(WG), 0, s, a, C0, (double)tol, (int)max_iter);
     HIP_TRY(ctx, hipGetLastError());
+
+    PersistPlan pp;
+    const bool persistent = ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, false, &pp);
+    if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
+        return fail(ctx, IDKM_ERR_UNSUPPORTED, "the persistent path needs k in {2,4,8,16}, k(d+1) <= 32 and W to fit in LDS");
+    if (persistent) {
+        a.C_out = C_out;
+        a.A_out = A_out;
+        a.Wq_out = Wq_out;
+        a.assign_out = assign_out;
+        st = launch_persistent(ctx, pp, a, (unsigned int)max_iter + 1u, s);
+        if (st != IDKM_OK) return st;
+        st = read_ctrl(ctx, s);
+        if (st != IDKM_OK) return st;
+        const Ctrl& c = *ctx->h_ctrl;
+        if (c.abort_flag || !c.done) return fail(ctx, IDKM_ERR_DEVICE, "a grid-wide wait hit its limit");
+        if (c.nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "the codebook became non-finite");
+        ctx->has_forward = true;
+        if (info) {
+            info->iters = c.iters;
+            info->converged = c.converged;
+            info->residual = c.residual;
+            info->empty_clusters = c.empty;
+            info->path = IDKM_PATH_PERSISTENT;
+            info->alpha = 0.0;
+        }
+        return IDKM_OK;
+    }
+
     st = run_until_done(ctx, g, PASS_FWD, a, s, max_iter, [](const Ctrl& c) { return c.done != 0; });
     if (st != IDKM_OK) return st;
     if (ctx->h_ctrl->nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "the codebook became non-finite");
@@ -426,6 +530,32 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
 
     hipLaunchKernelGGL(k_init_backward, dim3(1), dim3(1), 0, s, a, (int)mode, (double)tol, (int)max_iter, (double)alpha);
     HIP_TRY(ctx, hipGetLastError());
+
+    PersistPlan pp;
+    const bool persistent = ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &pp);
+    if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
+        return fail(ctx, IDKM_ERR_UNSUPPORTED, "the persistent path needs k in {2,4,8,16}, k(d+1) <= 32 and W, dWq to fit in LDS");
+    if (persistent) {
+        const uint64_t ex = 1ull + (mode == IDKM_BWD_IMPLICIT ? (uint64_t)max_iter * 7ull : 0ull);
+        if (ex < 0x7fffffffull) {
+            st = launch_persistent(ctx, pp, a, (unsigned int)ex, s);
+            if (st != IDKM_OK) return st;
+            st = read_ctrl(ctx, s);
+            if (st != IDKM_OK) return st;
+            const Ctrl& c = *ctx->h_ctrl;
+            if (c.abort_flag || !c.b_done) return fail(ctx, IDKM_ERR_DEVICE, "a grid-wide wait hit its limit");
+            if (c.nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "the cotangent became non-finite");
+            if (info) {
+                info->iters = c.b_iters;
+                info->converged = c.b_converged;
+                info->residual = c.b_residual;
+                info->empty_clusters = c.empty;
+                info->path = IDKM_PATH_PERSISTENT;
+                info->alpha = c.b_alpha;
+            }
+            return IDKM_OK;
+        }
+    }
     st = launch_pass(ctx, g, PASS_B1, a, s);
     if (st != IDKM_OK) return st;
     if (mode == IDKM_BWD_IMPLICIT) {

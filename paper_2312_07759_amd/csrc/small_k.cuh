@@ -93,47 +93,26 @@ __device__ __forceinline__ float delta_small(const float (&df)[K][D], const floa
     return df[j][r] * ri[j];
 }
 
+// Everything one pass does for one weight vector i: E-step, then the pass's own
+// accumulation or per-vector output.  acc has K*(D+1) entries for the forward
+// passes ((n_j, s_j) interleaved), K*D for B1/B2, and is unused for B3.
 template <int K, int D, int DIST, int PASS>
-__global__ __launch_bounds__(WG) void small_pass(const Args a) {
-    constexpr bool STATS = (PASS == PASS_FWD || PASS == PASS_FIN);
-    constexpr bool BACK = (PASS == PASS_B1 || PASS == PASS_B2 || PASS == PASS_B3);
-    constexpr bool USE_G = (PASS == PASS_B1 || PASS == PASS_B3);
-    constexpr bool USE_H = (PASS == PASS_B2 || PASS == PASS_B3);
-    constexpr int ACCW = STATS ? (D + 1) : D;
-    constexpr int NACC = (PASS == PASS_B3) ? 1 : K * ACCW;
+struct SmallItem {
+    static constexpr bool STATS = (PASS == PASS_FWD || PASS == PASS_FIN);
+    static constexpr bool BACK = (PASS == PASS_B1 || PASS == PASS_B2 || PASS == PASS_B3);
+    static constexpr bool USE_G = (PASS == PASS_B1 || PASS == PASS_B3);
+    static constexpr bool USE_H = (PASS == PASS_B2 || PASS == PASS_B3);
+    static constexpr int ACCW = STATS ? (D + 1) : D;
+    static constexpr int NACC = (PASS == PASS_B3) ? 1 : K * ACCW;
 
-    if (PASS == PASS_FWD && a.ctrl->done) return;
-    if (PASS == PASS_B2 && a.ctrl->b_done) return;
-
-    float c[K][D], hs[K][D], ff[K][D];
+    static __device__ __forceinline__ void run(const Args& a, int64_t i, const float (&w)[D], const float (&g)[D],
+                                               const float (&c)[K][D], const float (&hs)[K][D],
+                                               const float (&ff)[K][D], float (&acc)[NACC]) {
+        float gs[D];
 #pragma unroll
-    for (int j = 0; j < K; ++j)
-#pragma unroll
-        for (int r = 0; r < D; ++r) {
-            c[j][r] = a.Cf[j * D + r];
-            hs[j][r] = USE_H ? a.Hs[j * D + r] : 0.f;
-            ff[j][r] = USE_H ? a.Ff[j * D + r] : 0.f;
-        }
-
-    float acc[NACC];
-#pragma unroll
-    for (int q = 0; q < NACC; ++q) acc[q] = 0.f;
-
-    const int64_t base = (int64_t)blockIdx.x * a.vec_per_wg;
-    int64_t end = base + a.vec_per_wg;
-    if (end > a.m) end = a.m;
-    const float nscale = a.nscale;
-
-    for (int64_t i = base + threadIdx.x; i < end; i += WG) {
-        float w[D], g[D], gs[D];
-        VecLoad<D>::load(a.W, i, w);
-        if (USE_G) {
-            VecLoad<D>::load(a.G, i, g);
-#pragma unroll
-            for (int r = 0; r < D; ++r) gs[r] = g[r] * a.inv_tau;
-        }
+        for (int r = 0; r < D; ++r) gs[r] = USE_G ? g[r] * a.inv_tau : 0.f;
         float at[K], df[K][D], ri[K];
-        estep_small<K, D, DIST, BACK>(w, c, nscale, at, df, ri);
+        estep_small<K, D, DIST, BACK>(w, c, a.nscale, at, df, ri);
 
         if (STATS) {
 #pragma unroll
@@ -217,6 +196,46 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
             }
             if (PASS == PASS_B3) VecLoad<D>::store(a.dW_out, i, out);
         }
+    }
+};
+
+template <int K, int D, int DIST, int PASS>
+__global__ __launch_bounds__(WG) void small_pass(const Args a) {
+    using Item = SmallItem<K, D, DIST, PASS>;
+    constexpr int NACC = Item::NACC;
+
+    if (PASS == PASS_FWD && a.ctrl->done) return;
+    if (PASS == PASS_B2 && a.ctrl->b_done) return;
+
+    float c[K][D], hs[K][D], ff[K][D];
+#pragma unroll
+    for (int j = 0; j < K; ++j)
+#pragma unroll
+        for (int r = 0; r < D; ++r) {
+            c[j][r] = a.Cf[j * D + r];
+            hs[j][r] = Item::USE_H ? a.Hs[j * D + r] : 0.f;
+            ff[j][r] = Item::USE_H ? a.Ff[j * D + r] : 0.f;
+        }
+
+    float acc[NACC];
+#pragma unroll
+    for (int q = 0; q < NACC; ++q) acc[q] = 0.f;
+
+    const int64_t base = (int64_t)blockIdx.x * a.vec_per_wg;
+    int64_t end = base + a.vec_per_wg;
+    if (end > a.m) end = a.m;
+
+#pragma unroll 2
+    for (int64_t i = base + threadIdx.x; i < end; i += WG) {
+        float w[D], g[D];
+        VecLoad<D>::load(a.W, i, w);
+        if (Item::USE_G) {
+            VecLoad<D>::load(a.G, i, g);
+        } else {
+#pragma unroll
+            for (int r = 0; r < D; ++r) g[r] = 0.f;
+        }
+        Item::run(a, i, w, g, c, hs, ff, acc);
     }
 
     if (PASS == PASS_B3) return;

@@ -88,13 +88,25 @@ FWD_CASES = [
 ]
 
 
+@pytest.mark.parametrize("path", ["stream", "persistent"])
 @pytest.mark.parametrize("dist", DISTS)
 @pytest.mark.parametrize("name,cfg,m", FWD_CASES, ids=[c[0] for c in FWD_CASES])
-def test_forward_solve_and_backward_on_config_shaped_inputs(ctx, name, cfg, m, dist):
+def test_forward_solve_and_backward_on_config_shaped_inputs(ctx, name, cfg, m, dist, path):
+    if path == "persistent" and cfg == "C4":
+        pytest.skip("k = 256 has no persistent kernel; the stream path serves it")
+    ctx.set_path(binding.PATH_STREAM if path == "stream" else binding.PATH_PERSISTENT)
+    try:
+        _forward_backward_case(ctx, cfg, m, dist, binding.PATH_STREAM if path == "stream" else binding.PATH_PERSISTENT)
+    finally:
+        ctx.set_path(binding.PATH_AUTO)
+
+
+def _forward_backward_case(ctx, cfg, m, dist, expect_path):
     p = wl.make_problem(cfg, dist, m=m)
     Wd, C0d = dev(p.W), dev(p.C0)
     out = ctx.forward(Wd, C0d, p.tau, p.tol, p.max_iter, dist, want_A=True, want_Wq=True, want_assign=True)
     info = out["info"]
+    assert info.path == expect_path
     ref = orc.soft_kmeans(p.W, p.C0, p.tau, p.tol, p.max_iter, dist)
     Cg = out["C"].cpu().numpy()
     assert rel(Cg, ref["C"]) < TOL_VAL, (info, ref["iters"], rel(Cg, ref["C"]))
@@ -123,7 +135,7 @@ def test_forward_solve_and_backward_on_config_shaped_inputs(ctx, name, cfg, m, d
     bj = ctx.backward(Gd, binding.BWD_JFB)
     rj = orc.backward(p.W, Cg, p.tau, dist, G, "jfb")
     assert rel(bj["dW"].cpu().numpy(), rj["dW"]) < TOL_GRAD
-    assert bj["info"].iters == 0
+    assert bj["info"].iters == 0 and bj["info"].path == expect_path
 
     kd = p.cfg.k * p.cfg.d
     passes = 60 if kd <= 64 else 25
