@@ -12,7 +12,7 @@ from dataclasses import dataclass
 from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libidkm.so")
+LIB_PATH = os.environ.get("IDKM_LIB", os.path.join(HERE, "libidkm.so"))
 
 IDKM_OK = 0
 STATUS_NAMES = {0: "IDKM_OK", 1: "IDKM_ERR_INVALID_ARG", 2: "IDKM_ERR_ALLOC", 3: "IDKM_ERR_DEVICE",

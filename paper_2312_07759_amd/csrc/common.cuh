@@ -119,6 +119,39 @@ __device__ __forceinline__ double wave_sum_d(double x) {
     for (int o = 1; o < 64; o <<= 1) x += __shfl_xor(x, o, 64);
     return x;
 }
+// The same fixed-order DPP network as wave_sum, on float64 (moves the two 32-bit halves).
+template <int CTRL, int ROWMASK>
+__device__ __forceinline__ double dpp_d(double x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, ROWMASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, ROWMASK, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+// Sums of lanes 0..31 and of lanes 32..63; valid in lane 31 and lane 63 respectively.
+__device__ __forceinline__ double half_sum_d_dpp(double x) {
+    x += dpp_d<0xB1, 0xf>(x);
+    x += dpp_d<0x4E, 0xf>(x);
+    x += dpp_d<0x141, 0xf>(x);
+    x += dpp_d<0x140, 0xf>(x);
+    x += dpp_d<0x142, 0xa>(x);
+    return x;
+}
+// Sum of all 64 lanes, returned to every lane.
+__device__ __forceinline__ double wave_sum_d_dpp(double x) {
+    x = half_sum_d_dpp(x);
+    x += dpp_d<0x143, 0xc>(x);
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(x), 63);
+    return __hiloint2double(hi, lo);
+}
+// s / n for n > 0 without the IEEE division sequence: float32 reciprocal refined by two Newton steps in float64
+// (relative error of the reciprocal ~1e-28 before rounding), then one multiply.
+__device__ __forceinline__ double fast_div_d(double s, double n) {
+    double r = (double)__builtin_amdgcn_rcpf((float)n);
+    r = r * (2.0 - n * r);
+    r = r * (2.0 - n * r);
+    r = r * (2.0 - n * r);
+    return s * r;
+}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }

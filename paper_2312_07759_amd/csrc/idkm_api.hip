@@ -4,6 +4,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -125,10 +126,15 @@ struct idkm_ctx {
     // persistent path
     int num_cu = 0;
     bool coop = false;
-    unsigned long long* xbuf = nullptr;  // [2][XROWS][num_cu] stamped exchange words
+    bool coop_launch = false;  // IDKM_COOPERATIVE=1 launches the persistent kernels cooperatively
+    int min_vec_per_thread = 4;  // vectors per thread before another workgroup is added (IDKM_MIN_VPT)
+    unsigned long long* xbuf = nullptr;  // exchange words: buf1 [2][PT][XLINE], then buf2 [2][XBCAST]
     size_t xbuf_words = 0;
     unsigned int seq_base = 0;
     unsigned int spin_limit = 1u << 20;
+#ifdef IDKM_TRACE
+    long long* trace = nullptr;
+#endif
     // forward state
     bool has_forward = false;
     const float* W = nullptr;
@@ -236,7 +242,8 @@ idkm_status launch_pass(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, hip
     return IDKM_OK;
 }
 
-constexpr int XROWS = 32;                 // widest exchange row count: K (D+1) <= 32
+constexpr size_t XBUF1_WORDS = (size_t)2 * PT * XLINE;
+constexpr size_t XBUF_WORDS = XBUF1_WORDS + (size_t)2 * XBCAST;
 constexpr size_t LDS_TILE_MAX = 144 * 1024;  // bytes of LDS a persistent workgroup may use for its tile
 
 struct PersistPlan {
@@ -249,13 +256,15 @@ struct PersistPlan {
 bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
     if (!ctx->coop || ctx->num_cu < 1) return false;
     const int k = ctx->k, d = ctx->d;
-    if (!(k >= 2 && k <= 16 && pow2(k) && d <= 4) || k * (d + 1) > XROWS) return false;
+    if (!(k >= 2 && k <= 16 && pow2(k) && d <= 4) || k * (d + 1) > XLINE) return false;
     pp->fn = persist_kernel(k, d, ctx->dist, bwd);
     if (!pp->fn) return false;
     const int64_t m = ctx->m;
-    int64_t g = (m + 4 * PT - 1) / (4 * PT);  // at least ~4 vectors per thread before adding workgroups
+    const int64_t chunk = (int64_t)ctx->min_vec_per_thread * PT;
+    int64_t g = (m + chunk - 1) / chunk;  // a few vectors per thread before adding workgroups
     if (g < 1) g = 1;
     if (g > ctx->num_cu) g = ctx->num_cu;
+    if (g > PT) g = PT;  // a reducer reads one workgroup per thread
     int64_t per = (m + g - 1) / g;
     per = (per + 3) / 4 * 4;
     const size_t lds = (size_t)per * d * sizeof(float) * (bwd ? 2 : 1);
@@ -267,24 +276,34 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
 }
 
 idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, unsigned int exchanges, hipStream_t s) {
-    if ((size_t)2 * XROWS * pp.grid > ctx->xbuf_words) return fail(ctx, IDKM_ERR_DEVICE, "exchange buffer too small");
+    if (pp.grid > PT || ctx->xbuf_words < XBUF_WORDS) return fail(ctx, IDKM_ERR_DEVICE, "exchange buffer too small");
     if (ctx->seq_base > 0xffffffffu - exchanges - 2u) {  // stamps would wrap: start over from a clean buffer
         hipLaunchKernelGGL(k_fill_u64, dim3(64), dim3(256), 0, s, ctx->xbuf, ctx->xbuf_words, 0ull);
         HIP_TRY(ctx, hipGetLastError());
         ctx->seq_base = 0;
     }
     PArgs pa;
-    pa.xbuf = ctx->xbuf;
+    pa.buf1 = ctx->xbuf;
+    pa.buf2 = ctx->xbuf + XBUF1_WORDS;
     pa.seq_base = ctx->seq_base;
     pa.spin_limit = ctx->spin_limit;
     pa.per = pp.per;
+#ifdef IDKM_TRACE
+    pa.trace = ctx->trace;
+#endif
     HIP_TRY(ctx, hipFuncSetAttribute((const void*)pp.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pp.lds));
     int nb = 0;
     HIP_TRY(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)pp.fn, PT, pp.lds));
     if (nb < 1 || (int64_t)nb * ctx->num_cu < pp.grid)
         return fail(ctx, IDKM_ERR_DEVICE, "persistent grid would not be co-resident");
-    void* args[] = {(void*)&a, (void*)&pa};
-    HIP_TRY(ctx, hipLaunchCooperativeKernel((const void*)pp.fn, dim3(pp.grid), dim3(PT), args, pp.lds, s));
+    if (ctx->coop_launch) {
+        void* args[] = {(void*)&a, (void*)&pa};
+        HIP_TRY(ctx, hipLaunchCooperativeKernel((const void*)pp.fn, dim3(pp.grid), dim3(PT), args, pp.lds, s));
+    } else {
+        // plain launch: the grid fits the device (checked above), every wait in the kernel is bounded
+        hipLaunchKernelGGL(pp.fn, dim3(pp.grid), dim3(PT), pp.lds, s, a, pa);
+        HIP_TRY(ctx, hipGetLastError());
+    }
     ctx->seq_base += exchanges;
     return IDKM_OK;
 }
@@ -386,7 +405,12 @@ idkm_status idkm_create(idkm_ctx** out, int device_id) {
         c->num_cu = prop.multiProcessorCount;
         c->coop = prop.cooperativeLaunch != 0;
     }
-    c->xbuf_words = (size_t)2 * XROWS * (c->num_cu > 0 ? c->num_cu : 1);
+    if (const char* e = std::getenv("IDKM_COOPERATIVE")) c->coop_launch = (e[0] == '1');
+    if (const char* e = std::getenv("IDKM_MIN_VPT")) {
+        int v = std::atoi(e);
+        if (v >= 1 && v <= 1024) c->min_vec_per_thread = v;
+    }
+    c->xbuf_words = XBUF_WORDS;
     ok &= hipMalloc(&c->xbuf, c->xbuf_words * sizeof(unsigned long long)) == hipSuccess;
     if (ok) ok &= hipMemset(c->xbuf, 0, c->xbuf_words * sizeof(unsigned long long)) == hipSuccess;
     if (ok) ok &= hipDeviceSynchronize() == hipSuccess;
@@ -579,6 +603,15 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     }
     return IDKM_OK;
 }
+
+#ifdef IDKM_TRACE
+// development builds only: device buffer of 2*64*8 int64 clock stamps filled by the persistent forward kernel
+idkm_status idkm_debug_trace(idkm_ctx* ctx, long long* dev_buf) {
+    if (!ctx) return IDKM_ERR_INVALID_ARG;
+    ctx->trace = dev_buf;
+    return IDKM_OK;
+}
+#endif
 
 idkm_status idkm_step_F(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, const float* C, int32_t k, float tau,
                         idkm_dist dist, float* Cplus_out, float* n_out, void* hip_stream) {

@@ -1,39 +1,53 @@
 // Persistent kernels for small codebooks: one launch per solve.  Each workgroup
 // keeps its tile of W (and of dL/dWq in the backward) in LDS for the whole solve,
 // so after the first read no pass touches HBM for its inputs; the only grid-wide
-// traffic per pass is one exchange of K (D+1) partial sums per workgroup.
+// traffic per pass is one two-hop exchange of O(k d) numbers.
 //
-// Exchange: every workgroup publishes its partial sums as 64-bit words
-// {sequence number, float32 value} with device-scope stores, then reads all
-// workgroups' words until every sequence number matches.  Value and stamp travel
-// in one atomic word, so no fence and no counter round trip is needed; two
-// buffers alternate by sequence parity.  All workgroups add the same words in
-// the same order, hence take bit-identical decisions.  Waits are bounded: after
-// spin_limit polls a workgroup raises Ctrl::abort_flag and leaves; the others
-// see the flag and leave too.  The grid must be co-resident (cooperative launch).
+// Exchange (per pass over W):
+//   hop 1  every workgroup stores its K (D+1) partial sums into its own column of
+//          buf1 as 64-bit words {sequence number, float32 value};
+//          the first R workgroups are "reducers": reducer r owns a slice of the
+//          codewords, reads that slice's rows (one word per workgroup, coalesced)
+//          (thread t <-> workgroup t), adds them in a fixed order in float64 and
+//          applies the O(k d) update (centre update of Alg. 1, or the averaged
+//          step of Sec. 4.2) to its slice;
+//   hop 2  reducers store the float32 values the next pass needs (codewords, or
+//          h/tau) plus a partial residual into buf2; every workgroup reads those
+//          few words and takes the same stop decision.
+// Value and stamp travel in one atomic word, so no fence and no counter round
+// trip is needed; two buffers alternate by sequence parity.  Waits are bounded:
+// after spin_limit polls a workgroup raises Ctrl::abort_flag and leaves; the
+// others see the flag and leave too.  The grid must fit the device at once.
 #pragma once
 #include "common.cuh"
 #include "small_k.cuh"
 
 namespace idkm {
 
-constexpr int PT = 256;  // threads per workgroup of the persistent kernels
+constexpr int PT = 256;      // threads per workgroup of the persistent kernels; also the largest grid
+constexpr int XLINE = 32;    // words reserved per workgroup in buf1 (K (D+1) <= 32)
+constexpr int XBCAST = 64;   // words reserved in buf2
 
 struct PArgs {
-    unsigned long long* xbuf;  // [2][NP][gridDim.x] stamped words
+    unsigned long long* buf1;  // [2][XLINE][PT] stamped partial sums, word (accumulator, workgroup)
+    unsigned long long* buf2;  // [2][XBCAST] stamped broadcast values
     unsigned int seq_base;     // sequence numbers seq_base+1 ... are used by this launch
     unsigned int spin_limit;   // polls before a wait gives up
     int per;                   // vectors per workgroup tile
+#ifdef IDKM_TRACE
+    long long* trace;          // [2 workgroups][64 passes][8 stamps] of the shader clock (development builds only)
+#endif
 };
 
-constexpr int next_pow2(int x) {
-    int p = 1;
-    while (p < x) p <<= 1;
-    return p;
-}
-// Rows of the exchange buffer for NACC accumulators: a power of two, and at least
-// PT/64 so that the threads sharing one row sit inside one wavefront.
-constexpr int xchg_rows(int nacc) { return next_pow2(nacc) < PT / 64 ? PT / 64 : next_pow2(nacc); }
+#ifdef IDKM_TRACE
+#define IDKM_STAMP(slot)                                                                                  \
+    do {                                                                                                  \
+        if (pa.trace && threadIdx.x == 0 && s_iters < 64 && (blockIdx.x == 0 || blockIdx.x == gridDim.x - 1)) \
+            pa.trace[((blockIdx.x == 0 ? 0 : 1) * 64 + s_iters) * 8 + (slot)] = (long long)clock64();      \
+    } while (0)
+#else
+#define IDKM_STAMP(slot) do { } while (0)
+#endif
 
 __device__ __forceinline__ unsigned long long ld_word(const unsigned long long* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -41,57 +55,70 @@ __device__ __forceinline__ unsigned long long ld_word(const unsigned long long* 
 __device__ __forceinline__ void st_word(unsigned long long* p, unsigned long long v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ unsigned long long pack_f(unsigned int seq, float v) {
+    return ((unsigned long long)seq << 32) | (unsigned long long)__float_as_uint(v);
+}
+__device__ __forceinline__ unsigned long long pack_u(unsigned int seq, unsigned int v) {
+    return ((unsigned long long)seq << 32) | (unsigned long long)v;
+}
 
-// Sums acc[q] over the whole grid into s_tot[q] (float64, fixed order).  Returns
-// false in every thread of the workgroup if the wait was abandoned.
+// Shared scratch of the exchange.
 template <int NACC>
-__device__ __forceinline__ bool grid_exchange(const PArgs& pa, Ctrl* ctrl, unsigned int seq, const float (&acc)[NACC],
-                                              double* s_wpart, double* s_tot, int* s_abort) {
-    constexpr int NP = xchg_rows(NACC);
-    constexpr int TPA = PT / NP;  // threads that share the words of one accumulator
-    static_assert(NP <= PT && TPA <= 64, "accumulator count does not fit the exchange layout");
+struct XShared {
+    double wpart[(PT / 64) * NACC];  // per-wavefront partial sums
+    float red[8][PT];                // reducer: words of every workgroup, transposed
+    double tot[8];                   // reducer: totals of its slice
+    unsigned int bc[XBCAST];         // payloads of the broadcast words
+    int abort;
+};
+
+// hop 1, sender side: workgroup partial of every accumulator into this workgroup's line.
+template <int NACC>
+__device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int seq, const float (&acc)[NACC],
+                                                 XShared<NACC>& xs) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int G = gridDim.x;
 #pragma unroll
     for (int q = 0; q < NACC; ++q) {
         const float v = wave_sum(acc[q]);
-        if (lane == 0) s_wpart[wave * NACC + q] = (double)v;
+        if (lane == 0) xs.wpart[wave * NACC + q] = (double)v;
     }
     __syncthreads();
-    unsigned long long* buf = pa.xbuf + (size_t)(seq & 1u) * NP * G;
     if (tid < NACC) {
         double s = 0.0;
 #pragma unroll
-        for (int w = 0; w < PT / 64; ++w) s += s_wpart[w * NACC + tid];
-        const unsigned long long word = ((unsigned long long)seq << 32) | (unsigned long long)__float_as_uint((float)s);
-        st_word(&buf[(size_t)tid * G + blockIdx.x], word);
+        for (int w = 0; w < PT / 64; ++w) s += xs.wpart[w * NACC + tid];
+        // row = accumulator, column = workgroup: a reducer's wavefront then reads 64 consecutive words per load
+        st_word(&pa.buf1[((size_t)(seq & 1u) * XLINE + tid) * PT + blockIdx.x], pack_f(seq, (float)s));
     }
-    const int ai = tid / TPA, sub = tid % TPA;
-    const int wpt = (G + TPA - 1) / TPA;
-    const int first = sub * wpt;
-    int cnt = G - first;
-    if (cnt > wpt) cnt = wpt;
-    double sum = 0.0;
+}
+
+// hop 1, reducer side: totals over all workgroups of words [first, first+WPR) into xs.tot (float64, fixed order).
+// Returns false if the wait was abandoned (uniform over the workgroup).
+template <int NACC, int WPR>
+__device__ __forceinline__ bool reduce_slice(const PArgs& pa, Ctrl* ctrl, unsigned int seq, int first,
+                                             XShared<NACC>& xs) {
+    static_assert(WPR <= 8, "a reducer handles at most 8 words per workgroup");
+    const int tid = threadIdx.x;
+    const int G = gridDim.x;
+    float f[WPR];
+#pragma unroll
+    for (int q = 0; q < WPR; ++q) f[q] = 0.f;
     bool aborted = false;
-    if (ai < NACC && cnt > 0) {
-        const unsigned long long* src = buf + (size_t)ai * G + first;
+    if (tid < G) {
+        const unsigned long long* src = pa.buf1 + ((size_t)(seq & 1u) * XLINE + first) * PT + tid;
         unsigned int spins = 0;
         for (;;) {
+            unsigned long long w[WPR];
+#pragma unroll
+            for (int q = 0; q < WPR; ++q) w[q] = ld_word(src + (size_t)q * PT);
             bool ok = true;
-            sum = 0.0;
-            for (int q = 0; q < cnt; q += 4) {
-                unsigned long long w0 = ld_word(src + q);
-                unsigned long long w1 = (q + 1 < cnt) ? ld_word(src + q + 1) : w0;
-                unsigned long long w2 = (q + 2 < cnt) ? ld_word(src + q + 2) : w0;
-                unsigned long long w3 = (q + 3 < cnt) ? ld_word(src + q + 3) : w0;
-                ok = ok && ((unsigned int)(w0 >> 32) == seq) && ((unsigned int)(w1 >> 32) == seq) &&
-                     ((unsigned int)(w2 >> 32) == seq) && ((unsigned int)(w3 >> 32) == seq);
-                sum += (double)__uint_as_float((unsigned int)w0);
-                if (q + 1 < cnt) sum += (double)__uint_as_float((unsigned int)w1);
-                if (q + 2 < cnt) sum += (double)__uint_as_float((unsigned int)w2);
-                if (q + 3 < cnt) sum += (double)__uint_as_float((unsigned int)w3);
+#pragma unroll
+            for (int q = 0; q < WPR; ++q) ok = ok && ((unsigned int)(w[q] >> 32) == seq);
+            if (ok) {
+#pragma unroll
+                for (int q = 0; q < WPR; ++q) f[q] = __uint_as_float((unsigned int)w[q]);
+                break;
             }
-            if (ok) break;
             ++spins;
             if (spins > pa.spin_limit ||
                 ((spins & 31u) == 0u && __hip_atomic_load(&ctrl->abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
@@ -101,14 +128,58 @@ __device__ __forceinline__ bool grid_exchange(const PArgs& pa, Ctrl* ctrl, unsig
         }
     }
 #pragma unroll
-    for (int o = 1; o < TPA; o <<= 1) sum += __shfl_xor(sum, o, 64);
-    if (ai < NACC && sub == 0) s_tot[ai] = sum;
+    for (int q = 0; q < WPR; ++q) xs.red[q][tid] = f[q];
     if (aborted) {
-        *s_abort = 1;
+        xs.abort = 1;
         __hip_atomic_store(&ctrl->abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
-    return *s_abort == 0;
+#ifdef IDKM_TRACE
+    if (pa.trace && threadIdx.x == 0 && blockIdx.x == 0) pa.trace[2 * 64 * 8 - 1] = (long long)clock64();
+#endif
+    if (xs.abort) return false;
+    // thread (q, part) adds workgroups part*8 .. part*8+7 of word q, then a fixed 32-lane DPP network
+    const int q = tid >> 5, part = tid & 31;
+    double s = 0.0;
+    if (q < WPR) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (double)xs.red[q][part * 8 + u];
+    }
+    s = half_sum_d_dpp(s);
+    if (q < WPR && part == 31) xs.tot[q] = s;
+    __syncthreads();
+    return true;
+}
+
+// hop 2, receiver side: waits for words [0, nwords) of buf2 and leaves their payloads in xs.bc.
+template <int NACC>
+__device__ __forceinline__ bool gather_bcast(const PArgs& pa, Ctrl* ctrl, unsigned int seq, int nwords,
+                                             XShared<NACC>& xs) {
+    const int tid = threadIdx.x;
+    bool aborted = false;
+    if (tid < nwords) {
+        const unsigned long long* src = pa.buf2 + (size_t)(seq & 1u) * XBCAST + tid;
+        unsigned int spins = 0;
+        for (;;) {
+            const unsigned long long w = ld_word(src);
+            if ((unsigned int)(w >> 32) == seq) {
+                xs.bc[tid] = (unsigned int)w;
+                break;
+            }
+            ++spins;
+            if (spins > pa.spin_limit ||
+                ((spins & 31u) == 0u && __hip_atomic_load(&ctrl->abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                aborted = true;
+                break;
+            }
+        }
+    }
+    if (aborted) {
+        xs.abort = 1;
+        __hip_atomic_store(&ctrl->abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    return xs.abort == 0;
 }
 
 // One pass over the workgroup's LDS tile.
@@ -140,22 +211,35 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
     }
 }
 
+// Codewords per reducer: as many as fit 8 words of (n_j, s_j) per workgroup.
+constexpr int cw_per_reducer(int K, int D) {
+    int kpr = 8 / (D + 1);
+    if (kpr < 1) kpr = 1;
+    int p = 1;
+    while (p * 2 <= kpr) p *= 2;
+    return p > K ? K : p;
+}
+
 // Forward solve (Alg. 1) and the evaluation at C*, in one launch.
 template <int K, int D, int DIST>
 __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) {
     constexpr int KD = K * D;
-    constexpr int NACC = K * (D + 1);
-    static_assert(KD <= 64, "codebook must fit one wavefront");
+    constexpr int ACCW = D + 1;
+    constexpr int NACC = K * ACCW;
+    constexpr int KPR = cw_per_reducer(K, D);  // codewords owned by one reducer
+    constexpr int R = K / KPR;                 // reducers
+    constexpr int WPR = KPR * ACCW;            // words a reducer reads per workgroup
+    constexpr int NB = KD;                     // broadcast words: the new codebook
+    static_assert(NACC <= XLINE && NB <= XBCAST && KD <= 64, "shape does not fit the exchange layout");
     extern __shared__ float s_tile[];
-    __shared__ double s_wpart[(PT / 64) * NACC];
-    __shared__ double s_tot[xchg_rows(NACC)];
-    __shared__ double s_Cd[KD];
+    __shared__ XShared<NACC> xs;
+    __shared__ double s_Cd[KD];  // float64 master copy (a reducer's own slice is the live one)
     __shared__ float s_Cf[KD];
-    __shared__ int s_abort, s_done, s_iters, s_conv, s_bad, s_empty;
+    __shared__ int s_done, s_iters, s_conv, s_bad;
     __shared__ double s_res;
 
-    const int tid = threadIdx.x;
-    const int64_t base = (int64_t)blockIdx.x * pa.per;
+    const int tid = threadIdx.x, wg = blockIdx.x;
+    const int64_t base = (int64_t)wg * pa.per;
     int cnt = 0;
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
     for (int i = tid; i < cnt * D; i += PT) s_tile[i] = a.W[base * D + i];
@@ -164,86 +248,99 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
         s_Cf[tid] = a.Cf[tid];
     }
     if (tid == 0) {
-        s_abort = 0;
+        xs.abort = 0;
         s_done = 0;
         s_iters = 0;
         s_conv = 0;
         s_bad = 0;
-        s_empty = 0;
         s_res = 0.0;
     }
     __syncthreads();
     const double tol = a.ctrl->tol;
     const int max_iter = a.ctrl->max_iter;
+    // reducer r is workgroup r; with fewer than R workgroups the first ones take several slices in turn
     unsigned int seq = pa.seq_base;
 
     float acc[NACC];
     while (!s_done) {
+        IDKM_STAMP(0);
         tile_pass<K, D, DIST, PASS_FWD>(a, s_tile, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
+        IDKM_STAMP(1);
         ++seq;
-        if (!grid_exchange<NACC>(pa, a.ctrl, seq, acc, s_wpart, s_tot, &s_abort)) return;
-        // centre update and stop test (Alg. 1), identically in every workgroup
-        if (tid < 64) {
-            double r2 = 0.0, bad = 0.0, empty = 0.0;
-            if (tid < KD) {
-                const int j = tid / D, r = tid - j * D;
-                const double n = s_tot[j * (D + 1)], s = s_tot[j * (D + 1) + 1 + r];
-                const double cold = s_Cd[tid];
-                const double cnew = (n > 0.0) ? s / n : cold;
-                if (!(n > 0.0) && r == 0) empty = 1.0;
-                if (!(n >= 0.0) || !(fabs(s) <= 1.7e308) || !(fabs(cnew) <= 1.7e308)) bad = 1.0;
-                const double df = cnew - cold;
-                r2 = df * df;
-                s_Cd[tid] = cnew;
-                s_Cf[tid] = (float)cnew;
-            }
-            r2 = wave_sum_d(r2);
-            bad = wave_sum_d(bad);
-            empty = wave_sum_d(empty);
-            if (tid == 0) {
-                const double res = sqrt(r2);
-                s_iters += 1;
-                s_res = res;
-                s_empty = (int)(empty + 0.5);
-                if (bad > 0.0) s_bad = 1;
-                const bool conv = res < tol;
-                s_conv = conv ? 1 : 0;
-                if (conv || bad > 0.0 || s_iters >= max_iter) s_done = 1;
+        publish_partials<NACC>(pa, seq, acc, xs);
+        IDKM_STAMP(2);
+        for (int r = wg; r < R; r += gridDim.x) {
+            if (!reduce_slice<NACC, WPR>(pa, a.ctrl, seq, r * WPR, xs)) return;
+            IDKM_STAMP(3);
+#ifdef IDKM_TRACE
+            if (pa.trace && threadIdx.x == 0 && blockIdx.x == 0 && s_iters < 64) pa.trace[s_iters * 8 + 6] = pa.trace[2 * 64 * 8 - 1];
+#endif
+            // centre update of this slice (Alg. 1), float64; a non-finite sum is broadcast as NaN
+            if (tid < KPR * D) {
+                const int jl = tid / D, rr = tid - jl * D, idx = (r * KPR + jl) * D + rr;
+                const double n = xs.tot[jl * ACCW], s = xs.tot[jl * ACCW + 1 + rr];
+                const double cold = s_Cd[idx];
+                double cnew = (n > 0.0) ? fast_div_d(s, n) : cold;
+                if (!(n >= 0.0) || !(fabs(s) <= 1.7e308) || !(fabs(cnew) <= 1.7e308)) cnew = __builtin_nan("");
+                s_Cd[idx] = cnew;
+                st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + idx], pack_f(seq, (float)cnew));
             }
         }
+        IDKM_STAMP(4);
+        if (!gather_bcast<NACC>(pa, a.ctrl, seq, NB, xs)) return;
+        IDKM_STAMP(5);
+        if (tid == 0) {
+            // ||C+ - C||_F^2 from the float32 codebooks every workgroup holds: the same words, the same order,
+            // hence the same stop decision everywhere
+            double r2 = 0.0;
+#pragma unroll
+            for (int q = 0; q < KD; ++q) {
+                const double df = (double)__uint_as_float(xs.bc[q]) - (double)s_Cf[q];
+                r2 += df * df;
+            }
+            s_iters += 1;
+            s_res = r2;  // squared; the root is taken once, when the solve is over
+            const bool bad = !(r2 <= 1.7e308);
+            if (bad) s_bad = 1;
+            const bool conv = r2 < tol * tol;
+            s_conv = conv ? 1 : 0;
+            if (conv || bad || s_iters >= max_iter) s_done = 1;
+        }
+        __syncthreads();
+        if (tid < KD) s_Cf[tid] = __uint_as_float(xs.bc[tid]);
         __syncthreads();
     }
 
     // evaluation at C*: outputs, and n*, F* for the backward
     tile_pass<K, D, DIST, PASS_FIN>(a, s_tile, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
     ++seq;
-    if (!grid_exchange<NACC>(pa, a.ctrl, seq, acc, s_wpart, s_tot, &s_abort)) return;
-    if (blockIdx.x == 0 && tid < 64) {
-        double bad = 0.0, empty = 0.0;
-        if (tid < KD) {
-            const int j = tid / D, r = tid - j * D;
-            const double n = s_tot[j * (D + 1)], s = s_tot[j * (D + 1) + 1 + r];
-            const double f = (n > 0.0) ? s / n : s_Cd[tid];
-            if (!(n > 0.0) && r == 0) empty = 1.0;
-            if (!(n >= 0.0) || !(fabs(s) <= 1.7e308)) bad = 1.0;
-            a.Cd[tid] = s_Cd[tid];
-            a.Cf[tid] = s_Cf[tid];
-            a.Fd[tid] = f;
-            a.Ff[tid] = (float)f;
-            if (r == 0) a.nd[j] = n;
-            if (a.C_out) a.C_out[tid] = s_Cf[tid];
+    publish_partials<NACC>(pa, seq, acc, xs);
+    for (int r = wg; r < R; r += gridDim.x) {
+        if (!reduce_slice<NACC, WPR>(pa, a.ctrl, seq, r * WPR, xs)) return;
+        if (tid < KPR * D) {
+            const int jl = tid / D, rr = tid - jl * D, j = r * KPR + jl, idx = j * D + rr;
+            const double n = xs.tot[jl * ACCW], s = xs.tot[jl * ACCW + 1 + rr];
+            const double cst = (double)s_Cf[idx];
+            const double f = (n > 0.0) ? fast_div_d(s, n) : cst;
+            if (!(n > 0.0) && rr == 0) atomicAdd(&a.ctrl->empty, 1);
+            if (!(n >= 0.0) || !(fabs(s) <= 1.7e308)) atomicOr(&a.ctrl->nonfinite, 1);
+            a.Cd[idx] = cst;
+            a.Cf[idx] = s_Cf[idx];
+            a.Fd[idx] = f;
+            a.Ff[idx] = (float)f;
+            if (rr == 0) a.nd[j] = n;
+            if (a.C_out) a.C_out[idx] = s_Cf[idx];
         }
-        bad = wave_sum_d(bad);
-        empty = wave_sum_d(empty);
-        if (tid == 0) {
-            Ctrl* c = a.ctrl;
-            c->iters = s_iters;
-            c->residual = s_res;
-            c->converged = s_conv;
-            c->empty = (int)(empty + 0.5);
-            c->nonfinite = (s_bad || bad > 0.0) ? 1 : 0;
-            c->done = 1;
-        }
+        __syncthreads();
+    }
+    if (wg == gridDim.x - 1 && tid == 0) {
+        // the last workgroup is never a reducer unless the grid is tiny; either way these fields are its own
+        Ctrl* c = a.ctrl;
+        c->iters = s_iters;
+        c->residual = sqrt(s_res);
+        c->converged = s_conv;
+        if (s_bad) atomicOr(&c->nonfinite, 1);
+        c->done = 1;
     }
 }
 
@@ -252,17 +349,20 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
 template <int K, int D, int DIST>
 __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) {
     constexpr int KD = K * D;
-    static_assert(KD <= 64, "codebook must fit one wavefront");
+    constexpr int KPR = (8 / D) > K ? K : (8 / D);  // codewords per reducer: 8 words of D components
+    constexpr int R = K / KPR;
+    constexpr int WPR = KPR * D;
+    constexpr int NB = KD + R;  // broadcast words: h/tau, then one partial squared norm per reducer
+    static_assert(KD <= XLINE && NB <= XBCAST && KD <= 64, "shape does not fit the exchange layout");
     extern __shared__ float s_tile[];
-    __shared__ double s_wpart[(PT / 64) * KD];
-    __shared__ double s_tot[xchg_rows(KD)];
-    __shared__ double s_v[KD], s_g[KD], s_n[K];
-    __shared__ float s_Cf[KD], s_Hs[KD], s_Ff[KD];
-    __shared__ int s_abort, s_done, s_iters, s_conv, s_attempt, s_grow, s_halv, s_bad;
+    __shared__ XShared<KD> xs;
+    __shared__ double s_v[KD], s_g[KD], s_rn[K];  // a reducer's own slice is the live one; s_rn = 1/(tau n)
+    __shared__ float s_Cf[KD], s_Hs[KD], s_Hv[KD], s_Ff[KD];
+    __shared__ int s_done, s_iters, s_conv, s_attempt, s_grow, s_halv, s_bad, s_restart;
     __shared__ double s_alpha, s_prev, s_vnorm, s_res;
 
-    const int tid = threadIdx.x;
-    const int64_t base = (int64_t)blockIdx.x * pa.per;
+    const int tid = threadIdx.x, wg = blockIdx.x;
+    const int64_t base = (int64_t)wg * pa.per;
     int cnt = 0;
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
     float* s_w = s_tile;
@@ -275,13 +375,17 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
         s_Cf[tid] = a.Cf[tid];
         s_Ff[tid] = a.Ff[tid];
         s_Hs[tid] = 0.f;
+        s_Hv[tid] = 0.f;
     }
-    if (tid < K) s_n[tid] = a.nd[tid];
+    if (tid < K) {
+        const double n = a.nd[tid];
+        s_rn[tid] = (n > 0.0) ? (double)a.inv_tau / n : 0.0;  // zero for an empty cluster
+    }
     const int mode = a.ctrl->b_mode;
     const double tol = a.ctrl->b_tol;
     const int max_iter = a.ctrl->b_max_iter;
     if (tid == 0) {
-        s_abort = 0;
+        xs.abort = 0;
         s_done = (mode == BWD_JFB) ? 1 : 0;
         s_iters = 0;
         s_conv = (mode == BWD_JFB) ? 1 : 0;
@@ -289,6 +393,7 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
         s_grow = 0;
         s_halv = 0;
         s_bad = 0;
+        s_restart = 0;
         s_alpha = a.ctrl->b_alpha;
         s_prev = __builtin_inf();
         s_vnorm = 0.0;
@@ -296,30 +401,41 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
     }
     __syncthreads();
     unsigned int seq = pa.seq_base;
-    const double inv_tau = (double)a.inv_tau;
 
     float acc[KD];
     // B1: v = dL/dC* with W fixed; the solve starts at g = v
     tile_pass<K, D, DIST, PASS_B1>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
     ++seq;
-    if (!grid_exchange<KD>(pa, a.ctrl, seq, acc, s_wpart, s_tot, &s_abort)) return;
-    if (tid < 64) {
-        double v2 = 0.0;
-        if (tid < KD) {
-            const double v = s_tot[tid];
-            const double n = s_n[tid / D];
-            s_v[tid] = v;
-            s_g[tid] = v;
-            s_Hs[tid] = (n > 0.0) ? (float)(v / n * inv_tau) : 0.f;
-            v2 = v * v;
-        }
-        v2 = wave_sum_d(v2);
-        if (tid == 0) {
-            s_vnorm = sqrt(v2);
-            if (!(v2 <= 1.7e308)) {
-                s_bad = 1;
-                s_done = 1;
+    publish_partials<KD>(pa, seq, acc, xs);
+    for (int r = wg; r < R; r += gridDim.x) {
+        if (!reduce_slice<KD, WPR>(pa, a.ctrl, seq, r * WPR, xs)) return;
+        if (tid < 64) {
+            double v2 = 0.0;
+            if (tid < WPR) {
+                const int idx = r * WPR + tid;
+                const double v = xs.tot[tid];
+                s_v[idx] = v;
+                s_g[idx] = v;
+                v2 = v * v;
+                const float h = (float)(v * s_rn[idx / D]);
+                st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + idx], pack_f(seq, h));
             }
+            v2 = wave_sum_d_dpp(v2);
+            if (tid == 0) st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + KD + r], pack_f(seq, (float)v2));
+        }
+    }
+    if (!gather_bcast<KD>(pa, a.ctrl, seq, NB, xs)) return;
+    if (tid < KD) {
+        s_Hs[tid] = __uint_as_float(xs.bc[tid]);
+        s_Hv[tid] = s_Hs[tid];
+    }
+    if (tid == 0) {
+        double v2 = 0.0;
+        for (int r = 0; r < R; ++r) v2 += (double)__uint_as_float(xs.bc[KD + r]);
+        s_vnorm = v2;  // squared norms throughout the solve; roots are taken when it is over
+        if (!(v2 <= 1.7e308)) {
+            s_bad = 1;
+            s_done = 1;
         }
     }
     __syncthreads();
@@ -327,25 +443,38 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
     while (!s_done) {
         tile_pass<K, D, DIST, PASS_B2>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
         ++seq;
-        if (!grid_exchange<KD>(pa, a.ctrl, seq, acc, s_wpart, s_tot, &s_abort)) return;
-        if (tid < 64) {
-            const double alpha = s_alpha;
-            double d2 = 0.0, gn = 0.0;
-            if (tid < KD) {
-                const double g = s_g[tid];
-                gn = alpha * (s_v[tid] + s_tot[tid]) + (1.0 - alpha) * g;
-                const double df = gn - g;
-                d2 = df * df;
+        publish_partials<KD>(pa, seq, acc, xs);
+        const double alpha = s_alpha;
+        for (int r = wg; r < R; r += gridDim.x) {
+            if (!reduce_slice<KD, WPR>(pa, a.ctrl, seq, r * WPR, xs)) return;
+            if (tid < 64) {
+                double d2 = 0.0;
+                if (tid < WPR) {
+                    const int idx = r * WPR + tid;
+                    const double g = s_g[idx];
+                    const double gn = alpha * (s_v[idx] + xs.tot[tid]) + (1.0 - alpha) * g;
+                    const double df = gn - g;
+                    d2 = df * df;
+                    s_g[idx] = gn;
+                    const float h = (float)(gn * s_rn[idx / D]);
+                    st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + idx], pack_f(seq, h));
+                }
+                d2 = wave_sum_d_dpp(d2);
+                if (tid == 0) st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + KD + r], pack_f(seq, (float)d2));
             }
-            d2 = wave_sum_d(d2);
-            // the same decision in every lane and every workgroup (cf. tail_b2)
-            const double dn = sqrt(d2);
+        }
+        if (!gather_bcast<KD>(pa, a.ctrl, seq, NB, xs)) return;
+        if (tid == 0) {
+            // the same decision in every workgroup (same words, same order)
+            double d2 = 0.0;
+            for (int r = 0; r < R; ++r) d2 += (double)__uint_as_float(xs.bc[KD + r]);
+            const double dn = d2;  // squared step norm: every comparison below is between squares
             bool restart = false, done = false, conv = false, diverged = false;
             int grow = s_grow;
             const int attempt = s_attempt + 1;
             if (!(dn <= 1.7e308)) {
                 diverged = true;
-            } else if (dn <= tol * s_vnorm) {
+            } else if (dn <= tol * tol * s_vnorm) {
                 conv = true;
                 done = true;
             } else {
@@ -359,51 +488,56 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
                 else
                     done = true;
             }
-            const double gnext = restart ? ((tid < KD) ? s_v[tid] : 0.0) : gn;
-            __builtin_amdgcn_wave_barrier();
+            s_iters += 1;
+            s_res = dn;
+            if (conv) s_conv = 1;
+            if (restart) {
+                s_alpha = alpha * 0.5;
+                s_halv += 1;
+                s_attempt = 0;
+                s_grow = 0;
+                s_prev = __builtin_inf();
+            } else {
+                s_attempt = attempt;
+                s_grow = grow;
+                if (!diverged && !conv) s_prev = dn;
+            }
+            s_restart = restart ? 1 : 0;
+            if (done) s_done = 1;
+        }
+        __syncthreads();
+        if (s_restart) {
+            // back to g = v with the halved alpha: every workgroup kept h(v)/tau, reducers reset their slice
             if (tid < KD) {
-                const double n = s_n[tid / D];
-                s_g[tid] = gnext;
-                s_Hs[tid] = (n > 0.0) ? (float)(gnext / n * inv_tau) : 0.f;
+                s_Hs[tid] = s_Hv[tid];
+                s_g[tid] = s_v[tid];
             }
-            if (tid == 0) {
-                s_iters += 1;
-                s_res = dn;
-                if (conv) s_conv = 1;
-                if (restart) {
-                    s_alpha = alpha * 0.5;
-                    s_halv += 1;
-                    s_attempt = 0;
-                    s_grow = 0;
-                    s_prev = __builtin_inf();
-                } else {
-                    s_attempt = attempt;
-                    s_grow = grow;
-                    if (!diverged && !conv) s_prev = dn;
-                }
-                if (done) s_done = 1;
-            }
+        } else if (tid < KD) {
+            s_Hs[tid] = __uint_as_float(xs.bc[tid]);
         }
         __syncthreads();
     }
 
     // B3: dW = direct + (dF/dW)^T g
     tile_pass<K, D, DIST, PASS_B3>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, reinterpret_cast<float(&)[1]>(acc[0]));
-    if (blockIdx.x == 0 && tid == 0) {
+    for (int r = wg; r < R; r += gridDim.x) {
+        if (tid < WPR) {
+            const int idx = r * WPR + tid;
+            a.gd[idx] = s_g[idx];
+            a.vd[idx] = s_v[idx];
+        }
+    }
+    if (wg == 0 && tid < KD) a.Hs[tid] = s_Hs[tid];
+    if (wg == gridDim.x - 1 && tid == 0) {
         Ctrl* c = a.ctrl;
         c->b_iters = s_iters;
         c->b_converged = s_conv;
-        c->b_residual = s_res;
+        c->b_residual = sqrt(s_res);
         c->b_alpha = s_alpha;
-        c->b_vnorm = s_vnorm;
+        c->b_vnorm = sqrt(s_vnorm);
         c->b_halvings = s_halv;
         c->b_done = 1;
-        if (s_bad) c->nonfinite = 1;
-    }
-    if (blockIdx.x == 0 && tid < KD) {
-        a.gd[tid] = s_g[tid];
-        a.vd[tid] = s_v[tid];
-        a.Hs[tid] = s_Hs[tid];
+        if (s_bad) atomicOr(&c->nonfinite, 1);
     }
 }
 
