@@ -131,6 +131,9 @@ struct idkm_ctx {
     unsigned long long* xbuf = nullptr;  // exchange words: buf1 [2][PT][XLINE], then buf2 [2][XBCAST]
     size_t xbuf_words = 0;
     unsigned int seq_base = 0;
+    unsigned int* abort_word = nullptr;  // device
+    PResult* h_res = nullptr;            // pinned host
+    int last_empty = 0;                  // empty clusters seen by the last forward
     unsigned int spin_limit = 1u << 20;
 #ifdef IDKM_TRACE
     long long* trace = nullptr;
@@ -275,19 +278,22 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
     return true;
 }
 
-idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, unsigned int exchanges, hipStream_t s) {
+idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PArgs pa, unsigned int exchanges,
+                              hipStream_t s) {
     if (pp.grid > PT || ctx->xbuf_words < XBUF_WORDS) return fail(ctx, IDKM_ERR_DEVICE, "exchange buffer too small");
     if (ctx->seq_base > 0xffffffffu - exchanges - 2u) {  // stamps would wrap: start over from a clean buffer
         hipLaunchKernelGGL(k_fill_u64, dim3(64), dim3(256), 0, s, ctx->xbuf, ctx->xbuf_words, 0ull);
         HIP_TRY(ctx, hipGetLastError());
         ctx->seq_base = 0;
     }
-    PArgs pa;
     pa.buf1 = ctx->xbuf;
     pa.buf2 = ctx->xbuf + XBUF1_WORDS;
     pa.seq_base = ctx->seq_base;
     pa.spin_limit = ctx->spin_limit;
     pa.per = pp.per;
+    pa.abort_word = ctx->abort_word;
+    pa.out = ctx->h_res;
+    std::memset(ctx->h_res, 0, sizeof(PResult));
 #ifdef IDKM_TRACE
     pa.trace = ctx->trace;
 #endif
@@ -304,7 +310,11 @@ idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, uns
         hipLaunchKernelGGL(pp.fn, dim3(pp.grid), dim3(PT), pp.lds, s, a, pa);
         HIP_TRY(ctx, hipGetLastError());
     }
+    const unsigned int id = ctx->seq_base + 1u;
     ctx->seq_base += exchanges;
+    // the kernel reports into pinned host memory; one wait, no copy
+    HIP_TRY(ctx, hipStreamSynchronize(s));
+    if (ctx->h_res->done != id) return fail(ctx, IDKM_ERR_DEVICE, "a grid-wide wait hit its limit");
     return IDKM_OK;
 }
 
@@ -410,6 +420,10 @@ idkm_status idkm_create(idkm_ctx** out, int device_id) {
         int v = std::atoi(e);
         if (v >= 1 && v <= 1024) c->min_vec_per_thread = v;
     }
+    ok &= hipMalloc(&c->abort_word, sizeof(unsigned int)) == hipSuccess;
+    if (ok) ok &= hipMemset(c->abort_word, 0, sizeof(unsigned int)) == hipSuccess;
+    ok &= hipHostMalloc(&c->h_res, sizeof(PResult)) == hipSuccess;
+    if (ok) std::memset(c->h_res, 0, sizeof(PResult));
     c->xbuf_words = XBUF_WORDS;
     ok &= hipMalloc(&c->xbuf, c->xbuf_words * sizeof(unsigned long long)) == hipSuccess;
     if (ok) ok &= hipMemset(c->xbuf, 0, c->xbuf_words * sizeof(unsigned long long)) == hipSuccess;
@@ -426,10 +440,11 @@ idkm_status idkm_destroy(idkm_ctx* c) {
     if (!c) return IDKM_ERR_INVALID_ARG;
     (void)hipSetDevice(c->device);
     (void)hipDeviceSynchronize();
-    void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials, c->xbuf};
+    void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials, c->xbuf, c->abort_word};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     if (c->h_ctrl) (void)hipHostFree(c->h_ctrl);
+    if (c->h_res) (void)hipHostFree(c->h_res);
     delete c;
     return IDKM_OK;
 }
@@ -471,9 +486,6 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
     ctx->tau = tau;
     Args a = base_args(ctx);
 
-    hipLaunchKernelGGL(k_init_forward, dim3(1), dim3(WG), 0, s, a, C0, (double)tol, (int)max_iter);
-    HIP_TRY(ctx, hipGetLastError());
-
     PersistPlan pp;
     const bool persistent = ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, false, &pp);
     if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
@@ -483,24 +495,35 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
         a.A_out = A_out;
         a.Wq_out = Wq_out;
         a.assign_out = assign_out;
-        st = launch_persistent(ctx, pp, a, (unsigned int)max_iter + 1u, s);
+        PArgs pa;
+        std::memset(&pa, 0, sizeof(pa));
+        pa.C0 = C0;
+        pa.tol = (double)tol;
+        pa.max_iter = (int)max_iter;
+        st = launch_persistent(ctx, pp, a, pa, (unsigned int)max_iter + 1u, s);
         if (st != IDKM_OK) return st;
-        st = read_ctrl(ctx, s);
-        if (st != IDKM_OK) return st;
-        const Ctrl& c = *ctx->h_ctrl;
-        if (c.abort_flag || !c.done) return fail(ctx, IDKM_ERR_DEVICE, "a grid-wide wait hit its limit");
-        if (c.nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "the codebook became non-finite");
+        const PResult& c = *ctx->h_res;
+        int empty = 0, bad = c.nonfinite;
+        for (int r = 0; r < 16; ++r) {
+            empty += c.empty[r];
+            bad |= c.bad[r];
+        }
+        if (bad) return fail(ctx, IDKM_ERR_NONFINITE, "the codebook became non-finite");
         ctx->has_forward = true;
+        ctx->last_empty = empty;
         if (info) {
             info->iters = c.iters;
             info->converged = c.converged;
             info->residual = c.residual;
-            info->empty_clusters = c.empty;
+            info->empty_clusters = empty;
             info->path = IDKM_PATH_PERSISTENT;
             info->alpha = 0.0;
         }
         return IDKM_OK;
     }
+
+    hipLaunchKernelGGL(k_init_forward, dim3(1), dim3(WG), 0, s, a, C0, (double)tol, (int)max_iter);
+    HIP_TRY(ctx, hipGetLastError());
 
     st = run_until_done(ctx, g, PASS_FWD, a, s, max_iter, [](const Ctrl& c) { return c.done != 0; });
     if (st != IDKM_OK) return st;
@@ -522,6 +545,7 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
         info->converged = conv;
         info->residual = res;
         info->empty_clusters = ctx->h_ctrl->empty;
+        ctx->last_empty = ctx->h_ctrl->empty;
         info->path = IDKM_PATH_STREAM;
         info->alpha = 0.0;
         if (ctx->h_ctrl->nonfinite) {
@@ -552,9 +576,6 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     a.G = dWq;
     a.dW_out = dW_out;
 
-    hipLaunchKernelGGL(k_init_backward, dim3(1), dim3(1), 0, s, a, (int)mode, (double)tol, (int)max_iter, (double)alpha);
-    HIP_TRY(ctx, hipGetLastError());
-
     PersistPlan pp;
     const bool persistent = ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &pp);
     if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
@@ -562,24 +583,29 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     if (persistent) {
         const uint64_t ex = 1ull + (mode == IDKM_BWD_IMPLICIT ? (uint64_t)max_iter * 7ull : 0ull);
         if (ex < 0x7fffffffull) {
-            st = launch_persistent(ctx, pp, a, (unsigned int)ex, s);
+            PArgs pa;
+            std::memset(&pa, 0, sizeof(pa));
+            pa.tol = (double)tol;
+            pa.max_iter = (int)max_iter;
+            pa.mode = (int)mode;
+            pa.alpha = (double)alpha;
+            st = launch_persistent(ctx, pp, a, pa, (unsigned int)ex, s);
             if (st != IDKM_OK) return st;
-            st = read_ctrl(ctx, s);
-            if (st != IDKM_OK) return st;
-            const Ctrl& c = *ctx->h_ctrl;
-            if (c.abort_flag || !c.b_done) return fail(ctx, IDKM_ERR_DEVICE, "a grid-wide wait hit its limit");
+            const PResult& c = *ctx->h_res;
             if (c.nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "the cotangent became non-finite");
             if (info) {
-                info->iters = c.b_iters;
-                info->converged = c.b_converged;
-                info->residual = c.b_residual;
-                info->empty_clusters = c.empty;
+                info->iters = c.iters;
+                info->converged = c.converged;
+                info->residual = c.residual;
+                info->empty_clusters = ctx->last_empty;
                 info->path = IDKM_PATH_PERSISTENT;
-                info->alpha = c.b_alpha;
+                info->alpha = c.alpha;
             }
             return IDKM_OK;
         }
     }
+    hipLaunchKernelGGL(k_init_backward, dim3(1), dim3(1), 0, s, a, (int)mode, (double)tol, (int)max_iter, (double)alpha);
+    HIP_TRY(ctx, hipGetLastError());
     st = launch_pass(ctx, g, PASS_B1, a, s);
     if (st != IDKM_OK) return st;
     if (mode == IDKM_BWD_IMPLICIT) {
@@ -596,7 +622,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
         info->iters = c.b_iters;
         info->converged = c.b_converged;
         info->residual = c.b_residual;
-        info->empty_clusters = c.empty;
+        info->empty_clusters = ctx->last_empty;
         info->path = IDKM_PATH_STREAM;
         info->alpha = c.b_alpha;
         if (c.nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "the cotangent became non-finite");

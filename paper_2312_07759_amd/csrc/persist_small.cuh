@@ -28,12 +28,27 @@ constexpr int PT = 256;      // threads per workgroup of the persistent kernels;
 constexpr int XLINE = 32;    // words reserved per workgroup in buf1 (K (D+1) <= 32)
 constexpr int XBCAST = 64;   // words reserved in buf2
 
+// What a persistent launch reports; lives in pinned host memory, written once by the kernel.
+struct PResult {
+    unsigned int done;  // == launch id when the kernel ran to its end
+    int iters, converged, nonfinite, halvings;
+    double residual, alpha, vnorm;
+    int empty[16], bad[16];  // per reducer, from the evaluation at C*
+};
+
 struct PArgs {
     unsigned long long* buf1;  // [2][XLINE][PT] stamped partial sums, word (accumulator, workgroup)
     unsigned long long* buf2;  // [2][XBCAST] stamped broadcast values
-    unsigned int seq_base;     // sequence numbers seq_base+1 ... are used by this launch
+    unsigned int seq_base;     // sequence numbers seq_base+1 ... are used by this launch; seq_base+1 is its id
     unsigned int spin_limit;   // polls before a wait gives up
     int per;                   // vectors per workgroup tile
+    const float* C0;           // forward: initial codebook [k,d]
+    double tol;                // stop rule of the solve (forward: absolute; backward: relative to ||v||)
+    int max_iter;
+    int mode;                  // backward: BWD_IMPLICIT or BWD_JFB
+    double alpha;              // backward: damping factor
+    unsigned int* abort_word;  // device word; holds this launch's id once a bounded wait has expired
+    PResult* out;              // pinned host memory
 #ifdef IDKM_TRACE
     long long* trace;          // [2 workgroups][64 passes][8 stamps] of the shader clock (development builds only)
 #endif
@@ -95,7 +110,7 @@ __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int s
 // hop 1, reducer side: totals over all workgroups of words [first, first+WPR) into xs.tot (float64, fixed order).
 // Returns false if the wait was abandoned (uniform over the workgroup).
 template <int NACC, int WPR>
-__device__ __forceinline__ bool reduce_slice(const PArgs& pa, Ctrl* ctrl, unsigned int seq, int first,
+__device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, int first,
                                              XShared<NACC>& xs) {
     static_assert(WPR <= 8, "a reducer handles at most 8 words per workgroup");
     const int tid = threadIdx.x;
@@ -121,7 +136,7 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, Ctrl* ctrl, unsign
             }
             ++spins;
             if (spins > pa.spin_limit ||
-                ((spins & 31u) == 0u && __hip_atomic_load(&ctrl->abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                ((spins & 31u) == 0u && __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u)) {
                 aborted = true;
                 break;
             }
@@ -131,7 +146,7 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, Ctrl* ctrl, unsign
     for (int q = 0; q < WPR; ++q) xs.red[q][tid] = f[q];
     if (aborted) {
         xs.abort = 1;
-        __hip_atomic_store(&ctrl->abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
 #ifdef IDKM_TRACE
@@ -153,7 +168,7 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, Ctrl* ctrl, unsign
 
 // hop 2, receiver side: waits for words [0, nwords) of buf2 and leaves their payloads in xs.bc.
 template <int NACC>
-__device__ __forceinline__ bool gather_bcast(const PArgs& pa, Ctrl* ctrl, unsigned int seq, int nwords,
+__device__ __forceinline__ bool gather_bcast(const PArgs& pa, unsigned int seq, int nwords,
                                              XShared<NACC>& xs) {
     const int tid = threadIdx.x;
     bool aborted = false;
@@ -168,7 +183,7 @@ __device__ __forceinline__ bool gather_bcast(const PArgs& pa, Ctrl* ctrl, unsign
             }
             ++spins;
             if (spins > pa.spin_limit ||
-                ((spins & 31u) == 0u && __hip_atomic_load(&ctrl->abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                ((spins & 31u) == 0u && __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u)) {
                 aborted = true;
                 break;
             }
@@ -176,7 +191,7 @@ __device__ __forceinline__ bool gather_bcast(const PArgs& pa, Ctrl* ctrl, unsign
     }
     if (aborted) {
         xs.abort = 1;
-        __hip_atomic_store(&ctrl->abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     return xs.abort == 0;
@@ -244,8 +259,9 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
     for (int i = tid; i < cnt * D; i += PT) s_tile[i] = a.W[base * D + i];
     if (tid < KD) {
-        s_Cd[tid] = a.Cd[tid];
-        s_Cf[tid] = a.Cf[tid];
+        const float c0 = pa.C0[tid];
+        s_Cd[tid] = (double)c0;
+        s_Cf[tid] = c0;
     }
     if (tid == 0) {
         xs.abort = 0;
@@ -256,8 +272,8 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
         s_res = 0.0;
     }
     __syncthreads();
-    const double tol = a.ctrl->tol;
-    const int max_iter = a.ctrl->max_iter;
+    const double tol = pa.tol;
+    const int max_iter = pa.max_iter;
     // reducer r is workgroup r; with fewer than R workgroups the first ones take several slices in turn
     unsigned int seq = pa.seq_base;
 
@@ -270,7 +286,7 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
         publish_partials<NACC>(pa, seq, acc, xs);
         IDKM_STAMP(2);
         for (int r = wg; r < R; r += gridDim.x) {
-            if (!reduce_slice<NACC, WPR>(pa, a.ctrl, seq, r * WPR, xs)) return;
+            if (!reduce_slice<NACC, WPR>(pa, seq, r * WPR, xs)) return;
             IDKM_STAMP(3);
 #ifdef IDKM_TRACE
             if (pa.trace && threadIdx.x == 0 && blockIdx.x == 0 && s_iters < 64) pa.trace[s_iters * 8 + 6] = pa.trace[2 * 64 * 8 - 1];
@@ -287,7 +303,7 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
             }
         }
         IDKM_STAMP(4);
-        if (!gather_bcast<NACC>(pa, a.ctrl, seq, NB, xs)) return;
+        if (!gather_bcast<NACC>(pa, seq, NB, xs)) return;
         IDKM_STAMP(5);
         if (tid == 0) {
             // ||C+ - C||_F^2 from the float32 codebooks every workgroup holds: the same words, the same order,
@@ -316,14 +332,12 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
     ++seq;
     publish_partials<NACC>(pa, seq, acc, xs);
     for (int r = wg; r < R; r += gridDim.x) {
-        if (!reduce_slice<NACC, WPR>(pa, a.ctrl, seq, r * WPR, xs)) return;
+        if (!reduce_slice<NACC, WPR>(pa, seq, r * WPR, xs)) return;
         if (tid < KPR * D) {
             const int jl = tid / D, rr = tid - jl * D, j = r * KPR + jl, idx = j * D + rr;
             const double n = xs.tot[jl * ACCW], s = xs.tot[jl * ACCW + 1 + rr];
             const double cst = (double)s_Cf[idx];
             const double f = (n > 0.0) ? fast_div_d(s, n) : cst;
-            if (!(n > 0.0) && rr == 0) atomicAdd(&a.ctrl->empty, 1);
-            if (!(n >= 0.0) || !(fabs(s) <= 1.7e308)) atomicOr(&a.ctrl->nonfinite, 1);
             a.Cd[idx] = cst;
             a.Cf[idx] = s_Cf[idx];
             a.Fd[idx] = f;
@@ -331,16 +345,27 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
             if (rr == 0) a.nd[j] = n;
             if (a.C_out) a.C_out[idx] = s_Cf[idx];
         }
+        if (tid == 0) {
+            int empty = 0, bad = 0;
+            for (int jl = 0; jl < KPR; ++jl) {
+                const double n = xs.tot[jl * ACCW];
+                if (!(n > 0.0)) empty++;
+                if (!(n >= 0.0)) bad = 1;
+                for (int rr = 0; rr < D; ++rr)
+                    if (!(fabs(xs.tot[jl * ACCW + 1 + rr]) <= 1.7e308)) bad = 1;
+            }
+            pa.out->empty[r] = empty;
+            pa.out->bad[r] = bad;
+        }
         __syncthreads();
     }
     if (wg == gridDim.x - 1 && tid == 0) {
-        // the last workgroup is never a reducer unless the grid is tiny; either way these fields are its own
-        Ctrl* c = a.ctrl;
-        c->iters = s_iters;
-        c->residual = sqrt(s_res);
-        c->converged = s_conv;
-        if (s_bad) atomicOr(&c->nonfinite, 1);
-        c->done = 1;
+        PResult* o = pa.out;
+        o->iters = s_iters;
+        o->residual = sqrt(s_res);
+        o->converged = s_conv;
+        o->nonfinite = s_bad;
+        o->done = pa.seq_base + 1u;
     }
 }
 
@@ -381,9 +406,9 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
         const double n = a.nd[tid];
         s_rn[tid] = (n > 0.0) ? (double)a.inv_tau / n : 0.0;  // zero for an empty cluster
     }
-    const int mode = a.ctrl->b_mode;
-    const double tol = a.ctrl->b_tol;
-    const int max_iter = a.ctrl->b_max_iter;
+    const int mode = pa.mode;
+    const double tol = pa.tol;
+    const int max_iter = pa.max_iter;
     if (tid == 0) {
         xs.abort = 0;
         s_done = (mode == BWD_JFB) ? 1 : 0;
@@ -394,7 +419,7 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
         s_halv = 0;
         s_bad = 0;
         s_restart = 0;
-        s_alpha = a.ctrl->b_alpha;
+        s_alpha = pa.alpha;
         s_prev = __builtin_inf();
         s_vnorm = 0.0;
         s_res = 0.0;
@@ -408,7 +433,7 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
     ++seq;
     publish_partials<KD>(pa, seq, acc, xs);
     for (int r = wg; r < R; r += gridDim.x) {
-        if (!reduce_slice<KD, WPR>(pa, a.ctrl, seq, r * WPR, xs)) return;
+        if (!reduce_slice<KD, WPR>(pa, seq, r * WPR, xs)) return;
         if (tid < 64) {
             double v2 = 0.0;
             if (tid < WPR) {
@@ -424,7 +449,7 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
             if (tid == 0) st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + KD + r], pack_f(seq, (float)v2));
         }
     }
-    if (!gather_bcast<KD>(pa, a.ctrl, seq, NB, xs)) return;
+    if (!gather_bcast<KD>(pa, seq, NB, xs)) return;
     if (tid < KD) {
         s_Hs[tid] = __uint_as_float(xs.bc[tid]);
         s_Hv[tid] = s_Hs[tid];
@@ -446,7 +471,7 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
         publish_partials<KD>(pa, seq, acc, xs);
         const double alpha = s_alpha;
         for (int r = wg; r < R; r += gridDim.x) {
-            if (!reduce_slice<KD, WPR>(pa, a.ctrl, seq, r * WPR, xs)) return;
+            if (!reduce_slice<KD, WPR>(pa, seq, r * WPR, xs)) return;
             if (tid < 64) {
                 double d2 = 0.0;
                 if (tid < WPR) {
@@ -463,7 +488,7 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
                 if (tid == 0) st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + KD + r], pack_f(seq, (float)d2));
             }
         }
-        if (!gather_bcast<KD>(pa, a.ctrl, seq, NB, xs)) return;
+        if (!gather_bcast<KD>(pa, seq, NB, xs)) return;
         if (tid == 0) {
             // the same decision in every workgroup (same words, same order)
             double d2 = 0.0;
@@ -529,15 +554,15 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
     }
     if (wg == 0 && tid < KD) a.Hs[tid] = s_Hs[tid];
     if (wg == gridDim.x - 1 && tid == 0) {
-        Ctrl* c = a.ctrl;
-        c->b_iters = s_iters;
-        c->b_converged = s_conv;
-        c->b_residual = sqrt(s_res);
-        c->b_alpha = s_alpha;
-        c->b_vnorm = sqrt(s_vnorm);
-        c->b_halvings = s_halv;
-        c->b_done = 1;
-        if (s_bad) atomicOr(&c->nonfinite, 1);
+        PResult* o = pa.out;
+        o->iters = s_iters;
+        o->converged = s_conv;
+        o->residual = sqrt(s_res);
+        o->alpha = s_alpha;
+        o->vnorm = sqrt(s_vnorm);
+        o->halvings = s_halv;
+        o->nonfinite = s_bad;
+        o->done = pa.seq_base + 1u;
     }
 }
 
