@@ -15,5 +15,7 @@ struct PArgs;
 typedef void (*PersistFn)(const Args, const PArgs);
 // Persistent forward / backward solve for the lane<->vector family; nullptr if K (D+1) > 32.
 PersistFn persist_kernel(int K, int D, int dist, bool bwd);
+// Persistent solve for the lane<->codeword family (launch with 1024 threads); nullptr if not instantiated.
+PersistFn persist_lane_kernel(int KPL, int D, int dist, bool bwd);
 
 }  // namespace idkm

@@ -13,6 +13,7 @@
 #include "common.cuh"
 #include "dispatch.h"
 #include "persist_small.cuh"
+#include "persist_lane.cuh"
 
 namespace idkm {
 KernelFn small_kernel_0(int, int, int);
@@ -22,6 +23,11 @@ KernelFn lane_kernel_1(int, int, int);
 
 KernelFn small_kernel(int K, int D, int dist, int pass) {
     return dist == DIST_L2 ? small_kernel_0(K, D, pass) : small_kernel_1(K, D, pass);
+}
+PersistFn persist_lane_kernel_0(int, int, bool);
+PersistFn persist_lane_kernel_1(int, int, bool);
+PersistFn persist_lane_kernel(int KPL, int D, int dist, bool bwd) {
+    return dist == DIST_L2 ? persist_lane_kernel_0(KPL, D, bwd) : persist_lane_kernel_1(KPL, D, bwd);
 }
 KernelFn lane_kernel(int KPL, int D, int dist, int pass) {
     return dist == DIST_L2 ? lane_kernel_0(KPL, D, pass) : lane_kernel_1(KPL, D, pass);
@@ -131,6 +137,7 @@ struct idkm_ctx {
     unsigned long long* xbuf = nullptr;  // exchange words: buf1 [2][PT][XLINE], then buf2 [2][XBCAST]
     size_t xbuf_words = 0;
     unsigned int seq_base = 0;
+    unsigned long long* lane_xbuf = nullptr;  // exchange words of the lane<->codeword persistent kernels (lazy)
     unsigned int* abort_word = nullptr;  // device
     PResult* h_res = nullptr;            // pinned host
     int last_empty = 0;                  // empty clusters seen by the last forward
@@ -251,18 +258,47 @@ constexpr size_t LDS_TILE_MAX = 144 * 1024;  // bytes of LDS a persistent workgr
 
 struct PersistPlan {
     PersistFn fn;
-    int grid, per;
+    int grid, per, threads;
+    bool lane;  // lane<->codeword family: own exchange buffers
     size_t lds;
 };
+constexpr size_t LANE_TILE_MAX = 94 * 1024;                       // the lane kernels keep ~55 KB of static LDS
+constexpr size_t LANE_BUF1_WORDS = (size_t)2 * PT * 1536;          // k (d+1) <= 1536
+constexpr size_t LANE_BUF2_WORDS = (size_t)2 * (1024 + 512);       // k d + k
+
 
 // Can (m, k, d) run as one persistent launch with `tiles` resident tensors (1: W; 2: W and dL/dWq)?
 bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
     if (!ctx->coop || ctx->num_cu < 1) return false;
     const int k = ctx->k, d = ctx->d;
-    if (!(k >= 2 && k <= 16 && pow2(k) && d <= 4) || k * (d + 1) > XLINE) return false;
+    const int64_t m = ctx->m;
+    if (!(k >= 2 && k <= 16 && pow2(k) && d <= 4)) {
+        // lane<->codeword family
+        int kpl = (k + 63) / 64, p = 1;
+        while (p < kpl) p <<= 1;
+        if (d > 4 || p * d > 16 || p * (d + 1) > 24) return false;
+        pp->fn = persist_lane_kernel(p, d, ctx->dist, bwd);
+        if (!pp->fn) return false;
+        int64_t g = (m + 255) / 256;  // at least 16 vectors per wavefront before adding workgroups
+        if (g < 1) g = 1;
+        if (g > ctx->num_cu) g = ctx->num_cu;
+        if (g > PT) g = PT;
+        int64_t per = (m + g - 1) / g;
+        per = (per + 3) / 4 * 4;
+        const size_t lds = (size_t)per * d * sizeof(float) * (bwd ? 2 : 1);
+        if (lds > LANE_TILE_MAX) return false;
+        pp->grid = (int)((m + per - 1) / per);
+        pp->per = (int)per;
+        pp->lds = lds;
+        pp->threads = LT;
+        pp->lane = true;
+        return true;
+    }
+    if (k * (d + 1) > XLINE) return false;
     pp->fn = persist_kernel(k, d, ctx->dist, bwd);
     if (!pp->fn) return false;
-    const int64_t m = ctx->m;
+    pp->threads = PT;
+    pp->lane = false;
     const int64_t chunk = (int64_t)ctx->min_vec_per_thread * PT;
     int64_t g = (m + chunk - 1) / chunk;  // a few vectors per thread before adding workgroups
     if (g < 1) g = 1;
@@ -281,13 +317,29 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
 idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PArgs pa, unsigned int exchanges,
                               hipStream_t s) {
     if (pp.grid > PT || ctx->xbuf_words < XBUF_WORDS) return fail(ctx, IDKM_ERR_DEVICE, "exchange buffer too small");
-    if (ctx->seq_base > 0xffffffffu - exchanges - 2u) {  // stamps would wrap: start over from a clean buffer
+    if (ctx->seq_base > 0xffffffffu - exchanges - 2u) {  // stamps would wrap: start over from clean buffers
         hipLaunchKernelGGL(k_fill_u64, dim3(64), dim3(256), 0, s, ctx->xbuf, ctx->xbuf_words, 0ull);
         HIP_TRY(ctx, hipGetLastError());
+        if (ctx->lane_xbuf) {
+            hipLaunchKernelGGL(k_fill_u64, dim3(256), dim3(256), 0, s, ctx->lane_xbuf, LANE_BUF1_WORDS + LANE_BUF2_WORDS, 0ull);
+            HIP_TRY(ctx, hipGetLastError());
+        }
         ctx->seq_base = 0;
     }
-    pa.buf1 = ctx->xbuf;
-    pa.buf2 = ctx->xbuf + XBUF1_WORDS;
+    if (pp.lane) {
+        if (!ctx->lane_xbuf) {
+            const size_t bytes = (LANE_BUF1_WORDS + LANE_BUF2_WORDS) * sizeof(unsigned long long);
+            if (hipMalloc(&ctx->lane_xbuf, bytes) != hipSuccess)
+                return fail(ctx, IDKM_ERR_ALLOC, "hipMalloc of the exchange buffer failed");
+            hipLaunchKernelGGL(k_fill_u64, dim3(256), dim3(256), 0, s, ctx->lane_xbuf, LANE_BUF1_WORDS + LANE_BUF2_WORDS, 0ull);
+            HIP_TRY(ctx, hipGetLastError());
+        }
+        pa.buf1 = ctx->lane_xbuf;
+        pa.buf2 = ctx->lane_xbuf + LANE_BUF1_WORDS;
+    } else {
+        pa.buf1 = ctx->xbuf;
+        pa.buf2 = ctx->xbuf + XBUF1_WORDS;
+    }
     pa.seq_base = ctx->seq_base;
     pa.spin_limit = ctx->spin_limit;
     pa.per = pp.per;
@@ -299,15 +351,15 @@ idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PAr
 #endif
     HIP_TRY(ctx, hipFuncSetAttribute((const void*)pp.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pp.lds));
     int nb = 0;
-    HIP_TRY(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)pp.fn, PT, pp.lds));
+    HIP_TRY(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)pp.fn, pp.threads, pp.lds));
     if (nb < 1 || (int64_t)nb * ctx->num_cu < pp.grid)
         return fail(ctx, IDKM_ERR_DEVICE, "persistent grid would not be co-resident");
     if (ctx->coop_launch) {
         void* args[] = {(void*)&a, (void*)&pa};
-        HIP_TRY(ctx, hipLaunchCooperativeKernel((const void*)pp.fn, dim3(pp.grid), dim3(PT), args, pp.lds, s));
+        HIP_TRY(ctx, hipLaunchCooperativeKernel((const void*)pp.fn, dim3(pp.grid), dim3(pp.threads), args, pp.lds, s));
     } else {
         // plain launch: the grid fits the device (checked above), every wait in the kernel is bounded
-        hipLaunchKernelGGL(pp.fn, dim3(pp.grid), dim3(PT), pp.lds, s, a, pa);
+        hipLaunchKernelGGL(pp.fn, dim3(pp.grid), dim3(pp.threads), pp.lds, s, a, pa);
         HIP_TRY(ctx, hipGetLastError());
     }
     const unsigned int id = ctx->seq_base + 1u;
@@ -440,7 +492,7 @@ idkm_status idkm_destroy(idkm_ctx* c) {
     if (!c) return IDKM_ERR_INVALID_ARG;
     (void)hipSetDevice(c->device);
     (void)hipDeviceSynchronize();
-    void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials, c->xbuf, c->abort_word};
+    void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials, c->xbuf, c->lane_xbuf, c->abort_word};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     if (c->h_ctrl) (void)hipHostFree(c->h_ctrl);
@@ -489,7 +541,7 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
     PersistPlan pp;
     const bool persistent = ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, false, &pp);
     if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
-        return fail(ctx, IDKM_ERR_UNSUPPORTED, "the persistent path needs k in {2,4,8,16}, k(d+1) <= 32 and W to fit in LDS");
+        return fail(ctx, IDKM_ERR_UNSUPPORTED, "the persistent path needs k <= 512, d <= 4 and the tile of W to fit in LDS");
     if (persistent) {
         a.C_out = C_out;
         a.A_out = A_out;
@@ -579,7 +631,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     PersistPlan pp;
     const bool persistent = ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &pp);
     if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
-        return fail(ctx, IDKM_ERR_UNSUPPORTED, "the persistent path needs k in {2,4,8,16}, k(d+1) <= 32 and W, dWq to fit in LDS");
+        return fail(ctx, IDKM_ERR_UNSUPPORTED, "the persistent path needs k <= 512, d <= 4 and the tiles of W and dWq to fit in LDS");
     if (persistent) {
         const uint64_t ex = 1ull + (mode == IDKM_BWD_IMPLICIT ? (uint64_t)max_iter * 7ull : 0ull);
         if (ex < 0x7fffffffull) {

@@ -1,0 +1,30 @@
+// Instantiations of the persistent lane<->codeword kernels for energy variant 0.
+#include "dispatch.h"
+#include "persist_lane.cuh"
+
+namespace idkm {
+
+template <int KPL, int D>
+static PersistFn pick(bool bwd) {
+    return bwd ? persist_lane_bwd<KPL, D, 0> : persist_lane_fwd<KPL, D, 0>;
+}
+
+// Offered for KPL*D <= 16 and KPL*(D+1) <= 24 (k <= 512), d <= 4.
+PersistFn persist_lane_kernel_0(int KPL, int D, bool bwd) {
+    switch (KPL * 16 + D) {
+        case 1 * 16 + 1: return pick<1, 1>(bwd);
+        case 1 * 16 + 2: return pick<1, 2>(bwd);
+        case 1 * 16 + 4: return pick<1, 4>(bwd);
+        case 2 * 16 + 1: return pick<2, 1>(bwd);
+        case 2 * 16 + 2: return pick<2, 2>(bwd);
+        case 2 * 16 + 4: return pick<2, 4>(bwd);
+        case 4 * 16 + 1: return pick<4, 1>(bwd);
+        case 4 * 16 + 2: return pick<4, 2>(bwd);
+        case 4 * 16 + 4: return pick<4, 4>(bwd);
+        case 8 * 16 + 1: return pick<8, 1>(bwd);
+        case 8 * 16 + 2: return pick<8, 2>(bwd);
+    }
+    return nullptr;
+}
+
+}  // namespace idkm

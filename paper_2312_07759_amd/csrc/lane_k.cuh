@@ -12,66 +12,57 @@ __device__ __forceinline__ float lane_bcast(float x, int l) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), l));
 }
 
+// Per-wavefront state of one pass: this lane's codewords and accumulators.
 template <int KPL, int D, int DIST, int PASS>
-__global__ __launch_bounds__(WG) void lane_pass(const Args a) {
-    constexpr bool STATS = (PASS == PASS_FWD || PASS == PASS_FIN);
-    constexpr bool BACK = (PASS == PASS_B1 || PASS == PASS_B2 || PASS == PASS_B3);
-    constexpr bool USE_G = (PASS == PASS_B1 || PASS == PASS_B3);
-    constexpr bool USE_H = (PASS == PASS_B2 || PASS == PASS_B3);
-    constexpr int ACCW = STATS ? (D + 1) : D;
-    constexpr int NA = (PASS == PASS_B3) ? 1 : KPL * ACCW;  // accumulators per lane
-
-    if (PASS == PASS_FWD && a.ctrl->done) return;
-    if (PASS == PASS_B2 && a.ctrl->b_done) return;
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int k = a.k;
-    const float inf = __builtin_inff();
+struct LaneWave {
+    static constexpr bool STATS = (PASS == PASS_FWD || PASS == PASS_FIN);
+    static constexpr bool BACK = (PASS == PASS_B1 || PASS == PASS_B2 || PASS == PASS_B3);
+    static constexpr bool USE_G = (PASS == PASS_B1 || PASS == PASS_B3);
+    static constexpr bool USE_H = (PASS == PASS_B2 || PASS == PASS_B3);
+    static constexpr int ACCW = STATS ? (D + 1) : D;
+    static constexpr int NA = (PASS == PASS_B3) ? 1 : KPL * ACCW;  // accumulators per lane
 
     float c[KPL][D], hs[KPL][D], ff[KPL][D];
     bool valid[KPL];
-#pragma unroll
-    for (int q = 0; q < KPL; ++q) {
-        const int j = lane + 64 * q;
-        valid[q] = j < k;
-#pragma unroll
-        for (int r = 0; r < D; ++r) {
-            c[q][r] = valid[q] ? a.Cf[j * D + r] : 0.f;
-            hs[q][r] = (USE_H && valid[q]) ? a.Hs[j * D + r] : 0.f;
-            ff[q][r] = (USE_H && valid[q]) ? a.Ff[j * D + r] : 0.f;
-        }
-    }
     float acc[NA];
+
+    // Cf/Hs/Ff may point to global memory or LDS.
+    __device__ __forceinline__ void init(int k, const float* Cf, const float* Hs, const float* Ff) {
+        const int lane = threadIdx.x & 63;
 #pragma unroll
-    for (int q = 0; q < NA; ++q) acc[q] = 0.f;
+        for (int q = 0; q < KPL; ++q) {
+            const int j = lane + 64 * q;
+            valid[q] = j < k;
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                c[q][r] = valid[q] ? Cf[j * D + r] : 0.f;
+                hs[q][r] = (USE_H && valid[q]) ? Hs[j * D + r] : 0.f;
+                ff[q][r] = (USE_H && valid[q]) ? Ff[j * D + r] : 0.f;
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < NA; ++q) acc[q] = 0.f;
+    }
 
-    const int64_t vpw = a.vec_per_wg / (WG / 64);
-    const int64_t wbase = (int64_t)blockIdx.x * a.vec_per_wg + (int64_t)wave * vpw;
-    int64_t wend = wbase + vpw;
-    if (wend > a.m) wend = a.m;
-    const float nscale = a.nscale;
-
-    for (int64_t b = wbase; b < wend; b += 64) {
-        const int64_t i = b + lane;
-        const bool in = i < wend;
-        float wv[D], gv[D], ov[D];
+    // Processes vectors gbase .. gbase+cnt-1 (cnt <= 64); lane l holds vector gbase+l in wv (and dL/dWq in gv).
+    // Per-vector outputs (Wq, assignment, dW) are collected in lane l and stored coalesced.
+    __device__ __forceinline__ void batch(const Args& a, int64_t gbase, int cnt, const float (&wv)[D],
+                                          const float (&gv)[D]) {
+        const int lane = threadIdx.x & 63;
+        const int k = a.k;
+        const float inf = __builtin_inff();
+        const float nscale = a.nscale;
+        float ov[D];
         int oa = 0;
 #pragma unroll
-        for (int r = 0; r < D; ++r) wv[r] = gv[r] = ov[r] = 0.f;
-        if (in) {
-            VecLoad<D>::load(a.W, i, wv);
-            if (USE_G) VecLoad<D>::load(a.G, i, gv);
-        }
-        const int cnt = (wend - b < 64) ? (int)(wend - b) : 64;
+        for (int r = 0; r < D; ++r) ov[r] = 0.f;
         for (int l = 0; l < cnt; ++l) {
             float w[D], g[D], gs[D];
 #pragma unroll
             for (int r = 0; r < D; ++r) {
                 w[r] = lane_bcast(wv[r], l);
-                if (USE_G) {
-                    g[r] = lane_bcast(gv[r], l);
-                    gs[r] = g[r] * a.inv_tau;
-                }
+                g[r] = USE_G ? lane_bcast(gv[r], l) : 0.f;
+                gs[r] = g[r] * a.inv_tau;
             }
             // E-step: energies of this lane's codewords, wavefront softmax (Eq. "aterms")
             float df[KPL][D], ri[KPL], u[KPL], at[KPL];
@@ -135,42 +126,28 @@ __global__ __launch_bounds__(WG) void lane_pass(const Args a) {
                 if (a.A_out) {
 #pragma unroll
                     for (int q = 0; q < KPL; ++q)
-                        if (valid[q]) a.A_out[(b + l) * (int64_t)k + lane + 64 * q] = at[q];
+                        if (valid[q]) a.A_out[(gbase + l) * (int64_t)k + lane + 64 * q] = at[q];
                 }
                 if (a.assign_out) {
-                    float bk = inf;
-                    int bj = 0x7fffffff;
+                    // closest codeword on a float32 key with separately rounded operations; lowest index on ties
+                    float key[KPL], bk = inf;
 #pragma unroll
                     for (int q = 0; q < KPL; ++q) {
-                        float key;
                         if (D == 1) {
-                            key = fabsf(df[q][0]);
+                            key[q] = fabsf(df[q][0]);
                         } else {
-                            key = __fmul_rn(df[q][0], df[q][0]);
+                            key[q] = __fmul_rn(df[q][0], df[q][0]);
 #pragma unroll
-                            for (int r = 1; r < D; ++r) key = __fadd_rn(key, __fmul_rn(df[q][r], df[q][r]));
+                            for (int r = 1; r < D; ++r) key[q] = __fadd_rn(key[q], __fmul_rn(df[q][r], df[q][r]));
                         }
-                        if (valid[q] && key < bk) {  // ascending j within the lane: strict < keeps the lowest
-                            bk = key;
-                            bj = lane + 64 * q;
-                        }
+                        if (!valid[q]) key[q] = inf;
+                        bk = fminf(bk, key[q]);
                     }
                     const float kmin = wave_min(bk);
-                    // lowest index among all codewords attaining the minimum key
                     int cand = 0x7fffffff;
 #pragma unroll
-                    for (int q = 0; q < KPL; ++q) {
-                        float key;
-                        if (D == 1) {
-                            key = fabsf(df[q][0]);
-                        } else {
-                            key = __fmul_rn(df[q][0], df[q][0]);
-#pragma unroll
-                            for (int r = 1; r < D; ++r) key = __fadd_rn(key, __fmul_rn(df[q][r], df[q][r]));
-                        }
-                        if (valid[q] && key == kmin && lane + 64 * q < cand) cand = lane + 64 * q;
-                    }
-                    (void)bj;
+                    for (int q = KPL - 1; q >= 0; --q)
+                        if (valid[q] && key[q] == kmin) cand = lane + 64 * q;
                     const int jmin = wave_min_i(cand);
                     if (lane == l) oa = jmin;
                 }
@@ -223,11 +200,45 @@ __global__ __launch_bounds__(WG) void lane_pass(const Args a) {
                 }
             }
         }
-        if (in) {
+        if (lane < cnt) {
+            const int64_t i = gbase + lane;
             if (PASS == PASS_FIN && a.Wq_out) VecLoad<D>::store(a.Wq_out, i, ov);
             if (PASS == PASS_FIN && a.assign_out) a.assign_out[i] = oa;
             if (PASS == PASS_B3) VecLoad<D>::store(a.dW_out, i, ov);
         }
+    }
+};
+
+template <int KPL, int D, int DIST, int PASS>
+__global__ __launch_bounds__(WG) void lane_pass(const Args a) {
+    using LW = LaneWave<KPL, D, DIST, PASS>;
+    constexpr int ACCW = LW::ACCW;
+    constexpr int NA = LW::NA;
+
+    if (PASS == PASS_FWD && a.ctrl->done) return;
+    if (PASS == PASS_B2 && a.ctrl->b_done) return;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k = a.k;
+    LW st;
+    st.init(k, a.Cf, a.Hs, a.Ff);
+
+    const int64_t vpw = a.vec_per_wg / (WG / 64);
+    const int64_t wbase = (int64_t)blockIdx.x * a.vec_per_wg + (int64_t)wave * vpw;
+    int64_t wend = wbase + vpw;
+    if (wend > a.m) wend = a.m;
+
+    for (int64_t b = wbase; b < wend; b += 64) {
+        const int64_t i = b + lane;
+        float wv[D], gv[D];
+#pragma unroll
+        for (int r = 0; r < D; ++r) wv[r] = gv[r] = 0.f;
+        if (i < wend) {
+            VecLoad<D>::load(a.W, i, wv);
+            if (LW::USE_G) VecLoad<D>::load(a.G, i, gv);
+        }
+        const int cnt = (wend - b < 64) ? (int)(wend - b) : 64;
+        st.batch(a, b, cnt, wv, gv);
     }
 
     if (PASS == PASS_B3) return;
@@ -239,9 +250,9 @@ __global__ __launch_bounds__(WG) void lane_pass(const Args a) {
 #pragma unroll
             for (int q = 0; q < NA; ++q) {
                 if (wv == 0)
-                    s_acc[lane][q] = (double)acc[q];
+                    s_acc[lane][q] = (double)st.acc[q];
                 else
-                    s_acc[lane][q] += (double)acc[q];
+                    s_acc[lane][q] += (double)st.acc[q];
             }
         }
         __syncthreads();

@@ -92,8 +92,6 @@ FWD_CASES = [
 @pytest.mark.parametrize("dist", DISTS)
 @pytest.mark.parametrize("name,cfg,m", FWD_CASES, ids=[c[0] for c in FWD_CASES])
 def test_forward_solve_and_backward_on_config_shaped_inputs(ctx, name, cfg, m, dist, path):
-    if path == "persistent" and cfg == "C4":
-        pytest.skip("k = 256 has no persistent kernel; the stream path serves it")
     ctx.set_path(binding.PATH_STREAM if path == "stream" else binding.PATH_PERSISTENT)
     try:
         _forward_backward_case(ctx, cfg, m, dist, binding.PATH_STREAM if path == "stream" else binding.PATH_PERSISTENT)
