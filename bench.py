@@ -85,6 +85,9 @@ def main() -> int:
     ap.add_argument("--no-others", action="store_true")
     ap.add_argument("--bwd-tol", type=float, default=1e-6)
     ap.add_argument("--bwd-max-iter", type=int, default=2000)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain elementwise copy of 64 Mi floats (reads 256 MiB, writes 256 MiB) three "
+                         "times, as the known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -109,6 +112,14 @@ def main() -> int:
         g = p.G if p.G is not None else wl.draw_weights(cfg.m * cfg.d, 1e-4, cfg.g_seed).reshape(cfg.m, cfg.d)
         return p, W, C0, torch.from_numpy(g).cuda()
 
+    if args.calib_copy:
+        x = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(3):
+            torch.add(x, 1.0, out=y)
+        torch.cuda.synchronize()
+        del x, y
+
     dist = wl.DIST_SQL2 if args.dist == "sql2" else wl.DIST_L2
     p, W, C0, G = load(args.workload, dist)
     cfg = p.cfg
@@ -130,6 +141,14 @@ def main() -> int:
     fwd_ms, bwd_ms, jfb_ms, finfo, binfo = measure(ctx, binding, torch, np, p, dist, W, C0, G,
                                                    max(5, min(args.steps, 20)), args.bwd_tol, args.bwd_max_iter)
     roofline = roofline_of(cfg, dist, fwd_ms, finfo)
+    # HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command
+    # (counters cannot be read from inside the process; the summary under profiles/ gives the commands)
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}_{wl.DIST_NAMES[dist]}.json")
+    if finfo.path == 2 and os.path.exists(tpath):
+        with open(tpath) as f:
+            t = json.load(f)
+        roofline["traffic"] = {"fetch_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
+                               "algorithmic_bytes": 8 * cfg.m * cfg.d, "per": t["per"], "source": t["source"]}
 
     others = None
     if not args.no_others:
@@ -147,6 +166,29 @@ def main() -> int:
                            "implicit_ms": round(b_ms, 4), "implicit_passes": bi.iters,
                            "implicit_converged": bi.converged, "jfb_ms": round(j_ms, 4),
                            "alu_frac": round(r["frac"], 4), "avg_eval_us": round(r["avg_eval_us"], 3)})
+
+        # the whole-network sweep: 21 ResNet18 tensors, each quantised independently at k = 2 and k = 4 (d = 1)
+        for dd in (1, 0):
+            tot = {"fwd_ms": 0.0, "implicit_ms": 0.0, "jfb_ms": 0.0, "fwd_iters": 0, "implicit_passes": 0,
+                   "unconverged_fwd": 0, "unconverged_bwd": 0, "weights": 0, "layers": 0}
+            for kk in (2, 4):
+                for ti in range(len(wl.RESNET18_TENSORS)):
+                    q = wl.make_problem(wl.sweep_config(ti, kk, dd), dd)
+                    Wt, Ct, Gt = (torch.from_numpy(x).cuda() for x in (q.W, q.C0, q.G))
+                    measure(ctx, binding, torch, np, q, dd, Wt, Ct, Gt, 1, args.bwd_tol, 2000)
+                    f_ms, b_ms, j_ms, fi, bi = measure(ctx, binding, torch, np, q, dd, Wt, Ct, Gt, 2, args.bwd_tol, 2000)
+                    tot["fwd_ms"] += f_ms
+                    tot["implicit_ms"] += b_ms
+                    tot["jfb_ms"] += j_ms
+                    tot["fwd_iters"] += fi.iters
+                    tot["implicit_passes"] += bi.iters
+                    tot["unconverged_fwd"] += 0 if fi.converged else 1
+                    tot["unconverged_bwd"] += 0 if bi.converged else 1
+                    tot["weights"] += q.cfg.m
+                    tot["layers"] += 1
+            others.append({"workload": "C5 (21 ResNet18 tensors x k in {2,4}, one call per tensor)",
+                           "dist": wl.DIST_NAMES[dd], **{a: (round(b, 3) if isinstance(b, float) else b) for a, b in tot.items()},
+                           "fwd_iters_per_s": round(tot["fwd_iters"] / (tot["fwd_ms"] * 1e-3), 1)})
 
     cpu = None
     if not args.no_cpu_baseline:

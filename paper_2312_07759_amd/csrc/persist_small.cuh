@@ -303,28 +303,51 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
             }
         }
         IDKM_STAMP(4);
-        if (!gather_bcast<NACC>(pa, seq, NB, xs)) return;
-        IDKM_STAMP(5);
-        if (tid == 0) {
-            // ||C+ - C||_F^2 from the float32 codebooks every workgroup holds: the same words, the same order,
-            // hence the same stop decision everywhere
-            double r2 = 0.0;
-#pragma unroll
-            for (int q = 0; q < KD; ++q) {
-                const double df = (double)__uint_as_float(xs.bc[q]) - (double)s_Cf[q];
-                r2 += df * df;
+        // hop 2 and the stop test, all inside wavefront 0: lane q waits for codeword component q, the squared
+        // step ||C+ - C||_F^2 is formed from the float32 codebooks every workgroup holds (the same words through
+        // the same DPP network, hence the same decision everywhere), lane 0 decides; one barrier publishes it.
+        if (tid < 64) {
+            double df2 = 0.0;
+            bool aborted = false;
+            if (tid < KD) {
+                const unsigned long long* src = pa.buf2 + (size_t)(seq & 1u) * XBCAST + tid;
+                unsigned int spins = 0;
+                for (;;) {
+                    const unsigned long long w = ld_word(src);
+                    if ((unsigned int)(w >> 32) == seq) {
+                        const float cn = __uint_as_float((unsigned int)w);
+                        const double df = (double)cn - (double)s_Cf[tid];
+                        df2 = df * df;
+                        s_Cf[tid] = cn;
+                        break;
+                    }
+                    ++spins;
+                    if (spins > pa.spin_limit ||
+                        ((spins & 31u) == 0u &&
+                         __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u)) {
+                        aborted = true;
+                        break;
+                    }
+                }
             }
-            s_iters += 1;
-            s_res = r2;  // squared; the root is taken once, when the solve is over
-            const bool bad = !(r2 <= 1.7e308);
-            if (bad) s_bad = 1;
-            const bool conv = r2 < tol * tol;
-            s_conv = conv ? 1 : 0;
-            if (conv || bad || s_iters >= max_iter) s_done = 1;
+            if (aborted) {
+                xs.abort = 1;
+                __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            const double r2 = wave_sum_d_dpp(df2);
+            if (tid == 0) {
+                s_iters += 1;
+                s_res = r2;  // squared; the root is taken once, when the solve is over
+                const bool bad = !(r2 <= 1.7e308);
+                if (bad) s_bad = 1;
+                const bool conv = r2 < tol * tol;
+                s_conv = conv ? 1 : 0;
+                if (conv || bad || s_iters >= max_iter) s_done = 1;
+            }
         }
         __syncthreads();
-        if (tid < KD) s_Cf[tid] = __uint_as_float(xs.bc[tid]);
-        __syncthreads();
+        if (xs.abort) return;
+        IDKM_STAMP(5);
     }
 
     // evaluation at C*: outputs, and n*, F* for the backward
