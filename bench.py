@@ -38,6 +38,22 @@ def fwd_lane_ops_per_vector(k: int, d: int, dist: int) -> int:
     return k * (3 * d + 5) + TRANS_COST * trans
 
 
+def measure_dense(ctx, binding, torch, np, G, reps):
+    """Median event time (ms) of the dense (explicit-Jacobian) backward, or None where it is not offered."""
+    ts = []
+    try:
+        for _ in range(reps + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ctx.backward(G, binding.BWD_DENSE)
+            e1.record()
+            ts.append((e0, e1))
+        torch.cuda.synchronize()
+    except binding.IdkmError:
+        return None
+    return float(np.median([a.elapsed_time(b) for a, b in ts[1:]]))
+
+
 def measure(ctx, binding, torch, np, p, dist, W, C0, G, reps, bwd_tol, bwd_max_iter):
     """Median event times (ms) of forward, implicit backward and JFB backward over `reps` runs."""
     recs = []
@@ -140,6 +156,7 @@ def main() -> int:
     # per-phase times with events on the stream the kernels run on (the binding passes torch's current stream)
     fwd_ms, bwd_ms, jfb_ms, finfo, binfo = measure(ctx, binding, torch, np, p, dist, W, C0, G,
                                                    max(5, min(args.steps, 20)), args.bwd_tol, args.bwd_max_iter)
+    dense_ms = measure_dense(ctx, binding, torch, np, G, 5)
     roofline = roofline_of(cfg, dist, fwd_ms, finfo)
     # HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command
     # (counters cannot be read from inside the process; the summary under profiles/ gives the commands)
@@ -159,7 +176,8 @@ def main() -> int:
             measure(ctx, binding, torch, np, q, dd, W, C0, G, 1, args.bwd_tol, 300)
             f_ms, b_ms, j_ms, fi, bi = measure(ctx, binding, torch, np, q, dd, W, C0, G, 3, args.bwd_tol, 300)
             r = roofline_of(q.cfg, dd, f_ms, fi)
-            others.append({"workload": name, "dist": wl.DIST_NAMES[dd], "m": q.cfg.m, "d": q.cfg.d, "k": q.cfg.k,
+            d_ms = measure_dense(ctx, binding, torch, np, G, 3)
+            others.append({"dense_ms": None if d_ms is None else round(d_ms, 4), "workload": name, "dist": wl.DIST_NAMES[dd], "m": q.cfg.m, "d": q.cfg.d, "k": q.cfg.k,
                            "path": {1: "stream", 2: "persistent"}.get(fi.path), "fwd_ms": round(f_ms, 4),
                            "fwd_iters": fi.iters, "fwd_converged": fi.converged,
                            "fwd_iters_per_s": round(fi.iters / (f_ms * 1e-3), 1),
@@ -227,6 +245,7 @@ def main() -> int:
         "implicit_backward": {"ms": bwd_ms, "passes": binfo.iters, "converged": binfo.converged,
                               "tol": args.bwd_tol},
         "jfb_backward": {"ms": jfb_ms},
+        "dense_backward": {"ms": dense_ms, "note": "explicit k d x k d Jacobian in one pass + direct solve (2 passes over W)"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "others": others,

@@ -45,14 +45,16 @@ typedef enum {
 
 typedef enum {
     IDKM_BWD_IMPLICIT = 0, /* solve the fixed point of Sec. 4.2 (Eq. "grad", "inv", "backiter") */
-    IDKM_BWD_JFB = 1       /* Jacobian-free: M* = I (Sec. 4.3, Eq. "jfbgrad") */
+    IDKM_BWD_JFB = 1,      /* Jacobian-free: M* = I (Sec. 4.3, Eq. "jfbgrad") */
+    IDKM_BWD_DENSE = 2     /* explicit k d x k d Jacobian dF/dC* accumulated in one pass over W, then a direct
+                              solve with (I - dF/dC*) (Eq. "grad", "inv"); offered for k d <= 16, k a power of two */
 } idkm_bwd_mode;
 
 /* How the device work is scheduled.  Results are identical up to rounding order. */
 typedef enum {
     IDKM_PATH_AUTO = 0,      /* persistent when the problem fits on chip, else stream */
     IDKM_PATH_STREAM = 1,    /* one kernel launch per pass over W */
-    IDKM_PATH_PERSISTENT = 2 /* one launch per solve, W held in registers, grid-wide exchange per pass */
+    IDKM_PATH_PERSISTENT = 2 /* one launch per solve, W held in LDS, one grid-wide exchange per pass */
 } idkm_path;
 
 typedef struct {
@@ -116,7 +118,10 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
  *       g <- alpha (v + (dF/dC*)^T g) + (1-alpha) g,  g_0 = v,
  *   stopped when ||g+ - g||_F <= tol ||v||_F or after max_iter passes; a non-finite step or a step norm
  *   that grows on 5 consecutive passes restarts from g = v with alpha halved (at most 6 times).
- *   IDKM_BWD_JFB sets g = v (no pass).  dL/dW = (direct term through A) + (dF/dW)^T g.
+ *   IDKM_BWD_JFB sets g = v (no pass).  IDKM_BWD_DENSE forms dF/dC* explicitly (the k x k matrix of Sec. 4.2,
+ *   k d x k d in general) in the same pass that computes v and solves (I - dF/dC*)^T g = v by Gaussian
+ *   elimination in float64: two passes over W in total, tol / max_iter / alpha are ignored, info.iters = 0 and
+ *   info.converged = 0 only if the matrix is singular.  dL/dW = (direct term through A) + (dF/dW)^T g.
  * The attention weights are recomputed on the fly in every pass; nothing of size m*k is stored.
  *
  *   dWq     device [m,d], upstream gradient dL/dWq.

@@ -12,12 +12,15 @@ constexpr int PASS_FIN = 1;  // evaluation at C*: Wq, A, assignments, and n*, F*
 constexpr int PASS_B1 = 2;   // v = dL/dC* with W fixed
 constexpr int PASS_B2 = 3;   // u = (dF/dC)^T g
 constexpr int PASS_B3 = 4;   // dW = direct + (dF/dW)^T g
+constexpr int PASS_BJ = 5;   // v and the explicit Jacobian dF/dC* in one pass, then a direct solve (k d <= 16)
 
 constexpr int DIST_L2 = 0;
 constexpr int DIST_SQL2 = 1;
 
 constexpr int BWD_IMPLICIT = 0;
 constexpr int BWD_JFB = 1;
+constexpr int BWD_DENSE = 2;
+constexpr int DENSE_MAX_KD = 16;
 
 constexpr int WG = 256;  // threads per workgroup of the streaming kernels (4 wavefronts)
 
@@ -386,6 +389,105 @@ __device__ __forceinline__ void tail_b2(const Args& a) {
     }
 }
 
+// Tail of the dense backward (Sec. 4.2, Eq. "grad"/"inv" taken literally): tot holds, for n = k d,
+//   T[n][n]  T[(j,r)][(l,s)] = sum_i (w_ir - F_jr) a_ij a_il delta_il,s
+//   U[n][d]  U[(j,r)][s]     = sum_i (w_ir - F_jr) a_ij delta_ij,s
+//   V[n]     v = dL/dC*
+// so that dF_jr/dc_ls = ([l == j] U[(j,r)][s] - T[(j,r)][(l,s)]) / (tau n_j).  Solves (I - dF/dC)^T g = v by
+// Gauss-Jordan elimination with partial pivoting in float64 (the workgroup's threads update the augmented
+// matrix in parallel) and leaves g, v and h/tau for the final pass.
+__device__ __forceinline__ void tail_bj(const Args& a) {
+    const int k = a.k, d = a.d, n = k * d, n1 = n + 1;
+    Ctrl* c = a.ctrl;
+    __shared__ double s_M[DENSE_MAX_KD * (DENSE_MAX_KD + 1)];
+    __shared__ int s_piv, s_sing;
+    const double* T = a.tot;
+    const double* U = a.tot + n * n;
+    const double* V = a.tot + n * n + n * d;
+    // augmented matrix [I - J^T | v]: row (l,s), column (j,r)
+    for (int t = threadIdx.x; t < n * n1; t += blockDim.x) {
+        const int row = t / n1, col = t - row * n1;
+        double val;
+        if (col == n) {
+            val = V[row];
+        } else {
+            const int l = row / d, s = row - l * d, j = col / d;
+            const double nj = a.nd[j];
+            double J = 0.0;
+            if (nj > 0.0) J = ((l == j ? U[col * d + s] : 0.0) - T[col * n + row]) * ((double)a.inv_tau / nj);
+            val = (row == col ? 1.0 : 0.0) - J;
+        }
+        s_M[t] = val;
+    }
+    if (threadIdx.x == 0) s_sing = 0;
+    __syncthreads();
+    for (int p = 0; p < n; ++p) {
+        if (threadIdx.x == 0) {
+            int best = p;
+            double bv = fabs(s_M[p * n1 + p]);
+            for (int i = p + 1; i < n; ++i) {
+                const double x = fabs(s_M[i * n1 + p]);
+                if (x > bv) {
+                    bv = x;
+                    best = i;
+                }
+            }
+            s_piv = best;
+            if (!(bv > 1e-300) || !(bv <= 1.7e308)) s_sing = 1;
+        }
+        __syncthreads();
+        const int piv = s_piv;
+        if (piv != p) {
+            for (int j = threadIdx.x; j < n1; j += blockDim.x) {
+                const double x = s_M[p * n1 + j];
+                s_M[p * n1 + j] = s_M[piv * n1 + j];
+                s_M[piv * n1 + j] = x;
+            }
+        }
+        __syncthreads();
+        // every thread owns at most two entries (n (n+1) <= 272 <= 2 blockDim); new values are formed before any is stored
+        double nv[2];
+        for (int u = 0; u < 2; ++u) {
+            const int t = threadIdx.x + u * blockDim.x;
+            nv[u] = 0.0;
+            if (t < n * n1) {
+                const int i = t / n1, j = t - i * n1;
+                const double pp = s_M[p * n1 + p];
+                nv[u] = (i == p) ? s_M[t] : s_M[t] - (s_M[i * n1 + p] / pp) * s_M[p * n1 + j];
+            }
+        }
+        __syncthreads();
+        for (int u = 0; u < 2; ++u) {
+            const int t = threadIdx.x + u * blockDim.x;
+            if (t < n * n1) s_M[t] = nv[u];
+        }
+        __syncthreads();
+    }
+    double v2 = 0.0;
+    int bad = 0;
+    for (int idx = threadIdx.x; idx < n; idx += blockDim.x) {
+        const double g = s_M[idx * n1 + n] / s_M[idx * n1 + idx];
+        const double v = V[idx];
+        if (!(fabs(g) <= 1.7e308)) bad = 1;
+        a.gd[idx] = g;
+        a.vd[idx] = v;
+        store_h(a, idx, g);
+        v2 += v * v;
+    }
+    v2 = block_sum_d(v2);
+    bad = block_sum_i(bad);
+    if (threadIdx.x == 0) {
+        const bool ok = !bad && !s_sing;
+        c->b_vnorm = sqrt(v2);
+        c->b_iters = 0;
+        c->b_residual = 0.0;
+        c->b_converged = ok ? 1 : 0;
+        c->b_done = 1;
+        if (!ok) c->nonfinite = 1;
+        c->ticket = 0;
+    }
+}
+
 template <int PASS>
 __device__ __forceinline__ void grid_tail(const Args& a, int nacc) {
     if (!arrive_last(a.ctrl)) return;
@@ -394,6 +496,7 @@ __device__ __forceinline__ void grid_tail(const Args& a, int nacc) {
     if (PASS == PASS_FIN) tail_final(a);
     if (PASS == PASS_B1) tail_b1(a);
     if (PASS == PASS_B2) tail_b2(a);
+    if (PASS == PASS_BJ) tail_bj(a);
 }
 
 }  // namespace idkm

@@ -614,7 +614,8 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     if (st != IDKM_OK) return st;
     if (!ctx->has_forward) return fail(ctx, IDKM_ERR_NO_FORWARD, "idkm_backward needs a successful idkm_forward first");
     if (!dWq || !dW_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "dWq and dW_out must be non-NULL");
-    if (mode != IDKM_BWD_IMPLICIT && mode != IDKM_BWD_JFB) return fail(ctx, IDKM_ERR_INVALID_ARG, "unknown mode");
+    if (mode != IDKM_BWD_IMPLICIT && mode != IDKM_BWD_JFB && mode != IDKM_BWD_DENSE)
+        return fail(ctx, IDKM_ERR_INVALID_ARG, "unknown mode");
     if (!(tol >= 0.f)) return fail(ctx, IDKM_ERR_INVALID_ARG, "tol must be >= 0");
     if (max_iter < 1) return fail(ctx, IDKM_ERR_INVALID_ARG, "max_iter must be >= 1");
     if (!(alpha > 0.f && alpha <= 1.f)) return fail(ctx, IDKM_ERR_INVALID_ARG, "alpha must be in (0,1]");
@@ -627,6 +628,42 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     Args a = base_args(ctx);
     a.G = dWq;
     a.dW_out = dW_out;
+
+    if (mode == IDKM_BWD_DENSE) {
+        // two launches whatever the path: (v, dF/dC*) + direct solve, then the final pass
+        if (!g.small || ctx->k * ctx->d > DENSE_MAX_KD)
+            return fail(ctx, IDKM_ERR_UNSUPPORTED, "the dense backward needs k in {2,4,8,16} and k*d <= 16");
+        const int kd = ctx->k * ctx->d;
+        const size_t nacc = (size_t)kd * kd + (size_t)kd * ctx->d + kd;
+        Geometry gj = g;
+        int64_t vpt = (ctx->m + (int64_t)WG * 256 - 1) / ((int64_t)WG * 256);  // about one workgroup per CU
+        if (vpt < 1) vpt = 1;
+        if (vpt > 64) vpt = 64;
+        gj.vec_per_wg = (int64_t)WG * vpt;
+        gj.nwg = (int)((ctx->m + gj.vec_per_wg - 1) / gj.vec_per_wg);
+        st = ensure_partials(ctx, (size_t)gj.nwg * nacc);
+        if (st != IDKM_OK) return st;
+        a.partials = ctx->partials;
+        hipLaunchKernelGGL(k_init_backward, dim3(1), dim3(1), 0, s, a, (int)mode, 0.0, 1, 1.0);
+        HIP_TRY(ctx, hipGetLastError());
+        st = launch_pass(ctx, gj, PASS_BJ, a, s);
+        if (st != IDKM_OK) return st;
+        st = launch_pass(ctx, g, PASS_B3, a, s);
+        if (st != IDKM_OK) return st;
+        if (info) {
+            st = read_ctrl(ctx, s);
+            if (st != IDKM_OK) return st;
+            const Ctrl& c = *ctx->h_ctrl;
+            info->iters = 0;
+            info->converged = c.b_converged;
+            info->residual = 0.0;
+            info->empty_clusters = ctx->last_empty;
+            info->path = IDKM_PATH_STREAM;
+            info->alpha = 1.0;
+            if (c.nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "I - dF/dC* is singular or non-finite");
+        }
+        return IDKM_OK;
+    }
 
     PersistPlan pp;
     const bool persistent = ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &pp);

@@ -4,6 +4,15 @@
 
 namespace idkm {
 
+template <int K, int D, bool OK>
+struct pick_bj {
+    static KernelFn get() { return nullptr; }
+};
+template <int K, int D>
+struct pick_bj<K, D, true> {
+    static KernelFn get() { return small_pass<K, D, 0, PASS_BJ>; }
+};
+
 template <int K, int D>
 static KernelFn pick(int pass) {
     switch (pass) {
@@ -12,6 +21,7 @@ static KernelFn pick(int pass) {
         case PASS_B1: return small_pass<K, D, 0, PASS_B1>;
         case PASS_B2: return small_pass<K, D, 0, PASS_B2>;
         case PASS_B3: return small_pass<K, D, 0, PASS_B3>;
+        case PASS_BJ: return pick_bj<K, D, (K * D <= DENSE_MAX_KD)>::get();
     }
     return nullptr;
 }

@@ -210,7 +210,7 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
         for (int r = 0; r < D; ++r) {
             c[j][r] = s_Cf[j * D + r];
             hs[j][r] = Item::USE_H ? s_Hs[j * D + r] : 0.f;
-            ff[j][r] = Item::USE_H ? s_Ff[j * D + r] : 0.f;
+            ff[j][r] = Item::USE_F ? s_Ff[j * D + r] : 0.f;
         }
 #pragma unroll
     for (int q = 0; q < Item::NACC; ++q) acc[q] = 0.f;

@@ -99,11 +99,14 @@ __device__ __forceinline__ float delta_small(const float (&df)[K][D], const floa
 template <int K, int D, int DIST, int PASS>
 struct SmallItem {
     static constexpr bool STATS = (PASS == PASS_FWD || PASS == PASS_FIN);
-    static constexpr bool BACK = (PASS == PASS_B1 || PASS == PASS_B2 || PASS == PASS_B3);
-    static constexpr bool USE_G = (PASS == PASS_B1 || PASS == PASS_B3);
+    static constexpr bool BACK = (PASS == PASS_B1 || PASS == PASS_B2 || PASS == PASS_B3 || PASS == PASS_BJ);
+    static constexpr bool USE_G = (PASS == PASS_B1 || PASS == PASS_B3 || PASS == PASS_BJ);
     static constexpr bool USE_H = (PASS == PASS_B2 || PASS == PASS_B3);
+    static constexpr bool USE_F = USE_H || PASS == PASS_BJ;  // needs F* = F(C*, W)
     static constexpr int ACCW = STATS ? (D + 1) : D;
-    static constexpr int NACC = (PASS == PASS_B3) ? 1 : K * ACCW;
+    static constexpr int KD = K * D;
+    // dense backward: T[KD][KD], U[KD][D], V[KD]
+    static constexpr int NACC = (PASS == PASS_B3) ? 1 : (PASS == PASS_BJ ? KD * KD + KD * D + KD : K * ACCW);
 
     static __device__ __forceinline__ void run(const Args& a, int64_t i, const float (&w)[D], const float (&g)[D],
                                                const float (&c)[K][D], const float (&hs)[K][D],
@@ -174,6 +177,33 @@ struct SmallItem {
                 q[j] = s;
                 qbar = fmaf(at[j], s, qbar);
             }
+            if (PASS == PASS_BJ) {
+                // explicit Jacobian terms: x_ls = a_l delta_l,s ; y_jr = (w_r - F_jr) a_j
+                float x[K][D], wf[K][D];
+#pragma unroll
+                for (int j = 0; j < K; ++j)
+#pragma unroll
+                    for (int r = 0; r < D; ++r) {
+                        x[j][r] = at[j] * delta_small<K, D, DIST>(df, ri, j, r);
+                        wf[j][r] = w[r] - ff[j][r];
+                    }
+#pragma unroll
+                for (int j = 0; j < K; ++j)
+#pragma unroll
+                    for (int r = 0; r < D; ++r) {
+                        const float y = wf[j][r] * at[j];
+                        const int row = j * D + r;
+#pragma unroll
+                        for (int l = 0; l < K; ++l)
+#pragma unroll
+                            for (int s2 = 0; s2 < D; ++s2)
+                                acc[row * KD + l * D + s2] = fmaf(y, x[l][s2], acc[row * KD + l * D + s2]);
+#pragma unroll
+                        for (int s2 = 0; s2 < D; ++s2)
+                            acc[KD * KD + row * D + s2] = fmaf(wf[j][r], x[j][s2], acc[KD * KD + row * D + s2]);
+                    }
+            }
+            constexpr int VOFF = (PASS == PASS_BJ) ? KD * KD + KD * D : 0;
             float out[D];
 #pragma unroll
             for (int r = 0; r < D; ++r) out[r] = 0.f;
@@ -188,9 +218,9 @@ struct SmallItem {
                         out[r] = fmaf(at[j], hs[j][r] * a.tau, out[r]);
                         out[r] = fmaf(-th, dl, out[r]);
                     } else {
-                        float t = acc[j * ACCW + r];
-                        if (PASS == PASS_B1) t = fmaf(at[j], g[r], t);
-                        acc[j * ACCW + r] = fmaf(th, dl, t);
+                        float t = acc[VOFF + j * ACCW + r];
+                        if (PASS == PASS_B1 || PASS == PASS_BJ) t = fmaf(at[j], g[r], t);
+                        acc[VOFF + j * ACCW + r] = fmaf(th, dl, t);
                     }
                 }
             }
@@ -214,7 +244,7 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
         for (int r = 0; r < D; ++r) {
             c[j][r] = a.Cf[j * D + r];
             hs[j][r] = Item::USE_H ? a.Hs[j * D + r] : 0.f;
-            ff[j][r] = Item::USE_H ? a.Ff[j * D + r] : 0.f;
+            ff[j][r] = Item::USE_F ? a.Ff[j * D + r] : 0.f;
         }
 
     float acc[NACC];
@@ -245,7 +275,8 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
     for (int q = 0; q < NACC; ++q) {
-        double v = wave_sum_d((double)acc[q]);
+        // few accumulators: float64 butterfly; the dense-backward pass has hundreds: float32 DPP network
+        double v = (NACC <= 96) ? wave_sum_d((double)acc[q]) : (double)wave_sum(acc[q]);
         if (lane == 0) s_part[wave][q] = v;
     }
     __syncthreads();

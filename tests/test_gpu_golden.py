@@ -70,6 +70,12 @@ def test_full_size_solved_layers(ctx, name, dist):
     dj = bj["dW"].cpu().numpy()
     assert rel(dj[idx], g["dW_jfb_rows"]) < TOL_GRAD
     assert abs(np.linalg.norm(dj.astype(np.float64)) / g["dW_jfb_norm"] - 1) < TOL_GRAD
+    # explicit Jacobian + direct solve: the same linear system the oracle solved by Gaussian elimination
+    bd = ctx.backward(G, binding.BWD_DENSE)
+    dd = bd["dW"].cpu().numpy()
+    assert bd["info"].converged
+    assert rel(dd[idx], g["dW_implicit_rows"]) < TOL_GRAD, rel(dd[idx], g["dW_implicit_rows"])
+    assert abs(np.linalg.norm(dd.astype(np.float64)) / g["dW_implicit_norm"] - 1) < TOL_GRAD
     bi = ctx.backward(G, binding.BWD_IMPLICIT, tol=1e-7, max_iter=20000, alpha=1.0)
     di = bi["dW"].cpu().numpy()
     if bi["info"].converged:

@@ -143,6 +143,12 @@ def _forward_backward_case(ctx, cfg, m, dist, expect_path):
     assert bi["info"].iters == ri["iters"] and not bi["info"].converged
     assert bi["info"].alpha == ri["alpha"]
     assert rel(bi["dW"].cpu().numpy(), ri["dW"]) < TOL_GRAD, rel(bi["dW"].cpu().numpy(), ri["dW"])
+    if kd <= 16 and p.cfg.k in (2, 4, 8, 16):
+        # explicit Jacobian + direct solve on the GPU against the oracle's Gaussian elimination
+        bd = ctx.backward(Gd, binding.BWD_DENSE)
+        rd = orc.backward(p.W, Cg, p.tau, dist, G, "dense")
+        assert bd["info"].converged and bd["info"].iters == 0
+        assert rel(bd["dW"].cpu().numpy(), rd["dW"]) < TOL_GRAD, rel(bd["dW"].cpu().numpy(), rd["dW"])
     if kd <= 64:
         # run to the stop rule and compare with the dense solve of the same linear system
         bc = ctx.backward(Gd, binding.BWD_IMPLICIT, tol=1e-7, max_iter=5000, alpha=1.0)
@@ -185,6 +191,36 @@ def test_results_are_bitwise_reproducible(ctx):
     for x, y in zip(runs[0], runs[1]):
         if isinstance(x, torch.Tensor):
             assert torch.equal(x, y)
+
+
+DENSE_CASES = [("k2d1", 3_001, 1, 2), ("k8d1", 9_000, 1, 8), ("k2d2", 4_097, 2, 2), ("k4d2", 5_000, 2, 4),
+               ("k8d2", 6_001, 2, 8), ("k2d4", 2_500, 4, 2), ("k4d4", 7_003, 4, 4)]
+
+
+@pytest.mark.parametrize("dist", DISTS)
+@pytest.mark.parametrize("name,m,d,k", DENSE_CASES, ids=[c[0] for c in DENSE_CASES])
+def test_dense_backward_matches_the_gaussian_solve(ctx, name, m, d, k, dist):
+    W, C0, G = _case(m, d, k, seed=300 + [c[0] for c in DENSE_CASES].index(name))
+    tau = 0.3
+    out = ctx.forward(dev(W), dev(C0), tau, 1e-6, 300, dist)
+    Cg = out["C"].cpu().numpy()
+    bd = ctx.backward(dev(G), binding.BWD_DENSE)
+    rd = orc.backward(W, Cg, tau, dist, G, "dense")
+    assert bd["info"].converged
+    assert rel(bd["dW"].cpu().numpy(), rd["dW"]) < TOL_GRAD, rel(bd["dW"].cpu().numpy(), rd["dW"])
+
+
+def test_dense_backward_is_refused_beyond_its_size_limit(ctx):
+    W, C0, G = _case(2_000, 2, 16, seed=400)  # k d = 32 > 16
+    ctx.forward(dev(W), dev(C0), 0.3, 1e-6, 5, wl.DIST_SQL2)
+    with pytest.raises(binding.IdkmError) as e:
+        ctx.backward(dev(G), binding.BWD_DENSE)
+    assert e.value.status == 6
+    W, C0, G = _case(2_000, 1, 64, seed=401)  # lane<->codeword family
+    ctx.forward(dev(W), dev(C0), 0.3, 1e-6, 5, wl.DIST_SQL2)
+    with pytest.raises(binding.IdkmError) as e:
+        ctx.backward(dev(G), binding.BWD_DENSE)
+    assert e.value.status == 6
 
 
 def test_edge_cases(ctx):
