@@ -43,6 +43,7 @@ struct Args {
     int64_t m;
     int k, d;
     float nscale;   // -log2(e)/tau: exp(-e/tau) = exp2(e*nscale)
+    float escale;   // sqrt(log2(e)/tau) for the squared energy, log2(e)/tau for the plain norm
     float inv_tau;  // 1/tau
     float tau;
     int64_t vec_per_wg;  // vectors handled by one workgroup

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
 #include <new>
 #include <string>
 
@@ -141,6 +142,7 @@ struct idkm_ctx {
     unsigned int* abort_word = nullptr;  // device
     PResult* h_res = nullptr;            // pinned host
     int last_empty = 0;                  // empty clusters seen by the last forward
+    std::map<const void*, std::pair<size_t, int>> checked;  // kernel -> (largest LDS size set, blocks per CU at that size)
     unsigned int spin_limit = 1u << 20;
 #ifdef IDKM_TRACE
     long long* trace = nullptr;
@@ -227,6 +229,8 @@ Args base_args(idkm_ctx* ctx) {
     a.tau = ctx->tau;
     a.inv_tau = 1.0f / ctx->tau;
     a.nscale = (float)(-1.4426950408889634 / (double)ctx->tau);
+    a.escale = (ctx->dist == DIST_SQL2) ? (float)std::sqrt(1.4426950408889634 / (double)ctx->tau)
+                                        : (float)(1.4426950408889634 / (double)ctx->tau);
     a.ctrl = ctx->ctrl;
     a.Cd = ctx->Cd;
     a.Cf = ctx->Cf;
@@ -349,10 +353,17 @@ idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PAr
 #ifdef IDKM_TRACE
     pa.trace = ctx->trace;
 #endif
-    HIP_TRY(ctx, hipFuncSetAttribute((const void*)pp.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pp.lds));
-    int nb = 0;
-    HIP_TRY(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)pp.fn, pp.threads, pp.lds));
-    if (nb < 1 || (int64_t)nb * ctx->num_cu < pp.grid)
+    // attribute and occupancy are queried once per (kernel, LDS size); later launches reuse the answer
+    auto& checked = ctx->checked[(const void*)pp.fn];
+    if (checked.first < pp.lds) {
+        HIP_TRY(ctx, hipFuncSetAttribute((const void*)pp.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pp.lds));
+        int nb = 0;
+        HIP_TRY(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)pp.fn, pp.threads, pp.lds));
+        if (nb < 1) return fail(ctx, IDKM_ERR_DEVICE, "persistent workgroup does not fit a compute unit");
+        checked.first = pp.lds;
+        checked.second = nb;
+    }
+    if ((int64_t)checked.second * ctx->num_cu < pp.grid)
         return fail(ctx, IDKM_ERR_DEVICE, "persistent grid would not be co-resident");
     if (ctx->coop_launch) {
         void* args[] = {(void*)&a, (void*)&pa};

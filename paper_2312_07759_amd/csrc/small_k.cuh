@@ -111,6 +111,37 @@ struct SmallItem {
     static __device__ __forceinline__ void run(const Args& a, int64_t i, const float (&w)[D], const float (&g)[D],
                                                const float (&c)[K][D], const float (&hs)[K][D],
                                                const float (&ff)[K][D], float (&acc)[NACC]) {
+        if (PASS == PASS_FWD && D == 1) {
+            // Scalar weights, forward loop: work in scaled coordinates t_j = s w - s c_j with
+            // s = sqrt(log2(e)/tau) (squared energy) or log2(e)/tau (plain norm), so that
+            // exp(-e_j/tau) = exp2(-t_j^2) resp. exp2(-|t_j|); the row shift is the smallest |t_j|
+            // (absolute values are free source modifiers) and the normalisation is folded into the
+            // M-step FMAs: 10 K + 5 issue slots per vector instead of 13 K + 2.
+            const float sc = a.escale;
+            const float ws = w[0] * sc;
+            float t[K];
+            float tmin = __builtin_inff();
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                t[j] = ws - c[j][0] * sc;  // s c_j is loop-invariant
+                tmin = fminf(tmin, fabsf(t[j]));
+            }
+            const float qmin = tmin * tmin;
+            float p[K], S = 0.f;
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                p[j] = (DIST == DIST_SQL2) ? fast_exp2(fmaf(-t[j], t[j], qmin)) : fast_exp2(tmin - fabsf(t[j]));
+                S += p[j];
+            }
+            const float rS = fast_rcp(S);
+            const float rw = rS * w[0];
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                acc[j * ACCW] = fmaf(p[j], rS, acc[j * ACCW]);
+                acc[j * ACCW + 1] = fmaf(p[j], rw, acc[j * ACCW + 1]);
+            }
+            return;
+        }
         float gs[D];
 #pragma unroll
         for (int r = 0; r < D; ++r) gs[r] = USE_G ? g[r] * a.inv_tau : 0.f;
