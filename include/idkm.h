@@ -83,6 +83,10 @@ idkm_status idkm_destroy(idkm_ctx* ctx);
 const char* idkm_last_error(const idkm_ctx* ctx);
 /* Select the scheduling path for subsequent calls (default IDKM_PATH_AUTO). */
 idkm_status idkm_set_path(idkm_ctx* ctx, idkm_path path);
+/* Bound of every device-side wait of the persistent kernels, in polls (default 2^20, about a second).  When a
+ * wait expires all workgroups leave the kernel and the call returns IDKM_ERR_DEVICE; the context stays usable.
+ * A limit of 0 makes the first unsuccessful poll give up (used to exercise that path). */
+idkm_status idkm_set_spin_limit(idkm_ctx* ctx, uint32_t polls);
 
 /*
  * Algorithm 1 (soft k-means) followed by one evaluation at the solution.

@@ -22,7 +22,7 @@ BWD_IMPLICIT, BWD_JFB, BWD_DENSE = 0, 1, 2
 PATH_AUTO, PATH_STREAM, PATH_PERSISTENT = 0, 1, 2
 
 EXPORTS = ["idkm_version", "idkm_limits", "idkm_status_string", "idkm_create", "idkm_destroy", "idkm_last_error",
-           "idkm_set_path", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT"]
+           "idkm_set_path", "idkm_set_spin_limit", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT"]
 
 
 class IdkmInfo(C.Structure):
@@ -67,6 +67,8 @@ def load_library():
     lib.idkm_last_error.restype = C.c_char_p
     lib.idkm_set_path.argtypes = [vp, C.c_int]
     lib.idkm_set_path.restype = C.c_int
+    lib.idkm_set_spin_limit.argtypes = [vp, C.c_uint32]
+    lib.idkm_set_spin_limit.restype = C.c_int
     lib.idkm_forward.argtypes = [vp, f32p, C.c_int64, C.c_int32, f32p, C.c_int32, C.c_float, C.c_float, C.c_int32,
                                  C.c_int, f32p, f32p, f32p, i32p, C.POINTER(IdkmInfo), vp]
     lib.idkm_forward.restype = C.c_int
@@ -141,6 +143,9 @@ class Context:
 
     def set_path(self, path: int):
         self._check(self._lib.idkm_set_path(self._h, int(path)))
+
+    def set_spin_limit(self, polls: int):
+        self._check(self._lib.idkm_set_spin_limit(self._h, int(polls)))
 
     def forward(self, W, C0, tau, tol, max_iter, dist, want_A=False, want_Wq=True, want_assign=False):
         """idkm_forward.  W [m,d], C0 [k,d] float32 device tensors.  Returns dict(C, A, Wq, assign, info)."""

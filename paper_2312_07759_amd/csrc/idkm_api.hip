@@ -522,6 +522,12 @@ idkm_status idkm_set_path(idkm_ctx* ctx, idkm_path path) {
     return IDKM_OK;
 }
 
+idkm_status idkm_set_spin_limit(idkm_ctx* ctx, uint32_t polls) {
+    if (!ctx) return IDKM_ERR_INVALID_ARG;
+    ctx->spin_limit = polls;
+    return IDKM_OK;
+}
+
 idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, const float* C0, int32_t k, float tau,
                          float tol, int32_t max_iter, idkm_dist dist, float* C_out, float* A_out, float* Wq_out,
                          int32_t* assign_out, idkm_info* info, void* hip_stream) {

@@ -53,6 +53,8 @@ STEP_CASES = [
     ("k3d1", 1_000, 1, 3, 0.1),       # odd k goes to the lane<->codeword family
     ("k32d8", 2_050, 8, 32, 1.0),
     ("k1d4", 300, 4, 1, 0.5),
+    ("k1024d4", 2_100, 4, 1024, 0.5),  # the largest codebook the library accepts (k d = 4096)
+    ("k512d8", 1_100, 8, 512, 1.0),    # the largest d
 ]
 
 
@@ -248,6 +250,29 @@ def test_edge_cases(ctx):
     np.testing.assert_allclose(o["C"].cpu().numpy(), W4, atol=1e-6)
 
 
+def test_an_expired_device_wait_is_reported_and_the_context_stays_usable(ctx):
+    # The host forces the condition: with a spin limit of 0 the first unsuccessful poll of a grid-wide wait gives
+    # up, every workgroup leaves the kernel normally, and the call reports a device error.
+    p = wl.make_problem("C3", wl.DIST_SQL2, m=100_003)
+    Wd, C0d = dev(p.W), dev(p.C0)
+    ctx.set_path(binding.PATH_PERSISTENT)
+    try:
+        ctx.set_spin_limit(0)
+        with pytest.raises(binding.IdkmError) as e:
+            ctx.forward(Wd, C0d, p.tau, p.tol, p.max_iter, wl.DIST_SQL2)
+        assert e.value.status == 3
+        with pytest.raises(binding.IdkmError) as e:  # no forward state was left behind
+            ctx.backward(dev(p.G), binding.BWD_JFB)
+        assert e.value.status == 5
+        ctx.set_spin_limit(1 << 20)
+        out = ctx.forward(Wd, C0d, p.tau, p.tol, p.max_iter, wl.DIST_SQL2)
+        ref = orc.soft_kmeans(p.W, p.C0, p.tau, p.tol, p.max_iter, wl.DIST_SQL2)
+        assert rel(out["C"].cpu().numpy(), ref["C"]) < TOL_VAL
+    finally:
+        ctx.set_spin_limit(1 << 20)
+        ctx.set_path(binding.PATH_AUTO)
+
+
 def test_error_paths(ctx):
     d = wl.DIST_SQL2
     W = dev(np.zeros((8, 1), dtype=np.float32))
@@ -265,6 +290,9 @@ def test_error_paths(ctx):
         with pytest.raises(binding.IdkmError) as e:
             ctx.forward(W, C0, args["tau"], args["tol"], args["max_iter"], args["dist"])
         assert e.value.status == status
+    with pytest.raises(binding.IdkmError) as e:  # empty input
+        ctx.forward(torch.zeros((0, 1), dtype=torch.float32, device="cuda"), C0, 0.1, 1e-6, 5, d)
+    assert e.value.status == 1
     with pytest.raises(binding.IdkmError) as e:  # k > m
         ctx.forward(dev(np.zeros((2, 1), dtype=np.float32)), dev(np.zeros((4, 1), dtype=np.float32)), 0.1, 1e-6, 5, d)
     assert e.value.status == 1
