@@ -11,6 +11,10 @@ KernelFn small_kernel(int K, int D, int dist, int pass);
 // Lane<->codeword family: KPL = ceil(k/64) rounded up to {1,2,4,8,16}, D in {1,2,4,8}, KPL*(D+1) <= 80.
 KernelFn lane_kernel(int KPL, int D, int dist, int pass);
 
+// Lane<->codeword family, stream path: reduction of the per-workgroup partials and the O(k d) tail of a pass.
+KernelFn lane_tail_kernel(int pass);
+void launch_reduce_rows(const Args& a, int nacc, int nwg, int pass, hipStream_t s);
+
 struct PArgs;
 typedef void (*PersistFn)(const Args, const PArgs);
 // Persistent forward / backward solve for the lane<->vector family; nullptr if K (D+1) > 32.

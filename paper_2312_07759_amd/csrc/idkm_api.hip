@@ -195,9 +195,10 @@ idkm_status plan(idkm_ctx* ctx, int64_t m, int k, int d, Geometry* g) {
         while (p < kpl) p <<= 1;
         g->kpl = p;
         if (p * (d + 1) > 80) return fail(ctx, IDKM_ERR_UNSUPPORTED, "ceil(k/64)*(d+1) must be <= 80");
+        // about 1024 workgroups for mid-sized layers, never more than 2048 (their partials are reduced afterwards)
         int64_t vpw = (m + 4095) / 4096;
         if (vpw < 1) vpw = 1;
-        if (vpw > 512) vpw = 512;
+        if (vpw > 512) vpw = (m + 8191) / 8192 > 512 ? (m + 8191) / 8192 : 512;
         g->vec_per_wg = vpw * (WG / 64);
     }
     int64_t nwg = (m + g->vec_per_wg - 1) / g->vec_per_wg;
@@ -253,6 +254,14 @@ idkm_status launch_pass(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, hip
     a.vec_per_wg = g.vec_per_wg;
     hipLaunchKernelGGL(fn, dim3(g.nwg), dim3(WG), 0, s, a);
     HIP_TRY(ctx, hipGetLastError());
+    if (!g.small && pass != PASS_B3) {
+        // this family carries k (d+1) sums per workgroup: a many-workgroup reduction, then a one-workgroup tail
+        const int nacc = ctx->k * ((pass == PASS_FWD || pass == PASS_FIN) ? ctx->d + 1 : ctx->d);
+        launch_reduce_rows(a, nacc, g.nwg, pass, s);
+        HIP_TRY(ctx, hipGetLastError());
+        hipLaunchKernelGGL(lane_tail_kernel(pass), dim3(1), dim3(WG), 0, s, a);
+        HIP_TRY(ctx, hipGetLastError());
+    }
     return IDKM_OK;
 }
 

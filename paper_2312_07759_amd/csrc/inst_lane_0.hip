@@ -40,4 +40,18 @@ KernelFn lane_kernel_0(int KPL, int D, int pass) {
     return nullptr;
 }
 
+KernelFn lane_tail_kernel(int pass) {
+    switch (pass) {
+        case PASS_FWD: return lane_tail<PASS_FWD>;
+        case PASS_FIN: return lane_tail<PASS_FIN>;
+        case PASS_B1: return lane_tail<PASS_B1>;
+        case PASS_B2: return lane_tail<PASS_B2>;
+    }
+    return nullptr;
+}
+
+void launch_reduce_rows(const Args& a, int nacc, int nwg, int pass, hipStream_t s) {
+    hipLaunchKernelGGL(reduce_rows<0>, dim3((nacc + 63) / 64), dim3(WG), 0, s, a, nacc, nwg, pass);
+}
+
 }  // namespace idkm

@@ -228,6 +228,11 @@ __global__ __launch_bounds__(WG) void lane_pass(const Args a) {
     int64_t wend = wbase + vpw;
     if (wend > a.m) wend = a.m;
 
+    // float32 sums absorb at most 256 vectors before they are folded into float64 ones
+    double acc64[NA];
+#pragma unroll
+    for (int q = 0; q < NA; ++q) acc64[q] = 0.0;
+    int since = 0;
     for (int64_t b = wbase; b < wend; b += 64) {
         const int64_t i = b + lane;
         float wv[D], gv[D];
@@ -239,6 +244,14 @@ __global__ __launch_bounds__(WG) void lane_pass(const Args a) {
         }
         const int cnt = (wend - b < 64) ? (int)(wend - b) : 64;
         st.batch(a, b, cnt, wv, gv);
+        if (PASS != PASS_B3 && ++since == 4) {
+            since = 0;
+#pragma unroll
+            for (int q = 0; q < NA; ++q) {
+                acc64[q] += (double)st.acc[q];
+                st.acc[q] = 0.f;
+            }
+        }
     }
 
     if (PASS == PASS_B3) return;
@@ -249,20 +262,59 @@ __global__ __launch_bounds__(WG) void lane_pass(const Args a) {
         if (wave == wv) {
 #pragma unroll
             for (int q = 0; q < NA; ++q) {
+                const double v = acc64[q] + (double)st.acc[q];
                 if (wv == 0)
-                    s_acc[lane][q] = (double)st.acc[q];
+                    s_acc[lane][q] = v;
                 else
-                    s_acc[lane][q] += (double)st.acc[q];
+                    s_acc[lane][q] += v;
             }
         }
         __syncthreads();
     }
+    // the partials of this family (k (d+1) values per workgroup) are reduced by reduce_rows + lane_tail
     const int nacc = k * ACCW;
     for (int idx = threadIdx.x; idx < nacc; idx += WG) {
         const int j = idx / ACCW, comp = idx - j * ACCW;
         a.partials[(size_t)blockIdx.x * nacc + idx] = s_acc[j & 63][(j >> 6) * ACCW + comp];
     }
-    grid_tail<PASS>(a, nacc);
+}
+
+// tot[acc] = sum over workgroups of partials[wg][acc], fixed order.  One workgroup per 64 accumulators; the four
+// wavefronts take interleaved quarters of the workgroups with eight loads in flight each.
+template <int UNUSED>  // a template only so that the header can be included by several translation units
+__global__ __launch_bounds__(WG) void reduce_rows(const Args a, int nacc, int nwg, int pass) {
+    if (pass == PASS_FWD && a.ctrl->done) return;
+    if (pass == PASS_B2 && a.ctrl->b_done) return;
+    __shared__ double s_q[WG / 64][64];
+    const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
+    const int acc = blockIdx.x * 64 + lane;
+    double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (acc < nacc) {
+        const double* __restrict__ p = a.partials + acc;
+        int wg = part;
+        for (; wg + 7 * 4 < nwg; wg += 8 * 4) {
+            double x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = p[(size_t)(wg + 4 * u) * nacc];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s[u] += x[u];
+        }
+        for (; wg < nwg; wg += 4) s[0] += p[(size_t)wg * nacc];
+    }
+    s_q[part][lane] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
+    __syncthreads();
+    if (part == 0 && acc < nacc) a.tot[acc] = (s_q[0][lane] + s_q[1][lane]) + (s_q[2][lane] + s_q[3][lane]);
+}
+
+// The O(k d) update and stop logic of a pass whose totals are already in a.tot (single workgroup).
+template <int PASS>
+__global__ __launch_bounds__(WG) void lane_tail(const Args a) {
+    if (PASS == PASS_FWD && a.ctrl->done) return;
+    if (PASS == PASS_B2 && a.ctrl->b_done) return;
+    if (PASS == PASS_FWD) tail_forward(a);
+    if (PASS == PASS_FIN) tail_final(a);
+    if (PASS == PASS_B1) tail_b1(a);
+    if (PASS == PASS_B2) tail_b2(a);
 }
 
 }  // namespace idkm

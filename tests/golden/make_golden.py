@@ -49,9 +49,6 @@ def dump(rec, out):
         json.dump(rnd(rec), f, separators=(",", ":"))
 
 
-def rows_of(fn_rows, W, idx):
-    """Evaluate a per-row oracle quantity on the sampled rows only (rows are independent given C)."""
-    return fn_rows(W[idx])
 
 
 def solved_layer(name, dist, out):
@@ -93,7 +90,7 @@ def stepwise_layer(name, dist, out, steps):
     p = wl.make_problem(name, dist)
     t0 = time.time()
     k, d = p.cfg.k, p.cfg.d
-    idx = sample_rows(p.cfg.m, 78)
+    idx = sample_rows(p.cfg.m, 78, 64)
     A = orc.attention(p.W, p.C0, p.tau, dist)
     F0, n0 = orc.mstep(A, p.W, p.C0)
     del A
