@@ -107,7 +107,33 @@ __device__ __forceinline__ float wave_max(float x) {
     x = fmaxf(x, dpp_f<0x143, 0xc>(ninf, x));
     return bcast_lane63(x);
 }
-__device__ __forceinline__ float wave_min(float x) { return -wave_max(-x); }
+__device__ __forceinline__ float wave_min(float x) {
+    const float pinf = __builtin_inff();
+    x = fminf(x, dpp_f<0xB1, 0xf>(pinf, x));
+    x = fminf(x, dpp_f<0x4E, 0xf>(pinf, x));
+    x = fminf(x, dpp_f<0x141, 0xf>(pinf, x));
+    x = fminf(x, dpp_f<0x140, 0xf>(pinf, x));
+    x = fminf(x, dpp_f<0x142, 0xa>(pinf, x));
+    x = fminf(x, dpp_f<0x143, 0xc>(pinf, x));
+    return bcast_lane63(x);
+}
+// Minimum over the wavefront of NON-NEGATIVE floats (energies), compared as unsigned integers: the ordering of
+// non-negative IEEE floats is that of their bit patterns, +inf included, and no canonicalisation is needed.  The
+// lane's own value is passed as the "old" operand, so lanes without a DPP source take min(x, x).
+template <int CTRL, int ROWMASK>
+__device__ __forceinline__ unsigned int dpp_self_u(unsigned int x) {
+    return (unsigned int)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, ROWMASK, 0xf, false);
+}
+__device__ __forceinline__ float wave_min_nonneg(float xf) {
+    unsigned int x = __float_as_uint(xf);
+    x = min(x, dpp_self_u<0xB1, 0xf>(x));
+    x = min(x, dpp_self_u<0x4E, 0xf>(x));
+    x = min(x, dpp_self_u<0x141, 0xf>(x));
+    x = min(x, dpp_self_u<0x140, 0xf>(x));
+    x = min(x, dpp_self_u<0x142, 0xa>(x));
+    x = min(x, dpp_self_u<0x143, 0xc>(x));
+    return __uint_as_float((unsigned int)__builtin_amdgcn_readlane((int)x, 63));
+}
 __device__ __forceinline__ int wave_min_i(int x) {
     const int big = 0x7fffffff;
     x = min(x, dpp_i<0xB1, 0xf>(big, x));

@@ -23,11 +23,12 @@ struct LaneWave {
     static constexpr int NA = (PASS == PASS_B3) ? 1 : KPL * ACCW;  // accumulators per lane
 
     float c[KPL][D], hs[KPL][D], ff[KPL][D];
+    float cs[KPL][D];  // forward loop only: codewords in scaled coordinates, padding lanes far away
     bool valid[KPL];
     float acc[NA];
 
     // Cf/Hs/Ff may point to global memory or LDS.
-    __device__ __forceinline__ void init(int k, const float* Cf, const float* Hs, const float* Ff) {
+    __device__ __forceinline__ void init(int k, const float* Cf, const float* Hs, const float* Ff, float escale = 0.f) {
         const int lane = threadIdx.x & 63;
 #pragma unroll
         for (int q = 0; q < KPL; ++q) {
@@ -36,6 +37,8 @@ struct LaneWave {
 #pragma unroll
             for (int r = 0; r < D; ++r) {
                 c[q][r] = valid[q] ? Cf[j * D + r] : 0.f;
+                // a padding codeword sits 1e18 away: its weight underflows to exactly zero without a select
+                cs[q][r] = valid[q] ? Cf[j * D + r] * escale : 1e18f;
                 hs[q][r] = (USE_H && valid[q]) ? Hs[j * D + r] : 0.f;
                 ff[q][r] = (USE_H && valid[q]) ? Ff[j * D + r] : 0.f;
             }
@@ -56,13 +59,74 @@ struct LaneWave {
         int oa = 0;
 #pragma unroll
         for (int r = 0; r < D; ++r) ov[r] = 0.f;
+        // forward loop: the lane's vector is moved to scaled coordinates once per batch
+        float wb[D];
+#pragma unroll
+        for (int r = 0; r < D; ++r) wb[r] = (PASS == PASS_FWD) ? wv[r] * a.escale : wv[r];
+        const float inv_escale = (PASS == PASS_FWD) ? 1.0f / a.escale : 0.f;
         for (int l = 0; l < cnt; ++l) {
             float w[D], g[D], gs[D];
 #pragma unroll
             for (int r = 0; r < D; ++r) {
-                w[r] = lane_bcast(wv[r], l);
+                w[r] = lane_bcast(wb[r], l);
                 g[r] = USE_G ? lane_bcast(gv[r], l) : 0.f;
                 gs[r] = g[r] * a.inv_tau;
+            }
+            if (PASS == PASS_FWD) {
+                // forward loop in scaled coordinates t = s w - s c (s^2 = log2(e)/tau for the squared energy,
+                // s = log2(e)/tau for the plain norm): exp(-e/tau) = exp2(-|t|^2) resp. exp2(-|t|); the
+                // normalisation is folded into the M-step FMAs.  wv was scaled before the loop, so the
+                // broadcast value feeds the subtraction straight from its scalar register.
+                float ev[KPL];
+#pragma unroll
+                for (int q = 0; q < KPL; ++q) {
+                    float t = w[0] - cs[q][0];
+                    float e2 = t * t;
+#pragma unroll
+                    for (int r = 1; r < D; ++r) {
+                        t = w[r] - cs[q][r];
+                        e2 = fmaf(t, t, e2);
+                    }
+                    if (DIST == DIST_SQL2)
+                        ev[q] = e2;
+                    else
+                        ev[q] = (D == 1) ? fabsf(w[0] - cs[q][0]) : fast_sqrt(e2);
+                }
+                // Squared energy: exp2(-e) cannot overflow and the row shift of the softmax is only needed when the
+                // whole row underflows (a vector many kernel widths from every codeword).  That is decided from the
+                // unshifted row sum, which is wave-uniform; only then is the row minimum found and the row redone.
+                // With the plain norm rows underflow routinely (e/tau is large at small tau): always shifted.
+                float p[KPL], S = 0.f;
+                if (DIST == DIST_SQL2) {
+#pragma unroll
+                    for (int q = 0; q < KPL; ++q) {
+                        p[q] = fast_exp2(-ev[q]);
+                        S = (q == 0) ? p[0] : S + p[q];
+                    }
+                    S = wave_sum(S);
+                }
+                if (DIST != DIST_SQL2 || S < 7.9e-31f) {  // below 2^-100
+                    float emin = ev[0];
+#pragma unroll
+                    for (int q = 1; q < KPL; ++q) emin = fminf(emin, ev[q]);
+                    emin = wave_min_nonneg(emin);
+                    S = 0.f;
+#pragma unroll
+                    for (int q = 0; q < KPL; ++q) {
+                        p[q] = fast_exp2(emin - ev[q]);
+                        S += p[q];
+                    }
+                    S = wave_sum(S);
+                }
+                const float rS = fast_rcp(S);
+                const float rSu = rS * inv_escale;  // undoes the scaling of w in the first-moment sums
+#pragma unroll
+                for (int q = 0; q < KPL; ++q) {
+                    acc[q * ACCW] = fmaf(p[q], rS, acc[q * ACCW]);
+#pragma unroll
+                    for (int r = 0; r < D; ++r) acc[q * ACCW + 1 + r] = fmaf(p[q], w[r] * rSu, acc[q * ACCW + 1 + r]);
+                }
+                continue;
             }
             // E-step: energies of this lane's codewords, wavefront softmax (Eq. "aterms")
             float df[KPL][D], ri[KPL], u[KPL], at[KPL];
@@ -221,7 +285,7 @@ __global__ __launch_bounds__(WG) void lane_pass(const Args a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int k = a.k;
     LW st;
-    st.init(k, a.Cf, a.Hs, a.Ff);
+    st.init(k, a.Cf, a.Hs, a.Ff, a.escale);
 
     const int64_t vpw = a.vec_per_wg / (WG / 64);
     const int64_t wbase = (int64_t)blockIdx.x * a.vec_per_wg + (int64_t)wave * vpw;

@@ -219,7 +219,7 @@ __global__ __launch_bounds__(LT) void persist_lane_fwd(const Args a, const PArgs
 
     while (!s_done) {
         LaneWave<KPL, D, DIST, PASS_FWD> st;
-        st.init(k, s_Cf, nullptr, nullptr);
+        st.init(k, s_Cf, nullptr, nullptr, a.escale);
         lane_tile_pass<KPL, D, DIST, PASS_FWD>(a, st, s_tile, nullptr, base, cnt);
         ++seq;
         publish_lane<NA, ACCW>(pa, seq, st.acc, k, s_acc);

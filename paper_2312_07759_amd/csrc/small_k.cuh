@@ -114,24 +114,25 @@ struct SmallItem {
         if (PASS == PASS_FWD && D == 1) {
             // Scalar weights, forward loop: work in scaled coordinates t_j = s w - s c_j with
             // s = sqrt(log2(e)/tau) (squared energy) or log2(e)/tau (plain norm), so that
-            // exp(-e_j/tau) = exp2(-t_j^2) resp. exp2(-|t_j|); the row shift is the smallest |t_j|
-            // (absolute values are free source modifiers) and the normalisation is folded into the
-            // M-step FMAs: 10 K + 5 issue slots per vector instead of 13 K + 2.
+            // exp(-e_j/tau) = exp2(-t_j^2) resp. exp2(-|t_j|), and the normalisation is folded into the
+            // M-step FMAs: 10 K + 4 issue slots per vector instead of 13 K + 2.
             const float sc = a.escale;
             const float ws = w[0] * sc;
             float t[K];
-            float tmin = __builtin_inff();
 #pragma unroll
-            for (int j = 0; j < K; ++j) {
-                t[j] = ws - c[j][0] * sc;  // s c_j is loop-invariant
-                tmin = fminf(tmin, fabsf(t[j]));
-            }
+            for (int j = 0; j < K; ++j) t[j] = ws - c[j][0] * sc;  // s c_j is loop-invariant
+            // The row shift of the softmax is the smallest |t_j| (absolute values are free source modifiers).
+            // A branch that skips it when the row cannot underflow was measured slower here: with one wavefront
+            // per SIMD the straight-line form lets two vectors interleave.
+            float tmin = fabsf(t[0]);
+#pragma unroll
+            for (int j = 1; j < K; ++j) tmin = fminf(tmin, fabsf(t[j]));
             const float qmin = tmin * tmin;
             float p[K], S = 0.f;
 #pragma unroll
             for (int j = 0; j < K; ++j) {
                 p[j] = (DIST == DIST_SQL2) ? fast_exp2(fmaf(-t[j], t[j], qmin)) : fast_exp2(tmin - fabsf(t[j]));
-                S += p[j];
+                S = (j == 0) ? p[0] : S + p[j];
             }
             const float rS = fast_rcp(S);
             const float rw = rS * w[0];

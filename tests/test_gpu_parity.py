@@ -81,6 +81,27 @@ def test_one_evaluation_of_F_and_one_JCT_pass(ctx, name, m, d, k, tau, dist):
     assert rel(u, uref) < TOL_GRAD, (name, rel(u, uref))
 
 
+@pytest.mark.parametrize("path", ["stream", "persistent"])
+@pytest.mark.parametrize("dist", DISTS)
+@pytest.mark.parametrize("m,d,k", [(5_003, 1, 4), (4_001, 2, 8), (3_000, 4, 256), (2_000, 1, 64)])
+def test_rows_whose_softmax_underflows_without_a_shift(ctx, m, d, k, dist, path):
+    # A few vectors sit so far from every codeword that exp(-e/tau) underflows in float32 for the whole row;
+    # the forward loop must then fall back to the shifted softmax for those rows.
+    W, C0, _ = _case(m, d, k, seed=500 + k)
+    W[::997] += 40.0
+    W[5] -= 75.0
+    tau = 0.05
+    ctx.set_path(binding.PATH_STREAM if path == "stream" else binding.PATH_PERSISTENT)
+    try:
+        out = ctx.forward(dev(W), dev(C0), tau, 0.0, 3, dist)
+    finally:
+        ctx.set_path(binding.PATH_AUTO)
+    ref = orc.soft_kmeans(W, C0, tau, 0.0, 3, dist)
+    assert out["info"].iters == 3
+    assert torch.isfinite(out["C"]).all()
+    assert rel(out["C"].cpu().numpy(), ref["C"]) < TOL_VAL
+
+
 FWD_CASES = [
     # name, config, m (None = full size)
     ("C1", "C1", None),
