@@ -137,6 +137,59 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
                           float alpha, float* dW_out, idkm_info* info, void* hip_stream);
 
 /*
+ * Batched calls for the per-layer loops of Algorithm 2 ("for all layers: find C*(W)" and the matching backward
+ * loop).  The layers are independent problems.  A batch owns one context per layer; layers that the persistent
+ * path serves and that share a kernel shape (k, d, dist) are solved by ONE launch in which every layer has its own
+ * team of workgroups, as many layers per launch as the device can hold resident at once.  Small layers are bound
+ * by the latency of the grid-wide exchange of every pass; teams that share compute units hide each other's
+ * waiting, and the launch and wait costs are paid once per batch instead of once per layer.  A layer that needs
+ * the stream path is solved synchronously in its turn.
+ *
+ *   idkm_batch_create   n_layers in [1, 1024] contexts
+ *   idkm_batch_forward  layers[i] is solved with the batch's i-th context, with the results idkm_forward gives;
+ *                       infos (host, [n]) and statuses (host, [n]) receive the per-layer results.  Work is issued
+ *                       on hip_stream; the call returns when every layer is complete.
+ *   idkm_batch_backward layer i must have had a successful idkm_batch_forward with the same index.
+ *   idkm_batch_launches number of batched kernel launches the last call needed (diagnostic)
+ *   idkm_batch_context  the i-th layer's context, owned by the batch (for idkm_set_path, idkm_set_spin_limit,
+ *                       idkm_last_error, idkm_step_JCT ...); NULL if i is out of range
+ * Return value: IDKM_OK if every layer succeeded, otherwise the status of the first layer that failed
+ * (idkm_batch_last_error gives its message); the other layers are still attempted.
+ */
+typedef struct idkm_batch idkm_batch; /* opaque */
+typedef struct {
+    const float* W;  /* device [m,d] */
+    int64_t m;
+    int32_t d;
+    const float* C0; /* device [k,d] */
+    int32_t k;
+    float tau, tol;
+    int32_t max_iter;
+    int32_t dist;        /* idkm_dist */
+    float* C_out;        /* device [k,d], required */
+    float* A_out;        /* device [m,k] or NULL */
+    float* Wq_out;       /* device [m,d] or NULL */
+    int32_t* assign_out; /* device [m] or NULL */
+} idkm_fwd_desc;
+typedef struct {
+    const float* dWq; /* device [m,d] */
+    int32_t mode;     /* idkm_bwd_mode */
+    float tol;
+    int32_t max_iter;
+    float alpha;
+    float* dW_out; /* device [m,d], required */
+} idkm_bwd_desc;
+idkm_status idkm_batch_create(idkm_batch** out, int device_id, int32_t n_layers);
+idkm_status idkm_batch_destroy(idkm_batch* b);
+const char* idkm_batch_last_error(const idkm_batch* b);
+int32_t idkm_batch_launches(const idkm_batch* b);
+idkm_ctx* idkm_batch_context(idkm_batch* b, int32_t i);
+idkm_status idkm_batch_forward(idkm_batch* b, const idkm_fwd_desc* layers, int32_t n, idkm_info* infos,
+                               idkm_status* statuses, void* hip_stream);
+idkm_status idkm_batch_backward(idkm_batch* b, const idkm_bwd_desc* layers, int32_t n, idkm_info* infos,
+                                idkm_status* statuses, void* hip_stream);
+
+/*
  * Single evaluations at a caller-supplied codebook C (device [k,d]), for testing one step in
  * isolation.  They overwrite the forward state of the context with (W, C, n = A^T 1, F(C, W)).
  *   idkm_step_F:   Cplus_out[k,d] = F(C, W)                         (Eq. "deepeqc"); n_out device [k] or NULL

@@ -22,12 +22,25 @@ BWD_IMPLICIT, BWD_JFB, BWD_DENSE = 0, 1, 2
 PATH_AUTO, PATH_STREAM, PATH_PERSISTENT = 0, 1, 2
 
 EXPORTS = ["idkm_version", "idkm_limits", "idkm_status_string", "idkm_create", "idkm_destroy", "idkm_last_error",
-           "idkm_set_path", "idkm_set_spin_limit", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT"]
+           "idkm_set_path", "idkm_set_spin_limit", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT",
+           "idkm_batch_create", "idkm_batch_destroy", "idkm_batch_last_error", "idkm_batch_launches",
+           "idkm_batch_context", "idkm_batch_forward", "idkm_batch_backward"]
 
 
 class IdkmInfo(C.Structure):
     _fields_ = [("iters", C.c_int32), ("converged", C.c_int32), ("residual", C.c_double),
                 ("empty_clusters", C.c_int32), ("path", C.c_int32), ("alpha", C.c_double)]
+
+
+class IdkmFwdDesc(C.Structure):
+    _fields_ = [("W", C.c_void_p), ("m", C.c_int64), ("d", C.c_int32), ("C0", C.c_void_p), ("k", C.c_int32),
+                ("tau", C.c_float), ("tol", C.c_float), ("max_iter", C.c_int32), ("dist", C.c_int32),
+                ("C_out", C.c_void_p), ("A_out", C.c_void_p), ("Wq_out", C.c_void_p), ("assign_out", C.c_void_p)]
+
+
+class IdkmBwdDesc(C.Structure):
+    _fields_ = [("dWq", C.c_void_p), ("mode", C.c_int32), ("tol", C.c_float), ("max_iter", C.c_int32),
+                ("alpha", C.c_float), ("dW_out", C.c_void_p)]
 
 
 class IdkmLimits(C.Structure):
@@ -78,6 +91,20 @@ def load_library():
     lib.idkm_step_F.restype = C.c_int
     lib.idkm_step_JCT.argtypes = [vp, f32p, f32p, vp]
     lib.idkm_step_JCT.restype = C.c_int
+    lib.idkm_batch_create.argtypes = [C.POINTER(vp), C.c_int, C.c_int32]
+    lib.idkm_batch_create.restype = C.c_int
+    lib.idkm_batch_destroy.argtypes = [vp]
+    lib.idkm_batch_destroy.restype = C.c_int
+    lib.idkm_batch_last_error.argtypes = [vp]
+    lib.idkm_batch_last_error.restype = C.c_char_p
+    lib.idkm_batch_launches.argtypes = [vp]
+    lib.idkm_batch_launches.restype = C.c_int32
+    lib.idkm_batch_context.argtypes = [vp, C.c_int32]
+    lib.idkm_batch_context.restype = vp
+    lib.idkm_batch_forward.argtypes = [vp, C.POINTER(IdkmFwdDesc), C.c_int32, C.POINTER(IdkmInfo), C.POINTER(C.c_int), vp]
+    lib.idkm_batch_forward.restype = C.c_int
+    lib.idkm_batch_backward.argtypes = [vp, C.POINTER(IdkmBwdDesc), C.c_int32, C.POINTER(IdkmInfo), C.POINTER(C.c_int), vp]
+    lib.idkm_batch_backward.restype = C.c_int
     _lib = lib
     return lib
 
@@ -201,6 +228,94 @@ class Context:
                                      _ptr(out, torch.float32, g.shape, "out"), _stream())
         self._check(st)
         return out
+
+
+class Batch:
+    """Owns an idkm_batch: one context per layer; forward/backward over all layers in as few launches as fit."""
+
+    def __init__(self, n_layers: int, device: int = 0):
+        self._lib = load_library()
+        h = C.c_void_p()
+        st = self._lib.idkm_batch_create(C.byref(h), int(device), int(n_layers))
+        if st != IDKM_OK:
+            raise IdkmError(st, "idkm_batch_create failed")
+        self._h = h
+        self.n_layers = int(n_layers)
+        self._keep = None
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.idkm_batch_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def launches(self) -> int:
+        return int(self._lib.idkm_batch_launches(self._h))
+
+    def set_path(self, path: int):
+        for i in range(self.n_layers):
+            st = self._lib.idkm_set_path(self._lib.idkm_batch_context(self._h, i), int(path))
+            if st != IDKM_OK:
+                raise IdkmError(st, "idkm_set_path failed")
+
+    def _finish(self, st, statuses, strict):
+        if st != IDKM_OK and strict:
+            raise IdkmError(st, self._lib.idkm_batch_last_error(self._h).decode())
+        return [int(x) for x in statuses]
+
+    def forward(self, layers, tau, tol, max_iter, dist, want_Wq=True, want_assign=False, strict=True):
+        """idkm_batch_forward.  layers: list of (W [m,d], C0 [k,d]) float32 device tensors (shapes may differ);
+        tau may be a scalar or one value per layer.  Returns a list of dict(C, Wq, assign, info, status)."""
+        import torch
+        n = len(layers)
+        taus = list(tau) if hasattr(tau, "__len__") else [tau] * n
+        descs = (IdkmFwdDesc * n)()
+        infos = (IdkmInfo * n)()
+        statuses = (C.c_int * n)()
+        outs = []
+        for i, (W, C0) in enumerate(layers):
+            m, d = W.shape
+            k = C0.shape[0]
+            Cout = torch.empty((k, d), dtype=torch.float32, device=W.device)
+            Wq = torch.empty((m, d), dtype=torch.float32, device=W.device) if want_Wq else None
+            asg = torch.empty((m,), dtype=torch.int32, device=W.device) if want_assign else None
+            descs[i] = IdkmFwdDesc(_ptr(W, torch.float32, (m, d), "W"), m, d, _ptr(C0, torch.float32, (k, d), "C0"), k,
+                                   float(taus[i]), float(tol), int(max_iter), int(dist),
+                                   _ptr(Cout, torch.float32, (k, d), "C_out"), None,
+                                   _ptr(Wq, torch.float32, (m, d), "Wq_out"), _ptr(asg, torch.int32, (m,), "assign_out"))
+            outs.append(dict(C=Cout, Wq=Wq, assign=asg))
+        st = self._lib.idkm_batch_forward(self._h, descs, n, infos, statuses, _stream())
+        sts = self._finish(st, statuses, strict)
+        self._keep = [W for W, _ in layers]  # the library borrows every W until the backward
+        for i, o in enumerate(outs):
+            o["info"] = _info(infos[i])
+            o["status"] = sts[i]
+        return outs
+
+    def backward(self, dWqs, mode, tol=1e-6, max_iter=1000, alpha=1.0, strict=True):
+        """idkm_batch_backward.  dWqs: one [m,d] float32 device tensor per layer.  Returns list of dict(dW, info, status)."""
+        import torch
+        n = len(dWqs)
+        descs = (IdkmBwdDesc * n)()
+        infos = (IdkmInfo * n)()
+        statuses = (C.c_int * n)()
+        outs = []
+        for i, g in enumerate(dWqs):
+            dW = torch.empty_like(g)
+            descs[i] = IdkmBwdDesc(_ptr(g, torch.float32, g.shape, "dWq"), int(mode), float(tol), int(max_iter),
+                                   float(alpha), _ptr(dW, torch.float32, g.shape, "dW_out"))
+            outs.append(dict(dW=dW))
+        st = self._lib.idkm_batch_backward(self._h, descs, n, infos, statuses, _stream())
+        sts = self._finish(st, statuses, strict)
+        for i, o in enumerate(outs):
+            o["info"] = _info(infos[i])
+            o["status"] = sts[i]
+        return outs
 
 
 def limits():

@@ -16,10 +16,17 @@ KernelFn lane_tail_kernel(int pass);
 void launch_reduce_rows(const Args& a, int nacc, int nwg, int pass, hipStream_t s);
 
 struct PArgs;
+struct BatchItem;
 typedef void (*PersistFn)(const Args, const PArgs);
-// Persistent forward / backward solve for the lane<->vector family; nullptr if K (D+1) > 32.
-PersistFn persist_kernel(int K, int D, int dist, bool bwd);
-// Persistent solve for the lane<->codeword family (launch with 1024 threads); nullptr if not instantiated.
-PersistFn persist_lane_kernel(int KPL, int D, int dist, bool bwd);
+typedef void (*PersistBatchFn)(const BatchItem*, const unsigned short*);
+// The two launch forms of one persistent solve: a single problem, or several problems of the same shape.
+struct PersistFns {
+    PersistFn one = nullptr;
+    PersistBatchFn batch = nullptr;
+};
+// Persistent forward / backward solve for the lane<->vector family; empty if K (D+1) > 32.
+PersistFns persist_kernel(int K, int D, int dist, bool bwd);
+// Persistent solve for the lane<->codeword family (launch with 1024 threads); empty if not instantiated.
+PersistFns persist_lane_kernel(int KPL, int D, int dist, bool bwd);
 
 }  // namespace idkm

@@ -8,7 +8,9 @@
 #include <cstring>
 #include <map>
 #include <new>
+#include <algorithm>
 #include <string>
+#include <vector>
 
 #include "../../include/idkm.h"
 #include "common.cuh"
@@ -25,9 +27,9 @@ KernelFn lane_kernel_1(int, int, int);
 KernelFn small_kernel(int K, int D, int dist, int pass) {
     return dist == DIST_L2 ? small_kernel_0(K, D, pass) : small_kernel_1(K, D, pass);
 }
-PersistFn persist_lane_kernel_0(int, int, bool);
-PersistFn persist_lane_kernel_1(int, int, bool);
-PersistFn persist_lane_kernel(int KPL, int D, int dist, bool bwd) {
+PersistFns persist_lane_kernel_0(int, int, bool);
+PersistFns persist_lane_kernel_1(int, int, bool);
+PersistFns persist_lane_kernel(int KPL, int D, int dist, bool bwd) {
     return dist == DIST_L2 ? persist_lane_kernel_0(KPL, D, bwd) : persist_lane_kernel_1(KPL, D, bwd);
 }
 KernelFn lane_kernel(int KPL, int D, int dist, int pass) {
@@ -118,6 +120,10 @@ __global__ void k_f64_to_f32(const double* src, float* dst, int n) {
 
 using namespace idkm;
 
+namespace {
+struct Deferred;
+}
+
 struct idkm_ctx {
     int device = 0;
     std::string err;
@@ -142,6 +148,12 @@ struct idkm_ctx {
     unsigned int* abort_word = nullptr;  // device
     PResult* h_res = nullptr;            // pinned host
     int last_empty = 0;                  // empty clusters seen by the last forward
+    // a persistent launch whose result has not been collected yet (batched calls defer the wait)
+    bool defer_wait = false;
+    int pending_kind = 0;  // 0 none, 1 forward, 2 backward
+    unsigned int pending_id = 0;
+    hipStream_t pending_stream = nullptr;
+    std::vector<Deferred>* sink = nullptr;  // set by a batched call: persistent launches are handed over, not issued
     std::map<const void*, std::pair<size_t, int>> checked;  // kernel -> (largest LDS size set, blocks per CU at that size)
     unsigned int spin_limit = 1u << 20;
 #ifdef IDKM_TRACE
@@ -271,9 +283,17 @@ constexpr size_t LDS_TILE_MAX = 144 * 1024;  // bytes of LDS a persistent workgr
 
 struct PersistPlan {
     PersistFn fn;
+    PersistBatchFn fn_batch;
     int grid, per, threads;
     bool lane;  // lane<->codeword family: own exchange buffers
     size_t lds;
+};
+// A persistent solve that a batched call will launch together with others.
+struct Deferred {
+    idkm_ctx* ctx;
+    PersistPlan pp;
+    Args a;
+    PArgs pa;
 };
 constexpr size_t LANE_TILE_MAX = 94 * 1024;                       // the lane kernels keep ~55 KB of static LDS
 constexpr size_t LANE_BUF1_WORDS = (size_t)2 * PT * 1536;          // k (d+1) <= 1536
@@ -290,7 +310,9 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
         int kpl = (k + 63) / 64, p = 1;
         while (p < kpl) p <<= 1;
         if (d > 4 || p * d > 16 || p * (d + 1) > 24) return false;
-        pp->fn = persist_lane_kernel(p, d, ctx->dist, bwd);
+        const PersistFns fl = persist_lane_kernel(p, d, ctx->dist, bwd);
+        pp->fn = fl.one;
+        pp->fn_batch = fl.batch;
         if (!pp->fn) return false;
         int64_t g = (m + 255) / 256;  // at least 16 vectors per wavefront before adding workgroups
         if (g < 1) g = 1;
@@ -308,7 +330,9 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
         return true;
     }
     if (k * (d + 1) > XLINE) return false;
-    pp->fn = persist_kernel(k, d, ctx->dist, bwd);
+    const PersistFns fs = persist_kernel(k, d, ctx->dist, bwd);
+    pp->fn = fs.one;
+    pp->fn_batch = fs.batch;
     if (!pp->fn) return false;
     pp->threads = PT;
     pp->lane = false;
@@ -362,6 +386,14 @@ idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PAr
 #ifdef IDKM_TRACE
     pa.trace = ctx->trace;
 #endif
+    if (ctx->sink) {
+        // part of a batched call: the batch launches this solve together with others of its shape
+        ctx->sink->push_back(Deferred{ctx, pp, a, pa});
+        ctx->pending_id = ctx->seq_base + 1u;
+        ctx->pending_stream = s;
+        ctx->seq_base += exchanges;
+        return IDKM_OK;
+    }
     // attribute and occupancy are queried once per (kernel, LDS size); later launches reuse the answer
     auto& checked = ctx->checked[(const void*)pp.fn];
     if (checked.first < pp.lds) {
@@ -382,11 +414,49 @@ idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PAr
         hipLaunchKernelGGL(pp.fn, dim3(pp.grid), dim3(pp.threads), pp.lds, s, a, pa);
         HIP_TRY(ctx, hipGetLastError());
     }
-    const unsigned int id = ctx->seq_base + 1u;
+    ctx->pending_id = ctx->seq_base + 1u;
+    ctx->pending_stream = s;
     ctx->seq_base += exchanges;
-    // the kernel reports into pinned host memory; one wait, no copy
-    HIP_TRY(ctx, hipStreamSynchronize(s));
-    if (ctx->h_res->done != id) return fail(ctx, IDKM_ERR_DEVICE, "a grid-wide wait hit its limit");
+    return IDKM_OK;
+}
+
+// Waits for the persistent launch recorded in ctx->pending_* and turns what the kernel reported (pinned host
+// memory: one wait, no copy) into a status and an idkm_info.
+idkm_status finish_persistent(idkm_ctx* ctx, idkm_info* info) {
+    const int kind = ctx->pending_kind;
+    if (!kind) return IDKM_OK;
+    ctx->pending_kind = 0;
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->pending_stream));
+    const PResult& c = *ctx->h_res;
+    if (c.done != ctx->pending_id) return fail(ctx, IDKM_ERR_DEVICE, "a grid-wide wait hit its limit");
+    if (kind == 1) {
+        int empty = 0, bad = c.nonfinite;
+        for (int r = 0; r < 16; ++r) {
+            empty += c.empty[r];
+            bad |= c.bad[r];
+        }
+        if (bad) return fail(ctx, IDKM_ERR_NONFINITE, "the codebook became non-finite");
+        ctx->has_forward = true;
+        ctx->last_empty = empty;
+        if (info) {
+            info->iters = c.iters;
+            info->converged = c.converged;
+            info->residual = c.residual;
+            info->empty_clusters = empty;
+            info->path = IDKM_PATH_PERSISTENT;
+            info->alpha = 0.0;
+        }
+    } else {
+        if (c.nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "the cotangent became non-finite");
+        if (info) {
+            info->iters = c.iters;
+            info->converged = c.converged;
+            info->residual = c.residual;
+            info->empty_clusters = ctx->last_empty;
+            info->path = IDKM_PATH_PERSISTENT;
+            info->alpha = c.alpha;
+        }
+    }
     return IDKM_OK;
 }
 
@@ -396,10 +466,14 @@ idkm_status read_ctrl(idkm_ctx* ctx, hipStream_t s) {
     return IDKM_OK;
 }
 
+idkm_status finish_persistent(idkm_ctx* ctx, idkm_info* info);
+
 idkm_status check_common(idkm_ctx* ctx) {
     if (!ctx) return IDKM_ERR_INVALID_ARG;
     ctx->err.clear();
     HIP_TRY(ctx, hipSetDevice(ctx->device));
+    if (ctx->pending_kind) (void)finish_persistent(ctx, nullptr);  // never leave an earlier launch uncollected
+    ctx->err.clear();
     return IDKM_OK;
 }
 
@@ -580,24 +654,8 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
         pa.max_iter = (int)max_iter;
         st = launch_persistent(ctx, pp, a, pa, (unsigned int)max_iter + 1u, s);
         if (st != IDKM_OK) return st;
-        const PResult& c = *ctx->h_res;
-        int empty = 0, bad = c.nonfinite;
-        for (int r = 0; r < 16; ++r) {
-            empty += c.empty[r];
-            bad |= c.bad[r];
-        }
-        if (bad) return fail(ctx, IDKM_ERR_NONFINITE, "the codebook became non-finite");
-        ctx->has_forward = true;
-        ctx->last_empty = empty;
-        if (info) {
-            info->iters = c.iters;
-            info->converged = c.converged;
-            info->residual = c.residual;
-            info->empty_clusters = empty;
-            info->path = IDKM_PATH_PERSISTENT;
-            info->alpha = 0.0;
-        }
-        return IDKM_OK;
+        ctx->pending_kind = 1;
+        return ctx->defer_wait ? IDKM_OK : finish_persistent(ctx, info);
     }
 
     hipLaunchKernelGGL(k_init_forward, dim3(1), dim3(WG), 0, s, a, C0, (double)tol, (int)max_iter);
@@ -706,17 +764,8 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
             pa.alpha = (double)alpha;
             st = launch_persistent(ctx, pp, a, pa, (unsigned int)ex, s);
             if (st != IDKM_OK) return st;
-            const PResult& c = *ctx->h_res;
-            if (c.nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "the cotangent became non-finite");
-            if (info) {
-                info->iters = c.iters;
-                info->converged = c.converged;
-                info->residual = c.residual;
-                info->empty_clusters = ctx->last_empty;
-                info->path = IDKM_PATH_PERSISTENT;
-                info->alpha = c.alpha;
-            }
-            return IDKM_OK;
+            ctx->pending_kind = 2;
+            return ctx->defer_wait ? IDKM_OK : finish_persistent(ctx, info);
         }
     }
     hipLaunchKernelGGL(k_init_backward, dim3(1), dim3(1), 0, s, a, (int)mode, (double)tol, (int)max_iter, (double)alpha);
@@ -753,6 +802,227 @@ idkm_status idkm_debug_trace(idkm_ctx* ctx, long long* dev_buf) {
     return IDKM_OK;
 }
 #endif
+
+}  // extern "C"
+
+struct idkm_batch {
+    int device = 0;
+    int num_cu = 0;
+    std::vector<idkm_ctx*> ctx;
+    std::vector<Deferred> deferred;
+    // launch tables: pinned host staging and their device copies
+    BatchItem *h_items = nullptr, *d_items = nullptr;
+    unsigned short *h_map = nullptr, *d_map = nullptr;
+    size_t map_cap = 0;
+    std::map<std::pair<const void*, size_t>, int> blocks_per_cu;  // (kernel, LDS rounded up to 1 KiB) -> occupancy
+    std::map<const void*, size_t> lds_attr;                       // kernel -> dynamic LDS limit set so far
+    int launches = 0;                                             // of the last batched call
+    std::string err;
+};
+
+namespace {
+
+idkm_status batch_fail(idkm_batch* b, idkm_status st, const std::string& msg) {
+    b->err = msg;
+    return st;
+}
+
+// Workgroups of `fn` with `lds` bytes of dynamic LDS that the device holds at once (0 on error).
+int64_t batch_capacity(idkm_batch* b, const void* fn, int threads, size_t lds) {
+    const size_t rounded = (lds + 1023) / 1024 * 1024;
+    auto key = std::make_pair(fn, rounded);
+    auto it = b->blocks_per_cu.find(key);
+    if (it == b->blocks_per_cu.end()) {
+        size_t& attr = b->lds_attr[fn];
+        if (attr < rounded) {
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)rounded) != hipSuccess) {
+                (void)hipGetLastError();
+                return 0;
+            }
+            attr = rounded;
+        }
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, threads, rounded) != hipSuccess) {
+            (void)hipGetLastError();
+            return 0;
+        }
+        it = b->blocks_per_cu.emplace(key, nb).first;
+    }
+    return (int64_t)it->second * b->num_cu;
+}
+
+// Launches the deferred solves: solves of one kernel shape share launches, each launch as large as the device
+// can hold at once (every team's workgroups must be resident together, since they wait for one another).
+idkm_status batch_launch(idkm_batch* b, hipStream_t s) {
+    std::vector<Deferred>& q = b->deferred;
+    b->launches = 0;
+    if (q.empty()) return IDKM_OK;
+    std::vector<char> taken(q.size(), 0);
+    size_t item_off = 0, map_off = 0;
+    for (size_t first = 0; first < q.size(); ++first) {
+        if (taken[first]) continue;
+        const void* fn = (const void*)q[first].pp.fn_batch;
+        const int threads = q[first].pp.threads;
+        size_t i = first;
+        while (i < q.size()) {
+            // one launch: members i.. of this shape while the grid stays co-resident
+            const size_t item_begin = item_off, map_begin = map_off;
+            size_t lds = 0;
+            int64_t total = 0;
+            for (; i < q.size(); ++i) {
+                if (taken[i] || (const void*)q[i].pp.fn_batch != fn) continue;
+                const size_t lds_new = std::max(lds, q[i].pp.lds);
+                const int64_t cap = batch_capacity(b, fn, threads, lds_new);
+                if (cap < q[i].pp.grid) return batch_fail(b, IDKM_ERR_DEVICE, "persistent grid would not be co-resident");
+                if (total + q[i].pp.grid > cap || total + q[i].pp.grid > 65535) break;  // full: next launch
+                if (map_off + (size_t)q[i].pp.grid > b->map_cap) return batch_fail(b, IDKM_ERR_DEVICE, "launch table overflow");
+                BatchItem& it = b->h_items[item_off];
+                it.a = q[i].a;
+                it.p = q[i].pa;
+                it.wg_begin = (int)total;
+                it.wg_count = q[i].pp.grid;
+                for (int w = 0; w < q[i].pp.grid; ++w) b->h_map[map_off + w] = (unsigned short)(item_off - item_begin);
+                map_off += (size_t)q[i].pp.grid;
+                item_off += 1;
+                total += q[i].pp.grid;
+                lds = lds_new;
+                taken[i] = 1;
+            }
+            if (total == 0) break;
+            if (hipMemcpyAsync(b->d_items + item_begin, b->h_items + item_begin, (item_off - item_begin) * sizeof(BatchItem),
+                               hipMemcpyHostToDevice, s) != hipSuccess ||
+                hipMemcpyAsync(b->d_map + map_begin, b->h_map + map_begin, (map_off - map_begin) * sizeof(unsigned short),
+                               hipMemcpyHostToDevice, s) != hipSuccess)
+                return batch_fail(b, IDKM_ERR_DEVICE, "copy of the launch tables failed");
+            hipLaunchKernelGGL(q[first].pp.fn_batch, dim3((unsigned)total), dim3(threads), lds, s,
+                               (const BatchItem*)(b->d_items + item_begin), (const unsigned short*)(b->d_map + map_begin));
+            if (hipGetLastError() != hipSuccess) return batch_fail(b, IDKM_ERR_DEVICE, "batched launch failed");
+            b->launches += 1;
+        }
+    }
+    return IDKM_OK;
+}
+
+// Collects the deferred solves after batch_launch (or abandons them if the launch failed).
+idkm_status batch_collect(idkm_batch* b, idkm_status launched, int32_t n, idkm_info* infos, idkm_status* statuses) {
+    idkm_status first = launched;
+    for (int i = 0; i < n; ++i) {
+        idkm_ctx* c = b->ctx[i];
+        if (statuses[i] == IDKM_OK && c->pending_kind) {
+            if (launched == IDKM_OK) {
+                statuses[i] = finish_persistent(c, &infos[i]);
+            } else {
+                c->pending_kind = 0;
+                statuses[i] = launched;
+                c->err = b->err;
+            }
+        }
+        if (statuses[i] != IDKM_OK && first == IDKM_OK) {
+            first = statuses[i];
+            b->err = "layer " + std::to_string(i) + ": " + c->err;
+        }
+    }
+    b->deferred.clear();
+    return first;
+}
+
+}  // namespace
+
+extern "C" {
+
+idkm_status idkm_batch_create(idkm_batch** out, int device_id, int32_t n_layers) {
+    if (!out) return IDKM_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (n_layers < 1 || n_layers > 1024) return IDKM_ERR_INVALID_ARG;
+    idkm_batch* b = new (std::nothrow) idkm_batch();
+    if (!b) return IDKM_ERR_ALLOC;
+    b->device = device_id;
+    for (int i = 0; i < n_layers; ++i) {
+        idkm_ctx* c = nullptr;
+        idkm_status st = idkm_create(&c, device_id);
+        if (st != IDKM_OK) {
+            idkm_batch_destroy(b);
+            return st;
+        }
+        b->ctx.push_back(c);
+    }
+    b->num_cu = b->ctx[0]->num_cu;
+    b->map_cap = (size_t)n_layers * PT;  // a team has at most PT workgroups
+    const bool ok = hipHostMalloc((void**)&b->h_items, (size_t)n_layers * sizeof(BatchItem), hipHostMallocDefault) == hipSuccess &&
+                    hipHostMalloc((void**)&b->h_map, b->map_cap * sizeof(unsigned short), hipHostMallocDefault) == hipSuccess &&
+                    hipMalloc((void**)&b->d_items, (size_t)n_layers * sizeof(BatchItem)) == hipSuccess &&
+                    hipMalloc((void**)&b->d_map, b->map_cap * sizeof(unsigned short)) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        idkm_batch_destroy(b);
+        return IDKM_ERR_ALLOC;
+    }
+    *out = b;
+    return IDKM_OK;
+}
+
+idkm_status idkm_batch_destroy(idkm_batch* b) {
+    if (!b) return IDKM_ERR_INVALID_ARG;
+    (void)hipSetDevice(b->device);
+    (void)hipDeviceSynchronize();
+    for (idkm_ctx* c : b->ctx) (void)idkm_destroy(c);
+    if (b->h_items) (void)hipHostFree(b->h_items);
+    if (b->h_map) (void)hipHostFree(b->h_map);
+    if (b->d_items) (void)hipFree(b->d_items);
+    if (b->d_map) (void)hipFree(b->d_map);
+    delete b;
+    return IDKM_OK;
+}
+
+const char* idkm_batch_last_error(const idkm_batch* b) { return b ? b->err.c_str() : "null batch"; }
+
+int32_t idkm_batch_launches(const idkm_batch* b) { return b ? b->launches : -1; }
+
+idkm_ctx* idkm_batch_context(idkm_batch* b, int32_t i) {
+    return (b && i >= 0 && i < (int32_t)b->ctx.size()) ? b->ctx[i] : nullptr;
+}
+
+idkm_status idkm_batch_forward(idkm_batch* b, const idkm_fwd_desc* layers, int32_t n, idkm_info* infos,
+                               idkm_status* statuses, void* hip_stream) {
+    if (!b || !layers || !infos || !statuses || n < 1 || n > (int32_t)b->ctx.size()) return IDKM_ERR_INVALID_ARG;
+    b->err.clear();
+    b->deferred.clear();
+    if (hipSetDevice(b->device) != hipSuccess) return IDKM_ERR_DEVICE;
+    for (int i = 0; i < n; ++i) {
+        idkm_ctx* c = b->ctx[i];
+        const idkm_fwd_desc& L = layers[i];
+        std::memset(&infos[i], 0, sizeof(idkm_info));
+        c->defer_wait = true;
+        c->sink = &b->deferred;
+        statuses[i] = idkm_forward(c, L.W, L.m, L.d, L.C0, L.k, L.tau, L.tol, L.max_iter, (idkm_dist)L.dist, L.C_out,
+                                   L.A_out, L.Wq_out, L.assign_out, &infos[i], hip_stream);
+        c->defer_wait = false;
+        c->sink = nullptr;
+    }
+    const idkm_status launched = batch_launch(b, (hipStream_t)hip_stream);
+    return batch_collect(b, launched, n, infos, statuses);
+}
+
+idkm_status idkm_batch_backward(idkm_batch* b, const idkm_bwd_desc* layers, int32_t n, idkm_info* infos,
+                                idkm_status* statuses, void* hip_stream) {
+    if (!b || !layers || !infos || !statuses || n < 1 || n > (int32_t)b->ctx.size()) return IDKM_ERR_INVALID_ARG;
+    b->err.clear();
+    b->deferred.clear();
+    if (hipSetDevice(b->device) != hipSuccess) return IDKM_ERR_DEVICE;
+    for (int i = 0; i < n; ++i) {
+        idkm_ctx* c = b->ctx[i];
+        const idkm_bwd_desc& L = layers[i];
+        std::memset(&infos[i], 0, sizeof(idkm_info));
+        c->defer_wait = true;
+        c->sink = &b->deferred;
+        statuses[i] = idkm_backward(c, L.dWq, (idkm_bwd_mode)L.mode, L.tol, L.max_iter, L.alpha, L.dW_out, &infos[i],
+                                    hip_stream);
+        c->defer_wait = false;
+        c->sink = nullptr;
+    }
+    const idkm_status launched = batch_launch(b, (hipStream_t)hip_stream);
+    return batch_collect(b, launched, n, infos, statuses);
+}
 
 idkm_status idkm_step_F(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, const float* C, int32_t k, float tau,
                         idkm_dist dist, float* Cplus_out, float* n_out, void* hip_stream) {

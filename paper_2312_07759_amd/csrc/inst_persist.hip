@@ -5,13 +5,16 @@
 namespace idkm {
 
 template <int K, int D>
-static PersistFn pick(int dist, bool bwd) {
-    if (dist == DIST_L2) return bwd ? persist_bwd<K, D, DIST_L2> : persist_fwd<K, D, DIST_L2>;
-    return bwd ? persist_bwd<K, D, DIST_SQL2> : persist_fwd<K, D, DIST_SQL2>;
+static PersistFns pick(int dist, bool bwd) {
+    if (dist == DIST_L2)
+        return bwd ? PersistFns{persist_bwd<K, D, DIST_L2>, persist_bwd_batch<K, D, DIST_L2>}
+                   : PersistFns{persist_fwd<K, D, DIST_L2>, persist_fwd_batch<K, D, DIST_L2>};
+    return bwd ? PersistFns{persist_bwd<K, D, DIST_SQL2>, persist_bwd_batch<K, D, DIST_SQL2>}
+               : PersistFns{persist_fwd<K, D, DIST_SQL2>, persist_fwd_batch<K, D, DIST_SQL2>};
 }
 
 // Offered when K (D+1) <= 32, the widest row the exchange layout carries.
-PersistFn persist_kernel(int K, int D, int dist, bool bwd) {
+PersistFns persist_kernel(int K, int D, int dist, bool bwd) {
     switch (K * 16 + D) {
         case 2 * 16 + 1: return pick<2, 1>(dist, bwd);
         case 4 * 16 + 1: return pick<4, 1>(dist, bwd);
@@ -23,7 +26,7 @@ PersistFn persist_kernel(int K, int D, int dist, bool bwd) {
         case 2 * 16 + 4: return pick<2, 4>(dist, bwd);
         case 4 * 16 + 4: return pick<4, 4>(dist, bwd);
     }
-    return nullptr;
+    return PersistFns{};
 }
 
 }  // namespace idkm

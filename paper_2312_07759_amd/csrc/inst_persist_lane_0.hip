@@ -5,12 +5,13 @@
 namespace idkm {
 
 template <int KPL, int D>
-static PersistFn pick(bool bwd) {
-    return bwd ? persist_lane_bwd<KPL, D, 0> : persist_lane_fwd<KPL, D, 0>;
+static PersistFns pick(bool bwd) {
+    return bwd ? PersistFns{persist_lane_bwd<KPL, D, 0>, persist_lane_bwd_batch<KPL, D, 0>}
+               : PersistFns{persist_lane_fwd<KPL, D, 0>, persist_lane_fwd_batch<KPL, D, 0>};
 }
 
 // Offered for KPL*D <= 16 and KPL*(D+1) <= 24 (k <= 512), d <= 4.
-PersistFn persist_lane_kernel_0(int KPL, int D, bool bwd) {
+PersistFns persist_lane_kernel_0(int KPL, int D, bool bwd) {
     switch (KPL * 16 + D) {
         case 1 * 16 + 1: return pick<1, 1>(bwd);
         case 1 * 16 + 2: return pick<1, 2>(bwd);
@@ -24,7 +25,7 @@ PersistFn persist_lane_kernel_0(int KPL, int D, bool bwd) {
         case 8 * 16 + 1: return pick<8, 1>(bwd);
         case 8 * 16 + 2: return pick<8, 2>(bwd);
     }
-    return nullptr;
+    return PersistFns{};
 }
 
 }  // namespace idkm

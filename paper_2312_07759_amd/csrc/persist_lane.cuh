@@ -82,7 +82,7 @@ __device__ __forceinline__ void publish_lane(const PArgs& pa, unsigned int seq, 
         __syncthreads();
     }
     const int nacc = k * ACCW;
-    unsigned long long* dst = pa.buf1 + ((size_t)(seq & 1u) * gridDim.x + blockIdx.x) * nacc;
+    unsigned long long* dst = pa.buf1 + ((size_t)(seq & 1u) * pa.G + pa.wg) * nacc;
     for (int idx = tid; idx < nacc; idx += LT) {
         const int j = idx / ACCW, comp = idx - j * ACCW;
         st_word(&dst[idx], pack_f(seq, (float)s_acc[j & 63][(j >> 6) * ACCW + comp]));
@@ -94,7 +94,7 @@ template <int WPR>
 __device__ __forceinline__ bool reduce_lane(const PArgs& pa, unsigned int seq, int nacc, int first, LShared& ls) {
     static_assert(WPR <= 8, "a reducer handles at most 8 words per workgroup");
     const int tid = threadIdx.x;
-    const int G = gridDim.x;
+    const int G = pa.G;
     if (tid < PT) {
         float f[WPR];
 #pragma unroll
@@ -179,7 +179,7 @@ __device__ __forceinline__ void lane_tile_pass(const Args& a, LaneWave<KPL, D, D
 
 // Forward solve (Alg. 1) and the evaluation at C*.
 template <int KPL, int D, int DIST>
-__global__ __launch_bounds__(LT) void persist_lane_fwd(const Args a, const PArgs pa) {
+__device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs& pa) {
     constexpr int ACCW = D + 1;
     constexpr int NA = KPL * ACCW;
     constexpr int KDP = 64 * KPL * D;  // padded codebook size
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(LT) void persist_lane_fwd(const Args a, const PArgs
     __shared__ int s_done, s_iters, s_conv, s_bad;
     __shared__ double s_res;
 
-    const int tid = threadIdx.x, wg = blockIdx.x, G = gridDim.x;
+    const int tid = threadIdx.x, wg = pa.wg, G = pa.G;
     const int k = a.k, kd = k * D, nacc = k * ACCW;
     const int stride2 = kd + k;
     const int64_t base = (int64_t)wg * pa.per;
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(LT) void persist_lane_fwd(const Args a, const PArgs
 
 // Backward: v, the averaged iteration of Sec. 4.2 (skipped for JFB), and dW.
 template <int KPL, int D, int DIST>
-__global__ __launch_bounds__(LT) void persist_lane_bwd(const Args a, const PArgs pa) {
+__device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs& pa) {
     constexpr int NA = KPL * D;
     constexpr int KDP = 64 * KPL * D;
     extern __shared__ float s_tile[];
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(LT) void persist_lane_bwd(const Args a, const PArgs
     __shared__ int s_done, s_iters, s_conv, s_attempt, s_grow, s_halv, s_bad, s_restart;
     __shared__ double s_alpha, s_prev, s_vnorm, s_res;
 
-    const int tid = threadIdx.x, wg = blockIdx.x, G = gridDim.x;
+    const int tid = threadIdx.x, wg = pa.wg, G = pa.G;
     const int k = a.k, kd = k * D;
     const int stride2 = kd + k;
     const int64_t base = (int64_t)wg * pa.per;
@@ -523,6 +523,40 @@ __global__ __launch_bounds__(LT) void persist_lane_bwd(const Args a, const PArgs
         o->nonfinite = s_bad;
         o->done = pa.seq_base + 1u;
     }
+}
+
+// Launch forms: one team per grid, or one team per batched problem (see persist_small.cuh).
+template <int KPL, int D, int DIST>
+__global__ __launch_bounds__(LT) void persist_lane_fwd(const Args a, const PArgs pa_in) {
+    PArgs pa = pa_in;
+    pa.wg = blockIdx.x;
+    pa.G = gridDim.x;
+    persist_lane_fwd_body<KPL, D, DIST>(a, pa);
+}
+template <int KPL, int D, int DIST>
+__global__ __launch_bounds__(LT) void persist_lane_fwd_batch(const BatchItem* items, const unsigned short* item_of_wg) {
+    const BatchItem& it = items[item_of_wg[blockIdx.x]];
+    const Args a = it.a;
+    PArgs pa = it.p;
+    pa.wg = (int)blockIdx.x - it.wg_begin;
+    pa.G = it.wg_count;
+    persist_lane_fwd_body<KPL, D, DIST>(a, pa);
+}
+template <int KPL, int D, int DIST>
+__global__ __launch_bounds__(LT) void persist_lane_bwd(const Args a, const PArgs pa_in) {
+    PArgs pa = pa_in;
+    pa.wg = blockIdx.x;
+    pa.G = gridDim.x;
+    persist_lane_bwd_body<KPL, D, DIST>(a, pa);
+}
+template <int KPL, int D, int DIST>
+__global__ __launch_bounds__(LT) void persist_lane_bwd_batch(const BatchItem* items, const unsigned short* item_of_wg) {
+    const BatchItem& it = items[item_of_wg[blockIdx.x]];
+    const Args a = it.a;
+    PArgs pa = it.p;
+    pa.wg = (int)blockIdx.x - it.wg_begin;
+    pa.G = it.wg_count;
+    persist_lane_bwd_body<KPL, D, DIST>(a, pa);
 }
 
 }  // namespace idkm

@@ -49,16 +49,24 @@ struct PArgs {
     double alpha;              // backward: damping factor
     unsigned int* abort_word;  // device word; holds this launch's id once a bounded wait has expired
     PResult* out;              // pinned host memory
+    int wg, G;                 // this workgroup's index within its team and the team's size; filled in by the kernel
 #ifdef IDKM_TRACE
     long long* trace;          // [2 workgroups][64 passes][8 stamps] of the shader clock (development builds only)
 #endif
 };
 
+// One problem of a batched launch: the workgroups [wg_begin, wg_begin + wg_count) of the grid form its team.
+struct BatchItem {
+    Args a;
+    PArgs p;
+    int wg_begin, wg_count;
+};
+
 #ifdef IDKM_TRACE
 #define IDKM_STAMP(slot)                                                                                  \
     do {                                                                                                  \
-        if (pa.trace && threadIdx.x == 0 && s_iters < 64 && (blockIdx.x == 0 || blockIdx.x == gridDim.x - 1)) \
-            pa.trace[((blockIdx.x == 0 ? 0 : 1) * 64 + s_iters) * 8 + (slot)] = (long long)clock64();      \
+        if (pa.trace && threadIdx.x == 0 && s_iters < 64 && (pa.wg == 0 || pa.wg == pa.G - 1)) \
+            pa.trace[((pa.wg == 0 ? 0 : 1) * 64 + s_iters) * 8 + (slot)] = (long long)clock64();      \
     } while (0)
 #else
 #define IDKM_STAMP(slot) do { } while (0)
@@ -103,7 +111,7 @@ __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int s
 #pragma unroll
         for (int w = 0; w < PT / 64; ++w) s += xs.wpart[w * NACC + tid];
         // row = accumulator, column = workgroup: a reducer's wavefront then reads 64 consecutive words per load
-        st_word(&pa.buf1[((size_t)(seq & 1u) * XLINE + tid) * PT + blockIdx.x], pack_f(seq, (float)s));
+        st_word(&pa.buf1[((size_t)(seq & 1u) * XLINE + tid) * PT + pa.wg], pack_f(seq, (float)s));
     }
 }
 
@@ -114,7 +122,7 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
                                              XShared<NACC>& xs) {
     static_assert(WPR <= 8, "a reducer handles at most 8 words per workgroup");
     const int tid = threadIdx.x;
-    const int G = gridDim.x;
+    const int G = pa.G;
     float f[WPR];
 #pragma unroll
     for (int q = 0; q < WPR; ++q) f[q] = 0.f;
@@ -150,7 +158,7 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
     }
     __syncthreads();
 #ifdef IDKM_TRACE
-    if (pa.trace && threadIdx.x == 0 && blockIdx.x == 0) pa.trace[2 * 64 * 8 - 1] = (long long)clock64();
+    if (pa.trace && threadIdx.x == 0 && pa.wg == 0) pa.trace[2 * 64 * 8 - 1] = (long long)clock64();
 #endif
     if (xs.abort) return false;
     // thread (q, part) adds workgroups part*8 .. part*8+7 of word q, then a fixed 32-lane DPP network
@@ -237,7 +245,7 @@ constexpr int cw_per_reducer(int K, int D) {
 
 // Forward solve (Alg. 1) and the evaluation at C*, in one launch.
 template <int K, int D, int DIST>
-__global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) {
+__device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa) {
     constexpr int KD = K * D;
     constexpr int ACCW = D + 1;
     constexpr int NACC = K * ACCW;
@@ -253,7 +261,7 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
     __shared__ int s_done, s_iters, s_conv, s_bad;
     __shared__ double s_res;
 
-    const int tid = threadIdx.x, wg = blockIdx.x;
+    const int tid = threadIdx.x, wg = pa.wg;
     const int64_t base = (int64_t)wg * pa.per;
     int cnt = 0;
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
@@ -285,11 +293,11 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
         ++seq;
         publish_partials<NACC>(pa, seq, acc, xs);
         IDKM_STAMP(2);
-        for (int r = wg; r < R; r += gridDim.x) {
+        for (int r = wg; r < R; r += pa.G) {
             if (!reduce_slice<NACC, WPR>(pa, seq, r * WPR, xs)) return;
             IDKM_STAMP(3);
 #ifdef IDKM_TRACE
-            if (pa.trace && threadIdx.x == 0 && blockIdx.x == 0 && s_iters < 64) pa.trace[s_iters * 8 + 6] = pa.trace[2 * 64 * 8 - 1];
+            if (pa.trace && threadIdx.x == 0 && pa.wg == 0 && s_iters < 64) pa.trace[s_iters * 8 + 6] = pa.trace[2 * 64 * 8 - 1];
 #endif
             // centre update of this slice (Alg. 1), float64; a non-finite sum is broadcast as NaN
             if (tid < KPR * D) {
@@ -354,7 +362,7 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
     tile_pass<K, D, DIST, PASS_FIN>(a, s_tile, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
     ++seq;
     publish_partials<NACC>(pa, seq, acc, xs);
-    for (int r = wg; r < R; r += gridDim.x) {
+    for (int r = wg; r < R; r += pa.G) {
         if (!reduce_slice<NACC, WPR>(pa, seq, r * WPR, xs)) return;
         if (tid < KPR * D) {
             const int jl = tid / D, rr = tid - jl * D, j = r * KPR + jl, idx = j * D + rr;
@@ -382,7 +390,7 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
         }
         __syncthreads();
     }
-    if (wg == gridDim.x - 1 && tid == 0) {
+    if (wg == pa.G - 1 && tid == 0) {
         PResult* o = pa.out;
         o->iters = s_iters;
         o->residual = sqrt(s_res);
@@ -395,7 +403,7 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa) 
 // Backward (Alg. 2 per-layer steps): v, the averaged fixed-point iteration of
 // Sec. 4.2 for g (skipped for JFB), and dW, in one launch.
 template <int K, int D, int DIST>
-__global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) {
+__device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa) {
     constexpr int KD = K * D;
     constexpr int KPR = (8 / D) > K ? K : (8 / D);  // codewords per reducer: 8 words of D components
     constexpr int R = K / KPR;
@@ -409,7 +417,7 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
     __shared__ int s_done, s_iters, s_conv, s_attempt, s_grow, s_halv, s_bad, s_restart;
     __shared__ double s_alpha, s_prev, s_vnorm, s_res;
 
-    const int tid = threadIdx.x, wg = blockIdx.x;
+    const int tid = threadIdx.x, wg = pa.wg;
     const int64_t base = (int64_t)wg * pa.per;
     int cnt = 0;
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
@@ -455,7 +463,7 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
     tile_pass<K, D, DIST, PASS_B1>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
     ++seq;
     publish_partials<KD>(pa, seq, acc, xs);
-    for (int r = wg; r < R; r += gridDim.x) {
+    for (int r = wg; r < R; r += pa.G) {
         if (!reduce_slice<KD, WPR>(pa, seq, r * WPR, xs)) return;
         if (tid < 64) {
             double v2 = 0.0;
@@ -493,7 +501,7 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
         ++seq;
         publish_partials<KD>(pa, seq, acc, xs);
         const double alpha = s_alpha;
-        for (int r = wg; r < R; r += gridDim.x) {
+        for (int r = wg; r < R; r += pa.G) {
             if (!reduce_slice<KD, WPR>(pa, seq, r * WPR, xs)) return;
             if (tid < 64) {
                 double d2 = 0.0;
@@ -568,7 +576,7 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
 
     // B3: dW = direct + (dF/dW)^T g
     tile_pass<K, D, DIST, PASS_B3>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, reinterpret_cast<float(&)[1]>(acc[0]));
-    for (int r = wg; r < R; r += gridDim.x) {
+    for (int r = wg; r < R; r += pa.G) {
         if (tid < WPR) {
             const int idx = r * WPR + tid;
             a.gd[idx] = s_g[idx];
@@ -576,7 +584,7 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
         }
     }
     if (wg == 0 && tid < KD) a.Hs[tid] = s_Hs[tid];
-    if (wg == gridDim.x - 1 && tid == 0) {
+    if (wg == pa.G - 1 && tid == 0) {
         PResult* o = pa.out;
         o->iters = s_iters;
         o->converged = s_conv;
@@ -587,6 +595,43 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa) 
         o->nonfinite = s_bad;
         o->done = pa.seq_base + 1u;
     }
+}
+
+// One team per launch: the grid is the team.
+template <int K, int D, int DIST>
+__global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa_in) {
+    PArgs pa = pa_in;
+    pa.wg = blockIdx.x;
+    pa.G = gridDim.x;
+    persist_fwd_body<K, D, DIST>(a, pa);
+}
+template <int K, int D, int DIST>
+__global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa_in) {
+    PArgs pa = pa_in;
+    pa.wg = blockIdx.x;
+    pa.G = gridDim.x;
+    persist_bwd_body<K, D, DIST>(a, pa);
+}
+
+// Several independent problems of one shape (the layers of Alg. 2's loops) in one launch: item_of_wg maps a
+// workgroup to its problem; every team runs its own solve and leaves when that solve is over.
+template <int K, int D, int DIST>
+__global__ __launch_bounds__(PT) void persist_fwd_batch(const BatchItem* items, const unsigned short* item_of_wg) {
+    const BatchItem& it = items[item_of_wg[blockIdx.x]];
+    const Args a = it.a;
+    PArgs pa = it.p;
+    pa.wg = (int)blockIdx.x - it.wg_begin;
+    pa.G = it.wg_count;
+    persist_fwd_body<K, D, DIST>(a, pa);
+}
+template <int K, int D, int DIST>
+__global__ __launch_bounds__(PT) void persist_bwd_batch(const BatchItem* items, const unsigned short* item_of_wg) {
+    const BatchItem& it = items[item_of_wg[blockIdx.x]];
+    const Args a = it.a;
+    PArgs pa = it.p;
+    pa.wg = (int)blockIdx.x - it.wg_begin;
+    pa.G = it.wg_count;
+    persist_bwd_body<K, D, DIST>(a, pa);
 }
 
 }  // namespace idkm
