@@ -189,10 +189,13 @@ def main() -> int:
         for dd in (1, 0):
             tot = {"fwd_ms": 0.0, "implicit_ms": 0.0, "jfb_ms": 0.0, "fwd_iters": 0, "implicit_passes": 0,
                    "unconverged_fwd": 0, "unconverged_bwd": 0, "weights": 0, "layers": 0}
+            bt = {"fwd_ms": 0.0, "implicit_ms": 0.0, "jfb_ms": 0.0, "launches_fwd": 0}
             for kk in (2, 4):
+                held = []
                 for ti in range(len(wl.RESNET18_TENSORS)):
                     q = wl.make_problem(wl.sweep_config(ti, kk, dd), dd)
                     Wt, Ct, Gt = (torch.from_numpy(x).cuda() for x in (q.W, q.C0, q.G))
+                    held.append((q, Wt, Ct, Gt))
                     measure(ctx, binding, torch, np, q, dd, Wt, Ct, Gt, 1, args.bwd_tol, 2000)
                     f_ms, b_ms, j_ms, fi, bi = measure(ctx, binding, torch, np, q, dd, Wt, Ct, Gt, 2, args.bwd_tol, 2000)
                     tot["fwd_ms"] += f_ms
@@ -204,9 +207,37 @@ def main() -> int:
                     tot["unconverged_bwd"] += 0 if bi.converged else 1
                     tot["weights"] += q.cfg.m
                     tot["layers"] += 1
+                # the same 21 tensors through the batched entry points: one call for all layers
+                batch = binding.Batch(len(held))
+                pairs = [(Wt, Ct) for _, Wt, Ct, _ in held]
+                taus = [q.tau for q, _, _, _ in held]
+                Gs = [Gt for _, _, _, Gt in held]
+                q0 = held[0][0]
+                for rep in range(3):  # the first repetition warms up
+                    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+                    ev[0].record()
+                    batch.forward(pairs, taus, q0.tol, q0.max_iter, dd, want_Wq=True)
+                    ev[1].record()
+                    batch.backward(Gs, binding.BWD_IMPLICIT, tol=args.bwd_tol, max_iter=2000, alpha=1.0)
+                    ev[2].record()
+                    batch.backward(Gs, binding.BWD_JFB)
+                    ev[3].record()
+                    torch.cuda.synchronize()
+                    if rep:
+                        bt["fwd_ms"] += ev[0].elapsed_time(ev[1]) / 2
+                        bt["implicit_ms"] += ev[1].elapsed_time(ev[2]) / 2
+                        bt["jfb_ms"] += ev[2].elapsed_time(ev[3]) / 2
+                batch.forward(pairs, taus, q0.tol, q0.max_iter, dd, want_Wq=True)
+                bt["launches_fwd"] += batch.launches()
+                batch.close()
+                del held, pairs, Gs
             others.append({"workload": "C5 (21 ResNet18 tensors x k in {2,4}, one call per tensor)",
                            "dist": wl.DIST_NAMES[dd], **{a: (round(b, 3) if isinstance(b, float) else b) for a, b in tot.items()},
                            "fwd_iters_per_s": round(tot["fwd_iters"] / (tot["fwd_ms"] * 1e-3), 1)})
+            others.append({"workload": "C5 (21 ResNet18 tensors x k in {2,4}, one batched call per k)",
+                           "dist": wl.DIST_NAMES[dd], **{a: (round(b, 3) if isinstance(b, float) else b) for a, b in bt.items()},
+                           "fwd_iters": tot["fwd_iters"], "weights": tot["weights"], "layers": tot["layers"],
+                           "fwd_iters_per_s": round(tot["fwd_iters"] / (bt["fwd_ms"] * 1e-3), 1)})
 
     cpu = None
     if not args.no_cpu_baseline:
