@@ -14,7 +14,8 @@ Two energies are supported, selected by `dist`:
 Every function cites the passage of the paper it writes out.  Parity status:
 every function below is pinned by tests/test_oracle_*.py against closed forms,
 invariants, brute force (hard Lloyd), central finite differences, a dense
-linear solve and an independent autodiff of the matrix form; none is unpinned.
+linear solve and an independent autodiff of the matrix form; the code packing
+against Python big-integer arithmetic and a hand-worked stream; none is unpinned.
 """
 from __future__ import annotations
 
@@ -119,6 +120,53 @@ def hard_assign_f32(W32, C32):
             diff = (W32[:, r][:, None] - C32[:, r][None, :]).astype(np.float32)
             key = (key + (diff * diff).astype(np.float32)).astype(np.float32)
     return np.argmin(key, axis=1).astype(np.int32)
+
+
+def hard_quantize(W32, C32):
+    """q(W, C): every w_i replaced by its closest codeword (Sec. 3, the map written with a bold q), float32 rows of C."""
+    C32 = np.asarray(C32, dtype=np.float32)
+    return C32[hard_assign_f32(W32, C32)]
+
+
+def cluster_objective(W, C, assign):
+    """Sum_i ||w_i - c_assign(i)||^2 (Eq. "clusterobj"), float64."""
+    W, C = _f64(W), _f64(C)
+    diff = W - C[np.asarray(assign)]
+    return float(np.sum(diff * diff))
+
+
+def code_bits(k):
+    """Bits per code for a codebook of k codewords: the b with 2^b >= k (k = 2^b in the paper), at least 1."""
+    b = 1
+    while (1 << b) < k:
+        b += 1
+    return b
+
+
+def pack_codes(assign, k):
+    """The stored form of a quantised layer (Sec. 3: one of k = 2^b codewords per sub-vector, b bits each).
+
+    Code i occupies bits [i b, (i+1) b) of one little-endian bit stream (bit t of the stream is bit t mod 32 of
+    32-bit word t div 32); the last word is padded with zero bits.  Returns uint32[ceil(m b / 32)].
+    """
+    a = np.asarray(assign, dtype=np.int64)
+    b = code_bits(k)
+    assert a.min(initial=0) >= 0 and a.max(initial=0) < k
+    m = a.shape[0]
+    nwords = (m * b + 31) // 32
+    bits = np.zeros(nwords * 32, dtype=np.uint8)
+    for t in range(b):
+        bits[t:m * b:b] = (a >> t) & 1
+    by = np.packbits(bits, bitorder="little")
+    return by.view("<u4").astype(np.uint32)
+
+
+def unpack_codes(words, m, k):
+    """Inverse of pack_codes: int32[m]."""
+    b = code_bits(k)
+    by = np.asarray(words, dtype="<u4").view(np.uint8)
+    bits = np.unpackbits(by, bitorder="little")[:m * b].reshape(m, b).astype(np.int64)
+    return (bits << np.arange(b)[None, :]).sum(axis=1).astype(np.int32)
 
 
 # --------------------------------------------------------------------------- derivatives of F
