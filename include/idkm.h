@@ -137,6 +137,28 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
                           float alpha, float* dW_out, idkm_info* info, void* hip_stream);
 
 /*
+ * The stored form of a quantised layer (Sec. 3, product-quantisation set-up: every sub-vector w_i is replaced by
+ * its closest codeword q(w_i, C), one of k = 2^b, so a layer is kept as m codes of b bits plus the codebook).
+ *
+ *   idkm_code_bits     b = the smallest b >= 1 with 2^b >= k (0 if k < 1)
+ *   idkm_code_words    number of 32-bit words of the stream: ceil(m b / 32) (-1 for invalid m, k)
+ *   idkm_pack_codes    assign (device int32 [m], 16-byte aligned, values in [0, k); idkm_forward's assign_out)
+ *                      -> words_out (device uint32 [idkm_code_words(m, k)]).  Code i occupies bits [i b, (i+1) b) of
+ *                      one little-endian bit stream (stream bit t = bit t mod 32 of word t div 32); the unused high
+ *                      bits of the last word are zero.  Only the low b bits of each value are used.
+ *   idkm_unpack_quantize  words + codebook C (device [k,d]) -> Wh_out (device [m,d]) = q(W, C): row i is a bitwise
+ *                      copy of codeword row code_i.  A code >= k (possible only in a stream that idkm_pack_codes did
+ *                      not write when k is not a power of two) gives a row of NaN.
+ * Both enqueue one kernel on hip_stream and do not wait.  1 <= k <= 1024, 1 <= d <= 64; m = 0 is a no-op.
+ */
+int32_t idkm_code_bits(int32_t k);
+int64_t idkm_code_words(int64_t m, int32_t k);
+idkm_status idkm_pack_codes(idkm_ctx* ctx, const int32_t* assign, int64_t m, int32_t k, uint32_t* words_out,
+                            void* hip_stream);
+idkm_status idkm_unpack_quantize(idkm_ctx* ctx, const uint32_t* words, int64_t m, const float* C, int32_t k, int32_t d,
+                                 float* Wh_out, void* hip_stream);
+
+/*
  * Batched calls for the per-layer loops of Algorithm 2 ("for all layers: find C*(W)" and the matching backward
  * loop).  The layers are independent problems.  A batch owns one context per layer; layers that the persistent
  * path serves and that share a kernel shape (k, d, dist) are solved by ONE launch in which every layer has its own

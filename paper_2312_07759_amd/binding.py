@@ -23,6 +23,7 @@ PATH_AUTO, PATH_STREAM, PATH_PERSISTENT = 0, 1, 2
 
 EXPORTS = ["idkm_version", "idkm_limits", "idkm_status_string", "idkm_create", "idkm_destroy", "idkm_last_error",
            "idkm_set_path", "idkm_set_spin_limit", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT",
+           "idkm_code_bits", "idkm_code_words", "idkm_pack_codes", "idkm_unpack_quantize",
            "idkm_batch_create", "idkm_batch_destroy", "idkm_batch_last_error", "idkm_batch_launches",
            "idkm_batch_context", "idkm_batch_forward", "idkm_batch_backward"]
 
@@ -91,6 +92,14 @@ def load_library():
     lib.idkm_step_F.restype = C.c_int
     lib.idkm_step_JCT.argtypes = [vp, f32p, f32p, vp]
     lib.idkm_step_JCT.restype = C.c_int
+    lib.idkm_code_bits.argtypes = [C.c_int32]
+    lib.idkm_code_bits.restype = C.c_int32
+    lib.idkm_code_words.argtypes = [C.c_int64, C.c_int32]
+    lib.idkm_code_words.restype = C.c_int64
+    lib.idkm_pack_codes.argtypes = [vp, i32p, C.c_int64, C.c_int32, vp, vp]
+    lib.idkm_pack_codes.restype = C.c_int
+    lib.idkm_unpack_quantize.argtypes = [vp, vp, C.c_int64, f32p, C.c_int32, C.c_int32, f32p, vp]
+    lib.idkm_unpack_quantize.restype = C.c_int
     lib.idkm_batch_create.argtypes = [C.POINTER(vp), C.c_int, C.c_int32]
     lib.idkm_batch_create.restype = C.c_int
     lib.idkm_batch_destroy.argtypes = [vp]
@@ -205,6 +214,27 @@ class Context:
         self._check(st)
         return dict(dW=dW, info=_info(info))
 
+    def pack_codes(self, assign, k):
+        """idkm_pack_codes: int32 [m] device tensor -> int32 tensor holding the uint32 words of the b-bit stream."""
+        import torch
+        m = assign.shape[0]
+        words = torch.empty((max(code_words(m, k), 0),), dtype=torch.int32, device=assign.device)
+        st = self._lib.idkm_pack_codes(self._h, _ptr(assign, torch.int32, (m,), "assign"), m, int(k),
+                                       C.c_void_p(words.data_ptr()), _stream())
+        self._check(st)
+        return words
+
+    def unpack_quantize(self, words, m, Cb):
+        """idkm_unpack_quantize: stream words + codebook [k,d] -> q(W, C) [m,d]."""
+        import torch
+        k, d = Cb.shape
+        out = torch.empty((m, d), dtype=torch.float32, device=Cb.device)
+        st = self._lib.idkm_unpack_quantize(self._h, _ptr(words, torch.int32, (code_words(m, k),), "words"), m,
+                                            _ptr(Cb, torch.float32, (k, d), "C"), k, d,
+                                            _ptr(out, torch.float32, (m, d), "Wh_out"), _stream())
+        self._check(st)
+        return out
+
     def step_F(self, W, Cb, tau, dist):
         """idkm_step_F: one evaluation of F at Cb.  Returns (C+ [k,d], n [k])."""
         import torch
@@ -228,6 +258,14 @@ class Context:
                                      _ptr(out, torch.float32, g.shape, "out"), _stream())
         self._check(st)
         return out
+
+
+def code_bits(k: int) -> int:
+    return int(load_library().idkm_code_bits(int(k)))
+
+
+def code_words(m: int, k: int) -> int:
+    return int(load_library().idkm_code_words(int(m), int(k)))
 
 
 class Batch:

@@ -29,4 +29,9 @@ PersistFns persist_kernel(int K, int D, int dist, bool bwd);
 // Persistent solve for the lane<->codeword family (launch with 1024 threads); empty if not instantiated.
 PersistFns persist_lane_kernel(int KPL, int D, int dist, bool bwd);
 
+// b-bit code stream of the hard assignments and the reconstruction q(W, C) from it (codes.hip).
+void launch_pack_codes(const int32_t* assign, int64_t m, int bits, uint32_t* words, int64_t nwords, hipStream_t s);
+void launch_unpack_quantize(const uint32_t* words, int64_t nwords, int64_t m, int bits, const float* C, int k, int d,
+                            float* out, hipStream_t s);
+
 }  // namespace idkm

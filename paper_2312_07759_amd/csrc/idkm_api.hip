@@ -794,6 +794,45 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     return IDKM_OK;
 }
 
+int32_t idkm_code_bits(int32_t k) {
+    if (k < 1) return 0;
+    int b = 1;
+    while ((1 << b) < k) ++b;
+    return b;
+}
+
+int64_t idkm_code_words(int64_t m, int32_t k) {
+    if (m < 0 || k < 1 || k > 1024) return -1;
+    return (m * idkm_code_bits(k) + 31) / 32;
+}
+
+idkm_status idkm_pack_codes(idkm_ctx* ctx, const int32_t* assign, int64_t m, int32_t k, uint32_t* words_out,
+                            void* hip_stream) {
+    idkm_status st = check_common(ctx);
+    if (st != IDKM_OK) return st;
+    if (m < 0 || k < 1 || k > 1024) return fail(ctx, IDKM_ERR_INVALID_ARG, "need m >= 0 and 1 <= k <= 1024");
+    if (m == 0) return IDKM_OK;
+    if (!assign || !words_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "assign and words_out must be non-NULL");
+    if ((reinterpret_cast<uintptr_t>(assign) & 15u) != 0) return fail(ctx, IDKM_ERR_INVALID_ARG, "assign must be 16-byte aligned");
+    if (m > ((int64_t)1 << 36)) return fail(ctx, IDKM_ERR_INVALID_ARG, "m too large");
+    launch_pack_codes(assign, m, idkm_code_bits(k), words_out, idkm_code_words(m, k), (hipStream_t)hip_stream);
+    HIP_TRY(ctx, hipGetLastError());
+    return IDKM_OK;
+}
+
+idkm_status idkm_unpack_quantize(idkm_ctx* ctx, const uint32_t* words, int64_t m, const float* C, int32_t k, int32_t d,
+                                 float* Wh_out, void* hip_stream) {
+    idkm_status st = check_common(ctx);
+    if (st != IDKM_OK) return st;
+    if (m < 0 || k < 1 || k > 1024 || d < 1 || d > 64) return fail(ctx, IDKM_ERR_INVALID_ARG, "need m >= 0, 1 <= k <= 1024, 1 <= d <= 64");
+    if (m == 0) return IDKM_OK;
+    if (!words || !C || !Wh_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "words, C and Wh_out must be non-NULL");
+    if (m > ((int64_t)1 << 36)) return fail(ctx, IDKM_ERR_INVALID_ARG, "m too large");
+    launch_unpack_quantize(words, idkm_code_words(m, k), m, idkm_code_bits(k), C, k, d, Wh_out, (hipStream_t)hip_stream);
+    HIP_TRY(ctx, hipGetLastError());
+    return IDKM_OK;
+}
+
 #ifdef IDKM_TRACE
 // development builds only: device buffer of 2*64*8 int64 clock stamps filled by the persistent forward kernel
 idkm_status idkm_debug_trace(idkm_ctx* ctx, long long* dev_buf) {
