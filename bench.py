@@ -54,6 +54,20 @@ def measure_dense(ctx, binding, torch, np, G, reps):
     return float(np.median([a.elapsed_time(b) for a, b in ts[1:]]))
 
 
+def measure_gmres(ctx, binding, torch, np, G, reps, tol, max_iter):
+    """Median event time (ms) and the last info of the minimal-residual (Krylov) backward."""
+    ts = []
+    info = None
+    for _ in range(reps + 1):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        info = ctx.backward(G, binding.BWD_GMRES, tol=tol, max_iter=max_iter)["info"]
+        e1.record()
+        ts.append((e0, e1))
+    torch.cuda.synchronize()
+    return float(np.median([a.elapsed_time(b) for a, b in ts[1:]])), info
+
+
 def measure(ctx, binding, torch, np, p, dist, W, C0, G, reps, bwd_tol, bwd_max_iter):
     """Median event times (ms) of forward, implicit backward and JFB backward over `reps` runs."""
     recs = []
@@ -157,6 +171,7 @@ def main() -> int:
     fwd_ms, bwd_ms, jfb_ms, finfo, binfo = measure(ctx, binding, torch, np, p, dist, W, C0, G,
                                                    max(5, min(args.steps, 20)), args.bwd_tol, args.bwd_max_iter)
     dense_ms = measure_dense(ctx, binding, torch, np, G, 5)
+    gm_ms, gm_info = measure_gmres(ctx, binding, torch, np, G, 5, args.bwd_tol, args.bwd_max_iter)
     roofline = roofline_of(cfg, dist, fwd_ms, finfo)
     # HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command
     # (counters cannot be read from inside the process; the summary under profiles/ gives the commands)
@@ -177,12 +192,15 @@ def main() -> int:
             f_ms, b_ms, j_ms, fi, bi = measure(ctx, binding, torch, np, q, dd, W, C0, G, 3, args.bwd_tol, 300)
             r = roofline_of(q.cfg, dd, f_ms, fi)
             d_ms = measure_dense(ctx, binding, torch, np, G, 3)
+            g_ms, gi = measure_gmres(ctx, binding, torch, np, G, 2, args.bwd_tol, 300)
             others.append({"dense_ms": None if d_ms is None else round(d_ms, 4), "workload": name, "dist": wl.DIST_NAMES[dd], "m": q.cfg.m, "d": q.cfg.d, "k": q.cfg.k,
                            "path": {1: "stream", 2: "persistent"}.get(fi.path), "fwd_ms": round(f_ms, 4),
                            "fwd_iters": fi.iters, "fwd_converged": fi.converged,
                            "fwd_iters_per_s": round(fi.iters / (f_ms * 1e-3), 1),
                            "implicit_ms": round(b_ms, 4), "implicit_passes": bi.iters,
                            "implicit_converged": bi.converged, "jfb_ms": round(j_ms, 4),
+                           "gmres_ms": round(g_ms, 4), "gmres_passes": gi.iters, "gmres_converged": gi.converged,
+                           "gmres_residual": gi.residual,
                            "alu_frac": round(r["frac"], 4), "avg_eval_us": round(r["avg_eval_us"], 3)})
 
         # the whole-network sweep: 21 ResNet18 tensors, each quantised independently at k = 2 and k = 4 (d = 1)
@@ -276,6 +294,8 @@ def main() -> int:
         "implicit_backward": {"ms": bwd_ms, "passes": binfo.iters, "converged": binfo.converged,
                               "tol": args.bwd_tol},
         "jfb_backward": {"ms": jfb_ms},
+        "gmres_backward": {"ms": gm_ms, "passes": gm_info.iters, "converged": gm_info.converged, "tol": args.bwd_tol,
+                           "note": "restarted GMRES on (I - dF/dC*)^T g = v, one pass over W per basis vector (stream path)"},
         "dense_backward": {"ms": dense_ms, "note": "explicit k d x k d Jacobian in one pass + direct solve (2 passes over W)"},
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -46,8 +46,10 @@ typedef enum {
 typedef enum {
     IDKM_BWD_IMPLICIT = 0, /* solve the fixed point of Sec. 4.2 (Eq. "grad", "inv", "backiter") */
     IDKM_BWD_JFB = 1,      /* Jacobian-free: M* = I (Sec. 4.3, Eq. "jfbgrad") */
-    IDKM_BWD_DENSE = 2     /* explicit k d x k d Jacobian dF/dC* accumulated in one pass over W, then a direct
+    IDKM_BWD_DENSE = 2,    /* explicit k d x k d Jacobian dF/dC* accumulated in one pass over W, then a direct
                               solve with (I - dF/dC*) (Eq. "grad", "inv"); offered for k d <= 16, k a power of two */
+    IDKM_BWD_GMRES = 3     /* the same linear system (I - dF/dC*)^T g = v (Eq. "grad", "inv") by a restarted
+                              minimal-residual Krylov solve; one pass over W per basis vector, any shape */
 } idkm_bwd_mode;
 
 /* How the device work is scheduled.  Results are identical up to rounding order. */
@@ -125,7 +127,16 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
  *   IDKM_BWD_JFB sets g = v (no pass).  IDKM_BWD_DENSE forms dF/dC* explicitly (the k x k matrix of Sec. 4.2,
  *   k d x k d in general) in the same pass that computes v and solves (I - dF/dC*)^T g = v by Gaussian
  *   elimination in float64: two passes over W in total, tol / max_iter / alpha are ignored, info.iters = 0 and
- *   info.converged = 0 only if the matrix is singular.  dL/dW = (direct term through A) + (dF/dW)^T g.
+ *   info.converged = 0 only if the matrix is singular.
+ *   IDKM_BWD_GMRES solves the same system from g = 0 by restarted GMRES (basis length min(k d, 64), float64
+ *   orthogonalisation): every pass applies (dF/dC*)^T to one basis vector; when the estimated residual falls
+ *   below tol ||v||_F (or the basis is full) the iterate is updated and one more pass measures the true residual
+ *   ||v + (dF/dC*)^T g - g||_F, which is the step norm of the undamped iteration at g and is held to the same
+ *   test <= tol ||v||_F; otherwise a new cycle starts from that residual.  info.iters counts all these passes
+ *   (at most max_iter + 1), info.residual is the last true residual, alpha is ignored; two cycles in a row that
+ *   do not halve the residual end the solve with converged = 0.  With k d <= 64 the first cycle is exact up to
+ *   rounding.  Runs on the stream path (IDKM_PATH_PERSISTENT gives IDKM_ERR_UNSUPPORTED).
+ *   dL/dW = (direct term through A) + (dF/dW)^T g.
  * The attention weights are recomputed on the fly in every pass; nothing of size m*k is stored.
  *
  *   dWq     device [m,d], upstream gradient dL/dWq.

@@ -18,7 +18,7 @@ IDKM_OK = 0
 STATUS_NAMES = {0: "IDKM_OK", 1: "IDKM_ERR_INVALID_ARG", 2: "IDKM_ERR_ALLOC", 3: "IDKM_ERR_DEVICE",
                 4: "IDKM_ERR_NONFINITE", 5: "IDKM_ERR_NO_FORWARD", 6: "IDKM_ERR_UNSUPPORTED"}
 DIST_L2, DIST_SQL2 = 0, 1
-BWD_IMPLICIT, BWD_JFB, BWD_DENSE = 0, 1, 2
+BWD_IMPLICIT, BWD_JFB, BWD_DENSE, BWD_GMRES = 0, 1, 2, 3
 PATH_AUTO, PATH_STREAM, PATH_PERSISTENT = 0, 1, 2
 
 EXPORTS = ["idkm_version", "idkm_limits", "idkm_status_string", "idkm_create", "idkm_destroy", "idkm_last_error",

@@ -20,6 +20,8 @@ constexpr int DIST_SQL2 = 1;
 constexpr int BWD_IMPLICIT = 0;
 constexpr int BWD_JFB = 1;
 constexpr int BWD_DENSE = 2;
+constexpr int BWD_GMRES = 3;
+constexpr int GM_RMAX = 64;  // longest Krylov basis kept before a restart
 constexpr int DENSE_MAX_KD = 16;
 
 constexpr int WG = 256;  // threads per workgroup of the streaming kernels (4 wavefronts)
@@ -34,6 +36,12 @@ struct Ctrl {
     // backward (Sec. 4.2 averaged iteration)
     int b_done, b_iters, b_converged, b_attempt, b_grow, b_halvings, b_max_iter, b_mode;
     double b_alpha, b_prev, b_vnorm, b_residual, b_tol;
+    // backward, minimal-residual solve of (I - dF/dC)^T g = v
+    int k_phase;   // what the next pass applies (dF/dC)^T to: 0 a basis vector, 1 the iterate g
+    int k_j;       // basis vectors orthogonalised in this cycle
+    int k_R;       // basis length at which a cycle ends: min(k d, GM_RMAX)
+    int k_stall;   // consecutive cycles that did not halve the residual
+    double k_beta; // residual norm at the start of the cycle
 };
 
 // Kernel argument block.
@@ -59,6 +67,7 @@ struct Args {
     double* ud;  // [k,d] last (dF/dC)^T g
     float* Hs;   // [k,d] h/tau with h_j = g_j / n_j
     double* partials;  // [gridDim.x][nacc]
+    double* kry;       // Krylov workspace of the minimal-residual solve (see gm_layout), or null
     double* stage;     // [<=256 + nacc] staging for the final reduction
     double* tot;       // [nacc] reduced totals
     // outputs
@@ -336,7 +345,25 @@ __device__ __forceinline__ void tail_b1(const Args& a) {
         v2 += v * v;
     }
     v2 = block_sum_d(v2);
+    if (c->b_mode == BWD_GMRES) {
+        // minimal-residual solve from g = 0: the first residual is v itself, the first basis vector v/||v||
+        const double inv = (v2 > 0.0 && v2 <= 1.7e308) ? 1.0 / sqrt(v2) : 0.0;
+        for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
+            const double q = a.vd[idx] * inv;
+            a.gd[idx] = 0.0;
+            a.kry[idx] = q;
+            store_h(a, idx, q);
+        }
+    }
     if (threadIdx.x == 0) {
+        c->k_phase = 0;
+        c->k_j = 0;
+        c->k_stall = 0;
+        c->k_beta = sqrt(v2);
+        if (c->b_mode == BWD_GMRES) {
+            const int R = c->k_R;
+            a.kry[(size_t)(R + 1) * kd + (size_t)R * (R + 1) + 2 * (size_t)R] = sqrt(v2);  // sv[0] = ||r_0||
+        }
         c->b_vnorm = sqrt(v2);
         c->b_iters = 0;
         c->b_attempt = 0;
@@ -346,6 +373,10 @@ __device__ __forceinline__ void tail_b1(const Args& a) {
         c->b_residual = 0.0;
         c->b_converged = (c->b_mode == BWD_JFB) ? 1 : 0;
         c->b_done = (c->b_mode == BWD_JFB) ? 1 : 0;
+        if (c->b_mode == BWD_GMRES && v2 == 0.0) {  // v = 0: g = 0 is the solution
+            c->b_converged = 1;
+            c->b_done = 1;
+        }
         if (!(v2 <= 1.7e308)) {  // non-finite cotangent: nothing to iterate on
             c->nonfinite = 1;
             c->b_done = 1;
@@ -354,12 +385,192 @@ __device__ __forceinline__ void tail_b1(const Args& a) {
     }
 }
 
+// Layout of the Krylov workspace for basis length R and n = k d unknowns (doubles):
+//   Q  [(R+1)][n]   orthonormal basis          Hm [R][(R+1)]  Hessenberg columns, rotated in place to triangular
+//   cs, sn [R]      Givens rotations           sv [R+1]       rotated right-hand side       y [R]  coefficients
+__host__ __device__ inline size_t gm_doubles(int R, int n) {
+    return (size_t)(R + 1) * n + (size_t)R * (R + 1) + 2 * (size_t)R + (size_t)(R + 1) + (size_t)R;
+}
+
+// Tail of one pass of the minimal-residual solve of (I - dF/dC*)^T g = v, the linear system whose solution the
+// averaged iteration of Sec. 4.2 converges to (Eq. "grad", "inv").  Restarted GMRES from g = 0:
+//   phase 0  tot = (dF/dC)^T q_j.  w = q_j - tot, orthogonalised twice against q_0..q_j (classical Gram-Schmidt,
+//            one wavefront per inner product), Givens update of the least-squares problem; the cycle ends when the
+//            estimated residual is below tol ||v||, after R vectors, or when w vanishes; then g += Q y.
+//   phase 1  tot = (dF/dC)^T g.  True residual r = v + tot - g; ||r|| <= tol ||v|| is the stop test (the step
+//            g+ - g of the undamped iteration IS r, so this is the same test); otherwise r/||r|| starts a new cycle.
+// Every pass counts in b_iters.  Two consecutive cycles that do not halve the residual end the solve unconverged.
+__device__ __forceinline__ void tail_gmres(const Args& a) {
+    const int n = a.k * a.d;
+    Ctrl* c = a.ctrl;
+    const int R = c->k_R;
+    double* Q = a.kry;
+    double* Hm = Q + (size_t)(R + 1) * n;
+    double* cs = Hm + (size_t)R * (R + 1);
+    double* sn = cs + R;
+    double* sv = sn + R;
+    double* y = sv + (R + 1);
+    __shared__ double s_h[GM_RMAX + 1];
+    __shared__ int s_next;  // 0 next basis vector, 1 cycle over: apply to g, 2 new cycle from the residual, 3 done
+    __shared__ double s_scale;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+
+    if (c->k_phase == 0) {
+        const int j = c->k_j;
+        const double* qj = Q + (size_t)j * n;
+        double* w = Q + (size_t)(j + 1) * n;
+        double* hcol = Hm + (size_t)j * (R + 1);
+        for (int idx = tid; idx < n; idx += blockDim.x) w[idx] = qj[idx] - a.tot[idx];
+        for (int round = 0; round < 2; ++round) {
+            __syncthreads();
+            for (int i = wave; i <= j; i += nw) {
+                const double* qi = Q + (size_t)i * n;
+                double p = 0.0;
+                for (int idx = lane; idx < n; idx += 64) p += qi[idx] * w[idx];
+                p = wave_sum_d_dpp(p);
+                if (lane == 0) {
+                    s_h[i] = p;
+                    hcol[i] = round ? hcol[i] + p : p;
+                }
+            }
+            __syncthreads();
+            for (int idx = tid; idx < n; idx += blockDim.x) {
+                double x = w[idx];
+                for (int i = 0; i <= j; ++i) x -= s_h[i] * Q[(size_t)i * n + idx];
+                w[idx] = x;
+            }
+        }
+        __syncthreads();
+        double w2 = 0.0;
+        for (int idx = tid; idx < n; idx += blockDim.x) w2 += w[idx] * w[idx];
+        w2 = block_sum_d(w2);
+        if (tid == 0) {
+            const double hn = sqrt(w2);
+            // earlier rotations on the new column, then the rotation that removes hn
+            for (int i = 0; i < j; ++i) {
+                const double t0 = cs[i] * hcol[i] + sn[i] * hcol[i + 1];
+                hcol[i + 1] = -sn[i] * hcol[i] + cs[i] * hcol[i + 1];
+                hcol[i] = t0;
+            }
+            const double hj = hcol[j];
+            const double rr = sqrt(hj * hj + hn * hn);
+            const double cj = rr > 0.0 ? hj / rr : 1.0, sj = rr > 0.0 ? hn / rr : 0.0;
+            cs[j] = cj;
+            sn[j] = sj;
+            hcol[j] = rr;
+            sv[j + 1] = -sj * sv[j];
+            sv[j] = cj * sv[j];
+            const double est = fabs(sv[j + 1]);
+            c->b_iters += 1;
+            c->b_residual = est;
+            const bool finite = (w2 <= 1.7e308) && (rr <= 1.7e308);
+            const bool vanished = !(hn > 1e-14 * rr);  // the Krylov space is exhausted: the solution lies in it
+            const bool last = (j + 1 >= R) || (c->b_iters + 1 >= c->b_max_iter);
+            int next = 0;
+            if (!finite) {
+                c->nonfinite = 1;
+                c->b_done = 1;
+                next = 3;
+            } else if (vanished || last || est <= 0.5 * c->b_tol * c->b_vnorm) {
+                // back substitution of the (j+1) x (j+1) triangular system
+                const int nj = (rr > 0.0) ? j + 1 : j;
+                for (int i = nj - 1; i >= 0; --i) {
+                    double t0 = sv[i];
+                    for (int l = i + 1; l < nj; ++l) t0 -= Hm[(size_t)l * (R + 1) + i] * y[l];
+                    y[i] = t0 / Hm[(size_t)i * (R + 1) + i];
+                }
+                c->k_j = nj;
+                next = 1;
+            } else {
+                c->k_j = j + 1;
+                s_scale = 1.0 / hn;
+            }
+            s_next = next;
+            c->ticket = 0;
+        }
+        __syncthreads();
+        if (s_next == 0) {
+            const double inv = s_scale;
+            for (int idx = tid; idx < n; idx += blockDim.x) {
+                const double q = w[idx] * inv;
+                w[idx] = q;
+                store_h(a, idx, q);
+            }
+        } else if (s_next == 1) {
+            const int nj = c->k_j;
+            for (int idx = tid; idx < n; idx += blockDim.x) {
+                double g = a.gd[idx];
+                for (int i = 0; i < nj; ++i) g += y[i] * Q[(size_t)i * n + idx];
+                a.gd[idx] = g;
+                store_h(a, idx, g);
+            }
+            if (tid == 0) c->k_phase = 1;
+        }
+        return;
+    }
+
+    // phase 1: true residual at g
+    double r2 = 0.0;
+    for (int idx = tid; idx < n; idx += blockDim.x) {
+        const double u = a.tot[idx];
+        a.ud[idx] = u;
+        const double r = a.vd[idx] + u - a.gd[idx];
+        Q[idx] = r;
+        r2 += r * r;
+    }
+    r2 = block_sum_d(r2);
+    if (tid == 0) {
+        const double beta = sqrt(r2);
+        c->b_iters += 1;
+        c->b_residual = beta;
+        int next = 2;
+        if (!(r2 <= 1.7e308)) {
+            c->nonfinite = 1;
+            c->b_done = 1;
+            next = 3;
+        } else if (beta <= c->b_tol * c->b_vnorm) {
+            c->b_converged = 1;
+            c->b_done = 1;
+            next = 3;
+        } else {
+            c->k_stall = (beta > 0.5 * c->k_beta) ? c->k_stall + 1 : 0;
+            if (c->k_stall >= 2 || c->b_iters + 2 > c->b_max_iter) {
+                c->b_done = 1;
+                next = 3;
+            }
+        }
+        if (next == 2) {
+            c->k_beta = beta;
+            c->k_phase = 0;
+            c->k_j = 0;
+            sv[0] = beta;
+            s_scale = 1.0 / beta;
+        }
+        s_next = next;
+        c->ticket = 0;
+    }
+    __syncthreads();
+    if (s_next == 2) {
+        const double inv = s_scale;
+        for (int idx = tid; idx < n; idx += blockDim.x) {
+            const double q = Q[idx] * inv;
+            Q[idx] = q;
+            store_h(a, idx, q);
+        }
+    }
+    // when done, Hs already holds h(g)/tau from the end of the cycle: the final pass uses it as it is
+}
+
 // Tail of one pass of the averaged iteration (Sec. 4.2): tot = u = (dF/dC)^T g.
 //   g+ = alpha (v + u) + (1 - alpha) g ; stop when ||g+ - g|| <= tol ||v||.
 // A non-finite step or 5 consecutive growing steps restart from g = v with alpha/2.
 __device__ __forceinline__ void tail_b2(const Args& a) {
     const int kd = a.k * a.d;
     Ctrl* c = a.ctrl;
+    if (c->b_mode == BWD_GMRES) {
+        tail_gmres(a);
+        return;
+    }
     const double alpha = c->b_alpha;
     double d2 = 0.0;
     for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {

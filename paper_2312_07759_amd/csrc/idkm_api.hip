@@ -81,6 +81,12 @@ __global__ void k_init_backward(Args a, int mode, double tol, int max_iter, doub
     c->b_vnorm = 0.0;
     c->b_residual = 0.0;
     c->b_tol = tol;
+    const int kd = a.k * a.d;
+    c->k_R = kd < GM_RMAX ? kd : GM_RMAX;
+    c->k_phase = 0;
+    c->k_j = 0;
+    c->k_stall = 0;
+    c->k_beta = 0.0;
 }
 
 // Hs = (g / n) / tau from a caller-supplied float32 cotangent; arms one raw (dF/dC)^T pass.
@@ -136,6 +142,8 @@ struct idkm_ctx {
     double *stage = nullptr, *tot = nullptr;
     double* partials = nullptr;
     size_t partials_cap = 0;  // in doubles
+    double* kry = nullptr;    // Krylov workspace of IDKM_BWD_GMRES (allocated on first use)
+    size_t kry_cap = 0;       // in doubles
     // persistent path
     int num_cu = 0;
     bool coop = false;
@@ -222,6 +230,7 @@ idkm_status plan(idkm_ctx* ctx, int64_t m, int k, int d, Geometry* g) {
 idkm_status ensure_partials(idkm_ctx* ctx, size_t need) {
     if (need <= ctx->partials_cap) return IDKM_OK;
     if (ctx->partials) {
+        (void)hipDeviceSynchronize();  // earlier launches may still read the old buffer
         (void)hipFree(ctx->partials);
         ctx->partials = nullptr;
         ctx->partials_cap = 0;
@@ -255,6 +264,7 @@ Args base_args(idkm_ctx* ctx) {
     a.ud = ctx->ud;
     a.Hs = ctx->Hs;
     a.partials = ctx->partials;
+    a.kry = ctx->kry;
     a.stage = ctx->stage;
     a.tot = ctx->tot;
     return a;
@@ -586,7 +596,7 @@ idkm_status idkm_destroy(idkm_ctx* c) {
     if (!c) return IDKM_ERR_INVALID_ARG;
     (void)hipSetDevice(c->device);
     (void)hipDeviceSynchronize();
-    void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials, c->xbuf, c->lane_xbuf, c->abort_word};
+    void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials, c->kry, c->xbuf, c->lane_xbuf, c->abort_word};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     if (c->h_ctrl) (void)hipHostFree(c->h_ctrl);
@@ -698,7 +708,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     if (st != IDKM_OK) return st;
     if (!ctx->has_forward) return fail(ctx, IDKM_ERR_NO_FORWARD, "idkm_backward needs a successful idkm_forward first");
     if (!dWq || !dW_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "dWq and dW_out must be non-NULL");
-    if (mode != IDKM_BWD_IMPLICIT && mode != IDKM_BWD_JFB && mode != IDKM_BWD_DENSE)
+    if (mode != IDKM_BWD_IMPLICIT && mode != IDKM_BWD_JFB && mode != IDKM_BWD_DENSE && mode != IDKM_BWD_GMRES)
         return fail(ctx, IDKM_ERR_INVALID_ARG, "unknown mode");
     if (!(tol >= 0.f)) return fail(ctx, IDKM_ERR_INVALID_ARG, "tol must be >= 0");
     if (max_iter < 1) return fail(ctx, IDKM_ERR_INVALID_ARG, "max_iter must be >= 1");
@@ -709,6 +719,23 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     st = ensure_partials(ctx, (size_t)g.nwg * (size_t)ctx->k * (ctx->d + 1));
     if (st != IDKM_OK) return st;
     hipStream_t s = (hipStream_t)hip_stream;
+    if (mode == IDKM_BWD_GMRES) {
+        const int kd = ctx->k * ctx->d;
+        const size_t need = gm_doubles(kd < GM_RMAX ? kd : GM_RMAX, kd);
+        if (ctx->kry_cap < need) {
+            if (ctx->kry) {
+                HIP_TRY(ctx, hipStreamSynchronize(s));
+                (void)hipFree(ctx->kry);
+                ctx->kry = nullptr;
+                ctx->kry_cap = 0;
+            }
+            if (hipMalloc((void**)&ctx->kry, need * sizeof(double)) != hipSuccess) {
+                (void)hipGetLastError();
+                return fail(ctx, IDKM_ERR_ALLOC, "hipMalloc of the Krylov workspace failed");
+            }
+            ctx->kry_cap = need;
+        }
+    }
     Args a = base_args(ctx);
     a.G = dWq;
     a.dW_out = dW_out;
@@ -750,9 +777,12 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     }
 
     PersistPlan pp;
-    const bool persistent = ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &pp);
+    // the minimal-residual solve keeps its O(k d R) state in one workgroup's tail: stream path only
+    const bool persistent = mode != IDKM_BWD_GMRES && ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &pp);
     if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
-        return fail(ctx, IDKM_ERR_UNSUPPORTED, "the persistent path needs k <= 512, d <= 4 and the tiles of W and dWq to fit in LDS");
+        return fail(ctx, IDKM_ERR_UNSUPPORTED, mode == IDKM_BWD_GMRES
+                        ? "IDKM_BWD_GMRES runs on the stream path only"
+                        : "the persistent path needs k <= 512, d <= 4 and the tiles of W and dWq to fit in LDS");
     if (persistent) {
         const uint64_t ex = 1ull + (mode == IDKM_BWD_IMPLICIT ? (uint64_t)max_iter * 7ull : 0ull);
         if (ex < 0x7fffffffull) {
@@ -775,6 +805,9 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     if (mode == IDKM_BWD_IMPLICIT) {
         // every attempt (alpha, alpha/2, ...) may use max_iter passes; at most 7 attempts
         st = run_until_done(ctx, g, PASS_B2, a, s, (int64_t)max_iter * 7, [](const Ctrl& c) { return c.b_done != 0; });
+        if (st != IDKM_OK) return st;
+    } else if (mode == IDKM_BWD_GMRES) {
+        st = run_until_done(ctx, g, PASS_B2, a, s, (int64_t)max_iter + 2, [](const Ctrl& c) { return c.b_done != 0; });
         if (st != IDKM_OK) return st;
     }
     st = launch_pass(ctx, g, PASS_B3, a, s);

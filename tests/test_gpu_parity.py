@@ -332,3 +332,52 @@ def test_error_paths(ctx):
     with pytest.raises(binding.IdkmError) as e:
         ctx.backward(W, binding.BWD_IMPLICIT, alpha=1.5)
     assert e.value.status == 1
+
+
+# ---------------------------------------------------------------- minimal-residual (Krylov) backward
+
+# (name, m, d, k, tau): k d <= 64 ends in one exact cycle; k d > 64 needs restarts.  The temperatures keep
+# cond(I - dF/dC) below ~250 (float64 probe of these seeds), so that a float32 operator can reach the tolerance;
+# in the last two cases the spectral radius of dF/dC exceeds 1 (the plain iteration diverges, the system is regular).
+GMRES_CASES = [("k4d1", 70_001, 1, 4, 0.05), ("k16d1", 33_333, 1, 16, 0.005), ("k8d2", 20_011, 2, 8, 0.1),
+               ("k3d1", 1_000, 1, 3, 0.1), ("k64d4", 4_003, 4, 64, 0.2), ("k100d2", 3_001, 2, 100, 0.01)]
+
+
+@pytest.mark.parametrize("dist", DISTS)
+@pytest.mark.parametrize("name,m,d,k,tau", GMRES_CASES, ids=[c[0] for c in GMRES_CASES])
+def test_krylov_backward_solves_the_linear_system_of_the_implicit_gradient(ctx, name, m, d, k, tau, dist):
+    """g from IDKM_BWD_GMRES against the oracle's dense solve of (I - dF/dC*)^T g = v, the definition the
+    averaged iteration converges to; dW against the oracle's backward with that g."""
+    W, C0, G = _case(m, d, k, seed=300 + [c[0] for c in GMRES_CASES].index(name))
+    Wd = dev(W)
+    out = ctx.forward(Wd, dev(C0), tau, 1e-6, 60, dist, want_Wq=False)
+    Cg = out["C"].cpu().numpy()
+    Gd = dev(G)
+    r = ctx.backward(Gd, binding.BWD_GMRES, tol=1e-6, max_iter=400)
+    ref = orc.backward(W, Cg, tau, dist, G, "dense")
+    assert r["info"].converged, r["info"]
+    assert r["info"].residual <= 1e-6 * np.linalg.norm(ref["v"]) * 1.01
+    assert rel(r["dW"].cpu().numpy(), ref["dW"]) < TOL_GRAD
+    if k * d <= 64:
+        assert r["info"].iters <= k * d + 1 + (k * d + 1)      # one exact cycle (+ at most one refinement cycle)
+    # the solution itself, read back through one raw (dF/dC)^T pass at g_ref: J^T g_ref = g_ref - v
+    u = ctx.step_JCT(dev(ref["g"].astype(np.float32))).cpu().numpy()
+    assert rel(u, ref["g"] - ref["v"]) < TOL_GRAD
+    # and the stream-path averaged iteration, where it converges, lands on the same dW
+    ctx.set_path(binding.PATH_STREAM)
+    it = ctx.backward(Gd, binding.BWD_IMPLICIT, tol=1e-7, max_iter=3000, alpha=1.0)
+    ctx.set_path(binding.PATH_AUTO)
+    if it["info"].converged:
+        assert rel(r["dW"].cpu().numpy(), it["dW"].cpu().numpy()) < TOL_GRAD
+
+
+def test_krylov_backward_on_the_persistent_path_is_refused(ctx):
+    W, C0, G = _case(5_000, 1, 4, seed=1)
+    ctx.forward(dev(W), dev(C0), 0.05, 1e-6, 30, wl.DIST_SQL2)
+    ctx.set_path(binding.PATH_PERSISTENT)
+    with pytest.raises(binding.IdkmError) as e:
+        ctx.backward(dev(G), binding.BWD_GMRES)
+    ctx.set_path(binding.PATH_AUTO)
+    assert e.value.status == 6
+    r = ctx.backward(dev(G), binding.BWD_GMRES, tol=1e-6, max_iter=1)      # pass budget: ends unconverged or exact
+    assert r["info"].iters <= 2
