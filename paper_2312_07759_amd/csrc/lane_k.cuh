@@ -21,9 +21,13 @@ struct LaneWave {
     static constexpr bool USE_H = (PASS == PASS_B2 || PASS == PASS_B3);
     static constexpr int ACCW = STATS ? (D + 1) : D;
     static constexpr int NA = (PASS == PASS_B3) ? 1 : KPL * ACCW;  // accumulators per lane
+    // passes that work in scaled coordinates t = s (w - c): the forward loop, and the (dF/dC)^T pass of the
+    // squared energy
+    static constexpr bool SCALED = (PASS == PASS_FWD) || (PASS == PASS_B2 && DIST == DIST_SQL2);
 
     float c[KPL][D], hs[KPL][D], ff[KPL][D];
-    float cs[KPL][D];  // forward loop only: codewords in scaled coordinates, padding lanes far away
+    float cs[KPL][D];  // scaled passes only: codewords in scaled coordinates, padding lanes far away
+    float hf[KPL];     // scaled (dF/dC)^T pass: sum_r hs_r F_r, so that h.(w - F) = (hs/s).t_w - hf
     bool valid[KPL];
     float acc[NA];
 
@@ -41,6 +45,15 @@ struct LaneWave {
                 cs[q][r] = valid[q] ? Cf[j * D + r] * escale : 1e18f;
                 hs[q][r] = (USE_H && valid[q]) ? Hs[j * D + r] : 0.f;
                 ff[q][r] = (USE_H && valid[q]) ? Ff[j * D + r] : 0.f;
+            }
+            hf[q] = 0.f;
+            if (PASS == PASS_B2 && DIST == DIST_SQL2) {
+                const float inv = 1.0f / escale;
+#pragma unroll
+                for (int r = 0; r < D; ++r) {
+                    hf[q] = fmaf(hs[q][r], ff[q][r], hf[q]);
+                    hs[q][r] *= inv;  // meets the scaled vector
+                }
             }
         }
 #pragma unroll
@@ -62,8 +75,8 @@ struct LaneWave {
         // forward loop: the lane's vector is moved to scaled coordinates once per batch
         float wb[D];
 #pragma unroll
-        for (int r = 0; r < D; ++r) wb[r] = (PASS == PASS_FWD) ? wv[r] * a.escale : wv[r];
-        const float inv_escale = (PASS == PASS_FWD) ? 1.0f / a.escale : 0.f;
+        for (int r = 0; r < D; ++r) wb[r] = SCALED ? wv[r] * a.escale : wv[r];
+        const float inv_escale = SCALED ? 1.0f / a.escale : 0.f;
         for (int l = 0; l < cnt; ++l) {
             float w[D], g[D], gs[D];
 #pragma unroll
@@ -125,6 +138,57 @@ struct LaneWave {
                     acc[q * ACCW] = fmaf(p[q], rS, acc[q * ACCW]);
 #pragma unroll
                     for (int r = 0; r < D; ++r) acc[q * ACCW + 1 + r] = fmaf(p[q], w[r] * rSu, acc[q * ACCW + 1 + r]);
+                }
+                continue;
+            }
+            if (PASS == PASS_B2 && DIST == DIST_SQL2) {
+                // (dF/dC)^T pass in scaled coordinates, squared energy: the row softmax as in the forward loop
+                // (unshifted unless the whole row underflows); with t = s (w - c): delta = 2 (w - c) = (2/s) t and
+                // h.(w - F) = (h/s).(s w) - h.F, so the factor 2/(s S) joins the row's scalar and nothing per
+                // codeword is rescaled.
+                float t[KPL][D], ev[KPL], p[KPL], qv[KPL];
+                float S = 0.f;
+#pragma unroll
+                for (int q = 0; q < KPL; ++q) {
+                    t[q][0] = w[0] - cs[q][0];
+                    float e2 = t[q][0] * t[q][0];
+                    float sq = fmaf(hs[q][0], w[0], -hf[q]);
+#pragma unroll
+                    for (int r = 1; r < D; ++r) {
+                        t[q][r] = w[r] - cs[q][r];
+                        e2 = fmaf(t[q][r], t[q][r], e2);
+                        sq = fmaf(hs[q][r], w[r], sq);
+                    }
+                    ev[q] = e2;
+                    qv[q] = sq;
+                    p[q] = fast_exp2(-e2);
+                    S = (q == 0) ? p[0] : S + p[q];
+                }
+                S = wave_sum(S);
+                if (S < 7.9e-31f) {  // below 2^-100: redo the row shifted by its minimum
+                    float emin = ev[0];
+#pragma unroll
+                    for (int q = 1; q < KPL; ++q) emin = fminf(emin, ev[q]);
+                    emin = wave_min_nonneg(emin);
+                    S = 0.f;
+#pragma unroll
+                    for (int q = 0; q < KPL; ++q) {
+                        p[q] = fast_exp2(emin - ev[q]);
+                        S += p[q];
+                    }
+                    S = wave_sum(S);
+                }
+                const float rS = fast_rcp(S);
+                float qb = 0.f;
+#pragma unroll
+                for (int q = 0; q < KPL; ++q) qb = fmaf(p[q], qv[q], qb);
+                qb = wave_sum(qb) * rS;
+                const float f = 2.f * rS * inv_escale;
+#pragma unroll
+                for (int q = 0; q < KPL; ++q) {
+                    const float th = (p[q] * f) * (qv[q] - qb);
+#pragma unroll
+                    for (int r = 0; r < D; ++r) acc[q * ACCW + r] = fmaf(th, t[q][r], acc[q * ACCW + r]);
                 }
                 continue;
             }

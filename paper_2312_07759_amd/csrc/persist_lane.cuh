@@ -382,7 +382,7 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
     // B1
     {
         LaneWave<KPL, D, DIST, PASS_B1> st;
-        st.init(k, s_Cf, s_Hs, s_Ff);
+        st.init(k, s_Cf, s_Hs, s_Ff, a.escale);
         lane_tile_pass<KPL, D, DIST, PASS_B1>(a, st, s_w, s_gt, base, cnt);
         ++seq;
         publish_lane<NA, D>(pa, seq, st.acc, k, s_acc);
@@ -422,7 +422,7 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
 
     while (!s_done) {
         LaneWave<KPL, D, DIST, PASS_B2> st;
-        st.init(k, s_Cf, s_Hs, s_Ff);
+        st.init(k, s_Cf, s_Hs, s_Ff, a.escale);
         lane_tile_pass<KPL, D, DIST, PASS_B2>(a, st, s_w, s_gt, base, cnt);
         ++seq;
         publish_lane<NA, D>(pa, seq, st.acc, k, s_acc);
@@ -501,7 +501,7 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
     // B3
     {
         LaneWave<KPL, D, DIST, PASS_B3> st;
-        st.init(k, s_Cf, s_Hs, s_Ff);
+        st.init(k, s_Cf, s_Hs, s_Ff, a.escale);
         lane_tile_pass<KPL, D, DIST, PASS_B3>(a, st, s_w, s_gt, base, cnt);
     }
     for (int r = wg; r < k; r += G) {
