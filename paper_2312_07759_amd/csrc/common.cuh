@@ -28,8 +28,8 @@ constexpr int WG = 256;  // threads per workgroup of the streaming kernels (4 wa
 
 // Device-resident control block of one context.
 struct Ctrl {
-    unsigned int ticket;  // workgroups that have stored their partials in the current launch
-    int abort_flag;       // a bounded device-side wait expired
+    unsigned int launch_seq;  // stamp of the last stream-path launch that published partial sums
+    int abort_flag;           // a bounded device-side wait expired
     // forward (Alg. 1)
     int done, iters, converged, empty, nonfinite, max_iter;
     double residual, tol;
@@ -56,6 +56,7 @@ struct Args {
     float tau;
     int64_t vec_per_wg;  // vectors handled by one workgroup
     Ctrl* ctrl;
+    unsigned int* tickets;  // [TICKET_WORDS] arrival counters of the stream path (see arrive_last)
     // O(k d) solver state
     double* Cd;  // [k,d] current codebook, float64 master copy
     float* Cf;   // [k,d] float32 copy used by the E-step
@@ -196,54 +197,98 @@ __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcp
 __device__ __forceinline__ float fast_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
 __device__ __forceinline__ float fast_rsq(float x) { return __builtin_amdgcn_rsqf(x); }
 
+// ---------------------------------------------------------------- stamped words
+
+// Values that cross workgroups travel as 64-bit words {sequence number, 32-bit payload} written and read with
+// relaxed device-scope atomics: a reader that finds the expected stamp has the value that belongs to it, so no
+// fence (on this part: no write-back and invalidation of a whole L2) is needed on either side.
+__device__ __forceinline__ unsigned long long ld_word(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_word(unsigned long long* p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long pack_f(unsigned int seq, float v) {
+    return ((unsigned long long)seq << 32) | (unsigned long long)__float_as_uint(v);
+}
+__device__ __forceinline__ unsigned long long pack_u(unsigned int seq, unsigned int v) {
+    return ((unsigned long long)seq << 32) | (unsigned long long)v;
+}
+
 // ---------------------------------------------------------------- grid-level tail: last workgroup reduces
 
 // Called by all threads of a workgroup after its partials are stored.  Returns
 // true in every thread of the one workgroup that arrives last.
-__device__ __forceinline__ bool arrive_last(Ctrl* ctrl) {
+// Arrival is counted in two levels: workgroup b adds to counter b mod TSHARDS, and the workgroup that completes a
+// counter adds to the top one.  A thousand workgroups adding to ONE word from eight dies are served one after the
+// other by the memory side (tens of microseconds); 32 words in separate cache lines are served side by side.
+// The counters are zero between launches: the last workgroup clears them (grid_tail).
+constexpr int TSHARDS = 32;
+constexpr int TSTRIDE = 32;  // 32-bit words between counters: one 128-byte line each
+constexpr int TICKET_WORDS = (TSHARDS + 1) * TSTRIDE;
+__device__ __forceinline__ bool arrive_last(unsigned int* tickets) {
     __shared__ int s_last;
-    __threadfence();
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned int t = atomicAdd(&ctrl->ticket, 1u);
-        s_last = (t == gridDim.x - 1) ? 1 : 0;
+        const unsigned int nwg = gridDim.x, ns = nwg < (unsigned)TSHARDS ? nwg : (unsigned)TSHARDS;
+        const unsigned int sh = blockIdx.x % ns, members = (nwg - sh + ns - 1) / ns;
+        int last = 0;
+        if (__hip_atomic_fetch_add(&tickets[sh * TSTRIDE], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == members - 1u)
+            last = (__hip_atomic_fetch_add(&tickets[TSHARDS * TSTRIDE], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == ns - 1u) ? 1 : 0;
+        s_last = last;
     }
     __syncthreads();
-    if (!s_last) return false;
-    __threadfence();
-    return true;
+    return s_last != 0;
 }
 
-// Sum partials[wg][a] over wg in a fixed order into tot[a].  Two stages: P
-// interleaved slices, then the slices in order.
-__device__ __forceinline__ void reduce_partials(const Args& a, int nacc) {
-    const int nwg = gridDim.x;
-    int P = 1;
-    if (nacc < (int)blockDim.x) P = blockDim.x / nacc;
-    if (P > nwg) P = nwg;
-    const double* __restrict__ part = a.partials;
-    for (int idx = threadIdx.x; idx < nacc * P; idx += blockDim.x) {
-        int acc = idx % nacc, p = idx / nacc;
-        // eight independent chains keep eight loads in flight; the order is still fixed
-        double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        int wg = p;
-        for (; wg + 7 * P < nwg; wg += 8 * P) {
-            double x[8];
+// Sum over all workgroups of the stamped float32 partials xp[acc][wg] (written by every workgroup of this launch
+// before it took its ticket) into tot[acc], float64, in a fixed order.  The counters say that every workgroup has
+// issued its stores; the stamps say that a word has arrived, so a word that is still on its way is simply read
+// again (bounded).  Returns false in every thread if a word never arrived.
+__device__ __forceinline__ bool reduce_stamped(const Args& a, int nacc, unsigned int seq) {
+    __shared__ double s_red[8][WG];
+    __shared__ int s_fail;
+    const int tid = threadIdx.x, nwg = gridDim.x;
+    const unsigned long long* xp = reinterpret_cast<const unsigned long long*>(a.partials);
+    if (tid == 0) s_fail = 0;
+    __syncthreads();
+    for (int acc0 = 0; acc0 < nacc; acc0 += 8) {
+        double s[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) x[u] = part[(size_t)(wg + u * P) * nacc + acc];
+        for (int u = 0; u < 8; ++u) s[u] = 0.0;
+        for (int wg = tid; wg < nwg; wg += WG) {
+            unsigned int spins = 0;
+            for (;;) {
+                unsigned long long w[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) s[u] += x[u];
+                for (int u = 0; u < 8; ++u) w[u] = (acc0 + u < nacc) ? ld_word(xp + (size_t)(acc0 + u) * nwg + wg) : pack_f(seq, 0.f);
+                bool ok = true;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) ok = ok && ((unsigned int)(w[u] >> 32) == seq);
+                if (ok) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) s[u] += (double)__uint_as_float((unsigned int)w[u]);
+                    break;
+                }
+                if (++spins > (1u << 20)) {
+                    s_fail = 1;
+                    break;
+                }
+            }
         }
-        for (; wg < nwg; wg += P) s[0] += part[(size_t)wg * nacc + acc];
-        a.stage[idx] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s_red[u][tid] = s[u];
+        __syncthreads();
+        // thread (q, part) adds 8 consecutive entries of accumulator q, then a fixed 32-lane DPP network
+        const int q = tid >> 5, part = tid & 31;
+        double t = 0.0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t += s_red[q][part * 8 + u];
+        t = half_sum_d_dpp(t);
+        if (part == 31 && acc0 + q < nacc) a.tot[acc0 + q] = t;
+        __syncthreads();
     }
-    __syncthreads();
-    for (int acc = threadIdx.x; acc < nacc; acc += blockDim.x) {
-        double s = 0.0;
-        for (int p = 0; p < P; ++p) s += a.stage[p * nacc + acc];
-        a.tot[acc] = s;
-    }
-    __syncthreads();
+    return s_fail == 0;
 }
 
 // Block-wide sum of one double per thread (fixed order); result to all threads.
@@ -296,7 +341,7 @@ __device__ __forceinline__ void tail_forward(const Args& a) {
         bool conv = res < c->tol;
         c->converged = conv ? 1 : 0;
         if (conv || bad || c->iters >= c->max_iter) c->done = 1;
-        c->ticket = 0;
+        
     }
 }
 
@@ -321,7 +366,7 @@ __device__ __forceinline__ void tail_final(const Args& a) {
     if (threadIdx.x == 0) {
         c->empty = empty;
         if (bad) c->nonfinite = 1;
-        c->ticket = 0;
+        
     }
 }
 
@@ -381,7 +426,7 @@ __device__ __forceinline__ void tail_b1(const Args& a) {
             c->nonfinite = 1;
             c->b_done = 1;
         }
-        c->ticket = 0;
+        
     }
 }
 
@@ -486,7 +531,7 @@ __device__ __forceinline__ void tail_gmres(const Args& a) {
                 s_scale = 1.0 / hn;
             }
             s_next = next;
-            c->ticket = 0;
+            
         }
         __syncthreads();
         if (s_next == 0) {
@@ -547,7 +592,7 @@ __device__ __forceinline__ void tail_gmres(const Args& a) {
             s_scale = 1.0 / beta;
         }
         s_next = next;
-        c->ticket = 0;
+        
     }
     __syncthreads();
     if (s_next == 2) {
@@ -616,7 +661,7 @@ __device__ __forceinline__ void tail_b2(const Args& a) {
             }
         }
         s_restart = restart;
-        c->ticket = 0;
+        
     }
     __syncthreads();
     const int restart = s_restart;
@@ -722,14 +767,23 @@ __device__ __forceinline__ void tail_bj(const Args& a) {
         c->b_converged = ok ? 1 : 0;
         c->b_done = 1;
         if (!ok) c->nonfinite = 1;
-        c->ticket = 0;
+        
     }
 }
 
 template <int PASS>
-__device__ __forceinline__ void grid_tail(const Args& a, int nacc) {
-    if (!arrive_last(a.ctrl)) return;
-    reduce_partials(a, nacc);
+__device__ __forceinline__ void grid_tail(const Args& a, int nacc, unsigned int seq) {
+    if (!arrive_last(a.tickets)) return;
+    if (threadIdx.x <= TSHARDS) a.tickets[threadIdx.x * TSTRIDE] = 0u;  // every workgroup has arrived
+    if (threadIdx.x == 0) a.ctrl->launch_seq = seq;
+    if (!reduce_stamped(a, nacc, seq)) {
+        if (threadIdx.x == 0) {  // ends the host's loops; the call reports a device error
+            a.ctrl->abort_flag = 1;
+            a.ctrl->done = 1;
+            a.ctrl->b_done = 1;
+        }
+        return;
+    }
     if (PASS == PASS_FWD) tail_forward(a);
     if (PASS == PASS_FIN) tail_final(a);
     if (PASS == PASS_B1) tail_b1(a);

@@ -50,7 +50,6 @@ __global__ void k_init_forward(Args a, const float* C0, double tol, int max_iter
     }
     if (threadIdx.x == 0) {
         Ctrl* c = a.ctrl;
-        c->ticket = 0;
         c->abort_flag = 0;
         c->done = 0;
         c->iters = 0;
@@ -66,7 +65,6 @@ __global__ void k_init_forward(Args a, const float* C0, double tol, int max_iter
 
 __global__ void k_init_backward(Args a, int mode, double tol, int max_iter, double alpha) {
     Ctrl* c = a.ctrl;
-    c->ticket = 0;
     c->abort_flag = 0;
     c->b_done = 0;
     c->b_iters = 0;
@@ -89,6 +87,8 @@ __global__ void k_init_backward(Args a, int mode, double tol, int max_iter, doub
     c->k_beta = 0.0;
 }
 
+__global__ void k_reset_launch_seq(Ctrl* c) { c->launch_seq = 0; }
+
 // Hs = (g / n) / tau from a caller-supplied float32 cotangent; arms one raw (dF/dC)^T pass.
 __global__ void k_set_g(Args a, const float* g) {
     const int kd = a.k * a.d;
@@ -100,7 +100,6 @@ __global__ void k_set_g(Args a, const float* g) {
     }
     if (threadIdx.x == 0) {
         Ctrl* c = a.ctrl;
-        c->ticket = 0;
         c->b_done = 0;
         c->b_iters = 0;
         c->b_attempt = 0;
@@ -137,6 +136,8 @@ struct idkm_ctx {
     // device scratch
     Ctrl* ctrl = nullptr;
     Ctrl* h_ctrl = nullptr;  // pinned host mirror
+    unsigned int* tickets = nullptr;  // arrival counters of the stream path, zero between launches
+    unsigned int stream_launches = 0; // upper bound of Ctrl::launch_seq
     double *Cd = nullptr, *nd = nullptr, *Fd = nullptr, *gd = nullptr, *vd = nullptr, *ud = nullptr;
     float *Cf = nullptr, *Ff = nullptr, *Hs = nullptr;
     double *stage = nullptr, *tot = nullptr;
@@ -237,6 +238,8 @@ idkm_status ensure_partials(idkm_ctx* ctx, size_t need) {
     }
     if (hipMalloc(&ctx->partials, need * sizeof(double)) != hipSuccess)
         return fail(ctx, IDKM_ERR_ALLOC, "hipMalloc of the partial-sum buffer failed");
+    // stamped words: sequence number 0 is never used, so a cleared buffer holds no valid word
+    HIP_TRY(ctx, hipMemset(ctx->partials, 0, need * sizeof(double)));
     ctx->partials_cap = need;
     return IDKM_OK;
 }
@@ -254,6 +257,7 @@ Args base_args(idkm_ctx* ctx) {
     a.escale = (ctx->dist == DIST_SQL2) ? (float)std::sqrt(1.4426950408889634 / (double)ctx->tau)
                                         : (float)(1.4426950408889634 / (double)ctx->tau);
     a.ctrl = ctx->ctrl;
+    a.tickets = ctx->tickets;
     a.Cd = ctx->Cd;
     a.Cf = ctx->Cf;
     a.nd = ctx->nd;
@@ -274,6 +278,14 @@ idkm_status launch_pass(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, hip
     KernelFn fn = g.small ? small_kernel(ctx->k, ctx->d, ctx->dist, pass) : lane_kernel(g.kpl, ctx->d, ctx->dist, pass);
     if (!fn) return fail(ctx, IDKM_ERR_UNSUPPORTED, "no kernel for this (k, d)");
     a.vec_per_wg = g.vec_per_wg;
+    if (++ctx->stream_launches > 0x7fff0000u) {
+        // the sequence numbers that stamp the partial sums would wrap: start over from a cleared buffer
+        hipLaunchKernelGGL(k_fill_u64, dim3(256), dim3(256), 0, s, reinterpret_cast<unsigned long long*>(ctx->partials),
+                           ctx->partials_cap, 0ull);
+        hipLaunchKernelGGL(k_reset_launch_seq, dim3(1), dim3(1), 0, s, ctx->ctrl);
+        HIP_TRY(ctx, hipGetLastError());
+        ctx->stream_launches = 1;
+    }
     hipLaunchKernelGGL(fn, dim3(g.nwg), dim3(WG), 0, s, a);
     HIP_TRY(ctx, hipGetLastError());
     if (!g.small && pass != PASS_B3) {
@@ -473,6 +485,7 @@ idkm_status finish_persistent(idkm_ctx* ctx, idkm_info* info) {
 idkm_status read_ctrl(idkm_ctx* ctx, hipStream_t s) {
     HIP_TRY(ctx, hipMemcpyAsync(ctx->h_ctrl, ctx->ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, s));
     HIP_TRY(ctx, hipStreamSynchronize(s));
+    if (ctx->h_ctrl->abort_flag) return fail(ctx, IDKM_ERR_DEVICE, "partial sums of a pass did not arrive");
     return IDKM_OK;
 }
 
@@ -554,6 +567,7 @@ idkm_status idkm_create(idkm_ctx** out, int device_id) {
     c->device = device_id;
     bool ok = true;
     ok &= hipMalloc(&c->ctrl, sizeof(Ctrl)) == hipSuccess;
+    if (ok) ok &= hipMemset(c->ctrl, 0, sizeof(Ctrl)) == hipSuccess;
     ok &= hipHostMalloc(&c->h_ctrl, sizeof(Ctrl)) == hipSuccess;
     ok &= hipMalloc(&c->Cd, MAX_KD * sizeof(double)) == hipSuccess;
     ok &= hipMalloc(&c->Fd, MAX_KD * sizeof(double)) == hipSuccess;
@@ -576,6 +590,8 @@ idkm_status idkm_create(idkm_ctx** out, int device_id) {
         int v = std::atoi(e);
         if (v >= 1 && v <= 1024) c->min_vec_per_thread = v;
     }
+    ok &= hipMalloc(&c->tickets, TICKET_WORDS * sizeof(unsigned int)) == hipSuccess;
+    if (ok) ok &= hipMemset(c->tickets, 0, TICKET_WORDS * sizeof(unsigned int)) == hipSuccess;
     ok &= hipMalloc(&c->abort_word, sizeof(unsigned int)) == hipSuccess;
     if (ok) ok &= hipMemset(c->abort_word, 0, sizeof(unsigned int)) == hipSuccess;
     ok &= hipHostMalloc(&c->h_res, sizeof(PResult)) == hipSuccess;
@@ -596,7 +612,7 @@ idkm_status idkm_destroy(idkm_ctx* c) {
     if (!c) return IDKM_ERR_INVALID_ARG;
     (void)hipSetDevice(c->device);
     (void)hipDeviceSynchronize();
-    void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials, c->kry, c->xbuf, c->lane_xbuf, c->abort_word};
+    void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials, c->kry, c->tickets, c->xbuf, c->lane_xbuf, c->abort_word};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     if (c->h_ctrl) (void)hipHostFree(c->h_ctrl);

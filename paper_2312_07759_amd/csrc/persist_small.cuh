@@ -72,18 +72,6 @@ struct BatchItem {
 #define IDKM_STAMP(slot) do { } while (0)
 #endif
 
-__device__ __forceinline__ unsigned long long ld_word(const unsigned long long* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_word(unsigned long long* p, unsigned long long v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ unsigned long long pack_f(unsigned int seq, float v) {
-    return ((unsigned long long)seq << 32) | (unsigned long long)__float_as_uint(v);
-}
-__device__ __forceinline__ unsigned long long pack_u(unsigned int seq, unsigned int v) {
-    return ((unsigned long long)seq << 32) | (unsigned long long)v;
-}
 
 // Shared scratch of the exchange.
 template <int NACC>

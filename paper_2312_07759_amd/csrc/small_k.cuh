@@ -268,6 +268,7 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
 
     if (PASS == PASS_FWD && a.ctrl->done) return;
     if (PASS == PASS_B2 && a.ctrl->b_done) return;
+    const unsigned int seq = a.ctrl->launch_seq + 1u;  // stamp of this launch's partial sums
 
     float c[K][D], hs[K][D], ff[K][D];
 #pragma unroll
@@ -316,9 +317,10 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
         double s = 0.0;
 #pragma unroll
         for (int wv = 0; wv < WG / 64; ++wv) s += s_part[wv][q];
-        a.partials[(size_t)blockIdx.x * NACC + q] = s;
+        // row = accumulator, column = workgroup: the reducing workgroup reads 64 consecutive words per load
+        st_word(reinterpret_cast<unsigned long long*>(a.partials) + (size_t)q * gridDim.x + blockIdx.x, pack_f(seq, (float)s));
     }
-    grid_tail<PASS>(a, NACC);
+    grid_tail<PASS>(a, NACC, seq);
 }
 
 }  // namespace idkm
