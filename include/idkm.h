@@ -89,6 +89,9 @@ idkm_status idkm_set_path(idkm_ctx* ctx, idkm_path path);
  * wait expires all workgroups leave the kernel and the call returns IDKM_ERR_DEVICE; the context stays usable.
  * A limit of 0 makes the first unsuccessful poll give up (used to exercise that path). */
 idkm_status idkm_set_spin_limit(idkm_ctx* ctx, uint32_t polls);
+/* Longest Krylov basis IDKM_BWD_GMRES keeps before it restarts from the current residual: 1 .. 256, default 64
+ * (the basis never exceeds k d).  The workspace holds (basis + 1) k d doubles. */
+idkm_status idkm_set_gmres_basis(idkm_ctx* ctx, int32_t basis);
 
 /*
  * Algorithm 1 (soft k-means) followed by one evaluation at the solution.
@@ -128,13 +131,13 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
  *   k d x k d in general) in the same pass that computes v and solves (I - dF/dC*)^T g = v by Gaussian
  *   elimination in float64: two passes over W in total, tol / max_iter / alpha are ignored, info.iters = 0 and
  *   info.converged = 0 only if the matrix is singular.
- *   IDKM_BWD_GMRES solves the same system from g = 0 by restarted GMRES (basis length min(k d, 64), float64
+ *   IDKM_BWD_GMRES solves the same system from g = 0 by restarted GMRES (basis length min(k d, 64) unless idkm_set_gmres_basis changed it, float64
  *   orthogonalisation): every pass applies (dF/dC*)^T to one basis vector; when the estimated residual falls
  *   below tol ||v||_F (or the basis is full) the iterate is updated and one more pass measures the true residual
  *   ||v + (dF/dC*)^T g - g||_F, which is the step norm of the undamped iteration at g and is held to the same
  *   test <= tol ||v||_F; otherwise a new cycle starts from that residual.  info.iters counts all these passes
  *   (at most max_iter + 1), info.residual is the last true residual, alpha is ignored; two cycles in a row that
- *   do not halve the residual end the solve with converged = 0.  With k d <= 64 the first cycle is exact up to
+ *   leave more than 95 % of the residual end the solve with converged = 0.  With k d <= 64 the first cycle is exact up to
  *   rounding.  Runs on the stream path (IDKM_PATH_PERSISTENT gives IDKM_ERR_UNSUPPORTED).
  *   dL/dW = (direct term through A) + (dF/dW)^T g.
  * The attention weights are recomputed on the fly in every pass; nothing of size m*k is stored.

@@ -21,7 +21,7 @@ constexpr int BWD_IMPLICIT = 0;
 constexpr int BWD_JFB = 1;
 constexpr int BWD_DENSE = 2;
 constexpr int BWD_GMRES = 3;
-constexpr int GM_RMAX = 64;  // longest Krylov basis kept before a restart
+constexpr int GM_RMAX = 256;  // longest Krylov basis the workspace layout allows
 constexpr int DENSE_MAX_KD = 16;
 
 constexpr int WG = 256;  // threads per workgroup of the streaming kernels (4 wavefronts)
@@ -444,7 +444,8 @@ __host__ __device__ inline size_t gm_doubles(int R, int n) {
 //            estimated residual is below tol ||v||, after R vectors, or when w vanishes; then g += Q y.
 //   phase 1  tot = (dF/dC)^T g.  True residual r = v + tot - g; ||r|| <= tol ||v|| is the stop test (the step
 //            g+ - g of the undamped iteration IS r, so this is the same test); otherwise r/||r|| starts a new cycle.
-// Every pass counts in b_iters.  Two consecutive cycles that do not halve the residual end the solve unconverged.
+// Every pass counts in b_iters.  Two consecutive cycles that leave more than 95 % of the residual end the solve
+// unconverged (restarted GMRES can stagnate when I - dF/dC is far from definite).
 __device__ __forceinline__ void tail_gmres(const Args& a) {
     const int n = a.k * a.d;
     Ctrl* c = a.ctrl;
@@ -578,7 +579,7 @@ __device__ __forceinline__ void tail_gmres(const Args& a) {
             c->b_done = 1;
             next = 3;
         } else {
-            c->k_stall = (beta > 0.5 * c->k_beta) ? c->k_stall + 1 : 0;
+            c->k_stall = (beta > 0.95 * c->k_beta) ? c->k_stall + 1 : 0;
             if (c->k_stall >= 2 || c->b_iters + 2 > c->b_max_iter) {
                 c->b_done = 1;
                 next = 3;

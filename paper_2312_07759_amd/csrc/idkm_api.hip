@@ -63,7 +63,7 @@ __global__ void k_init_forward(Args a, const float* C0, double tol, int max_iter
     }
 }
 
-__global__ void k_init_backward(Args a, int mode, double tol, int max_iter, double alpha) {
+__global__ void k_init_backward(Args a, int mode, double tol, int max_iter, double alpha, int basis) {
     Ctrl* c = a.ctrl;
     c->abort_flag = 0;
     c->b_done = 0;
@@ -80,7 +80,7 @@ __global__ void k_init_backward(Args a, int mode, double tol, int max_iter, doub
     c->b_residual = 0.0;
     c->b_tol = tol;
     const int kd = a.k * a.d;
-    c->k_R = kd < GM_RMAX ? kd : GM_RMAX;
+    c->k_R = kd < basis ? kd : basis;
     c->k_phase = 0;
     c->k_j = 0;
     c->k_stall = 0;
@@ -138,6 +138,7 @@ struct idkm_ctx {
     Ctrl* h_ctrl = nullptr;  // pinned host mirror
     unsigned int* tickets = nullptr;  // arrival counters of the stream path, zero between launches
     unsigned int stream_launches = 0; // upper bound of Ctrl::launch_seq
+    int gmres_basis = 64;             // basis length of IDKM_BWD_GMRES before a restart (idkm_set_gmres_basis, <= GM_RMAX)
     double *Cd = nullptr, *nd = nullptr, *Fd = nullptr, *gd = nullptr, *vd = nullptr, *ud = nullptr;
     float *Cf = nullptr, *Ff = nullptr, *Hs = nullptr;
     double *stage = nullptr, *tot = nullptr;
@@ -631,6 +632,13 @@ idkm_status idkm_set_path(idkm_ctx* ctx, idkm_path path) {
     return IDKM_OK;
 }
 
+idkm_status idkm_set_gmres_basis(idkm_ctx* ctx, int32_t basis) {
+    if (!ctx) return IDKM_ERR_INVALID_ARG;
+    if (basis < 1 || basis > GM_RMAX) return fail(ctx, IDKM_ERR_INVALID_ARG, "basis must be in [1, 256]");
+    ctx->gmres_basis = basis;
+    return IDKM_OK;
+}
+
 idkm_status idkm_set_spin_limit(idkm_ctx* ctx, uint32_t polls) {
     if (!ctx) return IDKM_ERR_INVALID_ARG;
     ctx->spin_limit = polls;
@@ -737,7 +745,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     hipStream_t s = (hipStream_t)hip_stream;
     if (mode == IDKM_BWD_GMRES) {
         const int kd = ctx->k * ctx->d;
-        const size_t need = gm_doubles(kd < GM_RMAX ? kd : GM_RMAX, kd);
+        const size_t need = gm_doubles(kd < ctx->gmres_basis ? kd : ctx->gmres_basis, kd);
         if (ctx->kry_cap < need) {
             if (ctx->kry) {
                 HIP_TRY(ctx, hipStreamSynchronize(s));
@@ -771,7 +779,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
         st = ensure_partials(ctx, (size_t)gj.nwg * nacc);
         if (st != IDKM_OK) return st;
         a.partials = ctx->partials;
-        hipLaunchKernelGGL(k_init_backward, dim3(1), dim3(1), 0, s, a, (int)mode, 0.0, 1, 1.0);
+        hipLaunchKernelGGL(k_init_backward, dim3(1), dim3(1), 0, s, a, (int)mode, 0.0, 1, 1.0, 1);
         HIP_TRY(ctx, hipGetLastError());
         st = launch_pass(ctx, gj, PASS_BJ, a, s);
         if (st != IDKM_OK) return st;
@@ -814,7 +822,8 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
             return ctx->defer_wait ? IDKM_OK : finish_persistent(ctx, info);
         }
     }
-    hipLaunchKernelGGL(k_init_backward, dim3(1), dim3(1), 0, s, a, (int)mode, (double)tol, (int)max_iter, (double)alpha);
+    hipLaunchKernelGGL(k_init_backward, dim3(1), dim3(1), 0, s, a, (int)mode, (double)tol, (int)max_iter, (double)alpha,
+                       ctx->gmres_basis);
     HIP_TRY(ctx, hipGetLastError());
     st = launch_pass(ctx, g, PASS_B1, a, s);
     if (st != IDKM_OK) return st;

@@ -381,3 +381,25 @@ def test_krylov_backward_on_the_persistent_path_is_refused(ctx):
     assert e.value.status == 6
     r = ctx.backward(dev(G), binding.BWD_GMRES, tol=1e-6, max_iter=1)      # pass budget: ends unconverged or exact
     assert r["info"].iters <= 2
+
+
+@pytest.mark.parametrize("dist", DISTS)
+def test_krylov_backward_with_a_short_basis_restarts_and_still_converges(ctx, dist):
+    name, m, d, k, tau = GMRES_CASES[2]      # k d = 16
+    W, C0, G = _case(m, d, k, seed=302)
+    out = ctx.forward(dev(W), dev(C0), tau, 1e-6, 60, dist, want_Wq=False)
+    Cg = out["C"].cpu().numpy()
+    ref = orc.backward(W, Cg, tau, dist, G, "dense")
+    full = ctx.backward(dev(G), binding.BWD_GMRES, tol=1e-6, max_iter=400)
+    ctx.set_gmres_basis(5)
+    try:
+        short = ctx.backward(dev(G), binding.BWD_GMRES, tol=1e-6, max_iter=400)
+    finally:
+        ctx.set_gmres_basis(64)
+    assert short["info"].converged and full["info"].converged
+    assert short["info"].iters > full["info"].iters            # several cycles of 5 + 1 passes
+    assert rel(short["dW"].cpu().numpy(), ref["dW"]) < TOL_GRAD
+    with pytest.raises(binding.IdkmError):
+        ctx.set_gmres_basis(0)
+    with pytest.raises(binding.IdkmError):
+        ctx.set_gmres_basis(257)
