@@ -107,6 +107,23 @@ __device__ __forceinline__ float wave_sum(float x) {
     x += dpp_f<0x143, 0xc>(0.f, x);  // row_bcast31 into rows 2,3
     return bcast_lane63(x);
 }
+// The same network on N independent values, one step of all values at a time: the N chains overlap instead of
+// running one after the other (a DPP add waits ~20 cycles for its predecessor).  Totals end in lane 63 only.
+template <int N>
+__device__ __forceinline__ void wave_sum_multi_lane63(float (&x)[N]) {
+#pragma unroll
+    for (int q = 0; q < N; ++q) x[q] += dpp_f<0xB1, 0xf>(0.f, x[q]);
+#pragma unroll
+    for (int q = 0; q < N; ++q) x[q] += dpp_f<0x4E, 0xf>(0.f, x[q]);
+#pragma unroll
+    for (int q = 0; q < N; ++q) x[q] += dpp_f<0x141, 0xf>(0.f, x[q]);
+#pragma unroll
+    for (int q = 0; q < N; ++q) x[q] += dpp_f<0x140, 0xf>(0.f, x[q]);
+#pragma unroll
+    for (int q = 0; q < N; ++q) x[q] += dpp_f<0x142, 0xa>(0.f, x[q]);
+#pragma unroll
+    for (int q = 0; q < N; ++q) x[q] += dpp_f<0x143, 0xc>(0.f, x[q]);
+}
 __device__ __forceinline__ float wave_max(float x) {
     const float ninf = -__builtin_inff();
     x = fmaxf(x, dpp_f<0xB1, 0xf>(ninf, x));

@@ -51,7 +51,7 @@ struct PArgs {
     PResult* out;              // pinned host memory
     int wg, G;                 // this workgroup's index within its team and the team's size; filled in by the kernel
 #ifdef IDKM_TRACE
-    long long* trace;          // [2 workgroups][64 passes][8 stamps] of the shader clock (development builds only)
+    long long* trace;          // [2 workgroups][64 passes][8 stamps], then [256 workgroups][8 stamps] of pass 20 (development builds only)
 #endif
 };
 
@@ -65,11 +65,19 @@ struct BatchItem {
 #ifdef IDKM_TRACE
 #define IDKM_STAMP(slot)                                                                                  \
     do {                                                                                                  \
-        if (pa.trace && threadIdx.x == 0 && s_iters < 64 && (pa.wg == 0 || pa.wg == pa.G - 1)) \
-            pa.trace[((pa.wg == 0 ? 0 : 1) * 64 + s_iters) * 8 + (slot)] = (long long)clock64();      \
+        if (pa.trace && threadIdx.x == 0 && s_iters < 64 && (pa.wg == 0 || pa.wg == pa.G - 1))             \
+            pa.trace[((pa.wg == 0 ? 0 : 1) * 64 + s_iters) * 8 + (slot)] = (long long)clock64();           \
+        if (pa.trace && threadIdx.x == 0 && s_iters == 20 && pa.wg < 256)                                  \
+            pa.trace[2 * 64 * 8 + pa.wg * 8 + (slot)] = (long long)wall_clock64();                              \
+    } while (0)
+#define IDKM_SUB(slot)                                                                       \
+    do {                                                                                     \
+        if (pa.trace && threadIdx.x == 0 && pa.wg == 0)                                      \
+            pa.trace[2 * 64 * 8 + 256 * 8 + (slot)] = (long long)clock64();                  \
     } while (0)
 #else
 #define IDKM_STAMP(slot) do { } while (0)
+#define IDKM_SUB(slot) do { } while (0)
 #endif
 
 
@@ -88,18 +96,46 @@ template <int NACC>
 __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int seq, const float (&acc)[NACC],
                                                  XShared<NACC>& xs) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    IDKM_SUB(0);
+    float v[NACC];
 #pragma unroll
-    for (int q = 0; q < NACC; ++q) {
-        const float v = wave_sum(acc[q]);
-        if (lane == 0) xs.wpart[wave * NACC + q] = (double)v;
+    for (int q = 0; q < NACC; ++q) v[q] = acc[q];
+    wave_sum_multi_lane63<NACC>(v);
+    if (lane == 63) {
+#pragma unroll
+        for (int q = 0; q < NACC; ++q) xs.wpart[wave * NACC + q] = (double)v[q];
     }
+    IDKM_SUB(1);
     __syncthreads();
+    IDKM_SUB(2);
     if (tid < NACC) {
         double s = 0.0;
 #pragma unroll
         for (int w = 0; w < PT / 64; ++w) s += xs.wpart[w * NACC + tid];
         // row = accumulator, column = workgroup: a reducer's wavefront then reads 64 consecutive words per load
         st_word(&pa.buf1[((size_t)(seq & 1u) * XLINE + tid) * PT + pa.wg], pack_f(seq, (float)s));
+    }
+    IDKM_SUB(3);
+}
+
+// Bounded wait for NW stamped words (src, src + stride, ...) of this thread.  Returns false if the wait was
+// abandoned.  (Keeping several polls in flight does not shorten the wait: it is the store's way to the other
+// dies that takes the time, not the phase of the poll.)
+template <int NW>
+__device__ __forceinline__ bool poll_words(const PArgs& pa, const unsigned long long* src, size_t stride,
+                                           unsigned int seq, unsigned long long (&out)[NW]) {
+    unsigned int spins = 0;
+    for (;;) {
+#pragma unroll
+        for (int q = 0; q < NW; ++q) out[q] = ld_word(src + q * stride);
+        bool ok = true;
+#pragma unroll
+        for (int q = 0; q < NW; ++q) ok = ok && ((unsigned int)(out[q] >> 32) == seq);
+        if (ok) return true;
+        ++spins;
+        if (spins > pa.spin_limit ||
+            ((spins & 31u) == 0u && __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u))
+            return false;
     }
 }
 
@@ -110,6 +146,7 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
                                              XShared<NACC>& xs) {
     static_assert(WPR <= 8, "a reducer handles at most 8 words per workgroup");
     const int tid = threadIdx.x;
+    IDKM_SUB(4);
     const int G = pa.G;
     float f[WPR];
 #pragma unroll
@@ -117,27 +154,15 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
     bool aborted = false;
     if (tid < G) {
         const unsigned long long* src = pa.buf1 + ((size_t)(seq & 1u) * XLINE + first) * PT + tid;
-        unsigned int spins = 0;
-        for (;;) {
-            unsigned long long w[WPR];
+        unsigned long long w[WPR];
+        if (poll_words<WPR>(pa, src, PT, seq, w)) {
 #pragma unroll
-            for (int q = 0; q < WPR; ++q) w[q] = ld_word(src + (size_t)q * PT);
-            bool ok = true;
-#pragma unroll
-            for (int q = 0; q < WPR; ++q) ok = ok && ((unsigned int)(w[q] >> 32) == seq);
-            if (ok) {
-#pragma unroll
-                for (int q = 0; q < WPR; ++q) f[q] = __uint_as_float((unsigned int)w[q]);
-                break;
-            }
-            ++spins;
-            if (spins > pa.spin_limit ||
-                ((spins & 31u) == 0u && __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u)) {
-                aborted = true;
-                break;
-            }
+            for (int q = 0; q < WPR; ++q) f[q] = __uint_as_float((unsigned int)w[q]);
+        } else {
+            aborted = true;
         }
     }
+    IDKM_SUB(5);
 #pragma unroll
     for (int q = 0; q < WPR; ++q) xs.red[q][tid] = f[q];
     if (aborted) {
@@ -149,6 +174,7 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
     if (pa.trace && threadIdx.x == 0 && pa.wg == 0) pa.trace[2 * 64 * 8 - 1] = (long long)clock64();
 #endif
     if (xs.abort) return false;
+    IDKM_SUB(6);
     // thread (q, part) adds workgroups part*8 .. part*8+7 of word q, then a fixed 32-lane DPP network
     const int q = tid >> 5, part = tid & 31;
     double s = 0.0;
@@ -159,6 +185,7 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
     s = half_sum_d_dpp(s);
     if (q < WPR && part == 31) xs.tot[q] = s;
     __syncthreads();
+    IDKM_SUB(7);
     return true;
 }
 
@@ -170,20 +197,11 @@ __device__ __forceinline__ bool gather_bcast(const PArgs& pa, unsigned int seq, 
     bool aborted = false;
     if (tid < nwords) {
         const unsigned long long* src = pa.buf2 + (size_t)(seq & 1u) * XBCAST + tid;
-        unsigned int spins = 0;
-        for (;;) {
-            const unsigned long long w = ld_word(src);
-            if ((unsigned int)(w >> 32) == seq) {
-                xs.bc[tid] = (unsigned int)w;
-                break;
-            }
-            ++spins;
-            if (spins > pa.spin_limit ||
-                ((spins & 31u) == 0u && __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u)) {
-                aborted = true;
-                break;
-            }
-        }
+        unsigned long long w[1];
+        if (poll_words<1>(pa, src, 0, seq, w))
+            xs.bc[tid] = (unsigned int)w[0];
+        else
+            aborted = true;
     }
     if (aborted) {
         xs.abort = 1;
@@ -297,6 +315,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
                 s_Cd[idx] = cnew;
                 st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + idx], pack_f(seq, (float)cnew));
             }
+            IDKM_SUB(8);
         }
         IDKM_STAMP(4);
         // hop 2 and the stop test, all inside wavefront 0: lane q waits for codeword component q, the squared
@@ -307,29 +326,27 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
             bool aborted = false;
             if (tid < KD) {
                 const unsigned long long* src = pa.buf2 + (size_t)(seq & 1u) * XBCAST + tid;
-                unsigned int spins = 0;
-                for (;;) {
-                    const unsigned long long w = ld_word(src);
-                    if ((unsigned int)(w >> 32) == seq) {
-                        const float cn = __uint_as_float((unsigned int)w);
-                        const double df = (double)cn - (double)s_Cf[tid];
-                        df2 = df * df;
-                        s_Cf[tid] = cn;
-                        break;
-                    }
-                    ++spins;
-                    if (spins > pa.spin_limit ||
-                        ((spins & 31u) == 0u &&
-                         __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u)) {
-                        aborted = true;
-                        break;
-                    }
-                }
+                unsigned long long w[1];
+                float cn = 0.f;
+                // a slice this workgroup reduced itself is taken from its own copy (the same float32 value it
+                // has just broadcast): the reducer, which every other workgroup waits for, does not wait for the
+                // round trip of its own store
+                const bool own = ((tid / (KPR * D)) % pa.G) == wg;
+                if (own)
+                    cn = (float)s_Cd[tid];
+                else if (poll_words<1>(pa, src, 0, seq, w))
+                    cn = __uint_as_float((unsigned int)w[0]);
+                else
+                    aborted = true;
+                const double df = (double)cn - (double)s_Cf[tid];
+                df2 = df * df;
+                s_Cf[tid] = cn;
             }
             if (aborted) {
                 xs.abort = 1;
                 __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
+            IDKM_SUB(9);
             const double r2 = wave_sum_d_dpp(df2);
             if (tid == 0) {
                 s_iters += 1;
@@ -342,6 +359,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
             }
         }
         __syncthreads();
+        IDKM_SUB(10);
         if (xs.abort) return;
         IDKM_STAMP(5);
     }
