@@ -52,6 +52,11 @@ CONFIGS = {
                  3003, "normal", note="3x3x512x512 conv, 2 bits per weight"),
     "C4": Config("C4", 589_824, 4, 256, _STD_C3, 1003, "rows", 1004, 2e-4, 1e-6, 200,
                  3004, "normal", note="3x3x512x512 conv as 4-vectors, 8 bits per vector"),
+    # beyond the paper's networks: a layer whose weights do not fit the chip's LDS (64 MiB), so every pass streams
+    # W from memory; temperature tied to C3's as in the sweep (squared energy)
+    "XL": Config("XL", 16_777_216, 1, 4, math.sqrt(2.0 / 4096.0), 1005, "quantile", 0,
+                 5e-5 * (2.0 / 4096.0) / (2.0 / 4608.0), 1e-7, 200, 3005, "normal",
+                 note="4096x4096 linear layer, 2 bits per weight"),
 }
 
 # ResNet18 tensors for the whole-network sweep: (number of weights, fan_in).
