@@ -107,22 +107,71 @@ __device__ __forceinline__ float wave_sum(float x) {
     x += dpp_f<0x143, 0xc>(0.f, x);  // row_bcast31 into rows 2,3
     return bcast_lane63(x);
 }
-// The same network on N independent values, one step of all values at a time: the N chains overlap instead of
-// running one after the other (a DPP add waits ~20 cycles for its predecessor).  Totals end in lane 63 only.
+// Sums of N per-lane values (N a power of two) over the 16 lanes of every DPP row, with the number of live values
+// halved at each of the four exchange steps (lane bit s decides which half a lane keeps and which it hands to its
+// partner), so the whole reduction costs about 2 N exchange-adds instead of 4 N, and the chains of different values
+// run side by side.  On return a lane holds row totals in x[0 .. row_sum_live(N)): value i of row lane l is the
+// total of accumulator row_sum_index<N>(l, i); lanes for which row_sum_owner<N>(l) is false hold duplicates.
+// The order of additions is fixed.
+__host__ __device__ constexpr int row_sum_live(int n) { return n >= 16 ? n / 16 : 1; }
 template <int N>
-__device__ __forceinline__ void wave_sum_multi_lane63(float (&x)[N]) {
+__device__ __forceinline__ int row_sum_index(int l, int i) {
+    int idx = i, half = N / 2;
 #pragma unroll
-    for (int q = 0; q < N; ++q) x[q] += dpp_f<0xB1, 0xf>(0.f, x[q]);
+    for (int s = 0; s < 4; ++s) {
+        if (half >= 1) idx += ((l >> s) & 1) * half;
+        half /= 2;
+    }
+    return idx;
+}
+template <int N>
+__device__ __forceinline__ bool row_sum_owner(int l) {
+    // steps that no longer halve (one value left) are plain butterflies: both partners end with the same total
+    bool own = true;
+    int half = N / 2;
 #pragma unroll
-    for (int q = 0; q < N; ++q) x[q] += dpp_f<0x4E, 0xf>(0.f, x[q]);
+    for (int s = 0; s < 4; ++s) {
+        if (half < 1) own = own && (((l >> s) & 1) == 0);
+        half /= 2;
+    }
+    return own;
+}
+template <int S>
+__device__ __forceinline__ float row_xchg(float x) {
+    // value of the lane whose index differs in bit S (within a row of 16 lanes)
+    if (S == 0) return dpp_f<0xB1, 0xf>(0.f, x);                              // quad_perm [1,0,3,2]
+    if (S == 1) return dpp_f<0x4E, 0xf>(0.f, x);                              // quad_perm [2,3,0,1]
+    if (S == 2) return dpp_f<0x1B, 0xf>(0.f, dpp_f<0x141, 0xf>(0.f, x));      // 7-i, then i^3: together i^4
+    return dpp_f<0x128, 0xf>(0.f, x);                                         // row_ror:8 = i^8
+}
+template <int N, int S, int CUR>
+__device__ __forceinline__ void row_sum_step(float (&x)[N], int l) {
+    if constexpr (CUR >= 2) {
+        constexpr int HALF = CUR / 2;
+        const bool up = ((l >> S) & 1) != 0;
 #pragma unroll
-    for (int q = 0; q < N; ++q) x[q] += dpp_f<0x141, 0xf>(0.f, x[q]);
-#pragma unroll
-    for (int q = 0; q < N; ++q) x[q] += dpp_f<0x140, 0xf>(0.f, x[q]);
-#pragma unroll
-    for (int q = 0; q < N; ++q) x[q] += dpp_f<0x142, 0xa>(0.f, x[q]);
-#pragma unroll
-    for (int q = 0; q < N; ++q) x[q] += dpp_f<0x143, 0xc>(0.f, x[q]);
+        for (int i = 0; i < HALF; ++i) {
+            const float keep = up ? x[i + HALF] : x[i];
+            const float send = up ? x[i] : x[i + HALF];
+            x[i] = keep + row_xchg<S>(send);
+        }
+    } else {
+        x[0] += row_xchg<S>(x[0]);
+    }
+}
+template <int N>
+__device__ __forceinline__ void row_sums(float (&x)[N], int lane) {
+    static_assert(N >= 2 && (N & (N - 1)) == 0, "N must be a power of two");
+    const int l = lane & 15;
+    row_sum_step<N, 0, N>(x, l);
+    row_sum_step<N, 1, (N >= 2 ? N / 2 : 1)>(x, l);
+    row_sum_step<N, 2, (N >= 4 ? N / 4 : 1)>(x, l);
+    row_sum_step<N, 3, (N >= 8 ? N / 8 : 1)>(x, l);
+}
+constexpr int pow2_at_least(int n) {
+    int p = 2;
+    while (p < n) p *= 2;
+    return p;
 }
 __device__ __forceinline__ float wave_max(float x) {
     const float ninf = -__builtin_inff();

@@ -84,7 +84,7 @@ struct BatchItem {
 // Shared scratch of the exchange.
 template <int NACC>
 struct XShared {
-    double wpart[(PT / 64) * NACC];  // per-wavefront partial sums
+    float rpart[pow2_at_least(NACC)][PT / 16];  // partial sums of every row of 16 lanes, [accumulator][row]
     float red[8][PT];                // reducer: words of every workgroup, transposed
     double tot[8];                   // reducer: totals of its slice
     unsigned int bc[XBCAST];         // payloads of the broadcast words
@@ -97,21 +97,26 @@ __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int s
                                                  XShared<NACC>& xs) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     IDKM_SUB(0);
-    float v[NACC];
+    constexpr int NP = pow2_at_least(NACC);
+    float v[NP];
 #pragma unroll
-    for (int q = 0; q < NACC; ++q) v[q] = acc[q];
-    wave_sum_multi_lane63<NACC>(v);
-    if (lane == 63) {
+    for (int q = 0; q < NP; ++q) v[q] = (q < NACC) ? acc[q] : 0.f;
+    row_sums<NP>(v, lane);
+    if (row_sum_owner<NP>(lane & 15)) {
 #pragma unroll
-        for (int q = 0; q < NACC; ++q) xs.wpart[wave * NACC + q] = (double)v[q];
+        for (int i = 0; i < row_sum_live(NP); ++i) xs.rpart[row_sum_index<NP>(lane & 15, i)][tid >> 4] = v[i];
     }
     IDKM_SUB(1);
     __syncthreads();
     IDKM_SUB(2);
     if (tid < NACC) {
-        double s = 0.0;
+        // the 16 rows in float64, four chains of four and then the chains: a fixed order with a short dependency
+        double c4[4];
 #pragma unroll
-        for (int w = 0; w < PT / 64; ++w) s += xs.wpart[w * NACC + tid];
+        for (int u = 0; u < 4; ++u)
+            c4[u] = ((double)xs.rpart[tid][4 * u] + (double)xs.rpart[tid][4 * u + 1]) +
+                    ((double)xs.rpart[tid][4 * u + 2] + (double)xs.rpart[tid][4 * u + 3]);
+        const double s = (c4[0] + c4[1]) + (c4[2] + c4[3]);
         // row = accumulator, column = workgroup: a reducer's wavefront then reads 64 consecutive words per load
         st_word(&pa.buf1[((size_t)(seq & 1u) * XLINE + tid) * PT + pa.wg], pack_f(seq, (float)s));
     }
@@ -189,13 +194,16 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
     return true;
 }
 
-// hop 2, receiver side: waits for words [0, nwords) of buf2 and leaves their payloads in xs.bc.
-template <int NACC>
+// hop 2, receiver side: waits for words [0, nwords) of buf2 and leaves their payloads in xs.bc.  Words
+// [0, KD) belong to slices of WPR words, word KD + r to reducer r; a reducer has put the words of its own slices
+// into xs.bc already and does not wait for the round trip of its own stores.
+template <int NACC, int WPR, int KD>
 __device__ __forceinline__ bool gather_bcast(const PArgs& pa, unsigned int seq, int nwords,
                                              XShared<NACC>& xs) {
     const int tid = threadIdx.x;
     bool aborted = false;
-    if (tid < nwords) {
+    const int slice = (tid < KD) ? tid / WPR : tid - KD;
+    if (tid < nwords && (slice % pa.G) != pa.wg) {
         const unsigned long long* src = pa.buf2 + (size_t)(seq & 1u) * XBCAST + tid;
         unsigned long long w[1];
         if (poll_words<1>(pa, src, 0, seq, w))
@@ -259,7 +267,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     constexpr int R = K / KPR;                 // reducers
     constexpr int WPR = KPR * ACCW;            // words a reducer reads per workgroup
     constexpr int NB = KD;                     // broadcast words: the new codebook
-    static_assert(NACC <= XLINE && NB <= XBCAST && KD <= 64, "shape does not fit the exchange layout");
+    static_assert(NACC <= XLINE && NB <= XBCAST && KD <= 64 && PT / 16 == 16, "shape does not fit the exchange layout");
     extern __shared__ float s_tile[];
     __shared__ XShared<NACC> xs;
     __shared__ double s_Cd[KD];  // float64 master copy (a reducer's own slice is the live one)
@@ -481,12 +489,16 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                 v2 = v * v;
                 const float h = (float)(v * s_rn[idx / D]);
                 st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + idx], pack_f(seq, h));
+                xs.bc[idx] = __float_as_uint(h);
             }
             v2 = wave_sum_d_dpp(v2);
-            if (tid == 0) st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + KD + r], pack_f(seq, (float)v2));
+            if (tid == 0) {
+                st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + KD + r], pack_f(seq, (float)v2));
+                xs.bc[KD + r] = __float_as_uint((float)v2);
+            }
         }
     }
-    if (!gather_bcast<KD>(pa, seq, NB, xs)) return;
+    if (!gather_bcast<KD, WPR, KD>(pa, seq, NB, xs)) return;
     if (tid < KD) {
         s_Hs[tid] = __uint_as_float(xs.bc[tid]);
         s_Hv[tid] = s_Hs[tid];
@@ -520,12 +532,16 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                     s_g[idx] = gn;
                     const float h = (float)(gn * s_rn[idx / D]);
                     st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + idx], pack_f(seq, h));
+                    xs.bc[idx] = __float_as_uint(h);
                 }
                 d2 = wave_sum_d_dpp(d2);
-                if (tid == 0) st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + KD + r], pack_f(seq, (float)d2));
+                if (tid == 0) {
+                    st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + KD + r], pack_f(seq, (float)d2));
+                    xs.bc[KD + r] = __float_as_uint((float)d2);
+                }
             }
         }
-        if (!gather_bcast<KD>(pa, seq, NB, xs)) return;
+        if (!gather_bcast<KD, WPR, KD>(pa, seq, NB, xs)) return;
         if (tid == 0) {
             // the same decision in every workgroup (same words, same order)
             double d2 = 0.0;

@@ -303,28 +303,25 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
 
     if (PASS == PASS_B3) return;
 
-    // workgroup partial, fixed order: lanes (float32 DPP network, 16 accumulators' chains side by side), then
-    // wavefronts 0..3 in float64
-    __shared__ float s_part[WG / 64][NACC];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // workgroup partial, fixed order: the 16 lanes of a row (float32, 16 accumulators at a time), then the 16 rows
+    // of the workgroup in float64
+    __shared__ float s_part[WG / 16][NACC];
+    const int lane = threadIdx.x & 63;
     constexpr int CH = 16;
 #pragma unroll
     for (int q0 = 0; q0 < NACC; q0 += CH) {
         float v[CH];
 #pragma unroll
         for (int u = 0; u < CH; ++u) v[u] = (q0 + u < NACC) ? acc[q0 + u] : 0.f;
-        wave_sum_multi_lane63<CH>(v);
-        if (lane == 63) {
-#pragma unroll
-            for (int u = 0; u < CH; ++u)
-                if (q0 + u < NACC) s_part[wave][q0 + u] = v[u];
-        }
+        row_sums<CH>(v, lane);
+        const int q = q0 + row_sum_index<CH>(lane & 15, 0);
+        if (q < NACC) s_part[threadIdx.x >> 4][q] = v[0];
     }
     __syncthreads();
     for (int q = threadIdx.x; q < NACC; q += WG) {
         double s = 0.0;
 #pragma unroll
-        for (int wv = 0; wv < WG / 64; ++wv) s += (double)s_part[wv][q];
+        for (int r = 0; r < WG / 16; ++r) s += (double)s_part[r][q];
         // row = accumulator, column = workgroup: the reducing workgroup reads 64 consecutive words per load
         st_word(reinterpret_cast<unsigned long long*>(a.partials) + (size_t)q * gridDim.x + blockIdx.x, pack_f(seq, (float)s));
     }
