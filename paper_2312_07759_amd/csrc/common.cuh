@@ -249,6 +249,16 @@ __device__ __forceinline__ double wave_sum_d_dpp(double x) {
     const int hi = __builtin_amdgcn_readlane(__double2hiint(x), 63);
     return __hiloint2double(hi, lo);
 }
+// Sum of lanes 0 .. N-1 (the other lanes must hold zero), valid in lane 0: only as many butterfly steps as N needs.
+template <int N>
+__device__ __forceinline__ double first_lanes_sum_d_dpp(double x) {
+    if (N > 16) return wave_sum_d_dpp(x);
+    if (N > 1) x += dpp_d<0xB1, 0xf>(x);
+    if (N > 2) x += dpp_d<0x4E, 0xf>(x);
+    if (N > 4) x += dpp_d<0x141, 0xf>(x);
+    if (N > 8) x += dpp_d<0x140, 0xf>(x);
+    return x;
+}
 // s / n for n > 0 without the IEEE division sequence: float32 reciprocal refined by two Newton steps in float64
 // (the error of the reciprocal squares with each step), then one multiply.
 __device__ __forceinline__ double fast_div_d(double s, double n) {

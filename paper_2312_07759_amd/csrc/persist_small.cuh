@@ -355,7 +355,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
                 __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             IDKM_SUB(9);
-            const double r2 = wave_sum_d_dpp(df2);
+            const double r2 = first_lanes_sum_d_dpp<KD>(df2);  // lanes >= KD hold zero; lane 0 decides
             if (tid == 0) {
                 s_iters += 1;
                 s_res = r2;  // squared; the root is taken once, when the solve is over
@@ -491,7 +491,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                 st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + idx], pack_f(seq, h));
                 xs.bc[idx] = __float_as_uint(h);
             }
-            v2 = wave_sum_d_dpp(v2);
+            v2 = first_lanes_sum_d_dpp<WPR>(v2);
             if (tid == 0) {
                 st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + KD + r], pack_f(seq, (float)v2));
                 xs.bc[KD + r] = __float_as_uint((float)v2);
@@ -534,7 +534,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                     st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + idx], pack_f(seq, h));
                     xs.bc[idx] = __float_as_uint(h);
                 }
-                d2 = wave_sum_d_dpp(d2);
+                d2 = first_lanes_sum_d_dpp<WPR>(d2);
                 if (tid == 0) {
                     st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + KD + r], pack_f(seq, (float)d2));
                     xs.bc[KD + r] = __float_as_uint((float)d2);
