@@ -361,6 +361,9 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
     pp->lane = false;
     const int64_t chunk = (int64_t)ctx->min_vec_per_thread * PT;
     int64_t g = (m + chunk - 1) / chunk;  // a few vectors per thread before adding workgroups
+    // up to 16 vectors per thread one workgroup alone is faster (measured: 2.7 us per pass at m = 4096 against 3.7):
+    // it needs no exchange through memory
+    if (m <= (int64_t)16 * PT) g = 1;
     if (g < 1) g = 1;
     if (g > ctx->num_cu) g = ctx->num_cu;
     if (g > PT) g = PT;  // a reducer reads one workgroup per thread

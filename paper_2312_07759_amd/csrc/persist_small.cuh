@@ -88,6 +88,7 @@ struct XShared {
     float red[8][PT];                // reducer: words of every workgroup, transposed
     double tot[8];                   // reducer: totals of its slice
     unsigned int bc[XBCAST];         // payloads of the broadcast words
+    float own[XLINE];                // this workgroup's own partial sums (read back directly by a team of one)
     int abort;
 };
 
@@ -117,6 +118,7 @@ __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int s
             c4[u] = ((double)xs.rpart[tid][4 * u] + (double)xs.rpart[tid][4 * u + 1]) +
                     ((double)xs.rpart[tid][4 * u + 2] + (double)xs.rpart[tid][4 * u + 3]);
         const double s = (c4[0] + c4[1]) + (c4[2] + c4[3]);
+        xs.own[tid] = (float)s;
         // row = accumulator, column = workgroup: a reducer's wavefront then reads 64 consecutive words per load
         st_word(&pa.buf1[((size_t)(seq & 1u) * XLINE + tid) * PT + pa.wg], pack_f(seq, (float)s));
     }
@@ -157,7 +159,14 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
 #pragma unroll
     for (int q = 0; q < WPR; ++q) f[q] = 0.f;
     bool aborted = false;
-    if (tid < G) {
+    if (G == 1) {
+        // a team of one has nobody to wait for: its partial sums are the totals
+        __syncthreads();
+        if (tid == 0) {
+#pragma unroll
+            for (int q = 0; q < WPR; ++q) f[q] = xs.own[first + q];
+        }
+    } else if (tid < G) {
         const unsigned long long* src = pa.buf1 + ((size_t)(seq & 1u) * XLINE + first) * PT + tid;
         unsigned long long w[WPR];
         if (poll_words<WPR>(pa, src, PT, seq, w)) {
