@@ -13,6 +13,7 @@ KernelFn lane_kernel(int KPL, int D, int dist, int pass);
 
 // Lane<->codeword family, stream path: reduction of the per-workgroup partials and the O(k d) tail of a pass.
 KernelFn lane_tail_kernel(int pass);
+KernelFn lane_tail_wide_kernel();  // PASS_B2 tail for 1024 threads
 void launch_reduce_rows(const Args& a, int nacc, int nwg, int pass, hipStream_t s);
 
 struct PArgs;

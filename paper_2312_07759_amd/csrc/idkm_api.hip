@@ -138,6 +138,7 @@ struct idkm_ctx {
     Ctrl* h_ctrl = nullptr;  // pinned host mirror
     unsigned int* tickets = nullptr;  // arrival counters of the stream path, zero between launches
     unsigned int stream_launches = 0; // upper bound of Ctrl::launch_seq
+    bool wide_tail = false;           // lane family, GMRES with k d >= 512: the pass tail runs with 1024 threads
     int gmres_basis = 64;             // basis length of IDKM_BWD_GMRES before a restart (idkm_set_gmres_basis, <= GM_RMAX)
     double *Cd = nullptr, *nd = nullptr, *Fd = nullptr, *gd = nullptr, *vd = nullptr, *ud = nullptr;
     float *Cf = nullptr, *Ff = nullptr, *Hs = nullptr;
@@ -294,7 +295,10 @@ idkm_status launch_pass(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, hip
         const int nacc = ctx->k * ((pass == PASS_FWD || pass == PASS_FIN) ? ctx->d + 1 : ctx->d);
         launch_reduce_rows(a, nacc, g.nwg, pass, s);
         HIP_TRY(ctx, hipGetLastError());
-        hipLaunchKernelGGL(lane_tail_kernel(pass), dim3(1), dim3(WG), 0, s, a);
+        if (pass == PASS_B2 && ctx->wide_tail)
+            hipLaunchKernelGGL(lane_tail_wide_kernel(), dim3(1), dim3(1024), 0, s, a);
+        else
+            hipLaunchKernelGGL(lane_tail_kernel(pass), dim3(1), dim3(WG), 0, s, a);
         HIP_TRY(ctx, hipGetLastError());
     }
     return IDKM_OK;
@@ -835,7 +839,9 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
         st = run_until_done(ctx, g, PASS_B2, a, s, (int64_t)max_iter * 7, [](const Ctrl& c) { return c.b_done != 0; });
         if (st != IDKM_OK) return st;
     } else if (mode == IDKM_BWD_GMRES) {
+        ctx->wide_tail = !g.small && ctx->k * ctx->d >= 512;
         st = run_until_done(ctx, g, PASS_B2, a, s, (int64_t)max_iter + 2, [](const Ctrl& c) { return c.b_done != 0; });
+        ctx->wide_tail = false;
         if (st != IDKM_OK) return st;
     }
     st = launch_pass(ctx, g, PASS_B3, a, s);

@@ -50,6 +50,8 @@ KernelFn lane_tail_kernel(int pass) {
     return nullptr;
 }
 
+KernelFn lane_tail_wide_kernel() { return lane_tail_b2_wide<0>; }
+
 void launch_reduce_rows(const Args& a, int nacc, int nwg, int pass, hipStream_t s) {
     hipLaunchKernelGGL(reduce_rows<0>, dim3((nacc + 63) / 64), dim3(WG), 0, s, a, nacc, nwg, pass);
 }

@@ -445,4 +445,12 @@ __global__ __launch_bounds__(WG) void lane_tail(const Args a) {
     if (PASS == PASS_B2) tail_b2(a);
 }
 
+// The same tail with 16 wavefronts, for the minimal-residual solve at large k d: its inner products and vector
+// updates over the Krylov basis are spread over the threads of this one workgroup.
+template <int UNUSED>
+__global__ __launch_bounds__(1024) void lane_tail_b2_wide(const Args a) {
+    if (a.ctrl->b_done) return;
+    tail_b2(a);
+}
+
 }  // namespace idkm

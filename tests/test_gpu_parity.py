@@ -403,3 +403,20 @@ def test_krylov_backward_with_a_short_basis_restarts_and_still_converges(ctx, di
         ctx.set_gmres_basis(0)
     with pytest.raises(binding.IdkmError):
         ctx.set_gmres_basis(257)
+
+
+@pytest.mark.parametrize("dist,tau", [(wl.DIST_L2, 1.0), (wl.DIST_SQL2, 8.0)])
+def test_krylov_backward_at_the_largest_basis_vectors(ctx, dist, tau):
+    """k d = 1024 (lane<->codeword family, the 1024-thread pass tail).  A dense oracle solve would need 1024 passes of
+    the float64 oracle, so the reference is the oracle's own averaged iteration, run to 1e-9 where it converges fast
+    (the temperatures are chosen for that)."""
+    W, C0, G = wl.random_problem(3001, 4, 256, seed=333, std=0.5, spread=1.5)
+    W, C0, G = W.astype(np.float32), C0.astype(np.float32), G.astype(np.float32)
+    out = ctx.forward(dev(W), dev(C0), tau, 1e-6, 60, dist, want_Wq=False)
+    Cg = out["C"].cpu().numpy()
+    ref = orc.backward(W, Cg, tau, dist, G, "implicit", tol=1e-9, max_iter=300)
+    assert ref["converged"]
+    r = ctx.backward(dev(G), binding.BWD_GMRES, tol=1e-6, max_iter=300)
+    assert r["info"].converged and r["info"].path == binding.PATH_STREAM
+    assert r["info"].iters < ref["iters"] + 2
+    assert rel(r["dW"].cpu().numpy(), ref["dW"]) < TOL_GRAD
