@@ -207,7 +207,7 @@ def main() -> int:
         for dd in (1, 0):
             tot = {"fwd_ms": 0.0, "implicit_ms": 0.0, "jfb_ms": 0.0, "fwd_iters": 0, "implicit_passes": 0,
                    "unconverged_fwd": 0, "unconverged_bwd": 0, "weights": 0, "layers": 0}
-            bt = {"fwd_ms": 0.0, "implicit_ms": 0.0, "jfb_ms": 0.0, "launches_fwd": 0}
+            bt = {"fwd_ms": 0.0, "implicit_ms": 0.0, "jfb_ms": 0.0, "dense_ms": 0.0, "launches_fwd": 0}
             for kk in (2, 4):
                 held = []
                 for ti in range(len(wl.RESNET18_TENSORS)):
@@ -232,7 +232,7 @@ def main() -> int:
                 Gs = [Gt for _, _, _, Gt in held]
                 q0 = held[0][0]
                 for rep in range(3):  # the first repetition warms up
-                    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+                    ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
                     ev[0].record()
                     batch.forward(pairs, taus, q0.tol, q0.max_iter, dd, want_Wq=True)
                     ev[1].record()
@@ -240,8 +240,11 @@ def main() -> int:
                     ev[2].record()
                     batch.backward(Gs, binding.BWD_JFB)
                     ev[3].record()
+                    batch.backward(Gs, binding.BWD_DENSE)
+                    ev[4].record()
                     torch.cuda.synchronize()
                     if rep:
+                        bt["dense_ms"] += ev[3].elapsed_time(ev[4]) / 2
                         bt["fwd_ms"] += ev[0].elapsed_time(ev[1]) / 2
                         bt["implicit_ms"] += ev[1].elapsed_time(ev[2]) / 2
                         bt["jfb_ms"] += ev[2].elapsed_time(ev[3]) / 2

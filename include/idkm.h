@@ -130,7 +130,9 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
  *   IDKM_BWD_JFB sets g = v (no pass).  IDKM_BWD_DENSE forms dF/dC* explicitly (the k x k matrix of Sec. 4.2,
  *   k d x k d in general) in the same pass that computes v and solves (I - dF/dC*)^T g = v by Gaussian
  *   elimination in float64: two passes over W in total, tol / max_iter / alpha are ignored, info.iters = 0 and
- *   info.converged = 0 only if the matrix is singular.
+ *   info.converged = 0 only if the matrix is singular.  When the k d (k d + d + 1) sums fit one exchange line
+ *   (k = 2 with d <= 2, k = 4 with d = 1) and the tiles fit in LDS, the persistent kernel does all of it in one
+ *   launch (info.path says which form ran), and batched calls share that launch between layers.
  *   IDKM_BWD_GMRES solves the same system from g = 0 by restarted GMRES (basis length min(k d, 64) unless idkm_set_gmres_basis changed it, float64
  *   orthogonalisation): every pass applies (dF/dC*)^T to one basis vector; when the estimated residual falls
  *   below tol ||v||_F (or the basis is full) the iterate is updated and one more pass measures the true residual

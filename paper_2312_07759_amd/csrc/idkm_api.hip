@@ -772,10 +772,25 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     a.dW_out = dW_out;
 
     if (mode == IDKM_BWD_DENSE) {
-        // two launches whatever the path: (v, dF/dC*) + direct solve, then the final pass
         if (!g.small || ctx->k * ctx->d > DENSE_MAX_KD)
             return fail(ctx, IDKM_ERR_UNSUPPORTED, "the dense backward needs k in {2,4,8,16} and k*d <= 16");
         const int kd = ctx->k * ctx->d;
+        // when the K D (K D + D + 1) sums fit one exchange line the persistent kernel does it in one launch
+        // (and batched calls can share that launch between layers)
+        PersistPlan ppd;
+        if (kd * kd + kd * ctx->d + kd <= XLINE && ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &ppd)) {
+            PArgs pa;
+            std::memset(&pa, 0, sizeof(pa));
+            pa.tol = 0.0;
+            pa.max_iter = 1;
+            pa.mode = (int)mode;
+            pa.alpha = 1.0;
+            st = launch_persistent(ctx, ppd, a, pa, 1u, s);
+            if (st != IDKM_OK) return st;
+            ctx->pending_kind = 2;
+            return ctx->defer_wait ? IDKM_OK : finish_persistent(ctx, info);
+        }
+        // otherwise two launches whatever the path: (v, dF/dC*) + direct solve, then the final pass
         const size_t nacc = (size_t)kd * kd + (size_t)kd * ctx->d + kd;
         Geometry gj = g;
         int64_t vpt = (ctx->m + (int64_t)WG * 256 - 1) / ((int64_t)WG * 256);  // about one workgroup per CU

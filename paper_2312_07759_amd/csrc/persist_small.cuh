@@ -93,9 +93,8 @@ struct XShared {
 };
 
 // hop 1, sender side: workgroup partial of every accumulator into this workgroup's line.
-template <int NACC>
-__device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int seq, const float (&acc)[NACC],
-                                                 XShared<NACC>& xs) {
+template <int NACC, class XS>
+__device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int seq, const float (&acc)[NACC], XS& xs) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     IDKM_SUB(0);
     constexpr int NP = pow2_at_least(NACC);
@@ -148,9 +147,8 @@ __device__ __forceinline__ bool poll_words(const PArgs& pa, const unsigned long 
 
 // hop 1, reducer side: totals over all workgroups of words [first, first+WPR) into xs.tot (float64, fixed order).
 // Returns false if the wait was abandoned (uniform over the workgroup).
-template <int NACC, int WPR>
-__device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, int first,
-                                             XShared<NACC>& xs) {
+template <int NACC, int WPR, class XS>
+__device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, int first, XS& xs) {
     static_assert(WPR <= 8, "a reducer handles at most 8 words per workgroup");
     const int tid = threadIdx.x;
     IDKM_SUB(4);
@@ -206,13 +204,12 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
 // hop 2, receiver side: waits for words [0, nwords) of buf2 and leaves their payloads in xs.bc.  Words
 // [0, KD) belong to slices of WPR words, word KD + r to reducer r; a reducer has put the words of its own slices
 // into xs.bc already and does not wait for the round trip of its own stores.
-template <int NACC, int WPR, int KD>
-__device__ __forceinline__ bool gather_bcast(const PArgs& pa, unsigned int seq, int nwords,
-                                             XShared<NACC>& xs) {
+template <int NACC, int WPR, int KD, class XS>
+__device__ __forceinline__ bool gather_bcast(const PArgs& pa, unsigned int seq, int nwords, bool keep_own, XS& xs) {
     const int tid = threadIdx.x;
     bool aborted = false;
     const int slice = (tid < KD) ? tid / WPR : tid - KD;
-    if (tid < nwords && (slice % pa.G) != pa.wg) {
+    if (tid < nwords && !(keep_own && (slice % pa.G) == pa.wg)) {
         const unsigned long long* src = pa.buf2 + (size_t)(seq & 1u) * XBCAST + tid;
         unsigned long long w[1];
         if (poll_words<1>(pa, src, 0, seq, w))
@@ -433,8 +430,12 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     constexpr int WPR = KPR * D;
     constexpr int NB = KD + R;  // broadcast words: h/tau, then one partial squared norm per reducer
     static_assert(KD <= XLINE && NB <= XBCAST && KD <= 64, "shape does not fit the exchange layout");
+    // explicit-Jacobian mode (Eq. "grad", "inv" taken literally): offered when its K D (K D + D + 1) sums fit one
+    // exchange line
+    constexpr int NBJ = KD * KD + KD * D + KD;
+    constexpr bool HAS_DENSE = NBJ <= XLINE;
     extern __shared__ float s_tile[];
-    __shared__ XShared<KD> xs;
+    __shared__ XShared<HAS_DENSE ? NBJ : KD> xs;
     __shared__ double s_v[KD], s_g[KD], s_rn[K];  // a reducer's own slice is the live one; s_rn = 1/(tau n)
     __shared__ float s_Cf[KD], s_Hs[KD], s_Hv[KD], s_Ff[KD];
     __shared__ int s_done, s_iters, s_conv, s_attempt, s_grow, s_halv, s_bad, s_restart;
@@ -465,9 +466,9 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     const int max_iter = pa.max_iter;
     if (tid == 0) {
         xs.abort = 0;
-        s_done = (mode == BWD_JFB) ? 1 : 0;
+        s_done = (mode == BWD_JFB || mode == BWD_DENSE) ? 1 : 0;
         s_iters = 0;
-        s_conv = (mode == BWD_JFB) ? 1 : 0;
+        s_conv = (mode == BWD_JFB || mode == BWD_DENSE) ? 1 : 0;
         s_attempt = 0;
         s_grow = 0;
         s_halv = 0;
@@ -482,6 +483,79 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     unsigned int seq = pa.seq_base;
 
     float acc[KD];
+    bool dense_done = false;
+    if constexpr (HAS_DENSE) {
+        if (mode == BWD_DENSE) {
+            // one pass accumulates v and the sums T, U of dF/dC* (layout as in the stream path's tail_bj); workgroup 0
+            // adds them over the team, solves (I - dF/dC*)^T g = v by Gauss-Jordan elimination and broadcasts h/tau
+            float accj[NBJ];
+            tile_pass<K, D, DIST, PASS_BJ>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, accj);
+            ++seq;
+            publish_partials<NBJ>(pa, seq, accj, xs);
+            if (wg == 0) {
+                __shared__ double s_tj[NBJ];
+                __shared__ double s_M[KD * (KD + 1)];
+                for (int first = 0; first < NBJ; first += 4) {
+                    if (!reduce_slice<NBJ, 4>(pa, seq, first, xs)) return;
+                    if (tid < 4) s_tj[first + tid] = xs.tot[tid];
+                    __syncthreads();
+                }
+                if (tid == 0) {
+                    constexpr int n = KD, n1 = KD + 1;
+                    const double* T = s_tj;
+                    const double* U = s_tj + n * n;
+                    const double* V = s_tj + n * n + n * D;
+                    for (int row = 0; row < n; ++row) {
+                        const int l = row / D, sidx = row - l * D;
+                        for (int col = 0; col < n; ++col) {
+                            const int j = col / D;
+                            const double J = ((l == j ? U[col * D + sidx] : 0.0) - T[col * n + row]) * s_rn[j];
+                            s_M[row * n1 + col] = (row == col ? 1.0 : 0.0) - J;
+                        }
+                        s_M[row * n1 + n] = V[row];
+                    }
+                    bool sing = false;
+                    for (int p = 0; p < n; ++p) {
+                        int best = p;
+                        double bv = fabs(s_M[p * n1 + p]);
+                        for (int i = p + 1; i < n; ++i)
+                            if (fabs(s_M[i * n1 + p]) > bv) {
+                                bv = fabs(s_M[i * n1 + p]);
+                                best = i;
+                            }
+                        if (!(bv > 1e-300) || !(bv <= 1.7e308)) sing = true;
+                        if (best != p)
+                            for (int j = 0; j < n1; ++j) {
+                                const double x = s_M[p * n1 + j];
+                                s_M[p * n1 + j] = s_M[best * n1 + j];
+                                s_M[best * n1 + j] = x;
+                            }
+                        const double pp = s_M[p * n1 + p];
+                        for (int i = 0; i < n; ++i) {
+                            if (i == p) continue;
+                            const double f = s_M[i * n1 + p] / pp;
+                            for (int j = p; j < n1; ++j) s_M[i * n1 + j] -= f * s_M[p * n1 + j];
+                        }
+                    }
+                    double v2 = 0.0;
+                    for (int idx = 0; idx < n; ++idx) {
+                        const double g = s_M[idx * n1 + n] / s_M[idx * n1 + idx];
+                        if (!(fabs(g) <= 1.7e308)) sing = true;
+                        s_g[idx] = g;
+                        s_v[idx] = V[idx];
+                        v2 += V[idx] * V[idx];
+                        st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + idx], pack_f(seq, (float)(g * s_rn[idx / D])));
+                    }
+                    // a singular or non-finite system travels as a NaN norm: every workgroup then reports it
+                    if (sing) v2 = __builtin_nan("");
+                    for (int r = 0; r < R; ++r)
+                        st_word(&pa.buf2[(size_t)(seq & 1u) * XBCAST + KD + r], pack_f(seq, r == 0 ? (float)v2 : 0.f));
+                }
+            }
+            dense_done = true;
+        }
+    }
+    if (!dense_done) {
     // B1: v = dL/dC* with W fixed; the solve starts at g = v
     tile_pass<K, D, DIST, PASS_B1>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
     ++seq;
@@ -507,7 +581,8 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
             }
         }
     }
-    if (!gather_bcast<KD, WPR, KD>(pa, seq, NB, xs)) return;
+    }
+    if (!gather_bcast<KD, WPR, KD>(pa, seq, NB, !dense_done, xs)) return;
     if (tid < KD) {
         s_Hs[tid] = __uint_as_float(xs.bc[tid]);
         s_Hv[tid] = s_Hs[tid];
@@ -550,7 +625,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                 }
             }
         }
-        if (!gather_bcast<KD, WPR, KD>(pa, seq, NB, xs)) return;
+        if (!gather_bcast<KD, WPR, KD>(pa, seq, NB, true, xs)) return;
         if (tid == 0) {
             // the same decision in every workgroup (same words, same order)
             double d2 = 0.0;
@@ -607,11 +682,18 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
 
     // B3: dW = direct + (dF/dW)^T g
     tile_pass<K, D, DIST, PASS_B3>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, reinterpret_cast<float(&)[1]>(acc[0]));
-    for (int r = wg; r < R; r += pa.G) {
-        if (tid < WPR) {
-            const int idx = r * WPR + tid;
-            a.gd[idx] = s_g[idx];
-            a.vd[idx] = s_v[idx];
+    if (dense_done) {
+        if (wg == 0 && tid < KD) {
+            a.gd[tid] = s_g[tid];
+            a.vd[tid] = s_v[tid];
+        }
+    } else {
+        for (int r = wg; r < R; r += pa.G) {
+            if (tid < WPR) {
+                const int idx = r * WPR + tid;
+                a.gd[idx] = s_g[idx];
+                a.vd[idx] = s_v[idx];
+            }
         }
     }
     if (wg == 0 && tid < KD) a.Hs[tid] = s_Hs[tid];

@@ -60,6 +60,16 @@ def test_mixed_batch_matches_oracle_and_single_calls(dist):
     assert 1 <= b.launches() <= 4          # four persistent kernel shapes in MIXED, one launch each
     bw = b.backward(Gd, binding.BWD_IMPLICIT, tol=1e-6, max_iter=60, alpha=1.0)
     jf = b.backward(Gd, binding.BWD_JFB)
+    # explicit-Jacobian mode: the k=4, d=1 layers share one launch, the others are refused or solved in their turn
+    dn = b.backward(Gd, binding.BWD_DENSE, strict=False)
+    for i, (m, d, k) in enumerate(MIXED):
+        if k * d <= 16 and k in (2, 4, 8, 16):
+            assert dn[i]["status"] == 0 and dn[i]["info"].converged
+            rd = orc.backward(layers[i][0], fw[i]["C"].cpu().numpy(), layers[i][3], dist, layers[i][2], mode="dense")
+            assert rel(dn[i]["dW"].cpu().numpy(), rd["dW"]) < TOL_GRAD, i
+            assert dn[i]["info"].path == (binding.PATH_PERSISTENT if (k, d) == (4, 1) else binding.PATH_STREAM)
+        else:
+            assert dn[i]["status"] == 6
     single = binding.Context(0)
     for i, (W, C0, G, tau) in enumerate(layers):
         ref = orc.soft_kmeans(W, C0, tau, tol, iters, dist)

@@ -216,8 +216,8 @@ def test_results_are_bitwise_reproducible(ctx):
             assert torch.equal(x, y)
 
 
-DENSE_CASES = [("k2d1", 3_001, 1, 2), ("k8d1", 9_000, 1, 8), ("k2d2", 4_097, 2, 2), ("k4d2", 5_000, 2, 4),
-               ("k8d2", 6_001, 2, 8), ("k2d4", 2_500, 4, 2), ("k4d4", 7_003, 4, 4)]
+DENSE_CASES = [("k2d1", 3_001, 1, 2), ("k4d1", 70_001, 1, 4), ("k8d1", 9_000, 1, 8), ("k2d2", 4_097, 2, 2),
+               ("k4d2", 5_000, 2, 4), ("k8d2", 6_001, 2, 8), ("k2d4", 2_500, 4, 2), ("k4d4", 7_003, 4, 4)]
 
 
 @pytest.mark.parametrize("dist", DISTS)
@@ -227,10 +227,19 @@ def test_dense_backward_matches_the_gaussian_solve(ctx, name, m, d, k, dist):
     tau = 0.3
     out = ctx.forward(dev(W), dev(C0), tau, 1e-6, 300, dist)
     Cg = out["C"].cpu().numpy()
-    bd = ctx.backward(dev(G), binding.BWD_DENSE)
     rd = orc.backward(W, Cg, tau, dist, G, "dense")
-    assert bd["info"].converged
-    assert rel(bd["dW"].cpu().numpy(), rd["dW"]) < TOL_GRAD, rel(bd["dW"].cpu().numpy(), rd["dW"])
+    kd = k * d
+    one_launch = kd * kd + kd * d + kd <= 32      # the sums fit one exchange line: k=2 (d=1,2) and k=4 (d=1)
+    for path in (binding.PATH_STREAM, binding.PATH_PERSISTENT, binding.PATH_AUTO):
+        ctx.set_path(path)
+        try:
+            bd = ctx.backward(dev(G), binding.BWD_DENSE)
+        finally:
+            ctx.set_path(binding.PATH_AUTO)
+        assert bd["info"].converged and bd["info"].iters == 0
+        want = binding.PATH_STREAM if (path == binding.PATH_STREAM or not one_launch) else binding.PATH_PERSISTENT
+        assert bd["info"].path == want
+        assert rel(bd["dW"].cpu().numpy(), rd["dW"]) < TOL_GRAD, (path, rel(bd["dW"].cpu().numpy(), rd["dW"]))
 
 
 def test_dense_backward_is_refused_beyond_its_size_limit(ctx):
