@@ -188,16 +188,26 @@ class Context:
     def set_spin_limit(self, polls: int):
         self._check(self._lib.idkm_set_spin_limit(self._h, int(polls)))
 
-    def forward(self, W, C0, tau, tol, max_iter, dist, want_A=False, want_Wq=True, want_assign=False):
-        """idkm_forward.  W [m,d], C0 [k,d] float32 device tensors.  Returns dict(C, A, Wq, assign, info)."""
+    def forward(self, W, C0, tau, tol, max_iter, dist, want_A=False, want_Wq=True, want_assign=False, out=None):
+        """idkm_forward.  W [m,d], C0 [k,d] float32 device tensors.  Returns dict(C, A, Wq, assign, info).
+        `out` may hold preallocated tensors under the keys C, A, Wq, assign (as a training loop would keep them)."""
         import torch
         m, d = W.shape
         k = C0.shape[0]
         dev = W.device
-        Cout = torch.empty((k, d), dtype=torch.float32, device=dev)
-        A = torch.empty((m, k), dtype=torch.float32, device=dev) if want_A else None
-        Wq = torch.empty((m, d), dtype=torch.float32, device=dev) if want_Wq else None
-        asg = torch.empty((m,), dtype=torch.int32, device=dev) if want_assign else None
+        out = out or {}
+        Cout = out.get("C")
+        if Cout is None:
+            Cout = torch.empty((k, d), dtype=torch.float32, device=dev)
+        A = out.get("A") if want_A else None
+        if want_A and A is None:
+            A = torch.empty((m, k), dtype=torch.float32, device=dev)
+        Wq = out.get("Wq") if want_Wq else None
+        if want_Wq and Wq is None:
+            Wq = torch.empty((m, d), dtype=torch.float32, device=dev)
+        asg = out.get("assign") if want_assign else None
+        if want_assign and asg is None:
+            asg = torch.empty((m,), dtype=torch.int32, device=dev)
         info = IdkmInfo()
         st = self._lib.idkm_forward(self._h, _ptr(W, torch.float32, (m, d), "W"), m, d,
                                     _ptr(C0, torch.float32, (k, d), "C0"), k, float(tau), float(tol), int(max_iter),
@@ -208,10 +218,10 @@ class Context:
         self._keep = W  # the library borrows W until backward
         return dict(C=Cout, A=A, Wq=Wq, assign=asg, info=_info(info))
 
-    def backward(self, dWq, mode, tol=1e-6, max_iter=1000, alpha=1.0):
-        """idkm_backward.  dWq [m,d] float32 device tensor.  Returns dict(dW, info)."""
+    def backward(self, dWq, mode, tol=1e-6, max_iter=1000, alpha=1.0, out=None):
+        """idkm_backward.  dWq [m,d] float32 device tensor.  Returns dict(dW, info); `out` may be a preallocated dW."""
         import torch
-        dW = torch.empty_like(dWq)
+        dW = out if out is not None else torch.empty_like(dWq)
         info = IdkmInfo()
         st = self._lib.idkm_backward(self._h, _ptr(dWq, torch.float32, dWq.shape, "dWq"), int(mode), float(tol),
                                      int(max_iter), float(alpha), _ptr(dW, torch.float32, dWq.shape, "dW_out"),
