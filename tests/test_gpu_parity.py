@@ -429,3 +429,22 @@ def test_krylov_backward_at_the_largest_basis_vectors(ctx, dist, tau):
     assert r["info"].converged and r["info"].path == binding.PATH_STREAM
     assert r["info"].iters < ref["iters"] + 2
     assert rel(r["dW"].cpu().numpy(), ref["dW"]) < TOL_GRAD
+
+
+def test_autograd_front_end_gives_the_oracle_gradient_of_a_loss(ctx):
+    """L = sum((Wq - T)^2) through the autograd wrapper against the oracle's implicit gradient of the same loss."""
+    from paper_2312_07759_amd.autograd import SoftKMeansQuantize
+    W, C0, T = _case(20_011, 2, 8, seed=77)
+    tau, dist = 0.1, wl.DIST_SQL2
+    layer = SoftKMeansQuantize(tau, dist, tol=1e-7, max_iter=300, bwd_mode=binding.BWD_GMRES, bwd_tol=1e-7)
+    Wt = dev(W).requires_grad_(True)
+    Wq, Cstar = layer(Wt, dev(C0))
+    loss = ((Wq - dev(T)) ** 2).sum()
+    loss.backward()
+    Cg = Cstar.cpu().numpy()
+    G = (2.0 * (orc.soft_quantize(W, Cg, tau, dist) - T)).astype(np.float32)
+    ref = orc.backward(W, Cg, tau, dist, G, "dense")
+    assert layer.last_backward.converged
+    assert rel(Wt.grad.cpu().numpy(), ref["dW"]) < TOL_GRAD
+    assert not Cstar.requires_grad
+    layer.close()
