@@ -153,6 +153,18 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
                           float alpha, float* dW_out, idkm_info* info, void* hip_stream);
 
 /*
+ * Diagnostic: measures one of the ceilings a roofline of this path is drawn against, on the context's device.
+ *   kind 0  full-rate lane operations per second (dependent-free v_fma_f32 chains, 8 wavefronts per SIMD)
+ *   kind 1  exponentials per second (v_exp_f32 alone)
+ *   kind 2  bytes per second of a streaming read of buf (device, 16-byte aligned, n_floats floats)
+ *   kind 3, 4, 5  exponentials per second with 1, 2, 4 independent v_fma_f32 issued beside each of them
+ *           (shows how transcendental and full-rate operations share the issue slots)
+ * Waits for completion; *result (host) receives the rate.  Nothing on the method's path calls this.
+ */
+idkm_status idkm_calibrate(idkm_ctx* ctx, int32_t kind, const float* buf, int64_t n_floats, double* result,
+                           void* hip_stream);
+
+/*
  * The stored form of a quantised layer (Sec. 3, product-quantisation set-up: every sub-vector w_i is replaced by
  * its closest codeword q(w_i, C), one of k = 2^b, so a layer is kept as m codes of b bits plus the codebook).
  *

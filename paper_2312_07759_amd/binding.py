@@ -23,7 +23,7 @@ PATH_AUTO, PATH_STREAM, PATH_PERSISTENT = 0, 1, 2
 
 EXPORTS = ["idkm_version", "idkm_limits", "idkm_status_string", "idkm_create", "idkm_destroy", "idkm_last_error",
            "idkm_set_path", "idkm_set_spin_limit", "idkm_set_gmres_basis", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT",
-           "idkm_code_bits", "idkm_code_words", "idkm_pack_codes", "idkm_unpack_quantize",
+           "idkm_calibrate", "idkm_code_bits", "idkm_code_words", "idkm_pack_codes", "idkm_unpack_quantize",
            "idkm_batch_create", "idkm_batch_destroy", "idkm_batch_last_error", "idkm_batch_launches",
            "idkm_batch_context", "idkm_batch_forward", "idkm_batch_backward"]
 
@@ -94,6 +94,8 @@ def load_library():
     lib.idkm_step_F.restype = C.c_int
     lib.idkm_step_JCT.argtypes = [vp, f32p, f32p, vp]
     lib.idkm_step_JCT.restype = C.c_int
+    lib.idkm_calibrate.argtypes = [vp, C.c_int32, f32p, C.c_int64, C.POINTER(C.c_double), vp]
+    lib.idkm_calibrate.restype = C.c_int
     lib.idkm_code_bits.argtypes = [C.c_int32]
     lib.idkm_code_bits.restype = C.c_int32
     lib.idkm_code_words.argtypes = [C.c_int64, C.c_int32]
@@ -228,6 +230,15 @@ class Context:
                                      C.byref(info), _stream())
         self._check(st)
         return dict(dW=dW, info=_info(info))
+
+    def calibrate(self, kind, buf=None):
+        """idkm_calibrate: 0 lane-ops/s, 1 exponentials/s, 2 bytes/s of a streaming read of `buf` (float32 tensor)."""
+        import torch
+        r = C.c_double()
+        n = 0 if buf is None else buf.numel()
+        ptr = None if buf is None else _ptr(buf, torch.float32, buf.shape, "buf")
+        self._check(self._lib.idkm_calibrate(self._h, int(kind), ptr, n, C.byref(r), _stream()))
+        return float(r.value)
 
     def pack_codes(self, assign, k):
         """idkm_pack_codes: int32 [m] device tensor -> int32 tensor holding the uint32 words of the b-bit stream."""

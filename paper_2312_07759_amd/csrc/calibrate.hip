@@ -1,0 +1,71 @@
+// Micro-benchmarks of the ceilings the roofline uses: full-rate lane operations (v_fma_f32), transcendentals
+// (v_exp_f32) and a streaming read.  Diagnostic only; nothing on the method's path calls these.
+#include "dispatch.h"
+
+namespace idkm {
+
+// 16 independent chains per lane keep the pipeline full; `iters` rounds of 16 operations each.
+__global__ __launch_bounds__(256) void k_cal_fma(float* out, int iters, float a, float b) {
+    float x[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) x[u] = (float)(threadIdx.x + u) * 1e-3f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) x[u] = fmaf(x[u], a, b);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) s += x[u];
+    if (s == 12345.678f) out[0] = s;  // keeps the chains alive without a store in the common case
+}
+
+// NF full-rate operations (FMAs on separate chains) issued beside every exponential: NF = 0 gives the rate of the
+// transcendental alone (the negated absolute value is a free source modifier), NF > 0 shows how the two share the
+// issue slots.
+template <int NF>
+__global__ __launch_bounds__(256) void k_cal_exp(float* out, int iters, float a, float b) {
+    float x[8], y[8 * (NF > 0 ? NF : 1)];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) x[u] = (float)(threadIdx.x + u) * 1e-3f;
+#pragma unroll
+    for (int u = 0; u < 8 * (NF > 0 ? NF : 1); ++u) y[u] = (float)(threadIdx.x + u) * 1e-3f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            x[u] = __builtin_amdgcn_exp2f(-fabsf(x[u]));
+#pragma unroll
+            for (int f = 0; f < NF; ++f) y[u * NF + f] = fmaf(y[u * NF + f], a, b);
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += x[u];
+#pragma unroll
+    for (int u = 0; u < 8 * (NF > 0 ? NF : 1); ++u) s += y[u];
+    if (s == 12345.678f) out[0] = s;
+}
+
+// Grid-stride read of n float4 values.
+__global__ __launch_bounds__(256) void k_cal_read(const float4* __restrict__ src, size_t n, float* out) {
+    float s = 0.f;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const float4 v = src[i];
+        s += (v.x + v.y) + (v.z + v.w);
+    }
+    if (s == 12345.678f) out[0] = s;
+}
+
+void launch_cal_fma(float* out, int grid, int iters, hipStream_t s) {
+    hipLaunchKernelGGL(k_cal_fma, dim3(grid), dim3(256), 0, s, out, iters, 0.999f, 1e-3f);
+}
+void launch_cal_exp(float* out, int grid, int iters, int fmas, hipStream_t s) {
+    if (fmas == 0) hipLaunchKernelGGL(k_cal_exp<0>, dim3(grid), dim3(256), 0, s, out, iters, 0.999f, 1e-3f);
+    if (fmas == 1) hipLaunchKernelGGL(k_cal_exp<1>, dim3(grid), dim3(256), 0, s, out, iters, 0.999f, 1e-3f);
+    if (fmas == 2) hipLaunchKernelGGL(k_cal_exp<2>, dim3(grid), dim3(256), 0, s, out, iters, 0.999f, 1e-3f);
+    if (fmas == 4) hipLaunchKernelGGL(k_cal_exp<4>, dim3(grid), dim3(256), 0, s, out, iters, 0.999f, 1e-3f);
+}
+void launch_cal_read(const float* src, size_t n_floats, int grid, float* out, hipStream_t s) {
+    hipLaunchKernelGGL(k_cal_read, dim3(grid), dim3(256), 0, s, reinterpret_cast<const float4*>(src), n_floats / 4, out);
+}
+
+}  // namespace idkm

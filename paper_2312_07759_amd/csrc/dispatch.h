@@ -35,4 +35,9 @@ void launch_pack_codes(const int32_t* assign, int64_t m, int bits, uint32_t* wor
 void launch_unpack_quantize(const uint32_t* words, int64_t nwords, int64_t m, int bits, const float* C, int k, int d,
                             float* out, hipStream_t s);
 
+// Micro-benchmarks of the roofline's ceilings (calibrate.hip).
+void launch_cal_fma(float* out, int grid, int iters, hipStream_t s);
+void launch_cal_exp(float* out, int grid, int iters, int fmas, hipStream_t s);  // fmas in {0, 1, 2, 4}
+void launch_cal_read(const float* src, size_t n_floats, int grid, float* out, hipStream_t s);
+
 }  // namespace idkm

@@ -876,6 +876,46 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     return IDKM_OK;
 }
 
+idkm_status idkm_calibrate(idkm_ctx* ctx, int32_t kind, const float* buf, int64_t n_floats, double* result,
+                           void* hip_stream) {
+    idkm_status st = check_common(ctx);
+    if (st != IDKM_OK) return st;
+    if (!result || kind < 0 || kind > 5) return fail(ctx, IDKM_ERR_INVALID_ARG, "kind must be 0 .. 5 and result non-NULL");
+    if (kind == 2 && (!buf || n_floats < 4 || (reinterpret_cast<uintptr_t>(buf) & 15u) != 0))
+        return fail(ctx, IDKM_ERR_INVALID_ARG, "the streaming read needs a 16-byte aligned buffer");
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    HIP_TRY(ctx, hipEventCreate(&e0));
+    HIP_TRY(ctx, hipEventCreate(&e1));
+    const int grid = ctx->num_cu * 8;  // eight wavefronts per SIMD
+    const int iters = 4096;
+    float* sink = reinterpret_cast<float*>(ctx->tot);
+    double work = 0.0;
+    for (int rep = 0; rep < 2; ++rep) {  // the first repetition warms up
+        HIP_TRY(ctx, hipEventRecord(e0, s));
+        if (kind == 0) {
+            launch_cal_fma(sink, grid, iters, s);
+            work = (double)grid * 256.0 * iters * 16.0;  // lane operations
+        } else if (kind == 1 || kind >= 3) {
+            const int fmas = kind == 1 ? 0 : (kind == 3 ? 1 : (kind == 4 ? 2 : 4));
+            launch_cal_exp(sink, grid, iters, fmas, s);
+            work = (double)grid * 256.0 * iters * 8.0;  // exponentials
+        } else {
+            launch_cal_read(buf, (size_t)n_floats, grid * 2, sink, s);
+            work = (double)(n_floats / 4 * 4) * 4.0;     // bytes
+        }
+        HIP_TRY(ctx, hipGetLastError());
+        HIP_TRY(ctx, hipEventRecord(e1, s));
+        HIP_TRY(ctx, hipEventSynchronize(e1));
+    }
+    float ms = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    *result = work / ((double)ms * 1e-3);
+    return IDKM_OK;
+}
+
 int32_t idkm_code_bits(int32_t k) {
     if (k < 1) return 0;
     int b = 1;

@@ -242,8 +242,12 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
         }
 #pragma unroll
     for (int q = 0; q < Item::NACC; ++q) acc[q] = 0.f;
-#pragma unroll 2
-    for (int it = threadIdx.x; it < cnt; it += PT) {
+    // one wavefront per SIMD: the latencies of a vector's chain (LDS load, exponentials, reciprocal) are hidden by
+    // other vectors of the same lane, so vectors are taken in groups whose bodies the scheduler interleaves: in the
+    // forward passes groups of UNR while they last, then groups of 4, then single vectors
+    constexpr bool FWD_LIKE = (PASS == PASS_FWD || PASS == PASS_FIN);
+    constexpr int UNR = FWD_LIKE ? (K <= 4 ? 18 : (K == 8 ? 8 : 4)) : (K <= 4 ? 6 : (K == 8 ? 3 : 2));
+    auto one = [&](int it) {
         float w[D], g[D];
 #pragma unroll
         for (int r = 0; r < D; ++r) {
@@ -251,6 +255,24 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
             g[r] = Item::USE_G ? s_g[it * D + r] : 0.f;
         }
         Item::run(a, base + it, w, g, c, hs, ff, acc);
+    };
+    if constexpr (FWD_LIKE) {
+        int it = threadIdx.x;
+        for (; it + (UNR - 1) * PT < cnt; it += UNR * PT) {
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) one(it + u * PT);
+        }
+        if (UNR > 4) {
+            for (; it + 3 * PT < cnt; it += 4 * PT) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) one(it + u * PT);
+            }
+        }
+        for (; it < cnt; it += PT) one(it);
+    } else {
+        // the backward passes carry more state per vector; a plainly unrolled loop schedules them better (measured)
+#pragma unroll UNR
+        for (int it = threadIdx.x; it < cnt; it += PT) one(it);
     }
 }
 
