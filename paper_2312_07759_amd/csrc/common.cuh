@@ -317,11 +317,12 @@ __device__ __forceinline__ bool arrive_last(unsigned int* tickets) {
     return s_last != 0;
 }
 
+// (tot_out: LDS of the caller.)
 // Sum over all workgroups of the stamped float32 partials xp[acc][wg] (written by every workgroup of this launch
 // before it took its ticket) into tot[acc], float64, in a fixed order.  The counters say that every workgroup has
 // issued its stores; the stamps say that a word has arrived, so a word that is still on its way is simply read
 // again (bounded).  Returns false in every thread if a word never arrived.
-__device__ __forceinline__ bool reduce_stamped(const Args& a, int nacc, unsigned int seq) {
+__device__ __forceinline__ bool reduce_stamped(const Args& a, int nacc, unsigned int seq, double* tot_out) {
     __shared__ double s_red[8][WG];
     __shared__ int s_fail;
     const int tid = threadIdx.x, nwg = gridDim.x;
@@ -361,7 +362,7 @@ __device__ __forceinline__ bool reduce_stamped(const Args& a, int nacc, unsigned
 #pragma unroll
         for (int u = 0; u < 8; ++u) t += s_red[q][part * 8 + u];
         t = half_sum_d_dpp(t);
-        if (part == 31 && acc0 + q < nacc) a.tot[acc0 + q] = t;
+        if (part == 31 && acc0 + q < nacc) tot_out[acc0 + q] = t;
         __syncthreads();
     }
     return s_fail == 0;
@@ -371,7 +372,7 @@ __device__ __forceinline__ bool reduce_stamped(const Args& a, int nacc, unsigned
 __device__ __forceinline__ double block_sum_d(double x) {
     __shared__ double s_w[16];
     __shared__ double s_r;
-    x = wave_sum_d(x);
+    x = wave_sum_d_dpp(x);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = x;
     __syncthreads();
@@ -384,51 +385,78 @@ __device__ __forceinline__ double block_sum_d(double x) {
     return s_r;
 }
 __device__ __forceinline__ int block_sum_i(int x) { return (int)(block_sum_d((double)x) + 0.5); }
+// Three block-wide sums for the price of one (two barriers): x[0..2] are replaced by their totals in every thread.
+__device__ __forceinline__ void block_sum_d3(double (&x)[3]) {
+    __shared__ double s_w[16][3];
+    __shared__ double s_r[3];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) x[q] = wave_sum_d_dpp(x[q]);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int q = 0; q < 3; ++q) s_w[threadIdx.x >> 6][q] = x[q];
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        double t = 0.0;
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += s_w[w][threadIdx.x];
+        s_r[threadIdx.x] = t;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 3; ++q) x[q] = s_r[q];
+}
 
 // Tail of a forward evaluation (Alg. 1: centre update and stop test).  tot holds
 // [k][d+1] = (n_j, s_j).  A cluster with zero mass keeps its centre.
-__device__ __forceinline__ void tail_forward(const Args& a) {
+__device__ __forceinline__ void tail_forward(const Args& a, const double* tot) {
     const int k = a.k, d = a.d, kd = k * d;
     Ctrl* c = a.ctrl;
-    double r2 = 0.0;
-    int bad = 0, empty = 0;
+    // the control words are requested first, so that their way from memory overlaps the update below
+    int iters0 = 0, max_iter = 0;
+    double tol = 0.0;
+    if (threadIdx.x == 0) {
+        iters0 = c->iters;
+        max_iter = c->max_iter;
+        tol = c->tol;
+    }
+    double x[3] = {0.0, 0.0, 0.0};  // squared step, non-finite flag, empty clusters
     for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
         int j = idx / d, r = idx - j * d;
-        double n = a.tot[j * (d + 1)], s = a.tot[j * (d + 1) + 1 + r];
+        double n = tot[j * (d + 1)], s = tot[j * (d + 1) + 1 + r];
         double cold = a.Cd[idx];
-        double cnew = (n > 0.0) ? s / n : cold;
-        if (!(n > 0.0) && r == 0) empty++;
-        if (!(n >= 0.0) || !(fabs(s) <= 1.7e308) || !(fabs(cnew) <= 1.7e308)) bad = 1;  // NaN or Inf anywhere
+        double cnew = (n > 0.0) ? fast_div_d(s, n) : cold;
+        if (!(n > 0.0) && r == 0) x[2] += 1.0;
+        if (!(n >= 0.0) || !(fabs(s) <= 1.7e308) || !(fabs(cnew) <= 1.7e308)) x[1] = 1.0;  // NaN or Inf anywhere
         double df = cnew - cold;
-        r2 += df * df;
+        x[0] += df * df;
         a.Cd[idx] = cnew;
         a.Cf[idx] = (float)cnew;
         if (r == 0) a.nd[j] = n;
     }
-    r2 = block_sum_d(r2);
-    bad = block_sum_i(bad);
-    empty = block_sum_i(empty);
+    block_sum_d3(x);
     if (threadIdx.x == 0) {
-        double res = sqrt(r2);
-        c->iters += 1;
+        const double res = sqrt(x[0]);
+        const bool bad = x[1] > 0.0;
+        const int iters = iters0 + 1;
+        c->iters = iters;
         c->residual = res;
-        c->empty = empty;
+        c->empty = (int)(x[2] + 0.5);
         if (bad) c->nonfinite = 1;
-        bool conv = res < c->tol;
+        const bool conv = res < tol;
         c->converged = conv ? 1 : 0;
-        if (conv || bad || c->iters >= c->max_iter) c->done = 1;
-        
+        if (conv || bad || iters >= max_iter) c->done = 1;
     }
 }
 
 // Tail of the evaluation at C* (Sec. 4.2 "plug it into F one time"): keeps n*, F*.
-__device__ __forceinline__ void tail_final(const Args& a) {
+__device__ __forceinline__ void tail_final(const Args& a, const double* tot) {
     const int k = a.k, d = a.d, kd = k * d;
     Ctrl* c = a.ctrl;
     int empty = 0, bad = 0;
     for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
         int j = idx / d, r = idx - j * d;
-        double n = a.tot[j * (d + 1)], s = a.tot[j * (d + 1) + 1 + r];
+        double n = tot[j * (d + 1)], s = tot[j * (d + 1) + 1 + r];
         double f = (n > 0.0) ? s / n : a.Cd[idx];
         if (!(n > 0.0) && r == 0) empty++;
         if (!(n >= 0.0) || !(fabs(s) <= 1.7e308)) bad = 1;
@@ -454,12 +482,12 @@ __device__ __forceinline__ void store_h(const Args& a, int idx, double g) {
 }
 
 // Tail of B1: tot = v.  Starts the backward solve at g = v.
-__device__ __forceinline__ void tail_b1(const Args& a) {
+__device__ __forceinline__ void tail_b1(const Args& a, const double* tot) {
     const int kd = a.k * a.d;
     Ctrl* c = a.ctrl;
     double v2 = 0.0;
     for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
-        double v = a.tot[idx];
+        double v = tot[idx];
         a.vd[idx] = v;
         a.gd[idx] = v;
         store_h(a, idx, v);
@@ -522,7 +550,7 @@ __host__ __device__ inline size_t gm_doubles(int R, int n) {
 //            g+ - g of the undamped iteration IS r, so this is the same test); otherwise r/||r|| starts a new cycle.
 // Every pass counts in b_iters.  Two consecutive cycles that leave more than 95 % of the residual end the solve
 // unconverged (restarted GMRES can stagnate when I - dF/dC is far from definite).
-__device__ __forceinline__ void tail_gmres(const Args& a) {
+__device__ __forceinline__ void tail_gmres(const Args& a, const double* tot) {
     const int n = a.k * a.d;
     Ctrl* c = a.ctrl;
     const int R = c->k_R;
@@ -542,7 +570,7 @@ __device__ __forceinline__ void tail_gmres(const Args& a) {
         const double* qj = Q + (size_t)j * n;
         double* w = Q + (size_t)(j + 1) * n;
         double* hcol = Hm + (size_t)j * (R + 1);
-        for (int idx = tid; idx < n; idx += blockDim.x) w[idx] = qj[idx] - a.tot[idx];
+        for (int idx = tid; idx < n; idx += blockDim.x) w[idx] = qj[idx] - tot[idx];
         for (int round = 0; round < 2; ++round) {
             __syncthreads();
             for (int i = wave; i <= j; i += nw) {
@@ -634,7 +662,7 @@ __device__ __forceinline__ void tail_gmres(const Args& a) {
     // phase 1: true residual at g
     double r2 = 0.0;
     for (int idx = tid; idx < n; idx += blockDim.x) {
-        const double u = a.tot[idx];
+        const double u = tot[idx];
         a.ud[idx] = u;
         const double r = a.vd[idx] + u - a.gd[idx];
         Q[idx] = r;
@@ -686,17 +714,17 @@ __device__ __forceinline__ void tail_gmres(const Args& a) {
 // Tail of one pass of the averaged iteration (Sec. 4.2): tot = u = (dF/dC)^T g.
 //   g+ = alpha (v + u) + (1 - alpha) g ; stop when ||g+ - g|| <= tol ||v||.
 // A non-finite step or 5 consecutive growing steps restart from g = v with alpha/2.
-__device__ __forceinline__ void tail_b2(const Args& a) {
+__device__ __forceinline__ void tail_b2(const Args& a, const double* tot) {
     const int kd = a.k * a.d;
     Ctrl* c = a.ctrl;
     if (c->b_mode == BWD_GMRES) {
-        tail_gmres(a);
+        tail_gmres(a, tot);
         return;
     }
     const double alpha = c->b_alpha;
     double d2 = 0.0;
     for (int idx = threadIdx.x; idx < kd; idx += blockDim.x) {
-        double u = a.tot[idx];
+        double u = tot[idx];
         a.ud[idx] = u;
         double g = a.gd[idx];
         double gn = alpha * (a.vd[idx] + u) + (1.0 - alpha) * g;
@@ -756,14 +784,14 @@ __device__ __forceinline__ void tail_b2(const Args& a) {
 // so that dF_jr/dc_ls = ([l == j] U[(j,r)][s] - T[(j,r)][(l,s)]) / (tau n_j).  Solves (I - dF/dC)^T g = v by
 // Gauss-Jordan elimination with partial pivoting in float64 (the workgroup's threads update the augmented
 // matrix in parallel) and leaves g, v and h/tau for the final pass.
-__device__ __forceinline__ void tail_bj(const Args& a) {
+__device__ __forceinline__ void tail_bj(const Args& a, const double* tot) {
     const int k = a.k, d = a.d, n = k * d, n1 = n + 1;
     Ctrl* c = a.ctrl;
     __shared__ double s_M[DENSE_MAX_KD * (DENSE_MAX_KD + 1)];
     __shared__ int s_piv, s_sing;
-    const double* T = a.tot;
-    const double* U = a.tot + n * n;
-    const double* V = a.tot + n * n + n * d;
+    const double* T = tot;
+    const double* U = tot + n * n;
+    const double* V = tot + n * n + n * d;
     // augmented matrix [I - J^T | v]: row (l,s), column (j,r)
     for (int t = threadIdx.x; t < n * n1; t += blockDim.x) {
         const int row = t / n1, col = t - row * n1;
@@ -848,12 +876,15 @@ __device__ __forceinline__ void tail_bj(const Args& a) {
     }
 }
 
-template <int PASS>
-__device__ __forceinline__ void grid_tail(const Args& a, int nacc, unsigned int seq) {
+template <int PASS, int NACC>
+__device__ __forceinline__ void grid_tail(const Args& a, unsigned int seq) {
+    constexpr int nacc = NACC;
     if (!arrive_last(a.tickets)) return;
     if (threadIdx.x <= TSHARDS) a.tickets[threadIdx.x * TSTRIDE] = 0u;  // every workgroup has arrived
     if (threadIdx.x == 0) a.ctrl->launch_seq = seq;
-    if (!reduce_stamped(a, nacc, seq)) {
+    // the totals stay in LDS: the tail that follows reads them without a trip through memory
+    __shared__ double s_tot[NACC];
+    if (!reduce_stamped(a, nacc, seq, s_tot)) {
         if (threadIdx.x == 0) {  // ends the host's loops; the call reports a device error
             a.ctrl->abort_flag = 1;
             a.ctrl->done = 1;
@@ -861,11 +892,11 @@ __device__ __forceinline__ void grid_tail(const Args& a, int nacc, unsigned int 
         }
         return;
     }
-    if (PASS == PASS_FWD) tail_forward(a);
-    if (PASS == PASS_FIN) tail_final(a);
-    if (PASS == PASS_B1) tail_b1(a);
-    if (PASS == PASS_B2) tail_b2(a);
-    if (PASS == PASS_BJ) tail_bj(a);
+    if (PASS == PASS_FWD) tail_forward(a, s_tot);
+    if (PASS == PASS_FIN) tail_final(a, s_tot);
+    if (PASS == PASS_B1) tail_b1(a, s_tot);
+    if (PASS == PASS_B2) tail_b2(a, s_tot);
+    if (PASS == PASS_BJ) tail_bj(a, s_tot);
 }
 
 }  // namespace idkm

@@ -439,10 +439,10 @@ template <int PASS>
 __global__ __launch_bounds__(WG) void lane_tail(const Args a) {
     if (PASS == PASS_FWD && a.ctrl->done) return;
     if (PASS == PASS_B2 && a.ctrl->b_done) return;
-    if (PASS == PASS_FWD) tail_forward(a);
-    if (PASS == PASS_FIN) tail_final(a);
-    if (PASS == PASS_B1) tail_b1(a);
-    if (PASS == PASS_B2) tail_b2(a);
+    if (PASS == PASS_FWD) tail_forward(a, a.tot);
+    if (PASS == PASS_FIN) tail_final(a, a.tot);
+    if (PASS == PASS_B1) tail_b1(a, a.tot);
+    if (PASS == PASS_B2) tail_b2(a, a.tot);
 }
 
 // The same tail with 16 wavefronts, for the minimal-residual solve at large k d: its inner products and vector
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(WG) void lane_tail(const Args a) {
 template <int UNUSED>
 __global__ __launch_bounds__(1024) void lane_tail_b2_wide(const Args a) {
     if (a.ctrl->b_done) return;
-    tail_b2(a);
+    tail_b2(a, a.tot);
 }
 
 }  // namespace idkm

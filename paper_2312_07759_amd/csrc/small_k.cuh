@@ -325,7 +325,7 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
         // row = accumulator, column = workgroup: the reducing workgroup reads 64 consecutive words per load
         st_word(reinterpret_cast<unsigned long long*>(a.partials) + (size_t)q * gridDim.x + blockIdx.x, pack_f(seq, (float)s));
     }
-    grid_tail<PASS>(a, NACC, seq);
+    grid_tail<PASS, NACC>(a, seq);
 }
 
 }  // namespace idkm
