@@ -83,7 +83,8 @@ def test_one_evaluation_of_F_and_one_JCT_pass(ctx, name, m, d, k, tau, dist):
 
 @pytest.mark.parametrize("path", ["stream", "persistent"])
 @pytest.mark.parametrize("dist", DISTS)
-@pytest.mark.parametrize("m,d,k", [(5_003, 1, 4), (4_001, 2, 8), (3_000, 4, 256), (2_000, 1, 64)])
+@pytest.mark.parametrize("m,d,k", [(5_003, 1, 4), (4_001, 2, 8), (3_000, 4, 256), (2_000, 1, 64), (9_001, 1, 16),
+                                   (3_001, 1, 2), (1_300_007, 1, 4)])
 def test_rows_whose_softmax_underflows_without_a_shift(ctx, m, d, k, dist, path):
     # A few vectors sit so far from every codeword that exp(-e/tau) underflows in float32 for the whole row;
     # the forward loop must then fall back to the shifted softmax for those rows.
