@@ -226,7 +226,9 @@ __device__ __forceinline__ bool gather_bcast(const PArgs& pa, unsigned int seq, 
 }
 
 // One pass over the workgroup's LDS tile.
-template <int K, int D, int DIST, int PASS>
+// SHARED: the workgroup shares its SIMDs with other teams' workgroups (batched launches); the hardware then
+// interleaves wavefronts, and short groups keep the registers low enough for four or five workgroups per compute unit.
+template <int K, int D, int DIST, int PASS, bool SHARED>
 __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const float* s_g, int64_t base, int cnt,
                                           const float* s_Cf, const float* s_Hs, const float* s_Ff,
                                           float (&acc)[SmallItem<K, D, DIST, PASS>::NACC]) {
@@ -246,7 +248,8 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
     // other vectors of the same lane, so vectors are taken in groups whose bodies the scheduler interleaves: in the
     // forward passes groups of UNR while they last, then groups of 4, then single vectors
     constexpr bool FWD_LIKE = (PASS == PASS_FWD || PASS == PASS_FIN);
-    constexpr int UNR = FWD_LIKE ? (K <= 4 ? 18 : (K == 8 ? 8 : 4)) : (K <= 4 ? 6 : (K == 8 ? 3 : 2));
+    constexpr int UNR = SHARED ? (K <= 4 ? 4 : 2)
+                               : (FWD_LIKE ? (K <= 4 ? 18 : (K == 8 ? 8 : 4)) : (K <= 4 ? 6 : (K == 8 ? 3 : 2)));
     auto one = [&](int it) {
         float w[D], g[D];
 #pragma unroll
@@ -286,7 +289,7 @@ constexpr int cw_per_reducer(int K, int D) {
 }
 
 // Forward solve (Alg. 1) and the evaluation at C*, in one launch.
-template <int K, int D, int DIST>
+template <int K, int D, int DIST, bool SHARED>
 __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa) {
     constexpr int KD = K * D;
     constexpr int ACCW = D + 1;
@@ -330,7 +333,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     float acc[NACC];
     while (!s_done) {
         IDKM_STAMP(0);
-        tile_pass<K, D, DIST, PASS_FWD>(a, s_tile, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
+        tile_pass<K, D, DIST, PASS_FWD, SHARED>(a, s_tile, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
         IDKM_STAMP(1);
         ++seq;
         publish_partials<NACC>(pa, seq, acc, xs);
@@ -401,7 +404,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     }
 
     // evaluation at C*: outputs, and n*, F* for the backward
-    tile_pass<K, D, DIST, PASS_FIN>(a, s_tile, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
+    tile_pass<K, D, DIST, PASS_FIN, SHARED>(a, s_tile, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
     ++seq;
     publish_partials<NACC>(pa, seq, acc, xs);
     for (int r = wg; r < R; r += pa.G) {
@@ -444,7 +447,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
 
 // Backward (Alg. 2 per-layer steps): v, the averaged fixed-point iteration of
 // Sec. 4.2 for g (skipped for JFB), and dW, in one launch.
-template <int K, int D, int DIST>
+template <int K, int D, int DIST, bool SHARED>
 __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa) {
     constexpr int KD = K * D;
     constexpr int KPR = (8 / D) > K ? K : (8 / D);  // codewords per reducer: 8 words of D components
@@ -511,7 +514,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
             // one pass accumulates v and the sums T, U of dF/dC* (layout as in the stream path's tail_bj); workgroup 0
             // adds them over the team, solves (I - dF/dC*)^T g = v by Gauss-Jordan elimination and broadcasts h/tau
             float accj[NBJ];
-            tile_pass<K, D, DIST, PASS_BJ>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, accj);
+            tile_pass<K, D, DIST, PASS_BJ, SHARED>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, accj);
             ++seq;
             publish_partials<NBJ>(pa, seq, accj, xs);
             if (wg == 0) {
@@ -579,7 +582,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     }
     if (!dense_done) {
     // B1: v = dL/dC* with W fixed; the solve starts at g = v
-    tile_pass<K, D, DIST, PASS_B1>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
+    tile_pass<K, D, DIST, PASS_B1, SHARED>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
     ++seq;
     publish_partials<KD>(pa, seq, acc, xs);
     for (int r = wg; r < R; r += pa.G) {
@@ -621,7 +624,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     __syncthreads();
 
     while (!s_done) {
-        tile_pass<K, D, DIST, PASS_B2>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
+        tile_pass<K, D, DIST, PASS_B2, SHARED>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
         ++seq;
         publish_partials<KD>(pa, seq, acc, xs);
         const double alpha = s_alpha;
@@ -703,7 +706,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     }
 
     // B3: dW = direct + (dF/dW)^T g
-    tile_pass<K, D, DIST, PASS_B3>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, reinterpret_cast<float(&)[1]>(acc[0]));
+    tile_pass<K, D, DIST, PASS_B3, SHARED>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, reinterpret_cast<float(&)[1]>(acc[0]));
     if (dense_done) {
         if (wg == 0 && tid < KD) {
             a.gd[tid] = s_g[tid];
@@ -738,14 +741,14 @@ __global__ __launch_bounds__(PT) void persist_fwd(const Args a, const PArgs pa_i
     PArgs pa = pa_in;
     pa.wg = blockIdx.x;
     pa.G = gridDim.x;
-    persist_fwd_body<K, D, DIST>(a, pa);
+    persist_fwd_body<K, D, DIST, false>(a, pa);
 }
 template <int K, int D, int DIST>
 __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa_in) {
     PArgs pa = pa_in;
     pa.wg = blockIdx.x;
     pa.G = gridDim.x;
-    persist_bwd_body<K, D, DIST>(a, pa);
+    persist_bwd_body<K, D, DIST, false>(a, pa);
 }
 
 // Several independent problems of one shape (the layers of Alg. 2's loops) in one launch: item_of_wg maps a
@@ -757,7 +760,7 @@ __global__ __launch_bounds__(PT) void persist_fwd_batch(const BatchItem* items, 
     PArgs pa = it.p;
     pa.wg = (int)blockIdx.x - it.wg_begin;
     pa.G = it.wg_count;
-    persist_fwd_body<K, D, DIST>(a, pa);
+    persist_fwd_body<K, D, DIST, true>(a, pa);
 }
 template <int K, int D, int DIST>
 __global__ __launch_bounds__(PT) void persist_bwd_batch(const BatchItem* items, const unsigned short* item_of_wg) {
@@ -766,7 +769,7 @@ __global__ __launch_bounds__(PT) void persist_bwd_batch(const BatchItem* items, 
     PArgs pa = it.p;
     pa.wg = (int)blockIdx.x - it.wg_begin;
     pa.G = it.wg_count;
-    persist_bwd_body<K, D, DIST>(a, pa);
+    persist_bwd_body<K, D, DIST, true>(a, pa);
 }
 
 }  // namespace idkm
