@@ -89,6 +89,11 @@ idkm_status idkm_set_path(idkm_ctx* ctx, idkm_path path);
  * wait expires all workgroups leave the kernel and the call returns IDKM_ERR_DEVICE; the context stays usable.
  * A limit of 0 makes the first unsuccessful poll give up (used to exercise that path). */
 idkm_status idkm_set_spin_limit(idkm_ctx* ctx, uint32_t polls);
+/* Test support.  The words that cross workgroups are stamped with 32-bit sequence numbers that the context counts up
+ * over its lifetime (one per exchange of the persistent kernels, one per launch of the stream path); shortly before
+ * they would wrap the library clears its exchange buffers and starts over.  This call advances both counters by n
+ * (saturating just below the wrap), so that a test can cross that point without billions of calls. */
+idkm_status idkm_advance_sequence(idkm_ctx* ctx, uint32_t n, void* hip_stream);
 /* Longest Krylov basis IDKM_BWD_GMRES keeps before it restarts from the current residual: 1 .. 256, default 64
  * (the basis never exceeds k d).  The workspace holds (basis + 1) k d doubles. */
 idkm_status idkm_set_gmres_basis(idkm_ctx* ctx, int32_t basis);

@@ -22,7 +22,7 @@ BWD_IMPLICIT, BWD_JFB, BWD_DENSE, BWD_GMRES = 0, 1, 2, 3
 PATH_AUTO, PATH_STREAM, PATH_PERSISTENT = 0, 1, 2
 
 EXPORTS = ["idkm_version", "idkm_limits", "idkm_status_string", "idkm_create", "idkm_destroy", "idkm_last_error",
-           "idkm_set_path", "idkm_set_spin_limit", "idkm_set_gmres_basis", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT",
+           "idkm_set_path", "idkm_set_spin_limit", "idkm_set_gmres_basis", "idkm_advance_sequence", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT",
            "idkm_calibrate", "idkm_code_bits", "idkm_code_words", "idkm_pack_codes", "idkm_unpack_quantize",
            "idkm_batch_create", "idkm_batch_destroy", "idkm_batch_last_error", "idkm_batch_launches",
            "idkm_batch_context", "idkm_batch_forward", "idkm_batch_backward"]
@@ -83,6 +83,8 @@ def load_library():
     lib.idkm_set_path.restype = C.c_int
     lib.idkm_set_spin_limit.argtypes = [vp, C.c_uint32]
     lib.idkm_set_spin_limit.restype = C.c_int
+    lib.idkm_advance_sequence.argtypes = [vp, C.c_uint32, vp]
+    lib.idkm_advance_sequence.restype = C.c_int
     lib.idkm_set_gmres_basis.argtypes = [vp, C.c_int32]
     lib.idkm_set_gmres_basis.restype = C.c_int
     lib.idkm_forward.argtypes = [vp, f32p, C.c_int64, C.c_int32, f32p, C.c_int32, C.c_float, C.c_float, C.c_int32,
@@ -183,6 +185,9 @@ class Context:
 
     def set_path(self, path: int):
         self._check(self._lib.idkm_set_path(self._h, int(path)))
+
+    def advance_sequence(self, n: int):
+        self._check(self._lib.idkm_advance_sequence(self._h, int(n), _stream()))
 
     def set_gmres_basis(self, basis: int):
         self._check(self._lib.idkm_set_gmres_basis(self._h, int(basis)))

@@ -88,6 +88,7 @@ __global__ void k_init_backward(Args a, int mode, double tol, int max_iter, doub
 }
 
 __global__ void k_reset_launch_seq(Ctrl* c) { c->launch_seq = 0; }
+__global__ void k_add_launch_seq(Ctrl* c, unsigned int n) { c->launch_seq += n; }
 
 // Hs = (g / n) / tau from a caller-supplied float32 cotangent; arms one raw (dF/dC)^T pass.
 __global__ void k_set_g(Args a, const float* g) {
@@ -643,6 +644,20 @@ idkm_status idkm_set_gmres_basis(idkm_ctx* ctx, int32_t basis) {
     if (!ctx) return IDKM_ERR_INVALID_ARG;
     if (basis < 1 || basis > GM_RMAX) return fail(ctx, IDKM_ERR_INVALID_ARG, "basis must be in [1, 256]");
     ctx->gmres_basis = basis;
+    return IDKM_OK;
+}
+
+idkm_status idkm_advance_sequence(idkm_ctx* ctx, uint32_t n, void* hip_stream) {
+    idkm_status st = check_common(ctx);
+    if (st != IDKM_OK) return st;
+    // as if n more exchanges (persistent path) and n more launches (stream path) had been made
+    const uint64_t sb = (uint64_t)ctx->seq_base + n;
+    ctx->seq_base = sb > 0xfffffff0ull ? 0xfffffff0u : (unsigned int)sb;
+    const uint64_t sl = (uint64_t)ctx->stream_launches + n;
+    const unsigned int capped = sl > 0x7ffeff00ull ? 0x7ffeff00u : (unsigned int)sl;
+    hipLaunchKernelGGL(k_add_launch_seq, dim3(1), dim3(1), 0, (hipStream_t)hip_stream, ctx->ctrl, capped - ctx->stream_launches);
+    HIP_TRY(ctx, hipGetLastError());
+    ctx->stream_launches = capped;
     return IDKM_OK;
 }
 

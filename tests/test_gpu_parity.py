@@ -449,3 +449,30 @@ def test_autograd_front_end_gives_the_oracle_gradient_of_a_loss(ctx):
     assert rel(Wt.grad.cpu().numpy(), ref["dW"]) < TOL_GRAD
     assert not Cstar.requires_grad
     layer.close()
+
+
+@pytest.mark.parametrize("path", ["stream", "persistent"])
+@pytest.mark.parametrize("shape", [(30_011, 1, 4), (4_003, 4, 256)])
+def test_results_do_not_change_when_the_sequence_numbers_wrap(path, shape):
+    """The stamps of the exchanged words are 32-bit counters; just before they wrap the library clears its buffers and
+    starts over.  The counters are advanced to that point and the same solve is repeated across it."""
+    m, d, k = shape
+    W, C0, G = _case(m, d, k, seed=4242)
+    c = binding.Context(0)
+    c.set_path(binding.PATH_STREAM if path == "stream" else binding.PATH_PERSISTENT)
+    Wd, Cd, Gd = dev(W), dev(C0), dev(G)
+    tau = 0.3 if d == 1 else 1.0
+
+    def solve():
+        f = c.forward(Wd, Cd, tau, 0.0, 20, wl.DIST_SQL2)
+        b = c.backward(Gd, binding.BWD_IMPLICIT, tol=0.0, max_iter=15)
+        return f["C"].clone(), f["Wq"].clone(), b["dW"].clone(), f["info"].iters, b["info"].iters
+
+    first = solve()
+    c.advance_sequence(0xFFFFFFFF)          # saturates a few hundred steps below the wrap
+    for _ in range(40):                     # 40 x (21 + 17) exchanges or launches: well across it
+        again = solve()
+        assert again[3:] == first[3:]
+        for x, y in zip(first[:3], again[:3]):
+            assert torch.equal(x, y)
+    c.close()
