@@ -4,11 +4,11 @@
 // traffic per pass is one two-hop exchange of O(k d) numbers.
 //
 // Exchange (per pass over W):
-//   hop 1  every workgroup stores its K (D+1) partial sums into its own column of
+//   hop 1  every workgroup stores its K (D+1) partial sums into its own line of
 //          buf1 as 64-bit words {sequence number, float32 value};
 //          the first R workgroups are "reducers": reducer r owns a slice of the
-//          codewords, reads that slice's rows (one word per workgroup, coalesced)
-//          (thread t <-> workgroup t), adds them in a fixed order in float64 and
+//          codewords, reads that slice of every workgroup's line (consecutive
+//          lanes read consecutive words), adds them in a fixed order in float64 and
 //          applies the O(k d) update (centre update of Alg. 1, or the averaged
 //          step of Sec. 4.2) to its slice;
 //   hop 2  reducers store the float32 values the next pass needs (codewords, or
@@ -37,7 +37,7 @@ struct PResult {
 };
 
 struct PArgs {
-    unsigned long long* buf1;  // [2][XLINE][PT] stamped partial sums, word (accumulator, workgroup)
+    unsigned long long* buf1;  // [2][PT][XLINE] stamped partial sums, word (workgroup, accumulator)
     unsigned long long* buf2;  // [2][XBCAST] stamped broadcast values
     unsigned int seq_base;     // sequence numbers seq_base+1 ... are used by this launch; seq_base+1 is its id
     unsigned int spin_limit;   // polls before a wait gives up
@@ -85,7 +85,7 @@ struct BatchItem {
 template <int NACC>
 struct XShared {
     float rpart[pow2_at_least(NACC)][PT / 16];  // partial sums of every row of 16 lanes, [accumulator][row]
-    float red[8][PT];                // reducer: words of every workgroup, transposed
+    double red2[PT];                 // reducer: per-thread sums (thread t: word t mod WPR, workgroups t/WPR + k PT/WPR)
     double tot[8];                   // reducer: totals of its slice
     unsigned int bc[XBCAST];         // payloads of the broadcast words
     float own[XLINE];                // this workgroup's own partial sums (read back directly by a team of one)
@@ -118,8 +118,8 @@ __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int s
                     ((double)xs.rpart[tid][4 * u + 2] + (double)xs.rpart[tid][4 * u + 3]);
         const double s = (c4[0] + c4[1]) + (c4[2] + c4[3]);
         xs.own[tid] = (float)s;
-        // row = accumulator, column = workgroup: a reducer's wavefront then reads 64 consecutive words per load
-        st_word(&pa.buf1[((size_t)(seq & 1u) * XLINE + tid) * PT + pa.wg], pack_f(seq, (float)s));
+        // a workgroup's words lie together: one store transaction per workgroup and pass
+        st_word(&pa.buf1[((size_t)(seq & 1u) * PT + pa.wg) * XLINE + tid], pack_f(seq, (float)s));
     }
     IDKM_SUB(3);
 }
@@ -153,30 +153,44 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
     const int tid = threadIdx.x;
     IDKM_SUB(4);
     const int G = pa.G;
-    float f[WPR];
-#pragma unroll
-    for (int q = 0; q < WPR; ++q) f[q] = 0.f;
+    constexpr int GPT = PT / WPR;                 // workgroups one load instruction of the whole workgroup covers
+    constexpr int NL = (PT + GPT - 1) / GPT;      // loads per thread that cover PT workgroups
+    constexpr int PER = (GPT + 31) / 32;          // per-thread sums one thread of the second stage adds
+    // every workgroup's words lie together (one store transaction per workgroup); the reducer reads them as one flat
+    // array, thread t taking word t mod WPR of workgroups t/WPR, t/WPR + GPT, ...: consecutive lanes, consecutive words
+    const int q = tid % WPR, g0 = tid / WPR;
+    double s = 0.0;
     bool aborted = false;
     if (G == 1) {
         // a team of one has nobody to wait for: its partial sums are the totals
         __syncthreads();
-        if (tid == 0) {
+        if (tid < WPR) s = (double)xs.own[first + tid];
+    } else if (g0 < GPT && g0 < G) {
+        const unsigned long long* src = pa.buf1 + ((size_t)(seq & 1u) * PT + g0) * XLINE + first + q;
+        const int nv = (G - g0 + GPT - 1) / GPT;  // <= NL
+        unsigned int spins = 0;
+        for (;;) {
+            unsigned long long w[NL];
 #pragma unroll
-            for (int q = 0; q < WPR; ++q) f[q] = xs.own[first + q];
-        }
-    } else if (tid < G) {
-        const unsigned long long* src = pa.buf1 + ((size_t)(seq & 1u) * XLINE + first) * PT + tid;
-        unsigned long long w[WPR];
-        if (poll_words<WPR>(pa, src, PT, seq, w)) {
+            for (int u = 0; u < NL; ++u) w[u] = (u < nv) ? ld_word(src + (size_t)u * GPT * XLINE) : pack_f(seq, 0.f);
+            bool ok = true;
 #pragma unroll
-            for (int q = 0; q < WPR; ++q) f[q] = __uint_as_float((unsigned int)w[q]);
-        } else {
-            aborted = true;
+            for (int u = 0; u < NL; ++u) ok = ok && ((unsigned int)(w[u] >> 32) == seq);
+            if (ok) {
+#pragma unroll
+                for (int u = 0; u < NL; ++u) s += (double)__uint_as_float((unsigned int)w[u]);
+                break;
+            }
+            ++spins;
+            if (spins > pa.spin_limit ||
+                ((spins & 31u) == 0u && __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u)) {
+                aborted = true;
+                break;
+            }
         }
     }
     IDKM_SUB(5);
-#pragma unroll
-    for (int q = 0; q < WPR; ++q) xs.red[q][tid] = f[q];
+    xs.red2[tid] = s;
     if (aborted) {
         xs.abort = 1;
         __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -187,15 +201,18 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
 #endif
     if (xs.abort) return false;
     IDKM_SUB(6);
-    // thread (q, part) adds workgroups part*8 .. part*8+7 of word q, then a fixed 32-lane DPP network
-    const int q = tid >> 5, part = tid & 31;
-    double s = 0.0;
-    if (q < WPR) {
+    // thread (qq, part) adds PER consecutive per-thread sums of word qq, then a fixed 32-lane DPP network
+    const int qq = tid >> 5, part = tid & 31;
+    double t = 0.0;
+    if (qq < WPR) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += (double)xs.red[q][part * 8 + u];
+        for (int v = 0; v < PER; ++v) {
+            const int g = part * PER + v;
+            if (g < GPT) t += xs.red2[g * WPR + qq];
+        }
     }
-    s = half_sum_d_dpp(s);
-    if (q < WPR && part == 31) xs.tot[q] = s;
+    t = half_sum_d_dpp(t);
+    if (qq < WPR && part == 31) xs.tot[qq] = t;
     __syncthreads();
     IDKM_SUB(7);
     return true;
