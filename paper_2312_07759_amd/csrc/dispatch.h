@@ -24,11 +24,13 @@ typedef void (*PersistBatchFn)(const BatchItem*, const unsigned short*);
 struct PersistFns {
     PersistFn one = nullptr;
     PersistBatchFn batch = nullptr;
+    bool matrix = false;  // forward loop on the matrix cores: 512 threads, tile padded by 16 vectors plus one float per vector
 };
 // Persistent forward / backward solve for the lane<->vector family; empty if K (D+1) > 32.
 PersistFns persist_kernel(int K, int D, int dist, bool bwd);
 // Persistent solve for the lane<->codeword family (launch with 1024 threads); empty if not instantiated.
-PersistFns persist_lane_kernel(int KPL, int D, int dist, bool bwd);
+// matrix: prefer the matrix-core forward loop where one exists (d = 4, squared energy, k <= 256).
+PersistFns persist_lane_kernel(int KPL, int D, int dist, bool bwd, bool matrix);
 
 // b-bit code stream of the hard assignments and the reconstruction q(W, C) from it (codes.hip).
 void launch_pack_codes(const int32_t* assign, int64_t m, int bits, uint32_t* words, int64_t nwords, hipStream_t s);

@@ -28,9 +28,9 @@ KernelFn small_kernel(int K, int D, int dist, int pass) {
     return dist == DIST_L2 ? small_kernel_0(K, D, pass) : small_kernel_1(K, D, pass);
 }
 PersistFns persist_lane_kernel_0(int, int, bool);
-PersistFns persist_lane_kernel_1(int, int, bool);
-PersistFns persist_lane_kernel(int KPL, int D, int dist, bool bwd) {
-    return dist == DIST_L2 ? persist_lane_kernel_0(KPL, D, bwd) : persist_lane_kernel_1(KPL, D, bwd);
+PersistFns persist_lane_kernel_1(int, int, bool, bool);
+PersistFns persist_lane_kernel(int KPL, int D, int dist, bool bwd, bool matrix) {
+    return dist == DIST_L2 ? persist_lane_kernel_0(KPL, D, bwd) : persist_lane_kernel_1(KPL, D, bwd, matrix);
 }
 KernelFn lane_kernel(int KPL, int D, int dist, int pass) {
     return dist == DIST_L2 ? lane_kernel_0(KPL, D, pass) : lane_kernel_1(KPL, D, pass);
@@ -338,22 +338,31 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
         int kpl = (k + 63) / 64, p = 1;
         while (p < kpl) p <<= 1;
         if (d > 4 || p * d > 16 || p * (d + 1) > 24) return false;
-        const PersistFns fl = persist_lane_kernel(p, d, ctx->dist, bwd);
-        pp->fn = fl.one;
-        pp->fn_batch = fl.batch;
-        if (!pp->fn) return false;
         int64_t g = (m + 255) / 256;  // at least 16 vectors per wavefront before adding workgroups
         if (g < 1) g = 1;
         if (g > ctx->num_cu) g = ctx->num_cu;
         if (g > PT) g = PT;
         int64_t per = (m + g - 1) / g;
         per = (per + 3) / 4 * 4;
-        const size_t lds = (size_t)per * d * sizeof(float) * (bwd ? 2 : 1);
+        PersistFns fl = persist_lane_kernel(p, d, ctx->dist, bwd, true);
+        size_t lds = (size_t)per * d * sizeof(float) * (bwd ? 2 : 1);
+        if (fl.matrix) {
+            // tile padded by 16 vectors, then one float per vector; the kernel keeps 40 KB more static LDS.
+            // A tile too large for that goes to the vector-ALU kernel.
+            const size_t lds_m = (size_t)(per + 16) * (d + 1) * sizeof(float);
+            if (lds_m <= LANE_TILE_MAX - 40 * 1024)
+                lds = lds_m;
+            else
+                fl = persist_lane_kernel(p, d, ctx->dist, bwd, false);
+        }
+        pp->fn = fl.one;
+        pp->fn_batch = fl.batch;
+        if (!pp->fn) return false;
         if (lds > LANE_TILE_MAX) return false;
         pp->grid = (int)((m + per - 1) / per);
         pp->per = (int)per;
         pp->lds = lds;
-        pp->threads = LT;
+        pp->threads = fl.matrix ? MT : LT;
         pp->lane = true;
         return true;
     }

@@ -1,0 +1,208 @@
+// Matrix-core form of the forward loop for d = 4 and the squared energy (lane<->codeword family, k <= 256).
+//
+// In scaled coordinates t = s (w - c), s^2 = log2(e)/tau, the exponent of a weight of the row softmax
+// (Eq. "aterms") is  x_ij = -|t_ij|^2 = -s^2|w_i|^2 + 2 s^2 w_i.c_j - s^2|c_j|^2 :  a 16 x 16 tile of it is one
+// v_mfma_f32_16x16x4_f32 (the inner dimension is d = 4), with the vectors' squared norms as its additive operand and
+// the codewords' added to the result.  The three terms cancel, so w and c are first moved by a common reference
+// point mu inside the data (the mean of the initial codewords; the energy does not change): the rounding error of
+// x is then a few float32 ulps of s^2 times the squared spread of the data, not of its distance from the origin.
+// The first-moment sums of the M-step (Eq. "centers"),  s_j = sum_i a_ij w_i,  are outer products a_i (x) w_i:
+// v_mfma_f32_4x4x1 takes sixteen of them (4 codewords x 4 coordinates each) per instruction.  What stays on the
+// vector ALU per (vector, codeword) pair is the additive operand, exp2, the row sum and the mass n_j: 5 issue
+// slots instead of about 19.
+//
+// Operand layouts (lane l of the wavefront, q = l / 16):
+//   16x16x4:  A[i][kk] in lane i + 16 kk,  B[kk][j] in lane j + 16 kk,  D[i][j] in lane j + 16 (i / 4), register i % 4
+//   4x4x1  :  block = l / 4:  A[i] in lane 4 block + i,  B[j] in lane 4 block + j,  D[i][j] in lane 4 block + j, register i
+// so a lane that holds the weights of codeword 16 b + l % 16 for vectors 4 q + r (register r of the first product)
+// feeds register r straight into the second as the A operand of block l / 4, whose B operand is coordinate l % 4 of
+// vector 4 q + r.
+#pragma once
+#include "common.cuh"
+
+namespace idkm {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float row16_sum(float x) {
+    x += dpp_f<0xB1, 0xf>(0.f, x);   // quad_perm [1,0,3,2]
+    x += dpp_f<0x4E, 0xf>(0.f, x);   // quad_perm [2,3,0,1]
+    x += dpp_f<0x141, 0xf>(0.f, x);  // row_half_mirror
+    x += dpp_f<0x140, 0xf>(0.f, x);  // row_mirror
+    return x;                        // every lane of the row holds the row's total
+}
+__device__ __forceinline__ float row16_max(float x) {
+    const float ninf = -__builtin_inff();
+    x = fmaxf(x, dpp_f<0xB1, 0xf>(ninf, x));
+    x = fmaxf(x, dpp_f<0x4E, 0xf>(ninf, x));
+    x = fmaxf(x, dpp_f<0x141, 0xf>(ninf, x));
+    x = fmaxf(x, dpp_f<0x140, 0xf>(ninf, x));
+    return x;
+}
+
+// Per-wavefront state of one forward pass: NB = 4 KPL blocks of 16 codewords.
+template <int KPL>
+struct MfmaFwd {
+    static constexpr int NB = 4 * KPL;
+    static constexpr int TAB_STRIDE = 16 * NB + 16;  // entries per coordinate; the pad of 128 bytes spreads the four
+                                                     // lane groups of a wavefront over different LDS banks
+    f32x4 sacc[NB];  // first moments: register i = codeword 16 b + 4 ((l / 4) % 4) + i, coordinate l % 4, partial over q
+    float nacc[NB];  // masses: codeword 16 b + l % 16, partial over q
+    // codeword operands of the energy product, in LDS (they are the same for every step, and 32 registers more per
+    // lane would not fit): entry 16 b of `tab` = {2 s (c_j - mu)[l / 16], -s^2 |c_j - mu|^2}, j = 16 b + l % 16
+    const float2* tab;
+    float mu_q;  // coordinate l / 16 of the reference point
+
+    __device__ __forceinline__ void init(const float2* s_tab, const float* s_mu) {
+        const int lane = threadIdx.x & 63;
+        tab = s_tab + (lane >> 4) * TAB_STRIDE + (lane & 15);
+        mu_q = s_mu[lane >> 4];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            nacc[b] = 0.f;
+            sacc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+    // The table for init(): s_tab[kk][j] for the 16 NB (padded) codewords; a padding codeword sits at -1e30, so its
+    // weight is exactly zero.  Called by the whole workgroup (NT threads); the caller synchronises.
+    template <int NT>
+    static __device__ __forceinline__ void fill_table(float2* s_tab, int k, const float* Cf, const float* s_mu,
+                                                      float escale) {
+        for (int idx = threadIdx.x; idx < 4 * TAB_STRIDE; idx += NT) {
+            const int kk = idx / TAB_STRIDE, j = idx - kk * TAB_STRIDE;
+            float2 e = {0.f, -1e30f};
+            if (j < k) {
+                float n2 = 0.f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float c = (Cf[j * 4 + r] - s_mu[r]) * escale;
+                    n2 = fmaf(c, c, n2);
+                }
+                e.x = 2.f * escale * (Cf[j * 4 + kk] - s_mu[kk]);
+                e.y = -n2;
+            }
+            s_tab[idx] = e;
+        }
+    }
+
+    // Vectors v0 .. v0+15 of the tile (s_w: [.][4] float32, s_wn: -s^2|w - mu|^2 per vector); those at or beyond vend
+    // contribute nothing.  Both arrays are readable (finite values) up to index v0 + 15.
+    __device__ __forceinline__ void step(const float* s_w, const float* s_wn, int v0, int vend, float escale) {
+        const int lane = threadIdx.x & 63, j0 = lane & 15, q = lane >> 4;
+        // the table entries are read anew in every step (kept in registers across steps they would spill)
+        asm volatile("" ::: "memory");
+        const float aw = (s_w[(v0 + j0) * 4 + q] - mu_q) * escale;
+        const f32x4 wn = *reinterpret_cast<const f32x4*>(&s_wn[v0 + 4 * q]);
+        float x[NB][4];
+        auto exponents = [&]() {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                // the vectors' norms enter as the additive operand (one register quad for all blocks), the
+                // codeword's norm is added to the result
+                const float2 cj = tab[16 * b];
+                const f32x4 e = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, cj.x, wn, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) x[b][r] = e[r] + cj.y;
+            }
+        };
+        exponents();
+        // exp2 of a non-positive number cannot overflow; the row shift of the softmax is only needed when the whole
+        // row underflows (a vector many kernel widths from every codeword), which the unshifted row sum shows
+        float S[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                x[b][r] = fast_exp2(x[b][r]);
+                S[r] += x[b][r];
+            }
+        }
+        bool under = false;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            S[r] = row16_sum(S[r]);
+            under = under || (S[r] < 7.9e-31f);  // below 2^-100
+        }
+        if (__builtin_amdgcn_ballot_w64(under) != 0ull) {
+            exponents();
+            float mx[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                mx[r] = x[0][r];
+#pragma unroll
+                for (int b = 1; b < NB; ++b) mx[r] = fmaxf(mx[r], x[b][r]);
+                mx[r] = row16_max(mx[r]);
+                S[r] = 0.f;
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    x[b][r] = fast_exp2(x[b][r] - mx[r]);
+                    S[r] += x[b][r];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[r] = row16_sum(S[r]);
+        }
+        // the normalisation 1/S_i joins the vector (first moments) and the mass FMA
+        float rinv[4], bw[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int v = v0 + 4 * q + r;
+            rinv[r] = (v < vend) ? fast_rcp(S[r]) : 0.f;
+            bw[r] = s_w[v * 4 + (lane & 3)] * rinv[r];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                nacc[b] = fmaf(x[b][r], rinv[r], nacc[b]);
+                sacc[b] = __builtin_amdgcn_mfma_f32_4x4x1f32(x[b][r], bw[r], sacc[b], 0, 0, 0);
+            }
+        }
+    }
+};
+
+// One forward pass over the workgroup's tile: every wavefront takes an equal share of whole 16-vector steps.
+template <int KPL, int NT>
+__device__ __forceinline__ void mfma_tile_pass(MfmaFwd<KPL>& st, const float* s_w, const float* s_wn, int cnt,
+                                               float escale) {
+    constexpr int NW = NT / 64;
+    const int wave = threadIdx.x >> 6;
+    int share = (cnt + NW - 1) / NW;
+    share = (share + 15) & ~15;
+    const int w0 = wave * share;
+    const int w1 = (w0 + share < cnt) ? w0 + share : cnt;
+    for (int v = w0; v < w1; v += 16) st.step(s_w, s_wn, v, w1, escale);
+}
+
+// Workgroup totals of the accumulators as float32 per wavefront in s_part[NT / 64][64 KPL 5], word (codeword, n | s_r).
+template <int KPL, int NT>
+__device__ __forceinline__ void mfma_collect(const MfmaFwd<KPL>& st, float* s_part) {
+    constexpr int NB = 4 * KPL, ROW = 64 * KPL * 5;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q = lane >> 4, j0 = lane & 15, t = (lane >> 2) & 3, col = lane & 3;
+    float* out = s_part + wave * ROW;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        // the four lane groups q hold partial sums over different vectors: fixed order (q, q^1), then (., q^2)
+        float n = st.nacc[b];
+        n += __shfl_xor(n, 16);
+        n += __shfl_xor(n, 32);
+        float s[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            s[i] = st.sacc[b][i];
+            s[i] += __shfl_xor(s[i], 16);
+            s[i] += __shfl_xor(s[i], 32);
+        }
+        if (q == 0) {
+            out[(16 * b + j0) * 5] = n;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) out[(16 * b + 4 * t + i) * 5 + 1 + col] = s[i];
+        }
+    }
+}
+
+}  // namespace idkm

@@ -11,12 +11,15 @@
 #pragma once
 #include "common.cuh"
 #include "lane_k.cuh"
+#include "mfma_lane.cuh"
 #include "persist_small.cuh"
 
 namespace idkm {
 
 constexpr int LT = 1024;          // threads per workgroup (16 wavefronts, 4 per SIMD)
 constexpr int LWAVES = LT / 64;
+constexpr int MT = 512;           // threads per workgroup of the matrix-core forward kernel (2 wavefronts per SIMD:
+                                  // its accumulators and one 16 x 256 tile of weights need ~200 registers per lane)
 
 struct LShared {
     float red[8][PT];     // reducer: one codeword's words of every workgroup (at most PT workgroups)
@@ -50,6 +53,7 @@ __device__ __forceinline__ void raise_abort(const PArgs& pa, LShared& ls) {
 }
 
 // Sum of one float64 per thread over the workgroup, fixed order, returned to every thread.
+template <int NT = LT>
 __device__ __forceinline__ double block_sum_fixed(double x, LShared& ls) {
     x = wave_sum_d_dpp(x);
     if ((threadIdx.x & 63) == 0) ls.wsum[threadIdx.x >> 6] = x;
@@ -57,7 +61,7 @@ __device__ __forceinline__ double block_sum_fixed(double x, LShared& ls) {
     if (threadIdx.x == 0) {
         double s = 0.0;
 #pragma unroll
-        for (int w = 0; w < LWAVES; ++w) s += ls.wsum[w];
+        for (int w = 0; w < NT / 64; ++w) s += ls.wsum[w];
         ls.scalar = s;
     }
     __syncthreads();
@@ -65,11 +69,11 @@ __device__ __forceinline__ double block_sum_fixed(double x, LShared& ls) {
 }
 
 // Workgroup partial of the lane accumulators (wavefronts add one after the other, float64) and hop-1 store.
-template <int NA, int ACCW>
+template <int NA, int ACCW, int NT = LT>
 __device__ __forceinline__ void publish_lane(const PArgs& pa, unsigned int seq, const float (&acc)[NA], int k,
                                              double (*s_acc)[NA]) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int wv = 0; wv < LWAVES; ++wv) {
+    for (int wv = 0; wv < NT / 64; ++wv) {
         if (wave == wv) {
 #pragma unroll
             for (int q = 0; q < NA; ++q) {
@@ -83,7 +87,7 @@ __device__ __forceinline__ void publish_lane(const PArgs& pa, unsigned int seq, 
     }
     const int nacc = k * ACCW;
     unsigned long long* dst = pa.buf1 + ((size_t)(seq & 1u) * pa.G + pa.wg) * nacc;
-    for (int idx = tid; idx < nacc; idx += LT) {
+    for (int idx = tid; idx < nacc; idx += NT) {
         const int j = idx / ACCW, comp = idx - j * ACCW;
         st_word(&dst[idx], pack_f(seq, (float)s_acc[j & 63][(j >> 6) * ACCW + comp]));
     }
@@ -143,11 +147,12 @@ __device__ __forceinline__ bool reduce_lane(const PArgs& pa, unsigned int seq, i
 }
 
 // hop 2: every thread polls words tid, tid+LT, ... < nwords of buf2 into dst (LDS).
+template <int NT = LT>
 __device__ __forceinline__ bool gather_lane(const PArgs& pa, unsigned int seq, int nwords, int stride2,
                                             unsigned int* dst, LShared& ls) {
     const unsigned long long* src = pa.buf2 + (size_t)(seq & 1u) * stride2;
     bool ok = true;
-    for (int i = threadIdx.x; i < nwords; i += LT) {
+    for (int i = threadIdx.x; i < nwords; i += NT) {
         unsigned int p = 0;
         ok = ok && poll_word(pa, src + i, seq, &p);
         dst[i] = p;
@@ -157,12 +162,12 @@ __device__ __forceinline__ bool gather_lane(const PArgs& pa, unsigned int seq, i
     return ls.abort == 0;
 }
 
-template <int KPL, int D, int DIST, int PASS>
+template <int KPL, int D, int DIST, int PASS, int NT = LT>
 __device__ __forceinline__ void lane_tile_pass(const Args& a, LaneWave<KPL, D, DIST, PASS>& st, const float* s_w,
                                                const float* s_g, int64_t base, int cnt) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // every wavefront takes an equal contiguous share of the tile
-    const int share = (cnt + LWAVES - 1) / LWAVES;
+    const int share = (cnt + NT / 64 - 1) / (NT / 64);
     const int w0 = wave * share;
     const int w1 = (w0 + share < cnt) ? w0 + share : cnt;
     for (int b = w0; b < w1; b += 64) {
@@ -177,9 +182,22 @@ __device__ __forceinline__ void lane_tile_pass(const Args& a, LaneWave<KPL, D, D
     }
 }
 
-// Forward solve (Alg. 1) and the evaluation at C*.
-template <int KPL, int D, int DIST>
+#ifdef IDKM_TRACE
+#define IDKM_LSTAMP(slot)                                                                        \
+    do {                                                                                         \
+        if (pa.trace && threadIdx.x == 0 && s_iters == 20 && pa.wg < 256)                        \
+            pa.trace[2 * 64 * 8 + pa.wg * 8 + (slot)] = (long long)wall_clock64();               \
+    } while (0)
+#else
+#define IDKM_LSTAMP(slot)
+#endif
+
+// Forward solve (Alg. 1) and the evaluation at C*.  MFMA: the loop's passes run on the matrix cores (mfma_lane.cuh;
+// d = 4, squared energy), with NT = MT threads; the dynamic LDS then holds the tile padded by 16 zero vectors and,
+// behind it, -s^2 |w|^2 of every vector.
+template <int KPL, int D, int DIST, int NT = LT, bool MFMA = false>
 __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs& pa) {
+    static_assert(!MFMA || (D == 4 && DIST == DIST_SQL2 && KPL <= 4), "matrix-core loop: d = 4, squared energy, k <= 256");
     constexpr int ACCW = D + 1;
     constexpr int NA = KPL * ACCW;
     constexpr int KDP = 64 * KPL * D;  // padded codebook size
@@ -198,8 +216,8 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
     const int64_t base = (int64_t)wg * pa.per;
     int cnt = 0;
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
-    for (int i = tid; i < cnt * D; i += LT) s_tile[i] = a.W[base * D + i];
-    for (int i = tid; i < kd; i += LT) {
+    for (int i = tid; i < cnt * D; i += NT) s_tile[i] = a.W[base * D + i];
+    for (int i = tid; i < kd; i += NT) {
         const float c0 = pa.C0[i];
         s_Cd[i] = (double)c0;
         s_Cf[i] = c0;
@@ -213,16 +231,65 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
         s_res = 0.0;
     }
     __syncthreads();
+    const float* s_wn = s_tile + (size_t)(pa.per + 16) * D;
+    __shared__ float s_mu[4];
+    if constexpr (MFMA) {
+        // reference point of the centred coordinates: the mean of the initial codewords
+        if (tid < D) {
+            float sm = 0.f;
+            for (int j = 0; j < k; ++j) sm += s_Cf[j * D + tid];
+            s_mu[tid] = sm / (float)k;
+        }
+        float* wn = s_tile + (size_t)(pa.per + 16) * D;
+        for (int i = cnt * D + tid; i < (pa.per + 16) * D; i += NT) s_tile[i] = 0.f;
+        __syncthreads();
+        for (int i = tid; i < pa.per + 16; i += NT) {
+            float n2 = 0.f;
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                const float t = (s_tile[i * D + r] - s_mu[r]) * a.escale;
+                n2 = fmaf(t, t, n2);
+            }
+            wn[i] = -n2;
+        }
+        __syncthreads();
+    }
     const double tol = pa.tol;
     const int max_iter = pa.max_iter;
     unsigned int seq = pa.seq_base;
 
     while (!s_done) {
-        LaneWave<KPL, D, DIST, PASS_FWD> st;
-        st.init(k, s_Cf, nullptr, nullptr, a.escale);
-        lane_tile_pass<KPL, D, DIST, PASS_FWD>(a, st, s_tile, nullptr, base, cnt);
         ++seq;
-        publish_lane<NA, ACCW>(pa, seq, st.acc, k, s_acc);
+        IDKM_LSTAMP(0);
+        if constexpr (MFMA) {
+            __shared__ float s_part[NT / 64][64 * KPL * ACCW];
+            __shared__ float2 s_tab[4 * MfmaFwd<KPL>::TAB_STRIDE];
+            MfmaFwd<KPL>::template fill_table<NT>(s_tab, k, s_Cf, s_mu, a.escale);
+            __syncthreads();
+            {
+                MfmaFwd<KPL> st;
+                st.init(s_tab, s_mu);
+                mfma_tile_pass<KPL, NT>(st, s_tile, s_wn, cnt, a.escale);
+                IDKM_LSTAMP(1);
+                mfma_collect<KPL, NT>(st, &s_part[0][0]);
+            }
+            __syncthreads();
+            // wavefront totals add up in wavefront order, float64; hop-1 store as in publish_lane
+            unsigned long long* dst = pa.buf1 + ((size_t)(seq & 1u) * pa.G + pa.wg) * nacc;
+            for (int idx = tid; idx < nacc; idx += NT) {
+                double t = 0.0;
+#pragma unroll
+                for (int w = 0; w < NT / 64; ++w) t += (double)s_part[w][idx];
+                st_word(&dst[idx], pack_f(seq, (float)t));
+            }
+        } else {
+            LaneWave<KPL, D, DIST, PASS_FWD> st;
+            st.init(k, s_Cf, nullptr, nullptr, a.escale);
+            lane_tile_pass<KPL, D, DIST, PASS_FWD, NT>(a, st, s_tile, nullptr, base, cnt);
+            IDKM_LSTAMP(1);
+            publish_lane<NA, ACCW, NT>(pa, seq, st.acc, k, s_acc);
+        }
+        IDKM_LSTAMP(2);
         for (int r = wg; r < k; r += G) {
             if (!reduce_lane<ACCW>(pa, seq, nacc, r * ACCW, ls)) return;
             if (tid < D) {
@@ -235,14 +302,16 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
                 st_word(&pa.buf2[(size_t)(seq & 1u) * stride2 + idx], pack_f(seq, (float)cnew));
             }
         }
-        if (!gather_lane(pa, seq, kd, stride2, s_new, ls)) return;
+        IDKM_LSTAMP(3);
+        if (!gather_lane<NT>(pa, seq, kd, stride2, s_new, ls)) return;
+        IDKM_LSTAMP(4);
         double r2 = 0.0;
-        for (int i = tid; i < kd; i += LT) {
+        for (int i = tid; i < kd; i += NT) {
             const double df = (double)__uint_as_float(s_new[i]) - (double)s_Cf[i];
             r2 += df * df;
         }
-        r2 = block_sum_fixed(r2, ls);
-        for (int i = tid; i < kd; i += LT) s_Cf[i] = __uint_as_float(s_new[i]);
+        r2 = block_sum_fixed<NT>(r2, ls);
+        for (int i = tid; i < kd; i += NT) s_Cf[i] = __uint_as_float(s_new[i]);
         if (tid == 0) {
             s_iters += 1;
             s_res = r2;
@@ -259,9 +328,9 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
     {
         LaneWave<KPL, D, DIST, PASS_FIN> st;
         st.init(k, s_Cf, nullptr, nullptr);
-        lane_tile_pass<KPL, D, DIST, PASS_FIN>(a, st, s_tile, nullptr, base, cnt);
+        lane_tile_pass<KPL, D, DIST, PASS_FIN, NT>(a, st, s_tile, nullptr, base, cnt);
         ++seq;
-        publish_lane<NA, ACCW>(pa, seq, st.acc, k, s_acc);
+        publish_lane<NA, ACCW, NT>(pa, seq, st.acc, k, s_acc);
         for (int r = wg; r < k; r += G) {
             if (!reduce_lane<ACCW>(pa, seq, nacc, r * ACCW, ls)) return;
             if (tid < D) {
@@ -292,7 +361,7 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
         {
             const unsigned long long* src = pa.buf2 + (size_t)(seq & 1u) * stride2 + kd;
             bool ok = true;
-            for (int i = tid; i < k; i += LT) {
+            for (int i = tid; i < k; i += NT) {
                 unsigned int p = 0;
                 ok = ok && poll_word(pa, src + i, seq, &p);
                 s_new[i] = p;
@@ -302,13 +371,13 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
             if (ls.abort) return;
         }
         double empty = 0.0, bad = 0.0;
-        for (int i = tid; i < k; i += LT) {
+        for (int i = tid; i < k; i += NT) {
             const float n = __uint_as_float(s_new[i]);
             if (!(n >= 0.f)) bad += 1.0;
             else if (!(n > 0.f)) empty += 1.0;
         }
-        empty = block_sum_fixed(empty, ls);
-        bad = block_sum_fixed(bad, ls);
+        empty = block_sum_fixed<NT>(empty, ls);
+        bad = block_sum_fixed<NT>(bad, ls);
         if (tid == 0) {
             PResult* o = pa.out;
             o->iters = s_iters;
@@ -541,6 +610,23 @@ __global__ __launch_bounds__(LT) void persist_lane_fwd_batch(const BatchItem* it
     pa.wg = (int)blockIdx.x - it.wg_begin;
     pa.G = it.wg_count;
     persist_lane_fwd_body<KPL, D, DIST>(a, pa);
+}
+// Forward solve with the loop on the matrix cores (d = 4, squared energy): MT threads, see persist_lane_fwd_body.
+template <int KPL>
+__global__ __launch_bounds__(MT) void persist_mfma_fwd(const Args a, const PArgs pa_in) {
+    PArgs pa = pa_in;
+    pa.wg = blockIdx.x;
+    pa.G = gridDim.x;
+    persist_lane_fwd_body<KPL, 4, DIST_SQL2, MT, true>(a, pa);
+}
+template <int KPL>
+__global__ __launch_bounds__(MT) void persist_mfma_fwd_batch(const BatchItem* items, const unsigned short* item_of_wg) {
+    const BatchItem& it = items[item_of_wg[blockIdx.x]];
+    const Args a = it.a;
+    PArgs pa = it.p;
+    pa.wg = (int)blockIdx.x - it.wg_begin;
+    pa.G = it.wg_count;
+    persist_lane_fwd_body<KPL, 4, DIST_SQL2, MT, true>(a, pa);
 }
 template <int KPL, int D, int DIST>
 __global__ __launch_bounds__(LT) void persist_lane_bwd(const Args a, const PArgs pa_in) {

@@ -1,0 +1,108 @@
+"""The matrix-core form of the forward loop (d = 4, squared energy, 17 <= k <= 256, persistent path) against the
+float64 oracle.
+
+That loop evaluates the exponent of Eq. "aterms" in its expanded form  -s^2|w|^2 + 2 s^2 w.c - s^2|c|^2  (one
+16 x 16 x 4 matrix product per tile) instead of summing squared differences, so these cases aim at what the expansion
+could get wrong: codebooks that do not fill the last block of 16, tiles that end inside a 16-vector step, data far
+from the origin (the three terms cancel), rows whose weights all underflow before the row shift, and one-workgroup
+layers.  Bars as everywhere: C*, Wq 1e-4 norm-wise, hard assignments bit-exact on the kernel's own C*.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import idkm_oracle as orc
+from paper_2312_07759_amd import binding
+from paper_2312_07759_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL_VAL = 1e-4
+DIST = wl.DIST_SQL2
+
+
+def rel(x, ref):
+    x, ref = np.asarray(x, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(x - ref) / (den if den > 0 else 1.0))
+
+
+def dev(x):
+    return torch.as_tensor(np.ascontiguousarray(x), dtype=torch.float32).cuda()
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = binding.Context(0)
+    c.set_path(binding.PATH_PERSISTENT)
+    yield c
+    c.close()
+
+
+def _check(ctx, W, C0, tau, iters, tol=0.0):
+    W, C0 = W.astype(np.float32), C0.astype(np.float32)
+    out = ctx.forward(dev(W), dev(C0), tau, tol, iters, DIST, want_assign=True)
+    assert out["info"].path == binding.PATH_PERSISTENT
+    ref = orc.soft_kmeans(W, C0, tau, tol, iters, DIST)
+    Cg = out["C"].cpu().numpy()
+    assert np.isfinite(Cg).all()
+    assert abs(out["info"].iters - ref["iters"]) <= (0 if tol == 0.0 else 1)
+    assert rel(Cg, ref["C"]) < TOL_VAL, rel(Cg, ref["C"])
+    assert rel(out["Wq"].cpu().numpy(), orc.soft_quantize(W, Cg, tau, DIST)) < TOL_VAL
+    assert np.array_equal(out["assign"].cpu().numpy(), orc.hard_assign_f32(W, Cg))
+    return out, ref
+
+
+# (m, k): every register variant (k <= 64, <= 128, <= 256), codebooks that end inside a block of 16, tiles that end
+# inside a step, fewer vectors than one step, several workgroups with a ragged last one
+@pytest.mark.parametrize("m,k", [(4_001, 17), (9_973, 33), (1_000, 64), (20_011, 100), (7_777, 128), (40_001, 130),
+                                 (30_000, 255), (65_537, 256), (300, 256), (19, 17)])
+def test_shapes(ctx, m, k):
+    W, C0, _ = wl.random_problem(m, 4, k, seed=1000 + m % 97 + k, std=0.5, spread=1.5)
+    C0 = C0 + 0.01 * np.random.default_rng(k).standard_normal(C0.shape)
+    _check(ctx, W, C0, 0.3, 20)
+
+
+def test_data_far_from_the_origin(ctx):
+    # |w| is 100 times the spread of the data: without a reference point inside the data the expanded exponent
+    # loses about four digits here
+    rng = np.random.default_rng(5)
+    m, k = 30_011, 64
+    W = 5.0 + 0.05 * rng.standard_normal((m, 4))
+    C0 = W[rng.choice(m, k, replace=False)] + 0.002 * rng.standard_normal((k, 4))
+    _check(ctx, W, C0, 1e-3, 25)
+
+
+def test_rows_that_underflow_before_the_shift(ctx):
+    # a few vectors lie hundreds of kernel widths from every codeword: their unshifted weights are all zero in
+    # float32, and the row is redone with the shift by its maximum
+    rng = np.random.default_rng(6)
+    m, k = 12_345, 100
+    W = 0.05 * rng.standard_normal((m, 4))
+    far = rng.choice(m, 40, replace=False)
+    W[far] += rng.choice([-1.0, 1.0], size=(40, 4)) * 1.5
+    C0 = W[rng.choice(np.setdiff1d(np.arange(m), far), k, replace=False)].copy()
+    tau = 2e-4
+    e = ((W[far, None, :] - C0[None, :, :]) ** 2).sum(-1).min(1)
+    assert (e / tau * np.log2(np.e) > 200).all()          # beyond float32's exponent range without the shift
+    _check(ctx, W, C0, tau, 15)
+
+
+def test_stops_like_the_oracle(ctx):
+    W, C0, _ = wl.random_problem(25_000, 4, 48, seed=77, std=0.5, spread=1.5)
+    out, ref = _check(ctx, W, C0, 0.05, 200, tol=1e-5)
+    assert out["info"].converged == ref["converged"]
+
+
+def test_matches_the_vector_alu_kernels(ctx):
+    # the same solve on the stream path (vector-ALU kernels, summed squared differences)
+    W, C0, _ = wl.random_problem(50_021, 4, 200, seed=78, std=0.5, spread=1.5)
+    W, C0 = W.astype(np.float32), C0.astype(np.float32)
+    a = ctx.forward(dev(W), dev(C0), 0.2, 0.0, 30, DIST)
+    ctx.set_path(binding.PATH_STREAM)
+    try:
+        b = ctx.forward(dev(W), dev(C0), 0.2, 0.0, 30, DIST)
+    finally:
+        ctx.set_path(binding.PATH_PERSISTENT)
+    assert a["info"].path == binding.PATH_PERSISTENT and b["info"].path == binding.PATH_STREAM
+    assert rel(a["C"].cpu().numpy(), b["C"].cpu().numpy()) < 2e-5
