@@ -41,21 +41,29 @@ __device__ __forceinline__ float row16_max(float x) {
 }
 
 // Per-wavefront state of one forward pass: NB = 4 KPL blocks of 16 codewords.
+//
+// FOLD (chosen per pass, when s^2 |c_j - mu|^2 <= 100 for every codeword): the codeword's norm is not added to the
+// exponent; the loop works with p'_ij = exp2(x_ij + s^2|c_j - mu|^2) <= 2^100 and the factor 2^(-s^2|c_j - mu|^2)
+// of codeword j multiplies its term of the row sum (an FMA in place of the add) and, once per pass, its accumulators.
 template <int KPL>
 struct MfmaFwd {
     static constexpr int NB = 4 * KPL;
     static constexpr int TAB_STRIDE = 16 * NB + 16;  // entries per coordinate; the pad of 128 bytes spreads the four
                                                      // lane groups of a wavefront over different LDS banks
+    static constexpr float FOLD_LIMIT = 100.f;
     f32x4 sacc[NB];  // first moments: register i = codeword 16 b + 4 ((l / 4) % 4) + i, coordinate l % 4, partial over q
     float nacc[NB];  // masses: codeword 16 b + l % 16, partial over q
     // codeword operands of the energy product, in LDS (they are the same for every step, and 32 registers more per
-    // lane would not fit): entry 16 b of `tab` = {2 s (c_j - mu)[l / 16], -s^2 |c_j - mu|^2}, j = 16 b + l % 16
+    // lane would not fit): entry 16 b of `tab` = {2 s (c_j - mu)[l / 16], -s^2 |c_j - mu|^2}, j = 16 b + l % 16;
+    // entry 16 b of `fac` = 2^(-s^2 |c_j - mu|^2)
     const float2* tab;
+    const float* fac;
     float mu_q;  // coordinate l / 16 of the reference point
 
-    __device__ __forceinline__ void init(const float2* s_tab, const float* s_mu) {
+    __device__ __forceinline__ void init(const float2* s_tab, const float* s_fac, const float* s_mu) {
         const int lane = threadIdx.x & 63;
         tab = s_tab + (lane >> 4) * TAB_STRIDE + (lane & 15);
+        fac = s_fac + (lane & 15);
         mu_q = s_mu[lane >> 4];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
@@ -63,11 +71,13 @@ struct MfmaFwd {
             sacc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     }
-    // The table for init(): s_tab[kk][j] for the 16 NB (padded) codewords; a padding codeword sits at -1e30, so its
-    // weight is exactly zero.  Called by the whole workgroup (NT threads); the caller synchronises.
+    // The tables for init(): s_tab[kk][j], s_fac[j] for the 16 NB (padded) codewords; a padding codeword sits at
+    // -1e30, so its weight is exactly zero.  Called by the whole workgroup (NT threads), with a barrier inside;
+    // returns whether the pass may fold the codewords' norms.
     template <int NT>
-    static __device__ __forceinline__ void fill_table(float2* s_tab, int k, const float* Cf, const float* s_mu,
-                                                      float escale) {
+    static __device__ __forceinline__ bool fill_table(float2* s_tab, float* s_fac, int k, const float* Cf,
+                                                      const float* s_mu, float escale) {
+        int too_far = 0;
         for (int idx = threadIdx.x; idx < 4 * TAB_STRIDE; idx += NT) {
             const int kk = idx / TAB_STRIDE, j = idx - kk * TAB_STRIDE;
             float2 e = {0.f, -1e30f};
@@ -80,51 +90,84 @@ struct MfmaFwd {
                 }
                 e.x = 2.f * escale * (Cf[j * 4 + kk] - s_mu[kk]);
                 e.y = -n2;
+                if (!(n2 <= FOLD_LIMIT)) too_far = 1;
             }
             s_tab[idx] = e;
+            if (kk == 0) s_fac[j] = fast_exp2(e.y);
         }
+        return __syncthreads_or(too_far) == 0;
     }
 
     // Vectors v0 .. v0+15 of the tile (s_w: [.][4] float32, s_wn: -s^2|w - mu|^2 per vector); those at or beyond vend
     // contribute nothing.  Both arrays are readable (finite values) up to index v0 + 15.
+    template <bool FOLD>
     __device__ __forceinline__ void step(const float* s_w, const float* s_wn, int v0, int vend, float escale) {
         const int lane = threadIdx.x & 63, j0 = lane & 15, q = lane >> 4;
         // the table entries are read anew in every step (kept in registers across steps they would spill)
         asm volatile("" ::: "memory");
         const float aw = (s_w[(v0 + j0) * 4 + q] - mu_q) * escale;
         const f32x4 wn = *reinterpret_cast<const f32x4*>(&s_wn[v0 + 4 * q]);
-        float x[NB][4];
-        auto exponents = [&]() {
+        // the vectors' norms enter as the additive operand (one register quad for all blocks); the products are
+        // issued back to back (see the note on the M-step below)
+        // All operands of a group are fetched from LDS before the group starts (the scheduling barriers keep the
+        // loads from sinking between the matrix instructions, where each would stall the pipeline for its latency):
+        // first the codeword coordinates, then -- in flight while the products run -- the per-codeword term of the
+        // next group (the fold factor, or the norm).
+        float x[NB][4], cterm[NB];
+        auto products = [&](bool want_norms) {
+            float cbv[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) cbv[b] = tab[16 * b].x;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) cterm[b] = want_norms ? tab[16 * b].y : fac[16 * b];
+            f32x4 e[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, cbv[b], wn, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                // the vectors' norms enter as the additive operand (one register quad for all blocks), the
-                // codeword's norm is added to the result
-                const float2 cj = tab[16 * b];
-                const f32x4 e = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, cj.x, wn, 0, 0, 0);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) x[b][r] = e[r] + cj.y;
+                for (int r = 0; r < 4; ++r) x[b][r] = e[b][r];
             }
         };
-        exponents();
-        // exp2 of a non-positive number cannot overflow; the row shift of the softmax is only needed when the whole
-        // row underflows (a vector many kernel widths from every codeword), which the unshifted row sum shows
-        float S[4] = {0.f, 0.f, 0.f, 0.f};
+        auto add_norms = [&]() {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
+            for (int b = 0; b < NB; ++b) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                x[b][r] = fast_exp2(x[b][r]);
-                S[r] += x[b][r];
+                for (int r = 0; r < 4; ++r) x[b][r] += cterm[b];
             }
-        }
+        };
+        // weights (up to the fold factor, in cterm) from exponents in x, and their row sums
+        float S[4];
+        auto weights = [&](const float (&shift)[4]) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[r] = 0.f;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    x[b][r] = fast_exp2(x[b][r] - shift[r]);
+                    S[r] = FOLD ? fmaf(x[b][r], cterm[b], S[r]) : S[r] + x[b][r];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[r] = row16_sum(S[r]);
+        };
+        // exp2 of a non-positive number cannot overflow (folded: of a number <= FOLD_LIMIT); the row shift of the
+        // softmax is only needed when the whole row underflows (a vector many kernel widths from every codeword),
+        // which the unshifted row sum shows
+        products(!FOLD);
+        if (!FOLD) add_norms();
+        const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+        weights(zero);
         bool under = false;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            S[r] = row16_sum(S[r]);
-            under = under || (S[r] < 7.9e-31f);  // below 2^-100
-        }
+        for (int r = 0; r < 4; ++r) under = under || (S[r] < 7.9e-31f);  // below 2^-100
         if (__builtin_amdgcn_ballot_w64(under) != 0ull) {
-            exponents();
+            // the row maximum of the full exponent; folded, the shifted exponent again stays below FOLD_LIMIT
+            products(true);
+            add_norms();
             float mx[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -132,18 +175,9 @@ struct MfmaFwd {
 #pragma unroll
                 for (int b = 1; b < NB; ++b) mx[r] = fmaxf(mx[r], x[b][r]);
                 mx[r] = row16_max(mx[r]);
-                S[r] = 0.f;
             }
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    x[b][r] = fast_exp2(x[b][r] - mx[r]);
-                    S[r] += x[b][r];
-                }
-            }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) S[r] = row16_sum(S[r]);
+            if (FOLD) products(false);
+            weights(mx);
         }
         // the normalisation 1/S_i joins the vector (first moments) and the mass FMA
         float rinv[4], bw[4];
@@ -153,33 +187,44 @@ struct MfmaFwd {
             rinv[r] = (v < vend) ? fast_rcp(S[r]) : 0.f;
             bw[r] = s_w[v * 4 + (lane & 3)] * rinv[r];
         }
+        // Matrix and vector instructions do not overlap on this part, and every change from one kind to the other
+        // costs a few cycles more: the mass FMAs run as one group, the outer products back to back as another.
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                nacc[b] = fmaf(x[b][r], rinv[r], nacc[b]);
-                sacc[b] = __builtin_amdgcn_mfma_f32_4x4x1f32(x[b][r], bw[r], sacc[b], 0, 0, 0);
-            }
+            for (int b = 0; b < NB; ++b) nacc[b] = fmaf(x[b][r], rinv[r], nacc[b]);
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) sacc[b] = __builtin_amdgcn_mfma_f32_4x4x1f32(x[b][r], bw[r], sacc[b], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
 };
 
 // One forward pass over the workgroup's tile: every wavefront takes an equal share of whole 16-vector steps.
 template <int KPL, int NT>
 __device__ __forceinline__ void mfma_tile_pass(MfmaFwd<KPL>& st, const float* s_w, const float* s_wn, int cnt,
-                                               float escale) {
+                                               float escale, bool fold) {
     constexpr int NW = NT / 64;
     const int wave = threadIdx.x >> 6;
     int share = (cnt + NW - 1) / NW;
     share = (share + 15) & ~15;
     const int w0 = wave * share;
     const int w1 = (w0 + share < cnt) ? w0 + share : cnt;
-    for (int v = w0; v < w1; v += 16) st.step(s_w, s_wn, v, w1, escale);
+    if (fold) {
+        for (int v = w0; v < w1; v += 16) st.template step<true>(s_w, s_wn, v, w1, escale);
+    } else {
+        for (int v = w0; v < w1; v += 16) st.template step<false>(s_w, s_wn, v, w1, escale);
+    }
 }
 
 // Workgroup totals of the accumulators as float32 per wavefront in s_part[NT / 64][64 KPL 5], word (codeword, n | s_r).
+// fold: the accumulators still lack the factor of their codeword (s_fac).
 template <int KPL, int NT>
-__device__ __forceinline__ void mfma_collect(const MfmaFwd<KPL>& st, float* s_part) {
+__device__ __forceinline__ void mfma_collect(const MfmaFwd<KPL>& st, float* s_part, bool fold, const float* s_fac) {
     constexpr int NB = 4 * KPL, ROW = 64 * KPL * 5;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int q = lane >> 4, j0 = lane & 15, t = (lane >> 2) & 3, col = lane & 3;
@@ -198,9 +243,12 @@ __device__ __forceinline__ void mfma_collect(const MfmaFwd<KPL>& st, float* s_pa
             s[i] += __shfl_xor(s[i], 32);
         }
         if (q == 0) {
-            out[(16 * b + j0) * 5] = n;
+            out[(16 * b + j0) * 5] = fold ? n * s_fac[16 * b + j0] : n;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) out[(16 * b + 4 * t + i) * 5 + 1 + col] = s[i];
+            for (int i = 0; i < 4; ++i) {
+                const int j = 16 * b + 4 * t + i;
+                out[j * 5 + 1 + col] = fold ? s[i] * s_fac[j] : s[i];
+            }
         }
     }
 }

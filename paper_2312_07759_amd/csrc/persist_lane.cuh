@@ -264,16 +264,17 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
         if constexpr (MFMA) {
             __shared__ float s_part[NT / 64][64 * KPL * ACCW];
             __shared__ float2 s_tab[4 * MfmaFwd<KPL>::TAB_STRIDE];
-            MfmaFwd<KPL>::template fill_table<NT>(s_tab, k, s_Cf, s_mu, a.escale);
-            __syncthreads();
+            __shared__ float s_fac[MfmaFwd<KPL>::TAB_STRIDE];
+            const bool fold = MfmaFwd<KPL>::template fill_table<NT>(s_tab, s_fac, k, s_Cf, s_mu, a.escale);
             {
                 MfmaFwd<KPL> st;
-                st.init(s_tab, s_mu);
-                mfma_tile_pass<KPL, NT>(st, s_tile, s_wn, cnt, a.escale);
+                st.init(s_tab, s_fac, s_mu);
+                mfma_tile_pass<KPL, NT>(st, s_tile, s_wn, cnt, a.escale, fold);
                 IDKM_LSTAMP(1);
-                mfma_collect<KPL, NT>(st, &s_part[0][0]);
+                mfma_collect<KPL, NT>(st, &s_part[0][0], fold, s_fac);
             }
             __syncthreads();
+            IDKM_LSTAMP(5);
             // wavefront totals add up in wavefront order, float64; hop-1 store as in publish_lane
             unsigned long long* dst = pa.buf1 + ((size_t)(seq & 1u) * pa.G + pa.wg) * nacc;
             for (int idx = tid; idx < nacc; idx += NT) {
@@ -312,6 +313,7 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
         }
         r2 = block_sum_fixed<NT>(r2, ls);
         for (int i = tid; i < kd; i += NT) s_Cf[i] = __uint_as_float(s_new[i]);
+        IDKM_LSTAMP(6);
         if (tid == 0) {
             s_iters += 1;
             s_res = r2;

@@ -73,16 +73,20 @@ def test_data_far_from_the_origin(ctx):
     _check(ctx, W, C0, 1e-3, 25)
 
 
-def test_rows_that_underflow_before_the_shift(ctx):
+@pytest.mark.parametrize("tau", [2e-4, 2e-3])
+def test_rows_that_underflow_before_the_shift(ctx, tau):
     # a few vectors lie hundreds of kernel widths from every codeword: their unshifted weights are all zero in
-    # float32, and the row is redone with the shift by its maximum
+    # float32, and the row is redone with the shift by its maximum.  At the smaller temperature the codewords lie
+    # more than 100 squared kernel widths from their mean and the loop adds their norms to the exponent; at the
+    # larger one it folds them into factors instead, and the redone row has to stay within range there too.
     rng = np.random.default_rng(6)
     m, k = 12_345, 100
     W = 0.05 * rng.standard_normal((m, 4))
     far = rng.choice(m, 40, replace=False)
     W[far] += rng.choice([-1.0, 1.0], size=(40, 4)) * 1.5
     C0 = W[rng.choice(np.setdiff1d(np.arange(m), far), k, replace=False)].copy()
-    tau = 2e-4
+    spread = ((C0 - C0.mean(0)) ** 2).sum(1).max() * np.log2(np.e) / tau
+    assert spread > 150 if tau < 1e-3 else spread < 60
     e = ((W[far, None, :] - C0[None, :, :]) ** 2).sum(-1).min(1)
     assert (e / tau * np.log2(np.e) > 200).all()          # beyond float32's exponent range without the shift
     _check(ctx, W, C0, tau, 15)
