@@ -41,6 +41,16 @@ def fwd_lane_ops_per_vector(k: int, d: int, dist: int) -> int:
     return k * (3 * d + 5) + TRANS_COST * trans
 
 
+def matrix_core_lane_cycles_per_vector(k: int) -> int:
+    """The same count for the shapes whose forward loop runs on the matrix cores (d = 4, squared energy,
+    17 <= k <= 256, persistent path): per (vector, codeword) pair 8 float32 multiply-adds on the matrix cores
+    (4 of the energy product, 4 of the first moments) and 4 vector issue slots (exp2 = 2, row sum, mass).  A SIMD
+    retires 32 matrix multiply-adds or 16 lane operations per cycle and -- measured, idkm_calibrate kinds 6 and 7 --
+    never both at once, so a matrix multiply-add is half a lane-cycle: 8/2 + 4 = 8 lane-cycles per pair, plus the
+    reciprocal of the row sum."""
+    return k * 8 + TRANS_COST
+
+
 def measure_dense(ctx, binding, torch, np, G, reps):
     """Median event time (ms) of the dense (explicit-Jacobian) backward, or None where it is not offered."""
     ts = []
@@ -97,16 +107,23 @@ def measure(ctx, binding, torch, np, p, dist, W, C0, G, reps, bwd_tol, bwd_max_i
 def roofline_of(cfg, dist, fwd_ms, finfo):
     evals = finfo.iters + 1  # + the evaluation at C*
     per_eval = fwd_ms * 1e-3 / evals
-    ops = fwd_lane_ops_per_vector(cfg.k, cfg.d, dist)
+    valu_ops = fwd_lane_ops_per_vector(cfg.k, cfg.d, dist)
+    matrix = cfg.d == 4 and dist == 1 and 17 <= cfg.k <= 256 and finfo.path == 2
+    ops = matrix_core_lane_cycles_per_vector(cfg.k) if matrix else valu_ops
     alu = ops * cfg.m / per_eval
     hbm = 4.0 * cfg.m * cfg.d / per_eval
-    return {
+    out = {
         "bound": "alu", "kernel": "forward solve: evaluations of F (E-step + M-step over all m vectors)",
         "achieved": alu / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s", "frac": alu / PEAK_LANE_OPS,
         "traffic": None, "lane_ops_per_vector": ops,
         "evaluations_per_launch": evals if finfo.path == 2 else 1, "avg_eval_us": per_eval * 1e6,
         "hbm_effective_GBps": hbm / 1e9, "hbm_effective_frac": hbm / PEAK_HBM,
     }
+    if matrix:
+        out["note"] = ("forward loop on the matrix cores: a float32 matrix multiply-add counts as half a lane-cycle "
+                       "(32 per cycle and SIMD, not concurrent with the vector ALU)")
+        out["frac_of_vector_alu_bound"] = valu_ops * cfg.m / per_eval / PEAK_LANE_OPS
+    return out
 
 
 def main() -> int:
@@ -187,10 +204,15 @@ def main() -> int:
     dense_ms = measure_dense(ctx, binding, torch, np, G, 5)
     gm_ms, gm_info = measure_gmres(ctx, binding, torch, np, G, 5, args.bwd_tol, args.bwd_max_iter)
     roofline = roofline_of(cfg, dist, fwd_ms, finfo)
+    mfma_rate, mfma_mixed, mfma4_rate = ctx.calibrate(6), ctx.calibrate(7), ctx.calibrate(8)
     roofline["ceilings"] = {"fma_Tlane_ops": fma_rate / 1e12, "exp_T_per_s": exp_rate / 1e12,
+                            "mfma_f32_16x16x4_Tmac_per_s": mfma_rate / 1e12,
+                            "mfma_f32_16x16x4_Tmac_per_s_with_8_fma_each": mfma_mixed / 1e12,
+                            "mfma_f32_4x4x1_Tmac_per_s": mfma4_rate / 1e12,
                             "slots_per_transcendental": fma_rate / exp_rate, "stream_read_GBps": read_rate / 1e9,
                             "frac_of_measured_fma_rate": roofline["achieved"] * 1e12 / fma_rate,
-                            "note": "idkm_calibrate on this device: v_fma_f32 chains, v_exp_f32 chains, 256 MiB streaming read"}
+                            "note": "idkm_calibrate on this device: v_fma_f32 chains, v_exp_f32 chains, float32 matrix "
+                                    "instructions alone and with vector FMAs between them, 256 MiB streaming read"}
     # HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command
     # (counters cannot be read from inside the process; the summary under profiles/ gives the commands)
     tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}_{wl.DIST_NAMES[dist]}.json")

@@ -164,6 +164,10 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
  *   kind 2  bytes per second of a streaming read of buf (device, 16-byte aligned, n_floats floats)
  *   kind 3, 4, 5  exponentials per second with 1, 2, 4 independent v_fma_f32 issued beside each of them
  *           (shows how transcendental and full-rate operations share the issue slots)
+ *   kind 6  float32 multiply-adds per second of the matrix cores (v_mfma_f32_16x16x4_f32 alone, 2 wavefronts per SIMD)
+ *   kind 7  the same count with 8 independent v_fma_f32 issued after every matrix instruction (equal to kind 6 if
+ *           matrix and vector instructions overlapped; they do not on gfx950: about half)
+ *   kind 8  float32 multiply-adds per second of v_mfma_f32_4x4x1_f32 (16 blocks per instruction)
  * Waits for completion; *result (host) receives the rate.  Nothing on the method's path calls this.
  */
 idkm_status idkm_calibrate(idkm_ctx* ctx, int32_t kind, const float* buf, int64_t n_floats, double* result,

@@ -237,7 +237,9 @@ class Context:
         return dict(dW=dW, info=_info(info))
 
     def calibrate(self, kind, buf=None):
-        """idkm_calibrate: 0 lane-ops/s, 1 exponentials/s, 2 bytes/s of a streaming read of `buf` (float32 tensor)."""
+        """idkm_calibrate: 0 lane-ops/s, 1 exponentials/s, 2 bytes/s of a streaming read of `buf` (float32 tensor),
+        3-5 exponentials/s beside 1, 2, 4 FMAs, 6-8 float32 matrix multiply-adds/s (16x16x4, 16x16x4 with vector FMAs
+        between, 4x4x1)."""
         import torch
         r = C.c_double()
         n = 0 if buf is None else buf.numel()

@@ -40,6 +40,7 @@ void launch_unpack_quantize(const uint32_t* words, int64_t nwords, int64_t m, in
 // Micro-benchmarks of the roofline's ceilings (calibrate.hip).
 void launch_cal_fma(float* out, int grid, int iters, hipStream_t s);
 void launch_cal_exp(float* out, int grid, int iters, int fmas, hipStream_t s);  // fmas in {0, 1, 2, 4}
+void launch_cal_mfma(float* out, int grid, int iters, int mode, hipStream_t s);  // mode 0: 16x16x4, 1: + 8 FMAs each, 2: 4x4x1
 void launch_cal_read(const float* src, size_t n_floats, int grid, float* out, hipStream_t s);
 
 }  // namespace idkm

@@ -904,7 +904,7 @@ idkm_status idkm_calibrate(idkm_ctx* ctx, int32_t kind, const float* buf, int64_
                            void* hip_stream) {
     idkm_status st = check_common(ctx);
     if (st != IDKM_OK) return st;
-    if (!result || kind < 0 || kind > 5) return fail(ctx, IDKM_ERR_INVALID_ARG, "kind must be 0 .. 5 and result non-NULL");
+    if (!result || kind < 0 || kind > 8) return fail(ctx, IDKM_ERR_INVALID_ARG, "kind must be 0 .. 8 and result non-NULL");
     if (kind == 2 && (!buf || n_floats < 4 || (reinterpret_cast<uintptr_t>(buf) & 15u) != 0))
         return fail(ctx, IDKM_ERR_INVALID_ARG, "the streaming read needs a 16-byte aligned buffer");
     hipStream_t s = (hipStream_t)hip_stream;
@@ -920,6 +920,10 @@ idkm_status idkm_calibrate(idkm_ctx* ctx, int32_t kind, const float* buf, int64_
         if (kind == 0) {
             launch_cal_fma(sink, grid, iters, s);
             work = (double)grid * 256.0 * iters * 16.0;  // lane operations
+        } else if (kind >= 6) {
+            // one workgroup of 512 threads per compute unit: two wavefronts per SIMD, as in the kernel that uses them
+            launch_cal_mfma(sink, ctx->num_cu, iters, kind - 6, s);
+            work = (double)ctx->num_cu * 8.0 * iters * 8.0 * (kind == 8 ? 256.0 : 1024.0);  // multiply-adds
         } else if (kind == 1 || kind >= 3) {
             const int fmas = kind == 1 ? 0 : (kind == 3 ? 1 : (kind == 4 ? 2 : 4));
             launch_cal_exp(sink, grid, iters, fmas, s);
