@@ -41,14 +41,15 @@ def fwd_lane_ops_per_vector(k: int, d: int, dist: int) -> int:
     return k * (3 * d + 5) + TRANS_COST * trans
 
 
-def matrix_core_lane_cycles_per_vector(k: int) -> int:
-    """The same count for the shapes whose forward loop runs on the matrix cores (d = 4, squared energy,
-    17 <= k <= 256, persistent path): per (vector, codeword) pair 8 float32 multiply-adds on the matrix cores
-    (4 of the energy product, 4 of the first moments) and 4 vector issue slots (exp2 = 2, row sum, mass).  A SIMD
-    retires 32 matrix multiply-adds or 16 lane operations per cycle and -- measured, idkm_calibrate kinds 6 and 7 --
-    never both at once, so a matrix multiply-add is half a lane-cycle: 8/2 + 4 = 8 lane-cycles per pair, plus the
+def matrix_core_lane_cycles_per_vector(k: int, dist: int) -> int:
+    """The same count for the shapes whose forward loop runs on the matrix cores (d = 4, 17 <= k <= 256, persistent
+    path): per (vector, codeword) pair 8 float32 multiply-adds on the matrix cores (4 of the energy product, 4 of
+    the first moments) and, squared energy, 4 vector issue slots (exp2 = 2, row sum, mass); the plain norm adds the
+    codeword's norm, a square root (2), the row minimum and its subtraction: 9.  A SIMD retires 32 matrix
+    multiply-adds or 16 lane operations per cycle and -- measured, idkm_calibrate kinds 6 and 7 -- never both at
+    once, so a matrix multiply-add is half a lane-cycle: 8/2 + 4 = 8 (resp. 13) lane-cycles per pair, plus the
     reciprocal of the row sum."""
-    return k * 8 + TRANS_COST
+    return k * (8 if dist == 1 else 13) + TRANS_COST
 
 
 def measure_dense(ctx, binding, torch, np, G, reps):
@@ -108,8 +109,8 @@ def roofline_of(cfg, dist, fwd_ms, finfo):
     evals = finfo.iters + 1  # + the evaluation at C*
     per_eval = fwd_ms * 1e-3 / evals
     valu_ops = fwd_lane_ops_per_vector(cfg.k, cfg.d, dist)
-    matrix = cfg.d == 4 and dist == 1 and 17 <= cfg.k <= 256 and finfo.path == 2
-    ops = matrix_core_lane_cycles_per_vector(cfg.k) if matrix else valu_ops
+    matrix = cfg.d == 4 and 17 <= cfg.k <= 256 and finfo.path == 2
+    ops = matrix_core_lane_cycles_per_vector(cfg.k, dist) if matrix else valu_ops
     alu = ops * cfg.m / per_eval
     hbm = 4.0 * cfg.m * cfg.d / per_eval
     out = {

@@ -29,7 +29,7 @@ struct PersistFns {
 // Persistent forward / backward solve for the lane<->vector family; empty if K (D+1) > 32.
 PersistFns persist_kernel(int K, int D, int dist, bool bwd);
 // Persistent solve for the lane<->codeword family (launch with 1024 threads); empty if not instantiated.
-// matrix: prefer the matrix-core forward loop where one exists (d = 4, squared energy, k <= 256).
+// matrix: prefer the matrix-core forward loop where one exists (d = 4, k <= 256).
 PersistFns persist_lane_kernel(int KPL, int D, int dist, bool bwd, bool matrix);
 
 // b-bit code stream of the hard assignments and the reconstruction q(W, C) from it (codes.hip).

@@ -27,10 +27,10 @@ KernelFn lane_kernel_1(int, int, int);
 KernelFn small_kernel(int K, int D, int dist, int pass) {
     return dist == DIST_L2 ? small_kernel_0(K, D, pass) : small_kernel_1(K, D, pass);
 }
-PersistFns persist_lane_kernel_0(int, int, bool);
+PersistFns persist_lane_kernel_0(int, int, bool, bool);
 PersistFns persist_lane_kernel_1(int, int, bool, bool);
 PersistFns persist_lane_kernel(int KPL, int D, int dist, bool bwd, bool matrix) {
-    return dist == DIST_L2 ? persist_lane_kernel_0(KPL, D, bwd) : persist_lane_kernel_1(KPL, D, bwd, matrix);
+    return dist == DIST_L2 ? persist_lane_kernel_0(KPL, D, bwd, matrix) : persist_lane_kernel_1(KPL, D, bwd, matrix);
 }
 KernelFn lane_kernel(int KPL, int D, int dist, int pass) {
     return dist == DIST_L2 ? lane_kernel_0(KPL, D, pass) : lane_kernel_1(KPL, D, pass);

@@ -10,11 +10,11 @@ static PersistFns pick(bool bwd) {
                : PersistFns{persist_lane_fwd<KPL, D, 1>, persist_lane_fwd_batch<KPL, D, 1>};
 }
 
-// d = 4 with the squared energy: the forward loop runs on the matrix cores (k <= 256).
+// d = 4: the forward loop runs on the matrix cores (k <= 256).
 template <int KPL>
 static PersistFns pick4(bool bwd, bool matrix) {
     if (bwd || !matrix) return pick<KPL, 4>(bwd);
-    return PersistFns{persist_mfma_fwd<KPL>, persist_mfma_fwd_batch<KPL>, true};
+    return PersistFns{persist_mfma_fwd<KPL, 1>, persist_mfma_fwd_batch<KPL, 1>, true};
 }
 
 // Offered for KPL*D <= 16 and KPL*(D+1) <= 24 (k <= 512), d <= 4.

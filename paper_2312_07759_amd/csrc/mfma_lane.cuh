@@ -1,4 +1,5 @@
-// Matrix-core form of the forward loop for d = 4 and the squared energy (lane<->codeword family, k <= 256).
+// Matrix-core form of the forward loop for d = 4 (lane<->codeword family, k <= 256), written for the squared energy;
+// the plain norm takes the square root of the same product.
 //
 // In scaled coordinates t = s (w - c), s^2 = log2(e)/tau, the exponent of a weight of the row softmax
 // (Eq. "aterms") is  x_ij = -|t_ij|^2 = -s^2|w_i|^2 + 2 s^2 w_i.c_j - s^2|c_j|^2 :  a 16 x 16 tile of it is one
@@ -30,6 +31,14 @@ __device__ __forceinline__ float row16_sum(float x) {
     x += dpp_f<0x141, 0xf>(0.f, x);  // row_half_mirror
     x += dpp_f<0x140, 0xf>(0.f, x);  // row_mirror
     return x;                        // every lane of the row holds the row's total
+}
+__device__ __forceinline__ float row16_min(float x) {
+    const float pinf = __builtin_inff();
+    x = fminf(x, dpp_f<0xB1, 0xf>(pinf, x));
+    x = fminf(x, dpp_f<0x4E, 0xf>(pinf, x));
+    x = fminf(x, dpp_f<0x141, 0xf>(pinf, x));
+    x = fminf(x, dpp_f<0x140, 0xf>(pinf, x));
+    return x;
 }
 __device__ __forceinline__ float row16_max(float x) {
     const float ninf = -__builtin_inff();
@@ -100,8 +109,11 @@ struct MfmaFwd {
 
     // Vectors v0 .. v0+15 of the tile (s_w: [.][4] float32, s_wn: -s^2|w - mu|^2 per vector); those at or beyond vend
     // contribute nothing.  Both arrays are readable (finite values) up to index v0 + 15.
-    template <bool FOLD>
+    // DIST_L2 (s = log2(e)/tau): the energy is the square root of the same product, exp(-e/tau) = exp2(-|t|); rows
+    // underflow routinely there (|t| is large at small tau), so the row is always shifted by its minimum.
+    template <int DIST, bool FOLD>
     __device__ __forceinline__ void step(const float* s_w, const float* s_wn, int v0, int vend, float escale) {
+        static_assert(DIST == DIST_SQL2 || !FOLD, "the fold factors belong to the squared energy");
         const int lane = threadIdx.x & 63, j0 = lane & 15, q = lane >> 4;
         // the table entries are read anew in every step (kept in registers across steps they would spill)
         asm volatile("" ::: "memory");
@@ -159,12 +171,42 @@ struct MfmaFwd {
         // which the unshifted row sum shows
         products(!FOLD);
         if (!FOLD) add_norms();
+        if (DIST == DIST_L2) {
+            // x = -|t|^2 up to rounding (it may come out slightly positive next to a codeword: |.| is a free source
+            // modifier); a padding codeword is 1e15 away
+            float mn[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mn[r] = __builtin_inff();
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    x[b][r] = fast_sqrt(fabsf(x[b][r]));
+                    mn[r] = fminf(mn[r], x[b][r]);
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                mn[r] = row16_min(mn[r]);
+                S[r] = 0.f;
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    x[b][r] = fast_exp2(mn[r] - x[b][r]);
+                    S[r] += x[b][r];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[r] = row16_sum(S[r]);
+        }
         const float zero[4] = {0.f, 0.f, 0.f, 0.f};
-        weights(zero);
+        if (DIST == DIST_SQL2) weights(zero);
         bool under = false;
 #pragma unroll
         for (int r = 0; r < 4; ++r) under = under || (S[r] < 7.9e-31f);  // below 2^-100
-        if (__builtin_amdgcn_ballot_w64(under) != 0ull) {
+        if (DIST == DIST_SQL2 && __builtin_amdgcn_ballot_w64(under) != 0ull) {
             // the row maximum of the full exponent; folded, the shifted exponent again stays below FOLD_LIMIT
             products(true);
             add_norms();
@@ -205,7 +247,7 @@ struct MfmaFwd {
 };
 
 // One forward pass over the workgroup's tile: every wavefront takes an equal share of whole 16-vector steps.
-template <int KPL, int NT>
+template <int KPL, int DIST, int NT>
 __device__ __forceinline__ void mfma_tile_pass(MfmaFwd<KPL>& st, const float* s_w, const float* s_wn, int cnt,
                                                float escale, bool fold) {
     constexpr int NW = NT / 64;
@@ -214,10 +256,10 @@ __device__ __forceinline__ void mfma_tile_pass(MfmaFwd<KPL>& st, const float* s_
     share = (share + 15) & ~15;
     const int w0 = wave * share;
     const int w1 = (w0 + share < cnt) ? w0 + share : cnt;
-    if (fold) {
-        for (int v = w0; v < w1; v += 16) st.template step<true>(s_w, s_wn, v, w1, escale);
+    if (DIST == DIST_SQL2 && fold) {
+        for (int v = w0; v < w1; v += 16) st.template step<DIST_SQL2, true>(s_w, s_wn, v, w1, escale);
     } else {
-        for (int v = w0; v < w1; v += 16) st.template step<false>(s_w, s_wn, v, w1, escale);
+        for (int v = w0; v < w1; v += 16) st.template step<DIST, false>(s_w, s_wn, v, w1, escale);
     }
 }
 

@@ -193,11 +193,11 @@ __device__ __forceinline__ void lane_tile_pass(const Args& a, LaneWave<KPL, D, D
 #endif
 
 // Forward solve (Alg. 1) and the evaluation at C*.  MFMA: the loop's passes run on the matrix cores (mfma_lane.cuh;
-// d = 4, squared energy), with NT = MT threads; the dynamic LDS then holds the tile padded by 16 zero vectors and,
+// d = 4), with NT = MT threads; the dynamic LDS then holds the tile padded by 16 zero vectors and,
 // behind it, -s^2 |w|^2 of every vector.
 template <int KPL, int D, int DIST, int NT = LT, bool MFMA = false>
 __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs& pa) {
-    static_assert(!MFMA || (D == 4 && DIST == DIST_SQL2 && KPL <= 4), "matrix-core loop: d = 4, squared energy, k <= 256");
+    static_assert(!MFMA || (D == 4 && KPL <= 4), "matrix-core loop: d = 4, k <= 256");
     constexpr int ACCW = D + 1;
     constexpr int NA = KPL * ACCW;
     constexpr int KDP = 64 * KPL * D;  // padded codebook size
@@ -265,11 +265,12 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
             __shared__ float s_part[NT / 64][64 * KPL * ACCW];
             __shared__ float2 s_tab[4 * MfmaFwd<KPL>::TAB_STRIDE];
             __shared__ float s_fac[MfmaFwd<KPL>::TAB_STRIDE];
-            const bool fold = MfmaFwd<KPL>::template fill_table<NT>(s_tab, s_fac, k, s_Cf, s_mu, a.escale);
+            const bool fold = MfmaFwd<KPL>::template fill_table<NT>(s_tab, s_fac, k, s_Cf, s_mu, a.escale) &&
+                              DIST == DIST_SQL2;
             {
                 MfmaFwd<KPL> st;
                 st.init(s_tab, s_fac, s_mu);
-                mfma_tile_pass<KPL, NT>(st, s_tile, s_wn, cnt, a.escale, fold);
+                mfma_tile_pass<KPL, DIST, NT>(st, s_tile, s_wn, cnt, a.escale, fold);
                 IDKM_LSTAMP(1);
                 mfma_collect<KPL, NT>(st, &s_part[0][0], fold, s_fac);
             }
@@ -613,22 +614,22 @@ __global__ __launch_bounds__(LT) void persist_lane_fwd_batch(const BatchItem* it
     pa.G = it.wg_count;
     persist_lane_fwd_body<KPL, D, DIST>(a, pa);
 }
-// Forward solve with the loop on the matrix cores (d = 4, squared energy): MT threads, see persist_lane_fwd_body.
-template <int KPL>
+// Forward solve with the loop on the matrix cores (d = 4): MT threads, see persist_lane_fwd_body.
+template <int KPL, int DIST>
 __global__ __launch_bounds__(MT) void persist_mfma_fwd(const Args a, const PArgs pa_in) {
     PArgs pa = pa_in;
     pa.wg = blockIdx.x;
     pa.G = gridDim.x;
-    persist_lane_fwd_body<KPL, 4, DIST_SQL2, MT, true>(a, pa);
+    persist_lane_fwd_body<KPL, 4, DIST, MT, true>(a, pa);
 }
-template <int KPL>
+template <int KPL, int DIST>
 __global__ __launch_bounds__(MT) void persist_mfma_fwd_batch(const BatchItem* items, const unsigned short* item_of_wg) {
     const BatchItem& it = items[item_of_wg[blockIdx.x]];
     const Args a = it.a;
     PArgs pa = it.p;
     pa.wg = (int)blockIdx.x - it.wg_begin;
     pa.G = it.wg_count;
-    persist_lane_fwd_body<KPL, 4, DIST_SQL2, MT, true>(a, pa);
+    persist_lane_fwd_body<KPL, 4, DIST, MT, true>(a, pa);
 }
 template <int KPL, int D, int DIST>
 __global__ __launch_bounds__(LT) void persist_lane_bwd(const Args a, const PArgs pa_in) {
