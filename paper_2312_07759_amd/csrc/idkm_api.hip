@@ -167,6 +167,7 @@ struct idkm_ctx {
     hipStream_t pending_stream = nullptr;
     std::vector<Deferred>* sink = nullptr;  // set by a batched call: persistent launches are handed over, not issued
     std::map<const void*, std::pair<size_t, int>> checked;  // kernel -> (largest LDS size set, blocks per CU at that size)
+    std::map<const void*, size_t> static_lds;               // matrix-core kernels: bytes of static LDS
     unsigned int spin_limit = 1u << 20;
 #ifdef IDKM_TRACE
     long long* trace = nullptr;
@@ -323,13 +324,16 @@ struct Deferred {
     Args a;
     PArgs pa;
 };
+constexpr size_t LDS_PER_CU = 160 * 1024;
 constexpr size_t LANE_TILE_MAX = 94 * 1024;                       // the lane kernels keep ~55 KB of static LDS
 constexpr size_t LANE_BUF1_WORDS = (size_t)2 * PT * 1536;          // k (d+1) <= 1536
 constexpr size_t LANE_BUF2_WORDS = (size_t)2 * (1024 + 512);       // k d + k
 
 
 // Can (m, k, d) run as one persistent launch with `tiles` resident tensors (1: W; 2: W and dL/dWq)?
-bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
+// matrix_ok: the matrix-core kernels may serve the call (a JFB backward has no (dF/dC)^T pass to gain from them and
+// keeps the 1024-thread kernel for its two passes).
+bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp, bool matrix_ok = true) {
     if (!ctx->coop || ctx->num_cu < 1) return false;
     const int k = ctx->k, d = ctx->d;
     const int64_t m = ctx->m;
@@ -344,16 +348,29 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
         if (g > PT) g = PT;
         int64_t per = (m + g - 1) / g;
         per = (per + 3) / 4 * 4;
-        PersistFns fl = persist_lane_kernel(p, d, ctx->dist, bwd, true);
+        PersistFns fl = persist_lane_kernel(p, d, ctx->dist, bwd, matrix_ok);
         size_t lds = (size_t)per * d * sizeof(float) * (bwd ? 2 : 1);
         if (fl.matrix) {
-            // tile padded by 16 vectors, then one float per vector; the kernel keeps 40 KB more static LDS.
-            // A tile too large for that goes to the vector-ALU kernel.
+            // tile padded by 16 vectors, then one float per vector (dL/dWq is not kept); these kernels hold more
+            // static LDS than the vector-ALU ones.  A tile too large for what is left goes to the vector-ALU kernel.
             const size_t lds_m = (size_t)(per + 16) * (d + 1) * sizeof(float);
-            if (lds_m <= LANE_TILE_MAX - 40 * 1024)
-                lds = lds_m;
-            else
-                fl = persist_lane_kernel(p, d, ctx->dist, bwd, false);
+            size_t& fixed = ctx->static_lds[(const void*)fl.one];
+            if (fixed == 0) {
+                hipFuncAttributes at;
+                fixed = (hipFuncGetAttributes(&at, (const void*)fl.one) == hipSuccess) ? at.sharedSizeBytes : LDS_PER_CU;
+                (void)hipGetLastError();
+            }
+            if (fixed + lds_m <= LDS_PER_CU) {
+                pp->fn = fl.one;
+                pp->fn_batch = fl.batch;
+                pp->grid = (int)((m + per - 1) / per);
+                pp->per = (int)per;
+                pp->lds = lds_m;
+                pp->threads = MT;
+                pp->lane = true;
+                return true;
+            }
+            fl = persist_lane_kernel(p, d, ctx->dist, bwd, false);
         }
         pp->fn = fl.one;
         pp->fn_batch = fl.batch;
@@ -362,7 +379,7 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp) {
         pp->grid = (int)((m + per - 1) / per);
         pp->per = (int)per;
         pp->lds = lds;
-        pp->threads = fl.matrix ? MT : LT;
+        pp->threads = LT;
         pp->lane = true;
         return true;
     }
@@ -848,7 +865,8 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
 
     PersistPlan pp;
     // the minimal-residual solve keeps its O(k d R) state in one workgroup's tail: stream path only
-    const bool persistent = mode != IDKM_BWD_GMRES && ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &pp);
+    const bool persistent = mode != IDKM_BWD_GMRES && ctx->path != IDKM_PATH_STREAM &&
+                            plan_persistent(ctx, true, &pp, mode != IDKM_BWD_JFB);
     if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
         return fail(ctx, IDKM_ERR_UNSUPPORTED, mode == IDKM_BWD_GMRES
                         ? "IDKM_BWD_GMRES runs on the stream path only"

@@ -13,7 +13,8 @@ static PersistFns pick(bool bwd) {
 // d = 4: the forward loop runs on the matrix cores (k <= 256).
 template <int KPL>
 static PersistFns pick4(bool bwd, bool matrix) {
-    if (bwd || !matrix) return pick<KPL, 4>(bwd);
+    if (!matrix) return pick<KPL, 4>(bwd);
+    if (bwd) return PersistFns{persist_mfma_bwd<KPL>, persist_mfma_bwd_batch<KPL>, true};
     return PersistFns{persist_mfma_fwd<KPL, 1>, persist_mfma_fwd_batch<KPL, 1>, true};
 }
 

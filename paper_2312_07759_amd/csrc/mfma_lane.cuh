@@ -246,6 +246,232 @@ struct MfmaFwd {
     }
 };
 
+// Per-wavefront state of one (dF/dC)^T pass (Eq. "backiter", squared energy) on the matrix cores.
+//
+// With h_j = g_j / (tau n_j) (the pass's input, `Hs`), u_ij = h_j.(w_i - F_j), a_ij the row softmax and
+// ubar_i = sum_j a_ij u_ij, the pass returns  out_j = sum_i 2 a_ij (u_ij - ubar_i) (w_i - c_j)  (the caller divides by
+// tau n_j where needed, as for the vector-ALU pass).  u is a second 16x16x4 product (A: the scaled vectors again,
+// B: h_j / s, additive operand -h_j.(F_j - mu) from an LDS table of quads); the sum over i is the same pair of
+// accumulations as in the forward loop -- outer products th'_ij (x) (w_i - mu) 2/S_i and a scalar sum th'_ij 2/S_i per
+// codeword, th'_ij = p'_ij (u_ij - ubar_i) -- and  out_j = fac_j (sum th' (w - mu) - (c_j - mu) sum th').
+template <int KPL>
+struct MfmaB2 {
+    static constexpr int NB = 4 * KPL;
+    static constexpr int TAB_STRIDE = MfmaFwd<KPL>::TAB_STRIDE;
+    f32x4 sacc[NB];  // sum th' (w - mu) 2/S: layout as MfmaFwd::sacc
+    float tacc[NB];  // sum th' 2/S: layout as MfmaFwd::nacc
+    const float2* tab;   // as MfmaFwd::tab
+    const float* fac;    // as MfmaFwd::fac
+    const float* hsb;    // entry 16 b: h_j[l / 16] / s, j = 16 b + l % 16
+    const f32x4* hq;     // entry 16 b: four copies of -h_j.(F_j - mu)
+    float mu_q, mu_c;    // coordinates l / 16 and l % 4 of the reference point
+
+    __device__ __forceinline__ void init(const float2* s_tab, const float* s_fac, const float* s_hsb, const f32x4* s_hq,
+                                         const float* s_mu) {
+        const int lane = threadIdx.x & 63;
+        tab = s_tab + (lane >> 4) * TAB_STRIDE + (lane & 15);
+        fac = s_fac + (lane & 15);
+        hsb = s_hsb + (lane >> 4) * TAB_STRIDE + (lane & 15);
+        hq = s_hq + (lane & 15);
+        mu_q = s_mu[lane >> 4];
+        mu_c = s_mu[lane & 3];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            tacc[b] = 0.f;
+            sacc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+    // Per-pass tables of the cotangent: s_hsb[kk][j] = h_j[kk] / s, s_hq[j] = -h_j.(F_j - mu) four times.  Whole
+    // workgroup; the caller synchronises.
+    template <int NT>
+    static __device__ __forceinline__ void fill_cotangent(float* s_hsb, f32x4* s_hq, int k, const float* Hs,
+                                                          const float* Ff, const float* s_mu, float escale) {
+        const float inv = 1.0f / escale;
+        for (int idx = threadIdx.x; idx < 4 * TAB_STRIDE; idx += NT) {
+            const int kk = idx / TAB_STRIDE, j = idx - kk * TAB_STRIDE;
+            s_hsb[idx] = (j < k) ? Hs[j * 4 + kk] * inv : 0.f;
+            if (kk == 0) {
+                float hf = 0.f;
+                if (j < k) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) hf = fmaf(Hs[j * 4 + r], Ff[j * 4 + r] - s_mu[r], hf);
+                }
+                s_hq[j] = f32x4{-hf, -hf, -hf, -hf};
+            }
+        }
+    }
+
+    template <bool FOLD>
+    __device__ __forceinline__ void step(const float* s_w, const float* s_wn, int v0, int vend, float escale) {
+        const int lane = threadIdx.x & 63, j0 = lane & 15, q = lane >> 4;
+        asm volatile("" ::: "memory");
+        const float aw = (s_w[(v0 + j0) * 4 + q] - mu_q) * escale;
+        const f32x4 wn = *reinterpret_cast<const f32x4*>(&s_wn[v0 + 4 * q]);
+        float x[NB][4], cterm[NB];
+        auto products = [&](bool want_norms) {
+            float cbv[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) cbv[b] = tab[16 * b].x;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) cterm[b] = want_norms ? tab[16 * b].y : fac[16 * b];
+            f32x4 e[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, cbv[b], wn, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) x[b][r] = e[b][r];
+            }
+        };
+        auto add_norms = [&]() {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) x[b][r] += cterm[b];
+            }
+        };
+        float S[4];
+        auto weights = [&](const float (&shift)[4]) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[r] = 0.f;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    x[b][r] = fast_exp2(x[b][r] - shift[r]);
+                    S[r] = FOLD ? fmaf(x[b][r], cterm[b], S[r]) : S[r] + x[b][r];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[r] = row16_sum(S[r]);
+        };
+        products(!FOLD);
+        if (!FOLD) add_norms();
+        const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+        weights(zero);
+        bool under = false;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) under = under || (S[r] < 7.9e-31f);  // below 2^-100
+        if (__builtin_amdgcn_ballot_w64(under) != 0ull) {
+            products(true);
+            add_norms();
+            float mx[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                mx[r] = x[0][r];
+#pragma unroll
+                for (int b = 1; b < NB; ++b) mx[r] = fmaxf(mx[r], x[b][r]);
+                mx[r] = row16_max(mx[r]);
+            }
+            if (FOLD) products(false);
+            weights(mx);
+        }
+        // u_ij, then p' u in its place and the row sums Q_i = sum_j fac_j p'_ij u_ij
+        float u[NB][4];
+        {
+            float hv[NB];
+            f32x4 e[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                hv[b] = hsb[16 * b];
+                e[b] = hq[16 * b];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                if (FOLD) cterm[b] = fac[16 * b];  // again: the rare path above may have left norms there
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, hv[b], e[b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) u[b][r] = e[b][r];
+            }
+        }
+        float Q[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                u[b][r] *= x[b][r];
+                Q[r] = FOLD ? fmaf(u[b][r], cterm[b], Q[r]) : Q[r] + u[b][r];
+            }
+        }
+        float r2[4], nub[4], bw[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int v = v0 + 4 * q + r;
+            const float rS = (v < vend) ? fast_rcp(S[r]) : 0.f;
+            nub[r] = -(row16_sum(Q[r]) * rS);  // -ubar_i
+            r2[r] = 2.f * rS;
+            bw[r] = (s_w[v * 4 + (lane & 3)] - mu_c) * r2[r];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                u[b][r] = fmaf(nub[r], x[b][r], u[b][r]);  // th' = p' u - ubar p'
+                tacc[b] = fmaf(u[b][r], r2[r], tacc[b]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) sacc[b] = __builtin_amdgcn_mfma_f32_4x4x1f32(u[b][r], bw[r], sacc[b], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+};
+
+template <int KPL, int NT>
+__device__ __forceinline__ void mfma_b2_tile_pass(MfmaB2<KPL>& st, const float* s_w, const float* s_wn, int cnt,
+                                                  float escale, bool fold) {
+    constexpr int NW = NT / 64;
+    const int wave = threadIdx.x >> 6;
+    int share = (cnt + NW - 1) / NW;
+    share = (share + 15) & ~15;
+    const int w0 = wave * share;
+    const int w1 = (w0 + share < cnt) ? w0 + share : cnt;
+    if (fold) {
+        for (int v = w0; v < w1; v += 16) st.template step<true>(s_w, s_wn, v, w1, escale);
+    } else {
+        for (int v = w0; v < w1; v += 16) st.template step<false>(s_w, s_wn, v, w1, escale);
+    }
+}
+
+// Wavefront totals of the accumulators as float32 in s_part[NT / 64][64 KPL 5], word (codeword, sum th' | sum th' (w - mu)_r),
+// without the fold factor (the caller applies it together with the codeword term).
+template <int KPL, int NT>
+__device__ __forceinline__ void mfma_b2_collect(const MfmaB2<KPL>& st, float* s_part) {
+    constexpr int NB = 4 * KPL, ROW = 64 * KPL * 5;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q = lane >> 4, j0 = lane & 15, t = (lane >> 2) & 3, col = lane & 3;
+    float* out = s_part + wave * ROW;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        float n = st.tacc[b];
+        n += __shfl_xor(n, 16);
+        n += __shfl_xor(n, 32);
+        float s[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            s[i] = st.sacc[b][i];
+            s[i] += __shfl_xor(s[i], 16);
+            s[i] += __shfl_xor(s[i], 32);
+        }
+        if (q == 0) {
+            out[(16 * b + j0) * 5] = n;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) out[(16 * b + 4 * t + i) * 5 + 1 + col] = s[i];
+        }
+    }
+}
+
 // One forward pass over the workgroup's tile: every wavefront takes an equal share of whole 16-vector steps.
 template <int KPL, int DIST, int NT>
 __device__ __forceinline__ void mfma_tile_pass(MfmaFwd<KPL>& st, const float* s_w, const float* s_wn, int cnt,

@@ -393,9 +393,13 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
     }
 }
 
-// Backward: v, the averaged iteration of Sec. 4.2 (skipped for JFB), and dW.
-template <int KPL, int D, int DIST>
+// Backward: v, the averaged iteration of Sec. 4.2 (skipped for JFB), and dW.  MFMA: the (dF/dC)^T passes run on the
+// matrix cores (MfmaB2; d = 4, squared energy), with NT = MT threads; the dynamic LDS then holds the tile of W padded
+// by 16 zero vectors and -s^2 |w - mu|^2 of every vector, and dL/dWq -- needed by the first and the last pass only --
+// is read from memory.
+template <int KPL, int D, int DIST, int NT = LT, bool MFMA = false>
 __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs& pa) {
+    static_assert(!MFMA || (D == 4 && DIST == DIST_SQL2 && KPL <= 4), "matrix-core pass: d = 4, squared energy, k <= 256");
     constexpr int NA = KPL * D;
     constexpr int KDP = 64 * KPL * D;
     extern __shared__ float s_tile[];
@@ -415,18 +419,18 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
     int cnt = 0;
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
     float* s_w = s_tile;
-    float* s_gt = s_tile + (size_t)pa.per * D;
-    for (int i = tid; i < cnt * D; i += LT) {
+    const float* s_gt = MFMA ? a.G + base * D : s_tile + (size_t)pa.per * D;
+    for (int i = tid; i < cnt * D; i += NT) {
         s_w[i] = a.W[base * D + i];
-        s_gt[i] = a.G[base * D + i];
+        if (!MFMA) s_tile[(size_t)pa.per * D + i] = a.G[base * D + i];
     }
-    for (int i = tid; i < kd; i += LT) {
+    for (int i = tid; i < kd; i += NT) {
         s_Cf[i] = a.Cf[i];
         s_Ff[i] = a.Ff[i];
         s_Hs[i] = 0.f;
         s_Hv[i] = 0.f;
     }
-    for (int j = tid; j < k; j += LT) {
+    for (int j = tid; j < k; j += NT) {
         const double n = a.nd[j];
         s_rn[j] = (n > 0.0) ? (double)a.inv_tau / n : 0.0;
     }
@@ -450,14 +454,43 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
     }
     __syncthreads();
     unsigned int seq = pa.seq_base;
+    // matrix-core passes: reference point, vector norms and the codeword tables (C* does not change in the backward)
+    constexpr int TS = MfmaFwd<(KPL <= 4 ? KPL : 4)>::TAB_STRIDE;
+    __shared__ float2 s_tab0[MFMA ? 4 * TS : 1];
+    __shared__ float s_fac0[MFMA ? TS : 1];
+    __shared__ float s_hsb[MFMA ? 4 * TS : 1];
+    __shared__ f32x4 s_hq[MFMA ? TS : 1];
+    __shared__ float s_part[MFMA ? NT / 64 : 1][MFMA ? 64 * KPL * 5 : 1];
+    const float* s_wn = s_tile + (size_t)(pa.per + 16) * D;
+    __shared__ float s_mu[4];
+    bool fold = false;
+    if constexpr (MFMA) {
+        if (tid < D) {
+            float sm = 0.f;
+            for (int j = 0; j < k; ++j) sm += s_Cf[j * D + tid];
+            s_mu[tid] = sm / (float)k;
+        }
+        float* wn = s_tile + (size_t)(pa.per + 16) * D;
+        for (int i = cnt * D + tid; i < (pa.per + 16) * D; i += NT) s_tile[i] = 0.f;
+        __syncthreads();
+        for (int i = tid; i < pa.per + 16; i += NT) {
+            float n2 = 0.f;
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                const float t = (s_tile[i * D + r] - s_mu[r]) * a.escale;
+                n2 = fmaf(t, t, n2);
+            }
+            wn[i] = -n2;
+        }
+    }
 
     // B1
     {
         LaneWave<KPL, D, DIST, PASS_B1> st;
         st.init(k, s_Cf, s_Hs, s_Ff, a.escale);
-        lane_tile_pass<KPL, D, DIST, PASS_B1>(a, st, s_w, s_gt, base, cnt);
+        lane_tile_pass<KPL, D, DIST, PASS_B1, NT>(a, st, s_w, s_gt, base, cnt);
         ++seq;
-        publish_lane<NA, D>(pa, seq, st.acc, k, s_acc);
+        publish_lane<NA, D, NT>(pa, seq, st.acc, k, s_acc);
         for (int r = wg; r < k; r += G) {
             if (!reduce_lane<D>(pa, seq, kd, r * D, ls)) return;
             if (tid < 64) {
@@ -474,11 +507,11 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
                 if (tid == 0) st_word(&pa.buf2[(size_t)(seq & 1u) * stride2 + kd + r], pack_f(seq, (float)v2));
             }
         }
-        if (!gather_lane(pa, seq, kd + k, stride2, s_new, ls)) return;
+        if (!gather_lane<NT>(pa, seq, kd + k, stride2, s_new, ls)) return;
         double v2 = 0.0;
-        for (int i = tid; i < k; i += LT) v2 += (double)__uint_as_float(s_new[kd + i]);
-        v2 = block_sum_fixed(v2, ls);
-        for (int i = tid; i < kd; i += LT) {
+        for (int i = tid; i < k; i += NT) v2 += (double)__uint_as_float(s_new[kd + i]);
+        v2 = block_sum_fixed<NT>(v2, ls);
+        for (int i = tid; i < kd; i += NT) {
             s_Hs[i] = __uint_as_float(s_new[i]);
             s_Hv[i] = s_Hs[i];
         }
@@ -492,12 +525,38 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
         __syncthreads();
     }
 
+    if constexpr (MFMA) fold = MfmaFwd<KPL>::template fill_table<NT>(s_tab0, s_fac0, k, s_Cf, s_mu, a.escale);
     while (!s_done) {
-        LaneWave<KPL, D, DIST, PASS_B2> st;
-        st.init(k, s_Cf, s_Hs, s_Ff, a.escale);
-        lane_tile_pass<KPL, D, DIST, PASS_B2>(a, st, s_w, s_gt, base, cnt);
         ++seq;
-        publish_lane<NA, D>(pa, seq, st.acc, k, s_acc);
+        if constexpr (MFMA) {
+            MfmaB2<KPL>::template fill_cotangent<NT>(s_hsb, s_hq, k, s_Hs, s_Ff, s_mu, a.escale);
+            __syncthreads();
+            {
+                MfmaB2<KPL> st;
+                st.init(s_tab0, s_fac0, s_hsb, s_hq, s_mu);
+                mfma_b2_tile_pass<KPL, NT>(st, s_tile, s_wn, cnt, a.escale, fold);
+                mfma_b2_collect<KPL, NT>(st, &s_part[0][0]);
+            }
+            __syncthreads();
+            // wavefront totals add up in wavefront order (float64), then the codeword term and the fold factor
+            unsigned long long* dst = pa.buf1 + ((size_t)(seq & 1u) * pa.G + pa.wg) * kd;
+            for (int idx = tid; idx < kd; idx += NT) {
+                const int j = idx >> 2, r = idx & 3;
+                double sw = 0.0, st1 = 0.0;
+#pragma unroll
+                for (int w = 0; w < NT / 64; ++w) {
+                    sw += (double)s_part[w][j * 5 + 1 + r];
+                    st1 += (double)s_part[w][j * 5];
+                }
+                const double o = sw - (double)(s_Cf[idx] - s_mu[r]) * st1;
+                st_word(&dst[idx], pack_f(seq, (float)(fold ? o * (double)s_fac0[j] : o)));
+            }
+        } else {
+            LaneWave<KPL, D, DIST, PASS_B2> st;
+            st.init(k, s_Cf, s_Hs, s_Ff, a.escale);
+            lane_tile_pass<KPL, D, DIST, PASS_B2, NT>(a, st, s_w, s_gt, base, cnt);
+            publish_lane<NA, D, NT>(pa, seq, st.acc, k, s_acc);
+        }
         const double alpha = s_alpha;
         for (int r = wg; r < k; r += G) {
             if (!reduce_lane<D>(pa, seq, kd, r * D, ls)) return;
@@ -516,10 +575,10 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
                 if (tid == 0) st_word(&pa.buf2[(size_t)(seq & 1u) * stride2 + kd + r], pack_f(seq, (float)d2));
             }
         }
-        if (!gather_lane(pa, seq, kd + k, stride2, s_new, ls)) return;
+        if (!gather_lane<NT>(pa, seq, kd + k, stride2, s_new, ls)) return;
         double d2 = 0.0;
-        for (int i = tid; i < k; i += LT) d2 += (double)__uint_as_float(s_new[kd + i]);
-        d2 = block_sum_fixed(d2, ls);
+        for (int i = tid; i < k; i += NT) d2 += (double)__uint_as_float(s_new[kd + i]);
+        d2 = block_sum_fixed<NT>(d2, ls);
         if (tid == 0) {
             const double dn = d2;  // squared step norm: every comparison below is between squares
             bool restart = false, done = false, conv = false, diverged = false;
@@ -560,12 +619,12 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
         }
         __syncthreads();
         if (s_restart) {
-            for (int i = tid; i < kd; i += LT) {
+            for (int i = tid; i < kd; i += NT) {
                 s_Hs[i] = s_Hv[i];
                 s_g[i] = s_v[i];
             }
         } else {
-            for (int i = tid; i < kd; i += LT) s_Hs[i] = __uint_as_float(s_new[i]);
+            for (int i = tid; i < kd; i += NT) s_Hs[i] = __uint_as_float(s_new[i]);
         }
         __syncthreads();
     }
@@ -574,7 +633,7 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
     {
         LaneWave<KPL, D, DIST, PASS_B3> st;
         st.init(k, s_Cf, s_Hs, s_Ff, a.escale);
-        lane_tile_pass<KPL, D, DIST, PASS_B3>(a, st, s_w, s_gt, base, cnt);
+        lane_tile_pass<KPL, D, DIST, PASS_B3, NT>(a, st, s_w, s_gt, base, cnt);
     }
     for (int r = wg; r < k; r += G) {
         if (tid < D) {
@@ -583,7 +642,7 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
         }
     }
     if (wg == 0)
-        for (int i = tid; i < kd; i += LT) a.Hs[i] = s_Hs[i];
+        for (int i = tid; i < kd; i += NT) a.Hs[i] = s_Hs[i];
     if (wg == G - 1 && tid == 0) {
         PResult* o = pa.out;
         o->iters = s_iters;
@@ -630,6 +689,23 @@ __global__ __launch_bounds__(MT) void persist_mfma_fwd_batch(const BatchItem* it
     pa.wg = (int)blockIdx.x - it.wg_begin;
     pa.G = it.wg_count;
     persist_lane_fwd_body<KPL, 4, DIST, MT, true>(a, pa);
+}
+// Backward with the (dF/dC)^T passes on the matrix cores (d = 4, squared energy): MT threads, see persist_lane_bwd_body.
+template <int KPL>
+__global__ __launch_bounds__(MT) void persist_mfma_bwd(const Args a, const PArgs pa_in) {
+    PArgs pa = pa_in;
+    pa.wg = blockIdx.x;
+    pa.G = gridDim.x;
+    persist_lane_bwd_body<KPL, 4, DIST_SQL2, MT, true>(a, pa);
+}
+template <int KPL>
+__global__ __launch_bounds__(MT) void persist_mfma_bwd_batch(const BatchItem* items, const unsigned short* item_of_wg) {
+    const BatchItem& it = items[item_of_wg[blockIdx.x]];
+    const Args a = it.a;
+    PArgs pa = it.p;
+    pa.wg = (int)blockIdx.x - it.wg_begin;
+    pa.G = it.wg_count;
+    persist_lane_bwd_body<KPL, 4, DIST_SQL2, MT, true>(a, pa);
 }
 template <int KPL, int D, int DIST>
 __global__ __launch_bounds__(LT) void persist_lane_bwd(const Args a, const PArgs pa_in) {

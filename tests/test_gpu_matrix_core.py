@@ -124,3 +124,57 @@ def test_matches_the_vector_alu_kernels(ctx, dist):
         ctx.set_path(binding.PATH_PERSISTENT)
     assert a["info"].path == binding.PATH_PERSISTENT and b["info"].path == binding.PATH_STREAM
     assert rel(a["C"].cpu().numpy(), b["C"].cpu().numpy()) < 2e-5
+
+
+# ---- the (dF/dC)^T passes of the implicit backward on the matrix cores (squared energy)
+
+TOL_GRAD = 1e-3
+
+
+def _check_backward(ctx, W, C0, G, tau, iters=15, passes=12, alpha=1.0):
+    W, C0, G = W.astype(np.float32), C0.astype(np.float32), G.astype(np.float32)
+    out = ctx.forward(dev(W), dev(C0), tau, 0.0, iters, wl.DIST_SQL2)
+    Cg = out["C"].cpu().numpy()
+    bi = ctx.backward(dev(G), binding.BWD_IMPLICIT, tol=0.0, max_iter=passes, alpha=alpha)
+    assert bi["info"].path == binding.PATH_PERSISTENT
+    ri = orc.backward(W, Cg, tau, wl.DIST_SQL2, G, "implicit", tol=0.0, max_iter=passes, alpha=alpha)
+    if not (bi["info"].converged or ri["converged"]):
+        assert bi["info"].iters == ri["iters"] and bi["info"].alpha == ri["alpha"]
+    err = rel(bi["dW"].cpu().numpy(), ri["dW"])
+    assert err < TOL_GRAD, err
+    # the one-step variant of the same call keeps the vector-ALU kernel: both must agree with the oracle
+    bj = ctx.backward(dev(G), binding.BWD_JFB)
+    assert rel(bj["dW"].cpu().numpy(), orc.backward(W, Cg, tau, wl.DIST_SQL2, G, "jfb")["dW"]) < TOL_GRAD
+
+
+@pytest.mark.parametrize("m,k", [(4_001, 17), (20_011, 100), (7_777, 128), (30_000, 255), (65_537, 256), (300, 256)])
+def test_backward_shapes(ctx, m, k):
+    W, C0, G = wl.random_problem(m, 4, k, seed=2000 + m % 89 + k, std=0.5, spread=1.5)
+    C0 = C0 + 0.01 * np.random.default_rng(k).standard_normal(C0.shape)
+    _check_backward(ctx, W, C0, G, 0.3)
+
+
+def test_backward_damped(ctx):
+    W, C0, G = wl.random_problem(15_000, 4, 64, seed=2100, std=0.5, spread=1.5)
+    _check_backward(ctx, W, C0, G, 0.3, alpha=0.25)
+
+
+def test_backward_data_far_from_the_origin(ctx):
+    rng = np.random.default_rng(15)
+    m, k = 30_011, 64
+    W = 5.0 + 0.05 * rng.standard_normal((m, 4))
+    C0 = W[rng.choice(m, k, replace=False)] + 0.002 * rng.standard_normal((k, 4))
+    G = rng.standard_normal((m, 4))
+    _check_backward(ctx, W, C0, G, 1e-3, iters=25)
+
+
+@pytest.mark.parametrize("tau", [2e-4, 2e-3])
+def test_backward_rows_that_underflow(ctx, tau):
+    rng = np.random.default_rng(16)
+    m, k = 12_345, 100
+    W = 0.05 * rng.standard_normal((m, 4))
+    far = rng.choice(m, 40, replace=False)
+    W[far] += rng.choice([-1.0, 1.0], size=(40, 4)) * 1.5
+    C0 = W[rng.choice(np.setdiff1d(np.arange(m), far), k, replace=False)].copy()
+    G = rng.standard_normal((m, 4))
+    _check_backward(ctx, W, C0, G, tau, iters=15, passes=8)
