@@ -85,6 +85,11 @@ idkm_status idkm_destroy(idkm_ctx* ctx);
 const char* idkm_last_error(const idkm_ctx* ctx);
 /* Select the scheduling path for subsequent calls (default IDKM_PATH_AUTO). */
 idkm_status idkm_set_path(idkm_ctx* ctx, idkm_path path);
+/* Shapes with d = 4 and 17 <= k <= 256 run the forward loop (Alg. 1) and, for the squared energy, the (dF/dC)^T
+ * passes of the backward (Eq. "backiter") on the matrix cores.  enable = 0 sends them to the vector-ALU kernels
+ * that serve every other shape instead (diagnostics, comparisons); the default is 1.  Takes effect from the next
+ * idkm_forward; a backward follows the setting in force at its call. */
+idkm_status idkm_set_matrix_cores(idkm_ctx* ctx, int32_t enable);
 /* Bound of every device-side wait of the persistent kernels, in polls (default 2^20, about a second).  When a
  * wait expires all workgroups leave the kernel and the call returns IDKM_ERR_DEVICE; the context stays usable.
  * A limit of 0 makes the first unsuccessful poll give up (used to exercise that path). */

@@ -268,6 +268,21 @@ __device__ __forceinline__ double fast_div_d(double s, double n) {
     return s * r;
 }
 
+// Sum of squares with every multiplication and addition rounded on its own, in index order.  This is the float32 key
+// of the hard assignment for d > 1 and has to be the same number in every kernel and in a checker that emulates it;
+// the compiler's default would fuse the additions into multiply-adds (and the rounded-operation intrinsics are plain
+// operators in this toolchain), so contraction is switched off for these statements.
+template <int D>
+__device__ __forceinline__ float sum_sq_unfused(const float (&x)[D]) {
+#pragma clang fp contract(off)
+    float key = x[0] * x[0];
+#pragma unroll
+    for (int r = 1; r < D; ++r) {
+        const float sq = x[r] * x[r];
+        key = key + sq;
+    }
+    return key;
+}
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ __forceinline__ float fast_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }

@@ -11,6 +11,10 @@ KernelFn small_kernel(int K, int D, int dist, int pass);
 // Lane<->codeword family: KPL = ceil(k/64) rounded up to {1,2,4,8,16}, D in {1,2,4,8}, KPL*(D+1) <= 80.
 KernelFn lane_kernel(int KPL, int D, int dist, int pass);
 
+// Matrix-core form of a lane<->codeword pass for d = 4 (512 threads, dynamic LDS = (vec_per_wg + 16) * 20 bytes);
+// nullptr where there is none (KPL > 4; passes other than the forward loop and the squared energy's (dF/dC)^T).
+KernelFn mfma_lane_kernel(int KPL, int dist, int pass);
+
 // Lane<->codeword family, stream path: reduction of the per-workgroup partials and the O(k d) tail of a pass.
 KernelFn lane_tail_kernel(int pass);
 KernelFn lane_tail_wide_kernel();  // PASS_B2 tail for 1024 threads

@@ -169,6 +169,7 @@ struct idkm_ctx {
     std::map<const void*, std::pair<size_t, int>> checked;  // kernel -> (largest LDS size set, blocks per CU at that size)
     std::map<const void*, size_t> static_lds;               // matrix-core kernels: bytes of static LDS
     unsigned int spin_limit = 1u << 20;
+    bool use_matrix = true;           // d = 4, 17 <= k <= 256: matrix-core kernels where they exist
 #ifdef IDKM_TRACE
     long long* trace = nullptr;
 #endif
@@ -199,6 +200,10 @@ struct Geometry {
     int kpl;       // lane<->codeword family: codewords per lane
     int nwg;       // workgroups per pass
     int64_t vec_per_wg;
+    // d = 4, 17 <= k <= 256: the forward loop and the squared energy's (dF/dC)^T pass have a matrix-core form
+    bool matrix = false;
+    int nwg_m = 0;
+    int64_t vec_per_wg_m = 0;
 };
 
 bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
@@ -229,6 +234,20 @@ idkm_status plan(idkm_ctx* ctx, int64_t m, int k, int d, Geometry* g) {
     int64_t nwg = (m + g->vec_per_wg - 1) / g->vec_per_wg;
     if (nwg > 0x3fffffff) return fail(ctx, IDKM_ERR_UNSUPPORTED, "m too large");
     g->nwg = (int)nwg;
+    g->matrix = false;
+    if (!g->small && d == 4 && g->kpl <= 4 && ctx->use_matrix) {
+        // one workgroup of 512 threads per compute unit and round where the layer allows it; a chunk is a whole
+        // number of 16-vector steps for each of the 8 wavefronts and at most 46 KB of LDS
+        int64_t v = (m + ctx->num_cu - 1) / (ctx->num_cu > 0 ? ctx->num_cu : 1);
+        v = (v + 127) / 128 * 128;
+        if (v > 2304) v = 2304;
+        const int64_t n = (m + v - 1) / v;
+        if (n <= nwg) {  // the partial-sum buffer is sized for nwg workgroups
+            g->matrix = true;
+            g->vec_per_wg_m = v;
+            g->nwg_m = (int)n;
+        }
+    }
     return IDKM_OK;
 }
 
@@ -280,8 +299,10 @@ Args base_args(idkm_ctx* ctx) {
 
 idkm_status launch_pass(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, hipStream_t s) {
     KernelFn fn = g.small ? small_kernel(ctx->k, ctx->d, ctx->dist, pass) : lane_kernel(g.kpl, ctx->d, ctx->dist, pass);
-    if (!fn) return fail(ctx, IDKM_ERR_UNSUPPORTED, "no kernel for this (k, d)");
-    a.vec_per_wg = g.vec_per_wg;
+    KernelFn fn_m = g.matrix ? mfma_lane_kernel(g.kpl, ctx->dist, pass) : nullptr;
+    if (!fn && !fn_m) return fail(ctx, IDKM_ERR_UNSUPPORTED, "no kernel for this (k, d)");
+    const int nwg = fn_m ? g.nwg_m : g.nwg;
+    a.vec_per_wg = fn_m ? g.vec_per_wg_m : g.vec_per_wg;
     if (++ctx->stream_launches > 0x7fff0000u) {
         // the sequence numbers that stamp the partial sums would wrap: start over from a cleared buffer
         hipLaunchKernelGGL(k_fill_u64, dim3(256), dim3(256), 0, s, reinterpret_cast<unsigned long long*>(ctx->partials),
@@ -290,12 +311,15 @@ idkm_status launch_pass(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, hip
         HIP_TRY(ctx, hipGetLastError());
         ctx->stream_launches = 1;
     }
-    hipLaunchKernelGGL(fn, dim3(g.nwg), dim3(WG), 0, s, a);
+    if (fn_m)
+        hipLaunchKernelGGL(fn_m, dim3(nwg), dim3(512), (size_t)(a.vec_per_wg + 16) * 20, s, a);
+    else
+        hipLaunchKernelGGL(fn, dim3(nwg), dim3(WG), 0, s, a);
     HIP_TRY(ctx, hipGetLastError());
     if (!g.small && pass != PASS_B3) {
         // this family carries k (d+1) sums per workgroup: a many-workgroup reduction, then a one-workgroup tail
         const int nacc = ctx->k * ((pass == PASS_FWD || pass == PASS_FIN) ? ctx->d + 1 : ctx->d);
-        launch_reduce_rows(a, nacc, g.nwg, pass, s);
+        launch_reduce_rows(a, nacc, nwg, pass, s);
         HIP_TRY(ctx, hipGetLastError());
         if (pass == PASS_B2 && ctx->wide_tail)
             hipLaunchKernelGGL(lane_tail_wide_kernel(), dim3(1), dim3(1024), 0, s, a);
@@ -348,7 +372,7 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp, bool matrix_ok = 
         if (g > PT) g = PT;
         int64_t per = (m + g - 1) / g;
         per = (per + 3) / 4 * 4;
-        PersistFns fl = persist_lane_kernel(p, d, ctx->dist, bwd, matrix_ok);
+        PersistFns fl = persist_lane_kernel(p, d, ctx->dist, bwd, matrix_ok && ctx->use_matrix);
         size_t lds = (size_t)per * d * sizeof(float) * (bwd ? 2 : 1);
         if (fl.matrix) {
             // tile padded by 16 vectors, then one float per vector (dL/dWq is not kept); these kernels hold more
@@ -663,6 +687,12 @@ idkm_status idkm_set_path(idkm_ctx* ctx, idkm_path path) {
     if (path != IDKM_PATH_AUTO && path != IDKM_PATH_STREAM && path != IDKM_PATH_PERSISTENT)
         return fail(ctx, IDKM_ERR_INVALID_ARG, "unknown path");
     ctx->path = path;
+    return IDKM_OK;
+}
+
+idkm_status idkm_set_matrix_cores(idkm_ctx* ctx, int32_t enable) {
+    if (!ctx) return IDKM_ERR_INVALID_ARG;
+    ctx->use_matrix = enable != 0;
     return IDKM_OK;
 }
 

@@ -264,9 +264,7 @@ struct LaneWave {
                         if (D == 1) {
                             key[q] = fabsf(df[q][0]);
                         } else {
-                            key[q] = __fmul_rn(df[q][0], df[q][0]);
-#pragma unroll
-                            for (int r = 1; r < D; ++r) key[q] = __fadd_rn(key[q], __fmul_rn(df[q][r], df[q][r]));
+                            key[q] = sum_sq_unfused<D>(df[q]);
                         }
                         if (!valid[q]) key[q] = inf;
                         bk = fminf(bk, key[q]);

@@ -183,9 +183,7 @@ struct SmallItem {
                     if (D == 1) {
                         key = fabsf(df[j][0]);
                     } else {
-                        key = __fmul_rn(df[j][0], df[j][0]);
-#pragma unroll
-                        for (int r = 1; r < D; ++r) key = __fadd_rn(key, __fmul_rn(df[j][r], df[j][r]));
+                        key = sum_sq_unfused<D>(df[j]);
                     }
                     if (j == 0 || key < bk) {
                         bk = key;

@@ -1,5 +1,5 @@
-"""The matrix-core form of the forward loop (d = 4, 17 <= k <= 256, persistent path, both energies) against the
-float64 oracle.
+"""The matrix-core kernels (d = 4, 17 <= k <= 256: the forward loop for both energies, the (dF/dC)^T passes for the
+squared one; persistent and stream path) against the float64 oracle.
 
 That loop evaluates the exponent of Eq. "aterms" in its expanded form  -s^2|w|^2 + 2 s^2 w.c - s^2|c|^2  (one
 16 x 16 x 4 matrix product per tile) instead of summing squared differences, so these cases aim at what the expansion
@@ -39,10 +39,14 @@ def ctx():
     c.close()
 
 
-def _check(ctx, W, C0, tau, iters, tol=0.0, DIST=wl.DIST_SQL2):
+def _check(ctx, W, C0, tau, iters, tol=0.0, DIST=wl.DIST_SQL2, path=binding.PATH_PERSISTENT):
     W, C0 = W.astype(np.float32), C0.astype(np.float32)
-    out = ctx.forward(dev(W), dev(C0), tau, tol, iters, DIST, want_assign=True)
-    assert out["info"].path == binding.PATH_PERSISTENT
+    ctx.set_path(path)
+    try:
+        out = ctx.forward(dev(W), dev(C0), tau, tol, iters, DIST, want_assign=True)
+    finally:
+        ctx.set_path(binding.PATH_PERSISTENT)
+    assert out["info"].path == path
     ref = orc.soft_kmeans(W, C0, tau, tol, iters, DIST)
     Cg = out["C"].cpu().numpy()
     assert np.isfinite(Cg).all()
@@ -112,18 +116,34 @@ def test_codewords_on_top_of_vectors(ctx):
 
 
 @BOTH
-def test_matches_the_vector_alu_kernels(ctx, dist):
-    # the same solve on the stream path (vector-ALU kernels, summed squared differences)
-    W, C0, _ = wl.random_problem(50_021, 4, 200, seed=78, std=0.5, spread=1.5)
-    W, C0 = W.astype(np.float32), C0.astype(np.float32)
-    a = ctx.forward(dev(W), dev(C0), 0.2, 0.0, 30, dist)
-    ctx.set_path(binding.PATH_STREAM)
+@pytest.mark.parametrize("path", [binding.PATH_PERSISTENT, binding.PATH_STREAM], ids=["persistent", "stream"])
+def test_matches_the_vector_alu_kernels(ctx, dist, path):
+    # the same solve with the matrix-core kernels switched off (vector ALU, summed squared differences)
+    W, C0, G = wl.random_problem(50_021, 4, 200, seed=78, std=0.5, spread=1.5)
+    W, C0, G = W.astype(np.float32), C0.astype(np.float32), G.astype(np.float32)
+    ctx.set_path(path)
     try:
+        a = ctx.forward(dev(W), dev(C0), 0.2, 0.0, 30, dist)
+        ga = ctx.backward(dev(G), binding.BWD_IMPLICIT, tol=0.0, max_iter=10, alpha=1.0)
+        ctx.set_matrix_cores(False)
         b = ctx.forward(dev(W), dev(C0), 0.2, 0.0, 30, dist)
+        gb = ctx.backward(dev(G), binding.BWD_IMPLICIT, tol=0.0, max_iter=10, alpha=1.0)
     finally:
+        ctx.set_matrix_cores(True)
         ctx.set_path(binding.PATH_PERSISTENT)
-    assert a["info"].path == binding.PATH_PERSISTENT and b["info"].path == binding.PATH_STREAM
+    assert a["info"].path == path and b["info"].path == path
     assert rel(a["C"].cpu().numpy(), b["C"].cpu().numpy()) < 2e-5
+    # the two backward solves start from slightly different C*: a loose bar, the oracle comparisons are the test
+    assert rel(ga["dW"].cpu().numpy(), gb["dW"].cpu().numpy()) < 2e-3
+
+
+@BOTH
+@pytest.mark.parametrize("m,k", [(4_001, 17), (20_011, 100), (65_537, 256), (300, 256), (19, 17), (700_001, 64)])
+def test_stream_path_shapes(ctx, m, k, dist):
+    # one launch per pass: chunks of up to 2304 vectors, a ragged last workgroup, more workgroups than compute units
+    W, C0, _ = wl.random_problem(m, 4, k, seed=3000 + m % 97 + k, std=0.5, spread=1.5)
+    C0 = C0 + 0.01 * np.random.default_rng(k).standard_normal(C0.shape)
+    _check(ctx, W, C0, 0.3, 12 if m > 100_000 else 20, DIST=dist, path=binding.PATH_STREAM)
 
 
 # ---- the (dF/dC)^T passes of the implicit backward on the matrix cores (squared energy)
@@ -131,19 +151,23 @@ def test_matches_the_vector_alu_kernels(ctx, dist):
 TOL_GRAD = 1e-3
 
 
-def _check_backward(ctx, W, C0, G, tau, iters=15, passes=12, alpha=1.0):
+def _check_backward(ctx, W, C0, G, tau, iters=15, passes=12, alpha=1.0, path=binding.PATH_PERSISTENT):
     W, C0, G = W.astype(np.float32), C0.astype(np.float32), G.astype(np.float32)
-    out = ctx.forward(dev(W), dev(C0), tau, 0.0, iters, wl.DIST_SQL2)
-    Cg = out["C"].cpu().numpy()
-    bi = ctx.backward(dev(G), binding.BWD_IMPLICIT, tol=0.0, max_iter=passes, alpha=alpha)
-    assert bi["info"].path == binding.PATH_PERSISTENT
+    ctx.set_path(path)
+    try:
+        out = ctx.forward(dev(W), dev(C0), tau, 0.0, iters, wl.DIST_SQL2)
+        Cg = out["C"].cpu().numpy()
+        bi = ctx.backward(dev(G), binding.BWD_IMPLICIT, tol=0.0, max_iter=passes, alpha=alpha)
+        bj = ctx.backward(dev(G), binding.BWD_JFB)
+    finally:
+        ctx.set_path(binding.PATH_PERSISTENT)
+    assert bi["info"].path == path
     ri = orc.backward(W, Cg, tau, wl.DIST_SQL2, G, "implicit", tol=0.0, max_iter=passes, alpha=alpha)
     if not (bi["info"].converged or ri["converged"]):
         assert bi["info"].iters == ri["iters"] and bi["info"].alpha == ri["alpha"]
     err = rel(bi["dW"].cpu().numpy(), ri["dW"])
     assert err < TOL_GRAD, err
     # the one-step variant of the same call keeps the vector-ALU kernel: both must agree with the oracle
-    bj = ctx.backward(dev(G), binding.BWD_JFB)
     assert rel(bj["dW"].cpu().numpy(), orc.backward(W, Cg, tau, wl.DIST_SQL2, G, "jfb")["dW"]) < TOL_GRAD
 
 
@@ -152,6 +176,13 @@ def test_backward_shapes(ctx, m, k):
     W, C0, G = wl.random_problem(m, 4, k, seed=2000 + m % 89 + k, std=0.5, spread=1.5)
     C0 = C0 + 0.01 * np.random.default_rng(k).standard_normal(C0.shape)
     _check_backward(ctx, W, C0, G, 0.3)
+
+
+@pytest.mark.parametrize("m,k", [(4_001, 17), (20_011, 100), (65_537, 256), (300, 256)])
+def test_backward_stream_path(ctx, m, k):
+    W, C0, G = wl.random_problem(m, 4, k, seed=2200 + m % 89 + k, std=0.5, spread=1.5)
+    C0 = C0 + 0.01 * np.random.default_rng(k).standard_normal(C0.shape)
+    _check_backward(ctx, W, C0, G, 0.3, path=binding.PATH_STREAM)
 
 
 def test_backward_damped(ctx):

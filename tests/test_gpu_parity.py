@@ -476,3 +476,35 @@ def test_results_do_not_change_when_the_sequence_numbers_wrap(path, shape):
         for x, y in zip(first[:3], again[:3]):
             assert torch.equal(x, y)
     c.close()
+
+
+# More codewords than the data has clusters: in a soft solve the surplus codewords settle on (almost) the same points,
+# so for many vectors the best and the second-best key differ by an ulp or not at all.  The integer result then hangs
+# on the last bit of the key: it must be the documented expression -- every product and sum rounded on its own, in
+# index order, lowest index on ties -- on every kernel family and path.
+@pytest.mark.parametrize("m,d,k,clusters", [(300, 4, 256, 0), (500, 2, 100, 0), (20_000, 4, 16, 3), (20_000, 2, 8, 2),
+                                            (5_000, 4, 200, 5), (3_000, 8, 32, 4)])
+@pytest.mark.parametrize("path", [binding.PATH_STREAM, binding.PATH_PERSISTENT], ids=["stream", "persistent"])
+def test_assignments_with_nearly_tied_keys(ctx, m, d, k, clusters, path):
+    rng = np.random.default_rng(4242 + m + k)
+    if clusters:
+        centres = rng.standard_normal((clusters, d))
+        W = centres[rng.integers(0, clusters, m)] + 0.05 * rng.standard_normal((m, d))
+    else:
+        W = 0.5 * rng.standard_normal((m, d))
+    C0 = W[rng.choice(m, k, replace=False)] + 0.01 * rng.standard_normal((k, d))
+    W, C0 = W.astype(np.float32), C0.astype(np.float32)
+    ctx.set_path(path)
+    try:
+        for dist in DISTS:
+            try:
+                out = ctx.forward(dev(W), dev(C0), 0.3, 0.0, 25, dist, want_assign=True, want_Wq=False)
+            except binding.IdkmError as e:
+                assert path == binding.PATH_PERSISTENT and e.status == 6      # no persistent kernel for this shape
+                continue
+            Cg = out["C"].cpu().numpy()
+            ref = orc.hard_assign_f32(W, Cg)
+            got = out["assign"].cpu().numpy()
+            np.testing.assert_array_equal(got, ref)
+    finally:
+        ctx.set_path(binding.PATH_AUTO)
