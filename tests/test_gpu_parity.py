@@ -508,3 +508,31 @@ def test_assignments_with_nearly_tied_keys(ctx, m, d, k, clusters, path):
             np.testing.assert_array_equal(got, ref)
     finally:
         ctx.set_path(binding.PATH_AUTO)
+
+
+def test_warm_start_and_temperature_schedule(ctx):
+    # Alg. 2 solves the same layer again at every training step, and Sec. 6 suggests annealing the temperature: both
+    # are sequences of ordinary calls in which C0 is the previous C* and tau changes.  Each stage is held to the oracle
+    # from the same C0; the warm-started last stage must need fewer evaluations than a cold start at that temperature.
+    cfg = wl.CONFIGS["C3"]
+    p = wl.make_problem(cfg, wl.DIST_SQL2, m=100_003)
+    W = p.W
+    Wd = dev(W)
+    C = p.C0.copy()
+    rng = np.random.default_rng(11)
+    stage_iters = []
+    for stage, tau in enumerate([4 * p.tau, 2 * p.tau, p.tau, p.tau]):
+        if stage == 3:
+            # an SGD-like move of the weights (1 % of their spread) before the last solve
+            W = (W + 1e-2 * W.std() * rng.standard_normal(W.shape)).astype(np.float32)
+            Wd = dev(W)
+        out = ctx.forward(Wd, dev(C), tau, p.tol, p.max_iter, wl.DIST_SQL2, want_Wq=False)
+        ref = orc.soft_kmeans(W, C, tau, p.tol, p.max_iter, wl.DIST_SQL2)
+        Cg = out["C"].cpu().numpy()
+        assert out["info"].converged and ref["converged"]
+        assert abs(out["info"].iters - ref["iters"]) <= 1
+        assert rel(Cg, ref["C"]) < TOL_VAL
+        stage_iters.append(out["info"].iters)
+        C = Cg
+    cold = ctx.forward(Wd, dev(p.C0), p.tau, p.tol, p.max_iter, wl.DIST_SQL2, want_Wq=False)
+    assert stage_iters[-1] < cold["info"].iters
