@@ -355,6 +355,36 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
         ++seq;
         publish_partials<NACC>(pa, seq, acc, xs);
         IDKM_STAMP(2);
+        if (pa.G == 1) {
+            // a team of one has no exchange: its partial sums (xs.own, the float32 words it would have published)
+            // are the totals, and the whole codebook is updated here
+            __syncthreads();
+            if (tid < 64) {
+                double df2 = 0.0;
+                if (tid < KD) {
+                    const int j = tid / D, rr = tid - j * D;
+                    const double n = (double)xs.own[j * ACCW], sv = (double)xs.own[j * ACCW + 1 + rr];
+                    const double cold = s_Cd[tid];
+                    double cnew = (n > 0.0) ? fast_div_d(sv, n) : cold;
+                    if (!(n >= 0.0) || !(fabs(sv) <= 1.7e308) || !(fabs(cnew) <= 1.7e308)) cnew = __builtin_nan("");
+                    s_Cd[tid] = cnew;
+                    const float cn = (float)cnew;
+                    const double df = (double)cn - (double)s_Cf[tid];
+                    df2 = df * df;
+                    s_Cf[tid] = cn;
+                }
+                const double r2 = first_lanes_sum_d_dpp<KD>(df2);
+                if (tid == 0) {
+                    s_iters += 1;
+                    s_res = r2;
+                    const bool bad = !(r2 <= 1.7e308);
+                    if (bad) s_bad = 1;
+                    const bool conv = r2 < tol * tol;
+                    s_conv = conv ? 1 : 0;
+                    if (conv || bad || s_iters >= max_iter) s_done = 1;
+                }
+            }
+        } else {
         for (int r = wg; r < R; r += pa.G) {
             if (!reduce_slice<NACC, WPR>(pa, seq, r * WPR, xs)) return;
             IDKM_STAMP(3);
@@ -413,6 +443,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
                 s_conv = conv ? 1 : 0;
                 if (conv || bad || s_iters >= max_iter) s_done = 1;
             }
+        }
         }
         __syncthreads();
         IDKM_SUB(10);
@@ -645,6 +676,25 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         ++seq;
         publish_partials<KD>(pa, seq, acc, xs);
         const double alpha = s_alpha;
+        if (pa.G == 1) {
+            // a team of one has no exchange: its partial sums (xs.own) are the totals; the whole of g is updated
+            // here and the step norm goes where the decision below expects the reducers' parts
+            __syncthreads();
+            if (tid < 64) {
+                double d2 = 0.0;
+                if (tid < KD) {
+                    const double g = s_g[tid];
+                    const double gn = alpha * (s_v[tid] + (double)xs.own[tid]) + (1.0 - alpha) * g;
+                    const double df = gn - g;
+                    d2 = df * df;
+                    s_g[tid] = gn;
+                    xs.bc[tid] = __float_as_uint((float)(gn * s_rn[tid / D]));
+                }
+                d2 = first_lanes_sum_d_dpp<KD>(d2);
+                if (tid < R) xs.bc[KD + tid] = (tid == 0) ? __float_as_uint((float)d2) : 0u;
+            }
+            __syncthreads();
+        } else {
         for (int r = wg; r < R; r += pa.G) {
             if (!reduce_slice<KD, WPR>(pa, seq, r * WPR, xs)) return;
             if (tid < 64) {
@@ -668,6 +718,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
             }
         }
         if (!gather_bcast<KD, WPR, KD>(pa, seq, NB, true, xs)) return;
+        }
         if (tid == 0) {
             // the same decision in every workgroup (same words, same order)
             double d2 = 0.0;
