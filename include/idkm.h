@@ -90,6 +90,12 @@ idkm_status idkm_set_path(idkm_ctx* ctx, idkm_path path);
  * that serve every other shape instead (diagnostics, comparisons); the default is 1.  Takes effect from the next
  * idkm_forward; a backward follows the setting in force at its call. */
 idkm_status idkm_set_matrix_cores(idkm_ctx* ctx, int32_t enable);
+/* Persistent path, k in {2,4,8,16}: a workgroup keeps its share of W (and of dL/dWq in the backward) in LDS when it
+ * is at most `bytes` (default and maximum 147456).  A layer with larger shares (more than about 9.4 M weights) is
+ * served by the stream path under IDKM_PATH_AUTO; under IDKM_PATH_PERSISTENT the same one-launch solve reads W and
+ * dL/dWq from memory in every pass (needs both 16-byte aligned, else IDKM_ERR_UNSUPPORTED).  Smaller values of
+ * `bytes` send smaller layers that way (test support, comparisons). */
+idkm_status idkm_set_tile_limit(idkm_ctx* ctx, int64_t bytes);
 /* Bound of every device-side wait of the persistent kernels, in polls (default 2^20, about a second).  When a
  * wait expires all workgroups leave the kernel and the call returns IDKM_ERR_DEVICE; the context stays usable.
  * A limit of 0 makes the first unsuccessful poll give up (used to exercise that path). */

@@ -22,7 +22,7 @@ BWD_IMPLICIT, BWD_JFB, BWD_DENSE, BWD_GMRES = 0, 1, 2, 3
 PATH_AUTO, PATH_STREAM, PATH_PERSISTENT = 0, 1, 2
 
 EXPORTS = ["idkm_version", "idkm_limits", "idkm_status_string", "idkm_create", "idkm_destroy", "idkm_last_error",
-           "idkm_set_path", "idkm_set_matrix_cores", "idkm_set_spin_limit", "idkm_set_gmres_basis", "idkm_advance_sequence", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT",
+           "idkm_set_path", "idkm_set_matrix_cores", "idkm_set_tile_limit", "idkm_set_spin_limit", "idkm_set_gmres_basis", "idkm_advance_sequence", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT",
            "idkm_calibrate", "idkm_code_bits", "idkm_code_words", "idkm_pack_codes", "idkm_unpack_quantize",
            "idkm_batch_create", "idkm_batch_destroy", "idkm_batch_last_error", "idkm_batch_launches",
            "idkm_batch_context", "idkm_batch_forward", "idkm_batch_backward"]
@@ -81,6 +81,8 @@ def load_library():
     lib.idkm_last_error.restype = C.c_char_p
     lib.idkm_set_path.argtypes = [vp, C.c_int]
     lib.idkm_set_path.restype = C.c_int
+    lib.idkm_set_tile_limit.argtypes = [vp, C.c_int64]
+    lib.idkm_set_tile_limit.restype = C.c_int
     lib.idkm_set_matrix_cores.argtypes = [vp, C.c_int32]
     lib.idkm_set_matrix_cores.restype = C.c_int
     lib.idkm_set_spin_limit.argtypes = [vp, C.c_uint32]
@@ -187,6 +189,9 @@ class Context:
 
     def set_path(self, path: int):
         self._check(self._lib.idkm_set_path(self._h, int(path)))
+
+    def set_tile_limit(self, nbytes: int):
+        self._check(self._lib.idkm_set_tile_limit(self._h, int(nbytes)))
 
     def set_matrix_cores(self, enable: bool):
         self._check(self._lib.idkm_set_matrix_cores(self._h, 1 if enable else 0))

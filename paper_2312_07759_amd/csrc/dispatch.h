@@ -32,6 +32,9 @@ struct PersistFns {
 };
 // Persistent forward / backward solve for the lane<->vector family; empty if K (D+1) > 32.
 PersistFns persist_kernel(int K, int D, int dist, bool bwd);
+// The same for a layer that does not fit the chip's LDS: W (and dL/dWq) are read from memory in every pass, no
+// dynamic LDS; single-problem launch form only.
+PersistFns persist_kernel_global(int K, int D, int dist, bool bwd);
 // Persistent solve for the lane<->codeword family (launch with 1024 threads); empty if not instantiated.
 // matrix: prefer the matrix-core forward loop where one exists (d = 4, k <= 256).
 PersistFns persist_lane_kernel(int KPL, int D, int dist, bool bwd, bool matrix);

@@ -242,6 +242,8 @@ __device__ __forceinline__ bool gather_bcast(const PArgs& pa, unsigned int seq, 
     return xs.abort == 0;
 }
 
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
 // One pass over the workgroup's LDS tile.
 // SHARED: the workgroup shares its SIMDs with other teams' workgroups (batched launches); the hardware then
 // interleaves wavefronts, and short groups keep the registers low enough for four or five workgroups per compute unit.
@@ -296,6 +298,100 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
     }
 }
 
+// The same pass for a layer that does not fit the chip's LDS: W (and dL/dWq) are read from memory in every pass, 16
+// bytes per lane and load, with the loads of the next batch in flight while the current one is worked on (one
+// wavefront per SIMD has nothing else to hide their latency with).  The workgroups of the team take 4 KB blocks in
+// turn (block t G + wg in round t), so that at any moment the team reads one contiguous window of memory: with a
+// contiguous share per workgroup and a power-of-two layer, all workgroups would hit the same memory channel.
+// gw, gg: the whole tensors, 16-byte aligned.
+template <int K, int D, int DIST, int PASS>
+__device__ __forceinline__ void tile_pass_global(const Args& a, const float* gw, const float* gg, int wg, int G,
+                                                 const float* s_Cf, const float* s_Hs, const float* s_Ff,
+                                                 float (&acc)[SmallItem<K, D, DIST, PASS>::NACC]) {
+    using Item = SmallItem<K, D, DIST, PASS>;
+    float c[K][D], hs[K][D], ff[K][D];
+#pragma unroll
+    for (int j = 0; j < K; ++j)
+#pragma unroll
+        for (int r = 0; r < D; ++r) {
+            c[j][r] = s_Cf[j * D + r];
+            hs[j][r] = Item::USE_H ? s_Hs[j * D + r] : 0.f;
+            ff[j][r] = Item::USE_F ? s_Ff[j * D + r] : 0.f;
+        }
+#pragma unroll
+    for (int q = 0; q < Item::NACC; ++q) acc[q] = 0.f;
+    constexpr int VPL = 4 / D;                // vectors per 16-byte load
+    constexpr int NLD = Item::USE_G ? 4 : 8;  // loads in flight per lane and operand
+    const int64_t ngroups = a.m / VPL;        // whole 16-byte groups of the layer
+    const f32x4_t* w4 = reinterpret_cast<const f32x4_t*>(gw);
+    const f32x4_t* g4 = reinterpret_cast<const f32x4_t*>(gg);
+    auto work = [&](int64_t gi, const f32x4_t& wq, const f32x4_t& gq) {
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+            float w[D], g[D];
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                w[r] = wq[v * D + r];
+                g[r] = Item::USE_G ? gq[v * D + r] : 0.f;
+            }
+            Item::run(a, gi * VPL + v, w, g, c, hs, ff, acc);
+        }
+    };
+    const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4_t cw[NLD], cg[NLD], nw[NLD], ng[NLD];
+    const int64_t step = (int64_t)G * PT;           // groups per round of the team
+    int64_t gi = (int64_t)wg * PT + threadIdx.x;    // this lane's group in round 0
+#pragma unroll
+    for (int u = 0; u < NLD; ++u) {
+        const int64_t i = gi + u * step;
+        cw[u] = (i < ngroups) ? w4[i] : zero;
+        cg[u] = (Item::USE_G && i < ngroups) ? g4[i] : zero;
+    }
+    // the loop bound is the same for all lanes of the workgroup up to the last, partial block
+    for (; gi < ngroups; gi += NLD * step) {
+        const int64_t nx = gi + NLD * step;
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int64_t i = nx + u * step;
+            nw[u] = (i < ngroups) ? w4[i] : zero;
+            ng[u] = (Item::USE_G && i < ngroups) ? g4[i] : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            if (gi + u * step < ngroups) work(gi + u * step, cw[u], cg[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            cw[u] = nw[u];
+            cg[u] = ng[u];
+        }
+    }
+    // the vectors behind the last whole 16-byte group of the layer (fewer than VPL) go to the last workgroup
+    if (wg == G - 1) {
+        for (int64_t it = ngroups * VPL + threadIdx.x; it < a.m; it += PT) {
+            float w[D], g[D];
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                w[r] = gw[it * D + r];
+                g[r] = Item::USE_G ? gg[it * D + r] : 0.f;
+            }
+            Item::run(a, it, w, g, c, hs, ff, acc);
+        }
+    }
+}
+
+// A pass over the workgroup's share of the layer: its LDS tile (w, g: the tile; base, cnt: its place in the layer) or,
+// GLOBALW, its blocks of the tensors in memory (w, g: the whole tensors).
+template <int K, int D, int DIST, int PASS, bool SHARED, bool GLOBALW>
+__device__ __forceinline__ void any_tile_pass(const Args& a, const PArgs& pa, const float* w, const float* g,
+                                              int64_t base, int cnt, const float* s_Cf, const float* s_Hs,
+                                              const float* s_Ff, float (&acc)[SmallItem<K, D, DIST, PASS>::NACC]) {
+    if constexpr (GLOBALW)
+        tile_pass_global<K, D, DIST, PASS>(a, w, g, pa.wg, pa.G, s_Cf, s_Hs, s_Ff, acc);
+    else
+        tile_pass<K, D, DIST, PASS, SHARED>(a, w, g, base, cnt, s_Cf, s_Hs, s_Ff, acc);
+}
+
 // Codewords per reducer: as many as fit 8 words of (n_j, s_j) per workgroup.
 constexpr int cw_per_reducer(int K, int D) {
     int kpr = 8 / (D + 1);
@@ -306,7 +402,8 @@ constexpr int cw_per_reducer(int K, int D) {
 }
 
 // Forward solve (Alg. 1) and the evaluation at C*, in one launch.
-template <int K, int D, int DIST, bool SHARED>
+// GLOBALW: the layer does not fit the chip's LDS; every pass reads the workgroup's share of W from memory.
+template <int K, int D, int DIST, bool SHARED, bool GLOBALW = false>
 __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa) {
     constexpr int KD = K * D;
     constexpr int ACCW = D + 1;
@@ -327,7 +424,9 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     const int64_t base = (int64_t)wg * pa.per;
     int cnt = 0;
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
-    for (int i = tid; i < cnt * D; i += PT) s_tile[i] = a.W[base * D + i];
+    if (!GLOBALW)
+        for (int i = tid; i < cnt * D; i += PT) s_tile[i] = a.W[base * D + i];
+    const float* s_w = GLOBALW ? a.W : s_tile;
     if (tid < KD) {
         const float c0 = pa.C0[tid];
         s_Cd[tid] = (double)c0;
@@ -350,7 +449,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     float acc[NACC];
     while (!s_done) {
         IDKM_STAMP(0);
-        tile_pass<K, D, DIST, PASS_FWD, SHARED>(a, s_tile, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
+        any_tile_pass<K, D, DIST, PASS_FWD, SHARED, GLOBALW>(a, pa, s_w, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
         IDKM_STAMP(1);
         ++seq;
         publish_partials<NACC>(pa, seq, acc, xs);
@@ -452,7 +551,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     }
 
     // evaluation at C*: outputs, and n*, F* for the backward
-    tile_pass<K, D, DIST, PASS_FIN, SHARED>(a, s_tile, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
+    any_tile_pass<K, D, DIST, PASS_FIN, SHARED, GLOBALW>(a, pa, s_w, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
     ++seq;
     publish_partials<NACC>(pa, seq, acc, xs);
     for (int r = wg; r < R; r += pa.G) {
@@ -495,7 +594,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
 
 // Backward (Alg. 2 per-layer steps): v, the averaged fixed-point iteration of
 // Sec. 4.2 for g (skipped for JFB), and dW, in one launch.
-template <int K, int D, int DIST, bool SHARED>
+template <int K, int D, int DIST, bool SHARED, bool GLOBALW = false>
 __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa) {
     constexpr int KD = K * D;
     constexpr int KPR = (8 / D) > K ? K : (8 / D);  // codewords per reducer: 8 words of D components
@@ -518,11 +617,13 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     const int64_t base = (int64_t)wg * pa.per;
     int cnt = 0;
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
-    float* s_w = s_tile;
-    float* s_gt = s_tile + (size_t)pa.per * D;
-    for (int i = tid; i < cnt * D; i += PT) {
-        s_w[i] = a.W[base * D + i];
-        s_gt[i] = a.G[base * D + i];
+    const float* s_w = GLOBALW ? a.W : s_tile;
+    const float* s_gt = GLOBALW ? a.G : s_tile + (size_t)pa.per * D;
+    if (!GLOBALW) {
+        for (int i = tid; i < cnt * D; i += PT) {
+            s_tile[i] = a.W[base * D + i];
+            s_tile[(size_t)pa.per * D + i] = a.G[base * D + i];
+        }
     }
     if (tid < KD) {
         s_Cf[tid] = a.Cf[tid];
@@ -562,7 +663,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
             // one pass accumulates v and the sums T, U of dF/dC* (layout as in the stream path's tail_bj); workgroup 0
             // adds them over the team, solves (I - dF/dC*)^T g = v by Gauss-Jordan elimination and broadcasts h/tau
             float accj[NBJ];
-            tile_pass<K, D, DIST, PASS_BJ, SHARED>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, accj);
+            any_tile_pass<K, D, DIST, PASS_BJ, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, accj);
             ++seq;
             publish_partials<NBJ>(pa, seq, accj, xs);
             if (wg == 0) {
@@ -630,7 +731,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     }
     if (!dense_done) {
     // B1: v = dL/dC* with W fixed; the solve starts at g = v
-    tile_pass<K, D, DIST, PASS_B1, SHARED>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
+    any_tile_pass<K, D, DIST, PASS_B1, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
     ++seq;
     publish_partials<KD>(pa, seq, acc, xs);
     for (int r = wg; r < R; r += pa.G) {
@@ -672,7 +773,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     __syncthreads();
 
     while (!s_done) {
-        tile_pass<K, D, DIST, PASS_B2, SHARED>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
+        any_tile_pass<K, D, DIST, PASS_B2, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
         ++seq;
         publish_partials<KD>(pa, seq, acc, xs);
         const double alpha = s_alpha;
@@ -774,7 +875,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     }
 
     // B3: dW = direct + (dF/dW)^T g
-    tile_pass<K, D, DIST, PASS_B3, SHARED>(a, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, reinterpret_cast<float(&)[1]>(acc[0]));
+    any_tile_pass<K, D, DIST, PASS_B3, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, reinterpret_cast<float(&)[1]>(acc[0]));
     if (dense_done) {
         if (wg == 0 && tid < KD) {
             a.gd[tid] = s_g[tid];
@@ -817,6 +918,22 @@ __global__ __launch_bounds__(PT) void persist_bwd(const Args a, const PArgs pa_i
     pa.wg = blockIdx.x;
     pa.G = gridDim.x;
     persist_bwd_body<K, D, DIST, false>(a, pa);
+}
+
+// The same for a layer larger than the chip's LDS (W is read from memory in every pass; no dynamic LDS).
+template <int K, int D, int DIST>
+__global__ __launch_bounds__(PT) void persist_fwd_global(const Args a, const PArgs pa_in) {
+    PArgs pa = pa_in;
+    pa.wg = blockIdx.x;
+    pa.G = gridDim.x;
+    persist_fwd_body<K, D, DIST, false, true>(a, pa);
+}
+template <int K, int D, int DIST>
+__global__ __launch_bounds__(PT) void persist_bwd_global(const Args a, const PArgs pa_in) {
+    PArgs pa = pa_in;
+    pa.wg = blockIdx.x;
+    pa.G = gridDim.x;
+    persist_bwd_body<K, D, DIST, false, true>(a, pa);
 }
 
 // Several independent problems of one shape (the layers of Alg. 2's loops) in one launch: item_of_wg maps a
