@@ -11,9 +11,10 @@ KernelFn small_kernel(int K, int D, int dist, int pass);
 // Lane<->codeword family: KPL = ceil(k/64) rounded up to {1,2,4,8,16}, D in {1,2,4,8}, KPL*(D+1) <= 80.
 KernelFn lane_kernel(int KPL, int D, int dist, int pass);
 
-// Matrix-core form of a lane<->codeword pass for d = 4 (512 threads, dynamic LDS = (vec_per_wg + 16) * 20 bytes);
-// nullptr where there is none (KPL > 4; passes other than the forward loop and the squared energy's (dF/dC)^T).
+// Matrix-core form of a lane<->codeword pass for d = 4 (mfma_lane_threads threads, dynamic LDS = (vec_per_wg + 16) * 20 bytes);
+// nullptr where there is none (KPL > 4; passes other than the forward loop and (dF/dC)^T).
 KernelFn mfma_lane_kernel(int KPL, int dist, int pass);
+int mfma_lane_threads(int KPL, int dist, int pass);  // workgroup size that kernel is launched with
 
 // Lane<->codeword family, stream path: reduction of the per-workgroup partials and the O(k d) tail of a pass.
 KernelFn lane_tail_kernel(int pass);
@@ -28,7 +29,8 @@ typedef void (*PersistBatchFn)(const BatchItem*, const unsigned short*);
 struct PersistFns {
     PersistFn one = nullptr;
     PersistBatchFn batch = nullptr;
-    bool matrix = false;  // forward loop on the matrix cores: 512 threads, tile padded by 16 vectors plus one float per vector
+    bool matrix = false;  // matrix-core kernel: tile padded by 16 vectors plus one float per vector, `threads` per workgroup
+    int threads = 0;
 };
 // Persistent forward / backward solve for the lane<->vector family; empty if K (D+1) > 32.
 PersistFns persist_kernel(int K, int D, int dist, bool bwd);

@@ -313,7 +313,7 @@ idkm_status launch_pass(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, hip
         ctx->stream_launches = 1;
     }
     if (fn_m)
-        hipLaunchKernelGGL(fn_m, dim3(nwg), dim3(512), (size_t)(a.vec_per_wg + 16) * 20, s, a);
+        hipLaunchKernelGGL(fn_m, dim3(nwg), dim3(mfma_lane_threads(g.kpl, ctx->dist, pass)), (size_t)(a.vec_per_wg + 16) * 20, s, a);
     else
         hipLaunchKernelGGL(fn, dim3(nwg), dim3(WG), 0, s, a);
     HIP_TRY(ctx, hipGetLastError());
@@ -393,7 +393,7 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp, bool matrix_ok = 
                 pp->grid = (int)((m + per - 1) / per);
                 pp->per = (int)per;
                 pp->lds = lds_m;
-                pp->threads = MT;
+                pp->threads = fl.threads;
                 pp->lane = true;
                 return true;
             }

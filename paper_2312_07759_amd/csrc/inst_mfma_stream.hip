@@ -7,8 +7,13 @@ namespace idkm {
 template <int KPL>
 static KernelFn pick(int dist, int pass) {
     if (pass == PASS_FWD) return dist == DIST_L2 ? mfma_pass<KPL, DIST_L2, PASS_FWD> : mfma_pass<KPL, DIST_SQL2, PASS_FWD>;
-    if (pass == PASS_B2 && dist == DIST_SQL2) return mfma_pass<KPL, DIST_SQL2, PASS_B2>;
+    if (pass == PASS_B2) return dist == DIST_L2 ? mfma_pass<KPL, DIST_L2, PASS_B2> : mfma_pass<KPL, DIST_SQL2, PASS_B2>;
     return nullptr;
+}
+
+int mfma_lane_threads(int KPL, int dist, int pass) {
+    return (KPL == 4 && dist == DIST_L2 && pass == PASS_B2) ? mfma_stream_threads<4, DIST_L2, PASS_B2>()
+                                                             : mfma_stream_threads<1, DIST_SQL2, PASS_FWD>();
 }
 
 KernelFn mfma_lane_kernel(int KPL, int dist, int pass) {

@@ -13,8 +13,9 @@ static PersistFns pick(bool bwd) {
 // d = 4: the forward loop runs on the matrix cores (k <= 256).
 template <int KPL>
 static PersistFns pick4(bool bwd, bool matrix) {
-    if (bwd || !matrix) return pick<KPL, 4>(bwd);
-    return PersistFns{persist_mfma_fwd<KPL, 0>, persist_mfma_fwd_batch<KPL, 0>, true};
+    if (!matrix) return pick<KPL, 4>(bwd);
+    if (bwd) return PersistFns{persist_mfma_bwd<KPL, 0>, persist_mfma_bwd_batch<KPL, 0>, true, mfma_bwd_threads<KPL, 0>()};
+    return PersistFns{persist_mfma_fwd<KPL, 0>, persist_mfma_fwd_batch<KPL, 0>, true, MT};
 }
 
 // Offered for KPL*D <= 16 and KPL*(D+1) <= 24 (k <= 512), d <= 4.

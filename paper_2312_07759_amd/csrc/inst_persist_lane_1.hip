@@ -14,8 +14,8 @@ static PersistFns pick(bool bwd) {
 template <int KPL>
 static PersistFns pick4(bool bwd, bool matrix) {
     if (!matrix) return pick<KPL, 4>(bwd);
-    if (bwd) return PersistFns{persist_mfma_bwd<KPL>, persist_mfma_bwd_batch<KPL>, true};
-    return PersistFns{persist_mfma_fwd<KPL, 1>, persist_mfma_fwd_batch<KPL, 1>, true};
+    if (bwd) return PersistFns{persist_mfma_bwd<KPL, 1>, persist_mfma_bwd_batch<KPL, 1>, true, mfma_bwd_threads<KPL, 1>()};
+    return PersistFns{persist_mfma_fwd<KPL, 1>, persist_mfma_fwd_batch<KPL, 1>, true, MT};
 }
 
 // Offered for KPL*D <= 16 and KPL*(D+1) <= 24 (k <= 512), d <= 4.

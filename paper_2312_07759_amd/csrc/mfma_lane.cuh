@@ -246,7 +246,7 @@ struct MfmaFwd {
     }
 };
 
-// Per-wavefront state of one (dF/dC)^T pass (Eq. "backiter", squared energy) on the matrix cores.
+// Per-wavefront state of one (dF/dC)^T pass (Eq. "backiter") on the matrix cores; written out for the squared energy.
 //
 // With h_j = g_j / (tau n_j) (the pass's input, `Hs`), u_ij = h_j.(w_i - F_j), a_ij the row softmax and
 // ubar_i = sum_j a_ij u_ij, the pass returns  out_j = sum_i 2 a_ij (u_ij - ubar_i) (w_i - c_j)  (the caller divides by
@@ -301,8 +301,12 @@ struct MfmaB2 {
         }
     }
 
-    template <bool FOLD>
+    // DIST_L2 (s = log2(e)/tau): e_ij = sqrt(|x_ij|) in scaled units, the row is shifted by its minimum, and the
+    // derivative of the energy is the unit vector (w - c) s / e:  out_j = sum_i a_ij (u_ij - ubar_i) (w_i - c_j) s / e_ij,
+    // i.e. th'_ij = p_ij (u_ij - ubar_i) / e_ij with the per-vector factor s / S_i (zero where e_ij = 0 exactly).
+    template <int DIST, bool FOLD>
     __device__ __forceinline__ void step(const float* s_w, const float* s_wn, int v0, int vend, float escale) {
+        static_assert(DIST == DIST_SQL2 || !FOLD, "the fold factors belong to the squared energy");
         const int lane = threadIdx.x & 63, j0 = lane & 15, q = lane >> 4;
         asm volatile("" ::: "memory");
         const float aw = (s_w[(v0 + j0) * 4 + q] - mu_q) * escale;
@@ -347,30 +351,9 @@ struct MfmaB2 {
 #pragma unroll
             for (int r = 0; r < 4; ++r) S[r] = row16_sum(S[r]);
         };
-        products(!FOLD);
-        if (!FOLD) add_norms();
-        const float zero[4] = {0.f, 0.f, 0.f, 0.f};
-        weights(zero);
-        bool under = false;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) under = under || (S[r] < 7.9e-31f);  // below 2^-100
-        if (__builtin_amdgcn_ballot_w64(under) != 0ull) {
-            products(true);
-            add_norms();
-            float mx[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                mx[r] = x[0][r];
-#pragma unroll
-                for (int b = 1; b < NB; ++b) mx[r] = fmaxf(mx[r], x[b][r]);
-                mx[r] = row16_max(mx[r]);
-            }
-            if (FOLD) products(false);
-            weights(mx);
-        }
-        // u_ij, then p' u in its place and the row sums Q_i = sum_j fac_j p'_ij u_ij
+        // u_ij (second product) into u
         float u[NB][4];
-        {
+        auto cotangent_product = [&]() {
             float hv[NB];
             f32x4 e[NB];
 #pragma unroll
@@ -381,7 +364,7 @@ struct MfmaB2 {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                if (FOLD) cterm[b] = fac[16 * b];  // again: the rare path above may have left norms there
+                if (FOLD) cterm[b] = fac[16 * b];  // again: the rare path may have left norms there
             }
 #pragma unroll
             for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, hv[b], e[b], 0, 0, 0);
@@ -391,30 +374,92 @@ struct MfmaB2 {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) u[b][r] = e[b][r];
             }
-        }
+        };
         float Q[4] = {0.f, 0.f, 0.f, 0.f};
+        products(!FOLD);
+        if (!FOLD) add_norms();
+        if constexpr (DIST == DIST_SQL2) {
+            const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+            weights(zero);
+            bool under = false;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
+            for (int r = 0; r < 4; ++r) under = under || (S[r] < 7.9e-31f);  // below 2^-100
+            if (__builtin_amdgcn_ballot_w64(under) != 0ull) {
+                products(true);
+                add_norms();
+                float mx[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    mx[r] = x[0][r];
+#pragma unroll
+                    for (int b = 1; b < NB; ++b) mx[r] = fmaxf(mx[r], x[b][r]);
+                    mx[r] = row16_max(mx[r]);
+                }
+                if (FOLD) products(false);
+                weights(mx);
+            }
+            cotangent_product();
+            // p' u in place of u, and the row sums Q_i = sum_j fac_j p'_ij u_ij
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    u[b][r] *= x[b][r];
+                    Q[r] = FOLD ? fmaf(u[b][r], cterm[b], Q[r]) : Q[r] + u[b][r];
+                }
+            }
+        } else {
+            // energies and the row minimum; a padding codeword is 1e15 away
+            float mn[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mn[r] = __builtin_inff();
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    x[b][r] = fast_sqrt(fabsf(x[b][r]));
+                    mn[r] = fminf(mn[r], x[b][r]);
+                }
+            }
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                u[b][r] *= x[b][r];
-                Q[r] = FOLD ? fmaf(u[b][r], cterm[b], Q[r]) : Q[r] + u[b][r];
+                mn[r] = row16_min(mn[r]);
+                S[r] = 0.f;
             }
+            cotangent_product();
+            // weights p, row sums S and Q = sum p u; then p / e in place of the energy and p u / e in place of u
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float e = x[b][r];
+                    const float pw = fast_exp2(mn[r] - e);
+                    const float ri = (e > 0.f) ? fast_rcp(e) : 0.f;
+                    const float pu = pw * u[b][r];
+                    S[r] += pw;
+                    Q[r] += pu;
+                    x[b][r] = pw * ri;
+                    u[b][r] = pu * ri;
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[r] = row16_sum(S[r]);
         }
         float r2[4], nub[4], bw[4];
+        const float vfac = (DIST == DIST_SQL2) ? 2.f : escale;  // d e / d w = 2 (w - c), resp. (w - c) s / e_scaled
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int v = v0 + 4 * q + r;
             const float rS = (v < vend) ? fast_rcp(S[r]) : 0.f;
             nub[r] = -(row16_sum(Q[r]) * rS);  // -ubar_i
-            r2[r] = 2.f * rS;
+            r2[r] = vfac * rS;
             bw[r] = (s_w[v * 4 + (lane & 3)] - mu_c) * r2[r];
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                u[b][r] = fmaf(nub[r], x[b][r], u[b][r]);  // th' = p' u - ubar p'
+                u[b][r] = fmaf(nub[r], x[b][r], u[b][r]);  // th' = p' u - ubar p'  (plain norm: both over e)
                 tacc[b] = fmaf(u[b][r], r2[r], tacc[b]);
             }
         }
@@ -428,7 +473,7 @@ struct MfmaB2 {
     }
 };
 
-template <int KPL, int NT>
+template <int KPL, int DIST, int NT>
 __device__ __forceinline__ void mfma_b2_tile_pass(MfmaB2<KPL>& st, const float* s_w, const float* s_wn, int cnt,
                                                   float escale, bool fold) {
     constexpr int NW = NT / 64;
@@ -437,10 +482,10 @@ __device__ __forceinline__ void mfma_b2_tile_pass(MfmaB2<KPL>& st, const float* 
     share = (share + 15) & ~15;
     const int w0 = wave * share;
     const int w1 = (w0 + share < cnt) ? w0 + share : cnt;
-    if (fold) {
-        for (int v = w0; v < w1; v += 16) st.template step<true>(s_w, s_wn, v, w1, escale);
+    if (DIST == DIST_SQL2 && fold) {
+        for (int v = w0; v < w1; v += 16) st.template step<DIST_SQL2, true>(s_w, s_wn, v, w1, escale);
     } else {
-        for (int v = w0; v < w1; v += 16) st.template step<false>(s_w, s_wn, v, w1, escale);
+        for (int v = w0; v < w1; v += 16) st.template step<DIST, false>(s_w, s_wn, v, w1, escale);
     }
 }
 

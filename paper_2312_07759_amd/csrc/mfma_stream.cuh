@@ -1,7 +1,7 @@
 // Stream-path form of the matrix-core passes (d = 4, 17 <= k <= 256): one launch per pass, every workgroup copies its
 // chunk of W into LDS, runs the 16-vector steps of mfma_lane.cuh over it and leaves its partial sums in
 // a.partials[workgroup][.] (float64), which reduce_rows and the one-workgroup tail of the lane<->codeword family
-// then take as from lane_pass.  PASS_FWD (both energies) and PASS_B2 (squared energy).
+// then take as from lane_pass.  PASS_FWD and PASS_B2.
 #pragma once
 #include "common.cuh"
 #include "lane_k.cuh"
@@ -9,12 +9,18 @@
 
 namespace idkm {
 
-constexpr int MST = 512;  // threads per workgroup: 2 wavefronts per SIMD, as in the persistent kernels
+// Threads per workgroup: 2 wavefronts per SIMD, as in the persistent kernels; one for the plain norm's (dF/dC)^T pass
+// at k = 256, whose state does not fit 256 registers per lane.
+template <int KPL, int DIST, int PASS>
+constexpr int mfma_stream_threads() {
+    return (KPL == 4 && DIST == DIST_L2 && PASS == PASS_B2) ? 256 : 512;
+}
 
 // Dynamic LDS: (a.vec_per_wg + 16) vectors of 4 floats, then one float per vector.
 template <int KPL, int DIST, int PASS>
-__global__ __launch_bounds__(MST) void mfma_pass(const Args a) {
-    static_assert(PASS == PASS_FWD || (PASS == PASS_B2 && DIST == DIST_SQL2), "forward loop, or (dF/dC)^T of the squared energy");
+__global__ __launch_bounds__((mfma_stream_threads<KPL, DIST, PASS>())) void mfma_pass(const Args a) {
+    constexpr int MST = mfma_stream_threads<KPL, DIST, PASS>();
+    static_assert(PASS == PASS_FWD || PASS == PASS_B2, "forward loop or (dF/dC)^T pass");
     constexpr int TS = MfmaFwd<KPL>::TAB_STRIDE;
     constexpr bool B2 = (PASS == PASS_B2);
     if (PASS == PASS_FWD && a.ctrl->done) return;
@@ -59,7 +65,7 @@ __global__ __launch_bounds__(MST) void mfma_pass(const Args a) {
         {
             MfmaB2<KPL> st;
             st.init(s_tab, s_fac, s_hsb, s_hq, s_mu);
-            mfma_b2_tile_pass<KPL, MST>(st, s_tile, s_wn, cnt, a.escale, fold);
+            mfma_b2_tile_pass<KPL, DIST, MST>(st, s_tile, s_wn, cnt, a.escale, fold);
             mfma_b2_collect<KPL, MST>(st, &s_part[0][0]);
         }
         __syncthreads();

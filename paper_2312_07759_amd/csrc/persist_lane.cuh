@@ -394,12 +394,12 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
 }
 
 // Backward: v, the averaged iteration of Sec. 4.2 (skipped for JFB), and dW.  MFMA: the (dF/dC)^T passes run on the
-// matrix cores (MfmaB2; d = 4, squared energy), with NT = MT threads; the dynamic LDS then holds the tile of W padded
+// matrix cores (MfmaB2; d = 4), with NT = MT threads; the dynamic LDS then holds the tile of W padded
 // by 16 zero vectors and -s^2 |w - mu|^2 of every vector, and dL/dWq -- needed by the first and the last pass only --
 // is read from memory.
 template <int KPL, int D, int DIST, int NT = LT, bool MFMA = false>
 __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs& pa) {
-    static_assert(!MFMA || (D == 4 && DIST == DIST_SQL2 && KPL <= 4), "matrix-core pass: d = 4, squared energy, k <= 256");
+    static_assert(!MFMA || (D == 4 && KPL <= 4), "matrix-core pass: d = 4, k <= 256");
     constexpr int NA = KPL * D;
     constexpr int KDP = 64 * KPL * D;
     extern __shared__ float s_tile[];
@@ -525,7 +525,8 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
         __syncthreads();
     }
 
-    if constexpr (MFMA) fold = MfmaFwd<KPL>::template fill_table<NT>(s_tab0, s_fac0, k, s_Cf, s_mu, a.escale);
+    if constexpr (MFMA)
+        fold = MfmaFwd<KPL>::template fill_table<NT>(s_tab0, s_fac0, k, s_Cf, s_mu, a.escale) && DIST == DIST_SQL2;
     while (!s_done) {
         ++seq;
         if constexpr (MFMA) {
@@ -534,7 +535,7 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
             {
                 MfmaB2<KPL> st;
                 st.init(s_tab0, s_fac0, s_hsb, s_hq, s_mu);
-                mfma_b2_tile_pass<KPL, NT>(st, s_tile, s_wn, cnt, a.escale, fold);
+                mfma_b2_tile_pass<KPL, DIST, NT>(st, s_tile, s_wn, cnt, a.escale, fold);
                 mfma_b2_collect<KPL, NT>(st, &s_part[0][0]);
             }
             __syncthreads();
@@ -690,22 +691,28 @@ __global__ __launch_bounds__(MT) void persist_mfma_fwd_batch(const BatchItem* it
     pa.G = it.wg_count;
     persist_lane_fwd_body<KPL, 4, DIST, MT, true>(a, pa);
 }
-// Backward with the (dF/dC)^T passes on the matrix cores (d = 4, squared energy): MT threads, see persist_lane_bwd_body.
-template <int KPL>
-__global__ __launch_bounds__(MT) void persist_mfma_bwd(const Args a, const PArgs pa_in) {
+// Backward with the (dF/dC)^T passes on the matrix cores (d = 4), see persist_lane_bwd_body.  The plain norm's pass
+// keeps more per lane than 256 registers hold at k = 256 (energies and u for 16 x 256 pairs, the accumulators, the
+// row minima): that kernel runs one wavefront per SIMD, which may use the whole register file.
+template <int KPL, int DIST>
+constexpr int mfma_bwd_threads() {
+    return (DIST == DIST_L2 && KPL == 4) ? 256 : MT;
+}
+template <int KPL, int DIST>
+__global__ __launch_bounds__((mfma_bwd_threads<KPL, DIST>())) void persist_mfma_bwd(const Args a, const PArgs pa_in) {
     PArgs pa = pa_in;
     pa.wg = blockIdx.x;
     pa.G = gridDim.x;
-    persist_lane_bwd_body<KPL, 4, DIST_SQL2, MT, true>(a, pa);
+    persist_lane_bwd_body<KPL, 4, DIST, mfma_bwd_threads<KPL, DIST>(), true>(a, pa);
 }
-template <int KPL>
-__global__ __launch_bounds__(MT) void persist_mfma_bwd_batch(const BatchItem* items, const unsigned short* item_of_wg) {
+template <int KPL, int DIST>
+__global__ __launch_bounds__((mfma_bwd_threads<KPL, DIST>())) void persist_mfma_bwd_batch(const BatchItem* items, const unsigned short* item_of_wg) {
     const BatchItem& it = items[item_of_wg[blockIdx.x]];
     const Args a = it.a;
     PArgs pa = it.p;
     pa.wg = (int)blockIdx.x - it.wg_begin;
     pa.G = it.wg_count;
-    persist_lane_bwd_body<KPL, 4, DIST_SQL2, MT, true>(a, pa);
+    persist_lane_bwd_body<KPL, 4, DIST, mfma_bwd_threads<KPL, DIST>(), true>(a, pa);
 }
 template <int KPL, int D, int DIST>
 __global__ __launch_bounds__(LT) void persist_lane_bwd(const Args a, const PArgs pa_in) {

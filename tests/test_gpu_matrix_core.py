@@ -146,57 +146,72 @@ def test_stream_path_shapes(ctx, m, k, dist):
     _check(ctx, W, C0, 0.3, 12 if m > 100_000 else 20, DIST=dist, path=binding.PATH_STREAM)
 
 
-# ---- the (dF/dC)^T passes of the implicit backward on the matrix cores (squared energy)
+# ---- the (dF/dC)^T passes of the implicit backward on the matrix cores
 
 TOL_GRAD = 1e-3
 
 
-def _check_backward(ctx, W, C0, G, tau, iters=15, passes=12, alpha=1.0, path=binding.PATH_PERSISTENT):
+def _check_backward(ctx, W, C0, G, tau, iters=15, passes=12, alpha=1.0, path=binding.PATH_PERSISTENT, dist=wl.DIST_SQL2):
     W, C0, G = W.astype(np.float32), C0.astype(np.float32), G.astype(np.float32)
     ctx.set_path(path)
     try:
-        out = ctx.forward(dev(W), dev(C0), tau, 0.0, iters, wl.DIST_SQL2)
+        out = ctx.forward(dev(W), dev(C0), tau, 0.0, iters, dist)
         Cg = out["C"].cpu().numpy()
         bi = ctx.backward(dev(G), binding.BWD_IMPLICIT, tol=0.0, max_iter=passes, alpha=alpha)
         bj = ctx.backward(dev(G), binding.BWD_JFB)
     finally:
         ctx.set_path(binding.PATH_PERSISTENT)
     assert bi["info"].path == path
-    ri = orc.backward(W, Cg, tau, wl.DIST_SQL2, G, "implicit", tol=0.0, max_iter=passes, alpha=alpha)
+    ri = orc.backward(W, Cg, tau, dist, G, "implicit", tol=0.0, max_iter=passes, alpha=alpha)
     if not (bi["info"].converged or ri["converged"]):
         assert bi["info"].iters == ri["iters"] and bi["info"].alpha == ri["alpha"]
     err = rel(bi["dW"].cpu().numpy(), ri["dW"])
     assert err < TOL_GRAD, err
     # the one-step variant of the same call keeps the vector-ALU kernel: both must agree with the oracle
-    assert rel(bj["dW"].cpu().numpy(), orc.backward(W, Cg, tau, wl.DIST_SQL2, G, "jfb")["dW"]) < TOL_GRAD
+    assert rel(bj["dW"].cpu().numpy(), orc.backward(W, Cg, tau, dist, G, "jfb")["dW"]) < TOL_GRAD
 
 
+@BOTH
 @pytest.mark.parametrize("m,k", [(4_001, 17), (20_011, 100), (7_777, 128), (30_000, 255), (65_537, 256), (300, 256)])
-def test_backward_shapes(ctx, m, k):
+def test_backward_shapes(ctx, m, k, dist):
     W, C0, G = wl.random_problem(m, 4, k, seed=2000 + m % 89 + k, std=0.5, spread=1.5)
     C0 = C0 + 0.01 * np.random.default_rng(k).standard_normal(C0.shape)
-    _check_backward(ctx, W, C0, G, 0.3)
+    _check_backward(ctx, W, C0, G, 0.3, dist=dist)
 
 
+@BOTH
 @pytest.mark.parametrize("m,k", [(4_001, 17), (20_011, 100), (65_537, 256), (300, 256)])
-def test_backward_stream_path(ctx, m, k):
+def test_backward_stream_path(ctx, m, k, dist):
     W, C0, G = wl.random_problem(m, 4, k, seed=2200 + m % 89 + k, std=0.5, spread=1.5)
     C0 = C0 + 0.01 * np.random.default_rng(k).standard_normal(C0.shape)
-    _check_backward(ctx, W, C0, G, 0.3, path=binding.PATH_STREAM)
+    _check_backward(ctx, W, C0, G, 0.3, path=binding.PATH_STREAM, dist=dist)
 
 
-def test_backward_damped(ctx):
+@BOTH
+def test_backward_damped(ctx, dist):
     W, C0, G = wl.random_problem(15_000, 4, 64, seed=2100, std=0.5, spread=1.5)
-    _check_backward(ctx, W, C0, G, 0.3, alpha=0.25)
+    _check_backward(ctx, W, C0, G, 0.3, alpha=0.25, dist=dist)
 
 
-def test_backward_data_far_from_the_origin(ctx):
+@BOTH
+def test_backward_data_far_from_the_origin(ctx, dist):
     rng = np.random.default_rng(15)
     m, k = 30_011, 64
     W = 5.0 + 0.05 * rng.standard_normal((m, 4))
     C0 = W[rng.choice(m, k, replace=False)] + 0.002 * rng.standard_normal((k, 4))
     G = rng.standard_normal((m, 4))
-    _check_backward(ctx, W, C0, G, 1e-3, iters=25)
+    _check_backward(ctx, W, C0, G, 1e-3 if dist == wl.DIST_SQL2 else 1e-2, iters=25, dist=dist)
+
+
+def test_backward_codewords_on_top_of_vectors(ctx):
+    # plain norm: the derivative of the energy is the unit vector (w - c)/|w - c|, zero where the two coincide; with
+    # initial codewords that are rows of W and a single evaluation of F such pairs stay close to coincident
+    rng = np.random.default_rng(19)
+    m, k = 20_000, 96
+    W = 0.05 * rng.standard_normal((m, 4))
+    C0 = W[rng.choice(m, k, replace=False)].copy()
+    G = rng.standard_normal((m, 4))
+    _check_backward(ctx, W, C0, G, 5e-3, iters=1, passes=6, dist=wl.DIST_L2)
 
 
 @pytest.mark.parametrize("tau", [2e-4, 2e-3])
