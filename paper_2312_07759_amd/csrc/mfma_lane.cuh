@@ -304,9 +304,16 @@ struct MfmaB2 {
     // DIST_L2 (s = log2(e)/tau): e_ij = sqrt(|x_ij|) in scaled units, the row is shifted by its minimum, and the
     // derivative of the energy is the unit vector (w - c) s / e:  out_j = sum_i a_ij (u_ij - ubar_i) (w_i - c_j) s / e_ij,
     // i.e. th'_ij = p_ij (u_ij - ubar_i) / e_ij with the per-vector factor s / S_i (zero where e_ij = 0 exactly).
-    template <int DIST, bool FOLD>
-    __device__ __forceinline__ void step(const float* s_w, const float* s_wn, int v0, int vend, float escale) {
+    //
+    // B1 (first pass of the backward, squared energy): the same sums with u_ij = (G_i / tau).c_j -- the second product
+    // takes A = ag (coordinate l / 16 of G_i / (2 s tau) for vector v0 + l % 16) and the codeword operand of the first
+    // -- plus the term sum_i a_ij G_i, a second set of outer products p'_ij (x) G_i / S_i (gb[r]: coordinate l % 4 of
+    // G for vector v0 + 4 (l / 16) + r) into the same accumulators:  v_j = fac_j (sacc_j - (c_j - mu) tacc_j).
+    template <int DIST, bool FOLD, bool B1 = false>
+    __device__ __forceinline__ void step(const float* s_w, const float* s_wn, int v0, int vend, float escale,
+                                         float ag = 0.f, const float* gb = nullptr) {
         static_assert(DIST == DIST_SQL2 || !FOLD, "the fold factors belong to the squared energy");
+        static_assert(DIST == DIST_SQL2 || !B1, "the first pass has this form for the squared energy only");
         const int lane = threadIdx.x & 63, j0 = lane & 15, q = lane >> 4;
         asm volatile("" ::: "memory");
         const float aw = (s_w[(v0 + j0) * 4 + q] - mu_q) * escale;
@@ -358,8 +365,8 @@ struct MfmaB2 {
             f32x4 e[NB];
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                hv[b] = hsb[16 * b];
-                e[b] = hq[16 * b];
+                hv[b] = B1 ? tab[16 * b].x : hsb[16 * b];
+                e[b] = B1 ? f32x4{0.f, 0.f, 0.f, 0.f} : hq[16 * b];
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -367,7 +374,7 @@ struct MfmaB2 {
                 if (FOLD) cterm[b] = fac[16 * b];  // again: the rare path may have left norms there
             }
 #pragma unroll
-            for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, hv[b], e[b], 0, 0, 0);
+            for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(B1 ? ag : aw, hv[b], e[b], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
@@ -445,7 +452,7 @@ struct MfmaB2 {
 #pragma unroll
             for (int r = 0; r < 4; ++r) S[r] = row16_sum(S[r]);
         }
-        float r2[4], nub[4], bw[4];
+        float r2[4], nub[4], bw[4], gw[4];
         const float vfac = (DIST == DIST_SQL2) ? 2.f : escale;  // d e / d w = 2 (w - c), resp. (w - c) s / e_scaled
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -454,6 +461,16 @@ struct MfmaB2 {
             nub[r] = -(row16_sum(Q[r]) * rS);  // -ubar_i
             r2[r] = vfac * rS;
             bw[r] = (s_w[v * 4 + (lane & 3)] - mu_c) * r2[r];
+            gw[r] = B1 ? gb[r] * rS : 0.f;
+        }
+        if constexpr (B1) {
+            // sum_i a_ij G_i: the weights are still untouched in x
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) sacc[b] = __builtin_amdgcn_mfma_f32_4x4x1f32(x[b][r], gw[r], sacc[b], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -486,6 +503,38 @@ __device__ __forceinline__ void mfma_b2_tile_pass(MfmaB2<KPL>& st, const float* 
         for (int v = w0; v < w1; v += 16) st.template step<DIST_SQL2, true>(s_w, s_wn, v, w1, escale);
     } else {
         for (int v = w0; v < w1; v += 16) st.template step<DIST, false>(s_w, s_wn, v, w1, escale);
+    }
+}
+
+// The first pass of the backward (squared energy): G (the workgroup's share of dL/dWq, [cnt][4] in memory) is read
+// one step ahead, so that its latency is hidden behind the current step.
+template <int KPL, int NT>
+__device__ __forceinline__ void mfma_b1_tile_pass(MfmaB2<KPL>& st, const float* s_w, const float* s_wn, const float* gG,
+                                                  int cnt, float escale, float inv_tau, bool fold) {
+    constexpr int NW = NT / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j0 = lane & 15, q = lane >> 4, col = lane & 3;
+    int share = (cnt + NW - 1) / NW;
+    share = (share + 15) & ~15;
+    const int w0 = wave * share;
+    const int w1 = (w0 + share < cnt) ? w0 + share : cnt;
+    const float gscale = inv_tau / (2.f * escale);
+    auto fetch = [&](int v, float& ag, float (&gb)[4]) {
+        ag = (v + j0 < cnt) ? gG[(size_t)(v + j0) * 4 + q] * gscale : 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) gb[r] = (v + 4 * q + r < cnt) ? gG[(size_t)(v + 4 * q + r) * 4 + col] : 0.f;
+    };
+    float ag = 0.f, gb[4] = {0.f, 0.f, 0.f, 0.f}, ag_n = 0.f, gb_n[4] = {0.f, 0.f, 0.f, 0.f};
+    if (w0 < w1) fetch(w0, ag, gb);
+    for (int v = w0; v < w1; v += 16) {
+        if (v + 16 < w1) fetch(v + 16, ag_n, gb_n);
+        if (fold)
+            st.template step<DIST_SQL2, true, true>(s_w, s_wn, v, w1, escale, ag, gb);
+        else
+            st.template step<DIST_SQL2, false, true>(s_w, s_wn, v, w1, escale, ag, gb);
+        ag = ag_n;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) gb[r] = gb_n[r];
     }
 }
 

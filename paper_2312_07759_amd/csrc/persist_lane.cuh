@@ -484,13 +484,45 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
         }
     }
 
+    if constexpr (MFMA)
+        fold = MfmaFwd<KPL>::template fill_table<NT>(s_tab0, s_fac0, k, s_Cf, s_mu, a.escale) && DIST == DIST_SQL2;
+    // Hop-1 store of a matrix-core pass: wavefront totals add up in wavefront order (float64), then the codeword
+    // term and the fold factor (see MfmaB2).
+    auto publish_matrix = [&]() {
+        if constexpr (MFMA) {
+            unsigned long long* dst = pa.buf1 + ((size_t)(seq & 1u) * pa.G + pa.wg) * kd;
+            for (int idx = tid; idx < kd; idx += NT) {
+                const int j = idx >> 2, r = idx & 3;
+                double sw = 0.0, st1 = 0.0;
+#pragma unroll
+                for (int w = 0; w < NT / 64; ++w) {
+                    sw += (double)s_part[w][j * 5 + 1 + r];
+                    st1 += (double)s_part[w][j * 5];
+                }
+                const double o = sw - (double)(s_Cf[idx] - s_mu[r]) * st1;
+                st_word(&dst[idx], pack_f(seq, (float)(fold ? o * (double)s_fac0[j] : o)));
+            }
+        }
+    };
+
     // B1
     {
-        LaneWave<KPL, D, DIST, PASS_B1> st;
-        st.init(k, s_Cf, s_Hs, s_Ff, a.escale);
-        lane_tile_pass<KPL, D, DIST, PASS_B1, NT>(a, st, s_w, s_gt, base, cnt);
         ++seq;
-        publish_lane<NA, D, NT>(pa, seq, st.acc, k, s_acc);
+        if constexpr (MFMA && DIST == DIST_SQL2) {
+            {
+                MfmaB2<KPL> st;
+                st.init(s_tab0, s_fac0, s_hsb, s_hq, s_mu);
+                mfma_b1_tile_pass<KPL, NT>(st, s_tile, s_wn, s_gt, cnt, a.escale, a.inv_tau, fold);
+                mfma_b2_collect<KPL, NT>(st, &s_part[0][0]);
+            }
+            __syncthreads();
+            publish_matrix();
+        } else {
+            LaneWave<KPL, D, DIST, PASS_B1> st;
+            st.init(k, s_Cf, s_Hs, s_Ff, a.escale);
+            lane_tile_pass<KPL, D, DIST, PASS_B1, NT>(a, st, s_w, s_gt, base, cnt);
+            publish_lane<NA, D, NT>(pa, seq, st.acc, k, s_acc);
+        }
         for (int r = wg; r < k; r += G) {
             if (!reduce_lane<D>(pa, seq, kd, r * D, ls)) return;
             if (tid < 64) {
@@ -525,8 +557,6 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
         __syncthreads();
     }
 
-    if constexpr (MFMA)
-        fold = MfmaFwd<KPL>::template fill_table<NT>(s_tab0, s_fac0, k, s_Cf, s_mu, a.escale) && DIST == DIST_SQL2;
     while (!s_done) {
         ++seq;
         if constexpr (MFMA) {
@@ -539,19 +569,7 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
                 mfma_b2_collect<KPL, NT>(st, &s_part[0][0]);
             }
             __syncthreads();
-            // wavefront totals add up in wavefront order (float64), then the codeword term and the fold factor
-            unsigned long long* dst = pa.buf1 + ((size_t)(seq & 1u) * pa.G + pa.wg) * kd;
-            for (int idx = tid; idx < kd; idx += NT) {
-                const int j = idx >> 2, r = idx & 3;
-                double sw = 0.0, st1 = 0.0;
-#pragma unroll
-                for (int w = 0; w < NT / 64; ++w) {
-                    sw += (double)s_part[w][j * 5 + 1 + r];
-                    st1 += (double)s_part[w][j * 5];
-                }
-                const double o = sw - (double)(s_Cf[idx] - s_mu[r]) * st1;
-                st_word(&dst[idx], pack_f(seq, (float)(fold ? o * (double)s_fac0[j] : o)));
-            }
+            publish_matrix();
         } else {
             LaneWave<KPL, D, DIST, PASS_B2> st;
             st.init(k, s_Cf, s_Hs, s_Ff, a.escale);
