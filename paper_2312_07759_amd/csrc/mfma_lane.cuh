@@ -490,6 +490,222 @@ struct MfmaB2 {
     }
 };
 
+// The last pass of the backward (squared energy) on the matrix cores:
+//   dL/dW_i = sum_j a_ij h_j - (1/tau) sum_j (rho_ij + gamma_ij) delta_ij            (Eq. "grad", Alg. 2 backward step)
+// With z_ij = (G_i/tau).c_j + (h_j/tau).(w_i - F_j) (two chained 16x16x4 products), kappa_ij = a_ij (z_ij - zbar_i),
+// zbar_i = sum_j a_ij z_ij, and delta_ij = 2 (w_i - c_j), the second sum is -2 sum_j kappa_ij (c_j - mu) because
+// sum_j kappa_ij = 0:   dL/dW_i = (1/S_i) sum_j fac_j [ p'_ij h_j + kappa'_ij 2 (c_j - mu) ],  kappa' = p' (z - zbar).
+// The sum over codewords runs over the registers of a lane (16 blocks) and then over the 16 lanes of its DPP row;
+// lane l % 16 = 4 r + c stores coordinate c of vector v0 + 4 (l / 16) + r: one coalesced 256-byte store per step.
+template <int KPL>
+struct MfmaB3 {
+    static constexpr int NB = 4 * KPL;
+    static constexpr int TAB_STRIDE = MfmaFwd<KPL>::TAB_STRIDE;
+    const float2* tab;
+    const float* fac;
+    const float* hsb;
+    const f32x4* hq;
+    const f32x4* hc;  // entry 16 b: fac_j h_j (4 coordinates); entry TAB_STRIDE + 16 b: fac_j 2 (c_j - mu)
+    float mu_q;
+
+    __device__ __forceinline__ void init(const float2* s_tab, const float* s_fac, const float* s_hsb, const f32x4* s_hq,
+                                         const f32x4* s_hc, const float* s_mu) {
+        const int lane = threadIdx.x & 63;
+        tab = s_tab + (lane >> 4) * TAB_STRIDE + (lane & 15);
+        fac = s_fac + (lane & 15);
+        hsb = s_hsb + (lane >> 4) * TAB_STRIDE + (lane & 15);
+        hq = s_hq + (lane & 15);
+        hc = s_hc + (lane & 15);
+        mu_q = s_mu[lane >> 4];
+    }
+    // s_hc[0][j] = f_j tau Hs_j, s_hc[1][j] = f_j 2 (c_j - mu), f_j the fold factor (1 if the pass does not fold);
+    // Hs = h / tau as everywhere.  Whole workgroup; the caller synchronises.
+    template <int NT>
+    static __device__ __forceinline__ void fill_output_tables(f32x4* s_hc, int k, const float* Hs, const float* Cf,
+                                                              const float* s_mu, const float* s_fac, bool fold, float tau) {
+        for (int j = threadIdx.x; j < TAB_STRIDE; j += NT) {
+            f32x4 h = {0.f, 0.f, 0.f, 0.f}, c2 = {0.f, 0.f, 0.f, 0.f};
+            if (j < k) {
+                const float f = fold ? s_fac[j] : 1.f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    h[r] = f * tau * Hs[j * 4 + r];
+                    c2[r] = f * 2.f * (Cf[j * 4 + r] - s_mu[r]);
+                }
+            }
+            s_hc[j] = h;
+            s_hc[TAB_STRIDE + j] = c2;
+        }
+    }
+
+    // ag: coordinate l / 16 of G_i / (2 s tau) for vector v0 + l % 16 (as in the first pass); dW: the tile's share of
+    // the output, [cnt][4] in memory.
+    template <bool FOLD>
+    __device__ __forceinline__ void step(const float* s_w, const float* s_wn, int v0, int vend, float escale, float ag,
+                                         float* dW) {
+        const int lane = threadIdx.x & 63, j0 = lane & 15, q = lane >> 4;
+        asm volatile("" ::: "memory");
+        const float aw = (s_w[(v0 + j0) * 4 + q] - mu_q) * escale;
+        const f32x4 wn = *reinterpret_cast<const f32x4*>(&s_wn[v0 + 4 * q]);
+        float x[NB][4], cterm[NB];
+        auto products = [&](bool want_norms) {
+            float cbv[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) cbv[b] = tab[16 * b].x;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) cterm[b] = want_norms ? tab[16 * b].y : fac[16 * b];
+            f32x4 e[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, cbv[b], wn, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) x[b][r] = e[b][r];
+            }
+        };
+        auto add_norms = [&]() {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) x[b][r] += cterm[b];
+            }
+        };
+        float S[4];
+        auto weights = [&](const float (&shift)[4]) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[r] = 0.f;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    x[b][r] = fast_exp2(x[b][r] - shift[r]);
+                    S[r] = FOLD ? fmaf(x[b][r], cterm[b], S[r]) : S[r] + x[b][r];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[r] = row16_sum(S[r]);
+        };
+        products(!FOLD);
+        if (!FOLD) add_norms();
+        const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+        weights(zero);
+        bool under = false;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) under = under || (S[r] < 7.9e-31f);  // below 2^-100
+        if (__builtin_amdgcn_ballot_w64(under) != 0ull) {
+            products(true);
+            add_norms();
+            float mx[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                mx[r] = x[0][r];
+#pragma unroll
+                for (int b = 1; b < NB; ++b) mx[r] = fmaxf(mx[r], x[b][r]);
+                mx[r] = row16_max(mx[r]);
+            }
+            if (FOLD) products(false);
+            weights(mx);
+        }
+        // z_ij: h.(w - F) first, (G/tau).(c - mu) accumulated onto it
+        float z[NB][4];
+        {
+            float hv[NB], cbv[NB];
+            f32x4 e[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                hv[b] = hsb[16 * b];
+                cbv[b] = tab[16 * b].x;
+                e[b] = hq[16 * b];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                if (FOLD) cterm[b] = fac[16 * b];  // again: the rare path may have left norms there
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, hv[b], e[b], 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(ag, cbv[b], e[b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) z[b][r] = e[b][r];
+            }
+        }
+        float Z[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                z[b][r] *= x[b][r];
+                Z[r] = FOLD ? fmaf(z[b][r], cterm[b], Z[r]) : Z[r] + z[b][r];
+            }
+        }
+        float rS[4], nzb[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            rS[r] = fast_rcp(S[r]);
+            nzb[r] = -(row16_sum(Z[r]) * rS[r]);  // -zbar_i
+        }
+        float out[4][4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) out[r][c] = 0.f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const f32x4 hj = hc[16 * b], cj = hc[TAB_STRIDE + 16 * b];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float kap = fmaf(nzb[r], x[b][r], z[b][r]);  // kappa' = p' z - zbar p'
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    out[r][c] = fmaf(x[b][r], hj[c], out[r][c]);
+                    out[r][c] = fmaf(kap, cj[c], out[r][c]);
+                }
+            }
+        }
+        // over the 16 lanes of the row, then lane 4 r + c keeps (r, c)
+        float mine = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float t = row16_sum(out[r][c]) * rS[r];
+                if (j0 == 4 * r + c) mine = t;
+            }
+        }
+        const int v = v0 + 4 * q + (j0 >> 2);
+        if (v < vend) dW[(size_t)v * 4 + (j0 & 3)] = mine;
+    }
+};
+
+template <int KPL, int NT>
+__device__ __forceinline__ void mfma_b3_tile_pass(MfmaB3<KPL>& st, const float* s_w, const float* s_wn, const float* gG,
+                                                  float* dW, int cnt, float escale, float inv_tau, bool fold) {
+    constexpr int NW = NT / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j0 = lane & 15, q = lane >> 4;
+    int share = (cnt + NW - 1) / NW;
+    share = (share + 15) & ~15;
+    const int w0 = wave * share;
+    const int w1 = (w0 + share < cnt) ? w0 + share : cnt;
+    const float gscale = inv_tau / (2.f * escale);
+    auto fetch = [&](int v) { return (v + j0 < cnt) ? gG[(size_t)(v + j0) * 4 + q] * gscale : 0.f; };
+    float ag = (w0 < w1) ? fetch(w0) : 0.f;
+    for (int v = w0; v < w1; v += 16) {
+        const float ag_n = (v + 16 < w1) ? fetch(v + 16) : 0.f;
+        if (fold)
+            st.template step<true>(s_w, s_wn, v, w1, escale, ag, dW);
+        else
+            st.template step<false>(s_w, s_wn, v, w1, escale, ag, dW);
+        ag = ag_n;
+    }
+}
+
 template <int KPL, int DIST, int NT>
 __device__ __forceinline__ void mfma_b2_tile_pass(MfmaB2<KPL>& st, const float* s_w, const float* s_wn, int cnt,
                                                   float escale, bool fold) {
