@@ -111,8 +111,15 @@ struct MfmaFwd {
     // contribute nothing.  Both arrays are readable (finite values) up to index v0 + 15.
     // DIST_L2 (s = log2(e)/tau): the energy is the square root of the same product, exp(-e/tau) = exp2(-|t|); rows
     // underflow routinely there (|t| is large at small tau), so the row is always shifted by its minimum.
-    template <int DIST, bool FOLD>
-    __device__ __forceinline__ void step(const float* s_w, const float* s_wn, int v0, int vend, float escale) {
+    //
+    // WQ (the evaluation at C*): the step also writes the soft-quantised vectors of Eq. "softquant",
+    // Wq_i = sum_j a_ij c_j = mu + (1/S_i) sum_j p'_ij f_j (c_j - mu)  (ctab: entry 16 b = f_j (c_j - mu), f_j the fold
+    // factor or 1; smu: mu): the sum over codewords runs over the lane's registers and then over the 16 lanes of its
+    // DPP row, and lane l % 16 = 4 r + c stores coordinate c of vector v0 + 4 (l / 16) + r (wq: the tile's share of
+    // the output, [.][4] in memory).
+    template <int DIST, bool FOLD, bool WQ = false>
+    __device__ __forceinline__ void step(const float* s_w, const float* s_wn, int v0, int vend, float escale,
+                                         const f32x4* ctab = nullptr, const float* smu = nullptr, float* wq = nullptr) {
         static_assert(DIST == DIST_SQL2 || !FOLD, "the fold factors belong to the squared energy");
         const int lane = threadIdx.x & 63, j0 = lane & 15, q = lane >> 4;
         // the table entries are read anew in every step (kept in registers across steps they would spill)
@@ -229,6 +236,32 @@ struct MfmaFwd {
             rinv[r] = (v < vend) ? fast_rcp(S[r]) : 0.f;
             bw[r] = s_w[v * 4 + (lane & 3)] * rinv[r];
         }
+        if constexpr (WQ) {
+            float out[4][4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) out[r][c] = 0.f;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const f32x4 cj = ctab[16 * b];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) out[r][c] = fmaf(x[b][r], cj[c], out[r][c]);
+            }
+            float mine = 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float t = fmaf(row16_sum(out[r][c]), rinv[r], smu[c]);
+                    if (j0 == 4 * r + c) mine = t;
+                }
+            }
+            const int v = v0 + 4 * q + (j0 >> 2);
+            if (v < vend) wq[(size_t)v * 4 + (j0 & 3)] = mine;
+        }
         // Matrix and vector instructions do not overlap on this part, and every change from one kind to the other
         // costs a few cycles more: the mass FMAs run as one group, the outer products back to back as another.
 #pragma unroll
@@ -243,6 +276,20 @@ struct MfmaFwd {
             for (int b = 0; b < NB; ++b) sacc[b] = __builtin_amdgcn_mfma_f32_4x4x1f32(x[b][r], bw[r], sacc[b], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
+    }
+    // The table of the WQ step: s_ctab[j] = f_j (c_j - mu).  Whole workgroup; the caller synchronises.
+    template <int NT>
+    static __device__ __forceinline__ void fill_codeword_table(f32x4* s_ctab, int k, const float* Cf, const float* s_mu,
+                                                               const float* s_fac, bool fold) {
+        for (int j = threadIdx.x; j < TAB_STRIDE; j += NT) {
+            f32x4 c = {0.f, 0.f, 0.f, 0.f};
+            if (j < k) {
+                const float f = fold ? s_fac[j] : 1.f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) c[r] = f * (Cf[j * 4 + r] - s_mu[r]);
+            }
+            s_ctab[j] = c;
+        }
     }
 };
 
@@ -783,19 +830,21 @@ __device__ __forceinline__ void mfma_b2_collect(const MfmaB2<KPL>& st, float* s_
 }
 
 // One forward pass over the workgroup's tile: every wavefront takes an equal share of whole 16-vector steps.
-template <int KPL, int DIST, int NT>
+template <int KPL, int DIST, int NT, bool WQ = false>
 __device__ __forceinline__ void mfma_tile_pass(MfmaFwd<KPL>& st, const float* s_w, const float* s_wn, int cnt,
-                                               float escale, bool fold) {
+                                               float escale, bool fold, const f32x4* s_ctab = nullptr,
+                                               const float* s_mu = nullptr, float* wq = nullptr) {
     constexpr int NW = NT / 64;
     const int wave = threadIdx.x >> 6;
     int share = (cnt + NW - 1) / NW;
     share = (share + 15) & ~15;
     const int w0 = wave * share;
     const int w1 = (w0 + share < cnt) ? w0 + share : cnt;
+    const f32x4* ctab = WQ ? s_ctab + (threadIdx.x & 15) : nullptr;
     if (DIST == DIST_SQL2 && fold) {
-        for (int v = w0; v < w1; v += 16) st.template step<DIST_SQL2, true>(s_w, s_wn, v, w1, escale);
+        for (int v = w0; v < w1; v += 16) st.template step<DIST_SQL2, true, WQ>(s_w, s_wn, v, w1, escale, ctab, s_mu, wq);
     } else {
-        for (int v = w0; v < w1; v += 16) st.template step<DIST, false>(s_w, s_wn, v, w1, escale);
+        for (int v = w0; v < w1; v += 16) st.template step<DIST, false, WQ>(s_w, s_wn, v, w1, escale, ctab, s_mu, wq);
     }
 }
 

@@ -258,13 +258,29 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
     const int max_iter = pa.max_iter;
     unsigned int seq = pa.seq_base;
 
+    // matrix-core passes: per-wavefront partial sums, the codeword tables of the step, the table of the evaluation at C*
+    constexpr int TS = MfmaFwd<(KPL <= 4 ? KPL : 4)>::TAB_STRIDE;
+    __shared__ __align__(16) float s_part[MFMA ? NT / 64 : 1][MFMA ? 64 * KPL * ACCW : 1];
+    __shared__ float2 s_tab[MFMA ? 4 * TS : 1];
+    __shared__ float s_fac[MFMA ? TS : 1];
+    __shared__ f32x4 s_ctab[MFMA ? TS : 1];
+    // hop-1 store of a matrix-core pass: wavefront totals add up in wavefront order, float64, as in publish_lane
+    auto publish_matrix = [&]() {
+        if constexpr (MFMA) {
+            unsigned long long* dst = pa.buf1 + ((size_t)(seq & 1u) * pa.G + pa.wg) * nacc;
+            for (int idx = tid; idx < nacc; idx += NT) {
+                double t = 0.0;
+#pragma unroll
+                for (int w = 0; w < NT / 64; ++w) t += (double)s_part[w][idx];
+                st_word(&dst[idx], pack_f(seq, (float)t));
+            }
+        }
+    };
+
     while (!s_done) {
         ++seq;
         IDKM_LSTAMP(0);
         if constexpr (MFMA) {
-            __shared__ float s_part[NT / 64][64 * KPL * ACCW];
-            __shared__ float2 s_tab[4 * MfmaFwd<KPL>::TAB_STRIDE];
-            __shared__ float s_fac[MfmaFwd<KPL>::TAB_STRIDE];
             const bool fold = MfmaFwd<KPL>::template fill_table<NT>(s_tab, s_fac, k, s_Cf, s_mu, a.escale) &&
                               DIST == DIST_SQL2;
             {
@@ -276,14 +292,7 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
             }
             __syncthreads();
             IDKM_LSTAMP(5);
-            // wavefront totals add up in wavefront order, float64; hop-1 store as in publish_lane
-            unsigned long long* dst = pa.buf1 + ((size_t)(seq & 1u) * pa.G + pa.wg) * nacc;
-            for (int idx = tid; idx < nacc; idx += NT) {
-                double t = 0.0;
-#pragma unroll
-                for (int w = 0; w < NT / 64; ++w) t += (double)s_part[w][idx];
-                st_word(&dst[idx], pack_f(seq, (float)t));
-            }
+            publish_matrix();
         } else {
             LaneWave<KPL, D, DIST, PASS_FWD> st;
             st.init(k, s_Cf, nullptr, nullptr, a.escale);
@@ -329,11 +338,37 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
 
     // evaluation at C*
     {
-        LaneWave<KPL, D, DIST, PASS_FIN> st;
-        st.init(k, s_Cf, nullptr, nullptr);
-        lane_tile_pass<KPL, D, DIST, PASS_FIN, NT>(a, st, s_tile, nullptr, base, cnt);
         ++seq;
-        publish_lane<NA, ACCW, NT>(pa, seq, st.acc, k, s_acc);
+        bool done_here = false;
+        if constexpr (MFMA) {
+            // n*, F* and Wq on the matrix cores; the assignment (its float32 key has a prescribed form) and the
+            // matrix A are outputs of the vector-ALU pass
+            if (!a.assign_out && !a.A_out) {
+                const bool fold = MfmaFwd<KPL>::template fill_table<NT>(s_tab, s_fac, k, s_Cf, s_mu, a.escale) &&
+                                  DIST == DIST_SQL2;
+                MfmaFwd<KPL>::template fill_codeword_table<NT>(s_ctab, k, s_Cf, s_mu, s_fac, fold);
+                __syncthreads();
+                {
+                    MfmaFwd<KPL> st;
+                    st.init(s_tab, s_fac, s_mu);
+                    if (a.Wq_out)
+                        mfma_tile_pass<KPL, DIST, NT, true>(st, s_tile, s_wn, cnt, a.escale, fold, s_ctab, s_mu,
+                                                            a.Wq_out + base * D);
+                    else
+                        mfma_tile_pass<KPL, DIST, NT>(st, s_tile, s_wn, cnt, a.escale, fold);
+                    mfma_collect<KPL, NT>(st, &s_part[0][0], fold, s_fac);
+                }
+                __syncthreads();
+                publish_matrix();
+                done_here = true;
+            }
+        }
+        if (!done_here) {
+            LaneWave<KPL, D, DIST, PASS_FIN> st;
+            st.init(k, s_Cf, nullptr, nullptr);
+            lane_tile_pass<KPL, D, DIST, PASS_FIN, NT>(a, st, s_tile, nullptr, base, cnt);
+            publish_lane<NA, ACCW, NT>(pa, seq, st.acc, k, s_acc);
+        }
         for (int r = wg; r < k; r += G) {
             if (!reduce_lane<ACCW>(pa, seq, nacc, r * ACCW, ls)) return;
             if (tid < D) {

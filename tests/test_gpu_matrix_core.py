@@ -54,6 +54,15 @@ def _check(ctx, W, C0, tau, iters, tol=0.0, DIST=wl.DIST_SQL2, path=binding.PATH
     assert rel(Cg, ref["C"]) < TOL_VAL, rel(Cg, ref["C"])
     assert rel(out["Wq"].cpu().numpy(), orc.soft_quantize(W, Cg, tau, DIST)) < TOL_VAL
     assert np.array_equal(out["assign"].cpu().numpy(), orc.hard_assign_f32(W, Cg))
+    # without the assignment the evaluation at C* runs on the matrix cores as well (persistent path): same C*,
+    # Wq to the same bar, and a backward after it sees the same n*, F*
+    ctx.set_path(path)
+    try:
+        out2 = ctx.forward(dev(W), dev(C0), tau, tol, iters, DIST, want_assign=False)
+    finally:
+        ctx.set_path(binding.PATH_PERSISTENT)
+    assert np.array_equal(out2["C"].cpu().numpy(), Cg) and out2["info"].iters == out["info"].iters
+    assert rel(out2["Wq"].cpu().numpy(), orc.soft_quantize(W, Cg, tau, DIST)) < TOL_VAL
     return out, ref
 
 
