@@ -352,7 +352,7 @@ struct MfmaB2 {
     // derivative of the energy is the unit vector (w - c) s / e:  out_j = sum_i a_ij (u_ij - ubar_i) (w_i - c_j) s / e_ij,
     // i.e. th'_ij = p_ij (u_ij - ubar_i) / e_ij with the per-vector factor s / S_i (zero where e_ij = 0 exactly).
     //
-    // B1 (first pass of the backward, squared energy): the same sums with u_ij = (G_i / tau).c_j -- the second product
+    // B1 (first pass of the backward): the same sums with u_ij = (G_i / tau).c_j -- the second product
     // takes A = ag (coordinate l / 16 of G_i / (2 s tau) for vector v0 + l % 16) and the codeword operand of the first
     // -- plus the term sum_i a_ij G_i, a second set of outer products p'_ij (x) G_i / S_i (gb[r]: coordinate l % 4 of
     // G for vector v0 + 4 (l / 16) + r) into the same accumulators:  v_j = fac_j (sacc_j - (c_j - mu) tacc_j).
@@ -360,7 +360,6 @@ struct MfmaB2 {
     __device__ __forceinline__ void step(const float* s_w, const float* s_wn, int v0, int vend, float escale,
                                          float ag = 0.f, const float* gb = nullptr) {
         static_assert(DIST == DIST_SQL2 || !FOLD, "the fold factors belong to the squared energy");
-        static_assert(DIST == DIST_SQL2 || !B1, "the first pass has this form for the squared energy only");
         const int lane = threadIdx.x & 63, j0 = lane & 15, q = lane >> 4;
         asm volatile("" ::: "memory");
         const float aw = (s_w[(v0 + j0) * 4 + q] - mu_q) * escale;
@@ -430,6 +429,7 @@ struct MfmaB2 {
             }
         };
         float Q[4] = {0.f, 0.f, 0.f, 0.f};
+        float pwv[(B1 && DIST == DIST_L2) ? NB : 1][4];  // plain norm, first pass: the weights p
         products(!FOLD);
         if (!FOLD) add_norms();
         if constexpr (DIST == DIST_SQL2) {
@@ -482,6 +482,7 @@ struct MfmaB2 {
             }
             cotangent_product();
             // weights p, row sums S and Q = sum p u; then p / e in place of the energy and p u / e in place of u
+            // (the first pass needs the weights themselves as well, for sum_i a_ij G_i)
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
 #pragma unroll
@@ -494,6 +495,7 @@ struct MfmaB2 {
                     Q[r] += pu;
                     x[b][r] = pw * ri;
                     u[b][r] = pu * ri;
+                    if (B1) pwv[b][r] = pw;
                 }
             }
 #pragma unroll
@@ -511,11 +513,12 @@ struct MfmaB2 {
             gw[r] = B1 ? gb[r] * rS : 0.f;
         }
         if constexpr (B1) {
-            // sum_i a_ij G_i: the weights are still untouched in x
+            // sum_i a_ij G_i: the weights are still untouched in x (plain norm: kept aside in pwv)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
 #pragma unroll
-                for (int b = 0; b < NB; ++b) sacc[b] = __builtin_amdgcn_mfma_f32_4x4x1f32(x[b][r], gw[r], sacc[b], 0, 0, 0);
+                for (int b = 0; b < NB; ++b)
+                    sacc[b] = __builtin_amdgcn_mfma_f32_4x4x1f32(DIST == DIST_L2 ? pwv[b][r] : x[b][r], gw[r], sacc[b], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -769,9 +772,9 @@ __device__ __forceinline__ void mfma_b2_tile_pass(MfmaB2<KPL>& st, const float* 
     }
 }
 
-// The first pass of the backward (squared energy): G (the workgroup's share of dL/dWq, [cnt][4] in memory) is read
+// The first pass of the backward: G (the workgroup's share of dL/dWq, [cnt][4] in memory) is read
 // one step ahead, so that its latency is hidden behind the current step.
-template <int KPL, int NT>
+template <int KPL, int DIST, int NT>
 __device__ __forceinline__ void mfma_b1_tile_pass(MfmaB2<KPL>& st, const float* s_w, const float* s_wn, const float* gG,
                                                   int cnt, float escale, float inv_tau, bool fold) {
     constexpr int NW = NT / 64;
@@ -791,10 +794,10 @@ __device__ __forceinline__ void mfma_b1_tile_pass(MfmaB2<KPL>& st, const float* 
     if (w0 < w1) fetch(w0, ag, gb);
     for (int v = w0; v < w1; v += 16) {
         if (v + 16 < w1) fetch(v + 16, ag_n, gb_n);
-        if (fold)
+        if (DIST == DIST_SQL2 && fold)
             st.template step<DIST_SQL2, true, true>(s_w, s_wn, v, w1, escale, ag, gb);
         else
-            st.template step<DIST_SQL2, false, true>(s_w, s_wn, v, w1, escale, ag, gb);
+            st.template step<DIST, false, true>(s_w, s_wn, v, w1, escale, ag, gb);
         ag = ag_n;
 #pragma unroll
         for (int r = 0; r < 4; ++r) gb[r] = gb_n[r];

@@ -543,11 +543,11 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
     // B1
     {
         ++seq;
-        if constexpr (MFMA && DIST == DIST_SQL2) {
+        if constexpr (MFMA) {
             {
                 MfmaB2<KPL> st;
                 st.init(s_tab0, s_fac0, s_hsb, s_hq, s_mu);
-                mfma_b1_tile_pass<KPL, NT>(st, s_tile, s_wn, s_gt, cnt, a.escale, a.inv_tau, fold);
+                mfma_b1_tile_pass<KPL, DIST, NT>(st, s_tile, s_wn, s_gt, cnt, a.escale, a.inv_tau, fold);
                 mfma_b2_collect<KPL, NT>(st, &s_part[0][0]);
             }
             __syncthreads();
