@@ -132,7 +132,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "XL"])
+    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "P16", "XL"])
     ap.add_argument("--dist", default="sql2", choices=["sql2", "l2"])
     ap.add_argument("--path", default="auto", choices=["auto", "stream", "persistent"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -226,7 +226,8 @@ def main() -> int:
     others = None
     if not args.no_others:
         others = []
-        for name, dd in (("C1", 1), ("C1", 0), ("C2", 1), ("C2", 0), ("C3", 0), ("C4", 1), ("C4", 0), ("XL", 1)):
+        for name, dd in (("C1", 1), ("C1", 0), ("C2", 1), ("C2", 0), ("C3", 0), ("C4", 1), ("C4", 0), ("P16", 1),
+                         ("P16", 0), ("XL", 1)):
             del W, C0, G
             q, W, C0, G = load(name, dd)
             measure(ctx, binding, torch, np, q, dd, W, C0, G, 1, args.bwd_tol, 300)

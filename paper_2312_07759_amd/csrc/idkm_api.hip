@@ -872,7 +872,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
         // when the K D (K D + D + 1) sums fit one exchange line the persistent kernel does it in one launch
         // (and batched calls can share that launch between layers)
         PersistPlan ppd;
-        if (kd * kd + kd * ctx->d + kd <= XLINE && ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &ppd, true, dWq)) {
+        if (kd * kd + kd * ctx->d + kd <= XDENSE && ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &ppd, true, dWq)) {
             PArgs pa;
             std::memset(&pa, 0, sizeof(pa));
             pa.tol = 0.0;

@@ -13,7 +13,7 @@ static PersistFns pick(int dist, bool bwd) {
                : PersistFns{persist_fwd<K, D, DIST_SQL2>, persist_fwd_batch<K, D, DIST_SQL2>};
 }
 
-// Offered when K (D+1) <= 32, the widest row the exchange layout carries.
+// Offered for every shape of the lane<->vector family: K (D+1) <= 80 sums per workgroup.
 PersistFns persist_kernel(int K, int D, int dist, bool bwd) {
     switch (K * 16 + D) {
         case 2 * 16 + 1: return pick<2, 1>(dist, bwd);
@@ -25,6 +25,9 @@ PersistFns persist_kernel(int K, int D, int dist, bool bwd) {
         case 8 * 16 + 2: return pick<8, 2>(dist, bwd);
         case 2 * 16 + 4: return pick<2, 4>(dist, bwd);
         case 4 * 16 + 4: return pick<4, 4>(dist, bwd);
+        case 16 * 16 + 2: return pick<16, 2>(dist, bwd);
+        case 8 * 16 + 4: return pick<8, 4>(dist, bwd);
+        case 16 * 16 + 4: return pick<16, 4>(dist, bwd);
     }
     return PersistFns{};
 }

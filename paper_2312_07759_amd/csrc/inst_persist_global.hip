@@ -22,6 +22,9 @@ PersistFns persist_kernel_global(int K, int D, int dist, bool bwd) {
         case 8 * 16 + 2: return pick<8, 2>(dist, bwd);
         case 2 * 16 + 4: return pick<2, 4>(dist, bwd);
         case 4 * 16 + 4: return pick<4, 4>(dist, bwd);
+        case 16 * 16 + 2: return pick<16, 2>(dist, bwd);
+        case 8 * 16 + 4: return pick<8, 4>(dist, bwd);
+        case 16 * 16 + 4: return pick<16, 4>(dist, bwd);
     }
     return PersistFns{};
 }

@@ -25,8 +25,12 @@
 namespace idkm {
 
 constexpr int PT = 256;      // threads per workgroup of the persistent kernels; also the largest grid
-constexpr int XLINE = 32;    // words reserved per workgroup in buf1 (K (D+1) <= 32)
-constexpr int XBCAST = 64;   // words reserved in buf2
+constexpr int XLINE = 128;   // words reserved per workgroup in buf1 (K (D+1) <= 80, padded to a power of two)
+constexpr int XBCAST = 128;  // words reserved in buf2
+constexpr int XDENSE = 32;   // the explicit-Jacobian mode is offered while its K D (K D + D + 1) sums fit this many words
+// Words between the lines of two workgroups in buf1 for a pass with NACC sums per workgroup: shapes of up to 32 sums
+// keep the short lines they were tuned with.
+constexpr int xline_of(int nacc) { return nacc <= 32 ? 32 : XLINE; }
 
 // What a persistent launch reports; lives in pinned host memory, written once by the kernel.
 struct PResult {
@@ -37,7 +41,7 @@ struct PResult {
 };
 
 struct PArgs {
-    unsigned long long* buf1;  // [2][PT][XLINE] stamped partial sums, word (workgroup, accumulator)
+    unsigned long long* buf1;  // [2][PT][xline_of(NACC)] stamped partial sums, word (workgroup, accumulator)
     unsigned long long* buf2;  // [2][XBCAST] stamped broadcast values
     unsigned int seq_base;     // sequence numbers seq_base+1 ... are used by this launch; seq_base+1 is its id
     unsigned int spin_limit;   // polls before a wait gives up
@@ -119,7 +123,7 @@ __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int s
         const double s = (c4[0] + c4[1]) + (c4[2] + c4[3]);
         xs.own[tid] = (float)s;
         // a workgroup's words lie together: one store transaction per workgroup and pass
-        st_word(&pa.buf1[((size_t)(seq & 1u) * PT + pa.wg) * XLINE + tid], pack_f(seq, (float)s));
+        st_word(&pa.buf1[((size_t)(seq & 1u) * PT + pa.wg) * xline_of(NACC) + tid], pack_f(seq, (float)s));
     }
     IDKM_SUB(3);
 }
@@ -166,13 +170,14 @@ __device__ __forceinline__ bool reduce_slice(const PArgs& pa, unsigned int seq, 
         __syncthreads();
         if (tid < WPR) s = (double)xs.own[first + tid];
     } else if (g0 < GPT && g0 < G) {
-        const unsigned long long* src = pa.buf1 + ((size_t)(seq & 1u) * PT + g0) * XLINE + first + q;
+        constexpr int LINE = xline_of(NACC);
+        const unsigned long long* src = pa.buf1 + ((size_t)(seq & 1u) * PT + g0) * LINE + first + q;
         const int nv = (G - g0 + GPT - 1) / GPT;  // <= NL
         unsigned int spins = 0;
         for (;;) {
             unsigned long long w[NL];
 #pragma unroll
-            for (int u = 0; u < NL; ++u) w[u] = (u < nv) ? ld_word(src + (size_t)u * GPT * XLINE) : pack_f(seq, 0.f);
+            for (int u = 0; u < NL; ++u) w[u] = (u < nv) ? ld_word(src + (size_t)u * GPT * LINE) : pack_f(seq, 0.f);
             bool ok = true;
 #pragma unroll
             for (int u = 0; u < NL; ++u) ok = ok && ((unsigned int)(w[u] >> 32) == seq);
@@ -605,7 +610,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     // explicit-Jacobian mode (Eq. "grad", "inv" taken literally): offered when its K D (K D + D + 1) sums fit one
     // exchange line
     constexpr int NBJ = KD * KD + KD * D + KD;
-    constexpr bool HAS_DENSE = NBJ <= XLINE;
+    constexpr bool HAS_DENSE = NBJ <= XDENSE;
     extern __shared__ float s_tile[];
     __shared__ XShared<HAS_DENSE ? NBJ : KD> xs;
     __shared__ double s_v[KD], s_g[KD], s_rn[K];  // a reducer's own slice is the live one; s_rn = 1/(tau n)

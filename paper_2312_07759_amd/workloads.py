@@ -52,6 +52,10 @@ CONFIGS = {
                  3003, "normal", note="3x3x512x512 conv, 2 bits per weight"),
     "C4": Config("C4", 589_824, 4, 256, _STD_C3, 1003, "rows", 1004, 2e-4, 1e-6, 200,
                  3004, "normal", note="3x3x512x512 conv as 4-vectors, 8 bits per vector"),
+    # the largest codebook of the paper's ResNet18 table (k = 16, d = 4: one bit per weight) on the same tensor;
+    # temperature as C4's (same vectors, squared energy)
+    "P16": Config("P16", 589_824, 4, 16, _STD_C3, 1003, "rows", 1006, 2e-4, 1e-6, 200,
+                  3006, "normal", note="3x3x512x512 conv as 4-vectors, 4 bits per vector"),
     # beyond the paper's networks: a layer whose weights do not fit the chip's LDS (64 MiB), so every pass streams
     # W from memory; temperature tied to C3's as in the sweep (squared energy)
     "XL": Config("XL", 16_777_216, 1, 4, math.sqrt(2.0 / 4096.0), 1005, "quantile", 0,

@@ -36,7 +36,7 @@ def ctx():
     c.close()
 
 
-SHAPES = [(k, d) for k in (2, 4, 8, 16) for d in (1, 2, 4) if k * (d + 1) <= 32]
+SHAPES = [(k, d) for k in (2, 4, 8, 16) for d in (1, 2, 4)]
 
 
 @pytest.mark.parametrize("dist", [wl.DIST_SQL2, wl.DIST_L2], ids=["sql2", "l2"])
