@@ -96,20 +96,37 @@ struct XShared {
     int abort;
 };
 
+// Row totals of accumulators [OFF, NACC) into xs.rpart, taken in power-of-two pieces, largest first (80 sums are a
+// piece of 64 and one of 16, not one of 128 padded with zeros: the exchange network costs about three instructions
+// per value it starts with).
+constexpr int pow2_at_most(int n) {
+    int p = 2;
+    while (2 * p <= n) p *= 2;
+    return p;
+}
+template <int NACC, int OFF, class XS>
+__device__ __forceinline__ void publish_rows(const float (&acc)[NACC], XS& xs, int lane, int row) {
+    constexpr int NP = pow2_at_most(NACC - OFF);
+    float v[NP];
+#pragma unroll
+    for (int q = 0; q < NP; ++q) v[q] = (OFF + q < NACC) ? acc[OFF + q] : 0.f;
+    row_sums<NP>(v, lane);
+    if (row_sum_owner<NP>(lane & 15)) {
+#pragma unroll
+        for (int i = 0; i < row_sum_live(NP); ++i) {
+            const int q = OFF + row_sum_index<NP>(lane & 15, i);
+            if (q < NACC) xs.rpart[q][row] = v[i];
+        }
+    }
+    if constexpr (OFF + NP < NACC) publish_rows<NACC, OFF + NP>(acc, xs, lane, row);
+}
+
 // hop 1, sender side: workgroup partial of every accumulator into this workgroup's line.
 template <int NACC, class XS>
 __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int seq, const float (&acc)[NACC], XS& xs) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     IDKM_SUB(0);
-    constexpr int NP = pow2_at_least(NACC);
-    float v[NP];
-#pragma unroll
-    for (int q = 0; q < NP; ++q) v[q] = (q < NACC) ? acc[q] : 0.f;
-    row_sums<NP>(v, lane);
-    if (row_sum_owner<NP>(lane & 15)) {
-#pragma unroll
-        for (int i = 0; i < row_sum_live(NP); ++i) xs.rpart[row_sum_index<NP>(lane & 15, i)][tid >> 4] = v[i];
-    }
+    publish_rows<NACC, 0>(acc, xs, lane, tid >> 4);
     IDKM_SUB(1);
     __syncthreads();
     IDKM_SUB(2);
