@@ -363,7 +363,7 @@ __device__ __forceinline__ void tile_pass_global(const Args& a, const float* gw,
     const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
     f32x4_t cw[NLD], cg[NLD], nw[NLD], ng[NLD];
     const int64_t step = (int64_t)G * PT;           // groups per round of the team
-    int64_t gi = (int64_t)wg * PT + threadIdx.x;    // this lane's group in round 0
+    int64_t gi = (int64_t)wg * PT + threadIdx.x;    // this lane's group on its first turn
 #pragma unroll
     for (int u = 0; u < NLD; ++u) {
         const int64_t i = gi + u * step;
