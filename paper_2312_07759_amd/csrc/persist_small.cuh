@@ -283,6 +283,14 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
             hs[j][r] = Item::USE_H ? s_Hs[j * D + r] : 0.f;
             ff[j][r] = Item::USE_F ? s_Ff[j * D + r] : 0.f;
         }
+    Item::prepare(c, hs, ff);
+    if constexpr (Item::FOLD_HF) {
+        // the codebook is the same for all lanes: as scalar registers it leaves the vector registers to h and the sums
+#pragma unroll
+        for (int j = 0; j < K; ++j)
+#pragma unroll
+            for (int r = 0; r < D; ++r) c[j][r] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, c[j][r])));
+    }
 #pragma unroll
     for (int q = 0; q < Item::NACC; ++q) acc[q] = 0.f;
     // one wavefront per SIMD: the latencies of a vector's chain (LDS load, exponentials, reciprocal) are hidden by
@@ -341,6 +349,7 @@ __device__ __forceinline__ void tile_pass_global(const Args& a, const float* gw,
             hs[j][r] = Item::USE_H ? s_Hs[j * D + r] : 0.f;
             ff[j][r] = Item::USE_F ? s_Ff[j * D + r] : 0.f;
         }
+    Item::prepare(c, hs, ff);
 #pragma unroll
     for (int q = 0; q < Item::NACC; ++q) acc[q] = 0.f;
     constexpr int VPL = 4 / D;                // vectors per 16-byte load

@@ -108,6 +108,38 @@ struct SmallItem {
     // dense backward: T[KD][KD], U[KD][D], V[KD]
     static constexpr int NACC = (PASS == PASS_B3) ? 1 : (PASS == PASS_BJ ? KD * KD + KD * D + KD : K * ACCW);
 
+    // k d >= 32 with d >= 2, (dF/dC)^T pass and last pass: codebook, h and F* (up to 192 values) plus the sums and a
+    // vector's own state do not fit 256 registers, and what the compiler moves to the accumulation registers costs a
+    // vector-ALU move per use.  There h_j . (w - F*_j) is taken as h_j . (w - mu) - h_j . (F*_j - mu), mu the mean
+    // codeword (so that layers far from the origin lose nothing to cancellation): prepare() leaves the k products in
+    // ff[j][0] and mu_r in ff[r][1] (the other values of F* are not used again) and run() expects them there; d
+    // subtractions per vector instead of d per codeword.
+    static constexpr bool FOLD_HF = ((PASS == PASS_B2 || PASS == PASS_B3) && D >= 2 && K * D >= 32);
+
+    // Called once per pass by every caller of run(), after it has loaded the tables into registers.
+    static __device__ __forceinline__ void prepare(const float (&c)[K][D], const float (&hs)[K][D], float (&ff)[K][D]) {
+        if constexpr (FOLD_HF) {
+            static_assert(K >= D, "mu is kept in ff[0..D)[1]");
+            float mu[D];
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                float s = 0.f;
+#pragma unroll
+                for (int j = 0; j < K; ++j) s += c[j][r];
+                mu[r] = s * (1.f / K);
+            }
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                float s = 0.f;
+#pragma unroll
+                for (int r = 0; r < D; ++r) s = fmaf(hs[j][r], ff[j][r] - mu[r], s);
+                ff[j][0] = s;
+            }
+#pragma unroll
+            for (int r = 0; r < D; ++r) ff[r][1] = mu[r];
+        }
+    }
+
     static __device__ __forceinline__ void run(const Args& a, int64_t i, const float (&w)[D], const float (&g)[D],
                                                const float (&c)[K][D], const float (&hs)[K][D],
                                                const float (&ff)[K][D], float (&acc)[NACC]) {
@@ -199,6 +231,17 @@ struct SmallItem {
 #pragma unroll
             for (int j = 0; j < K; ++j) {
                 float s = 0.f;
+                if constexpr (FOLD_HF) {
+                    s = -ff[j][0];
+#pragma unroll
+                    for (int r = 0; r < D; ++r) {
+                        if (USE_G) s = fmaf(gs[r], c[j][r], s);
+                        s = fmaf(hs[j][r], w[r] - ff[r][1], s);  // (w - mu: the same for every j, formed once)
+                    }
+                    q[j] = s;
+                    qbar = fmaf(at[j], s, qbar);
+                    continue;
+                }
 #pragma unroll
                 for (int r = 0; r < D; ++r) {
                     if (USE_G) s = fmaf(gs[r], c[j][r], s);
@@ -277,6 +320,7 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
             hs[j][r] = Item::USE_H ? a.Hs[j * D + r] : 0.f;
             ff[j][r] = Item::USE_F ? a.Ff[j * D + r] : 0.f;
         }
+    Item::prepare(c, hs, ff);
 
     float acc[NACC];
 #pragma unroll

@@ -536,3 +536,32 @@ def test_warm_start_and_temperature_schedule(ctx):
         C = Cg
     cold = ctx.forward(Wd, dev(p.C0), p.tau, p.tol, p.max_iter, wl.DIST_SQL2, want_Wq=False)
     assert stage_iters[-1] < cold["info"].iters
+
+
+# The widest shapes of the lane<->vector family (k d >= 32, d >= 2) take h_j . (w - F*_j) apart into h_j . (w - mu)
+# and a per-codeword constant in their (dF/dC)^T and last passes.  With a layer a hundred spreads away from the origin
+# the two parts would be large and nearly equal if mu were not the centre of the codebook.
+@pytest.mark.parametrize("path", [binding.PATH_STREAM, binding.PATH_PERSISTENT], ids=["stream", "persistent"])
+@pytest.mark.parametrize("dist", DISTS)
+@pytest.mark.parametrize("k,d", [(16, 4), (8, 4), (16, 2)])
+def test_backward_of_a_wide_shape_far_from_the_origin(ctx, k, d, dist, path):
+    rng = np.random.default_rng(770 + 16 * k + d)
+    m = 20_011
+    W = (5.0 + 0.05 * rng.standard_normal((m, d))).astype(np.float32)
+    C0 = (W[rng.choice(m, k, replace=False)] + 0.002 * rng.standard_normal((k, d))).astype(np.float32)
+    G = rng.standard_normal((m, d)).astype(np.float32)
+    tau = 1e-3 if dist == wl.DIST_SQL2 else 1e-2
+    ctx.set_path(path)
+    try:
+        out = ctx.forward(dev(W), dev(C0), tau, 0.0, 25, dist)
+        assert out["info"].path == path
+        Cg = out["C"].cpu().numpy()
+        assert rel(Cg, orc.soft_kmeans(W, C0, tau, 0.0, 25, dist)["C"]) < TOL_VAL
+        Gd = dev(G)
+        bj = ctx.backward(Gd, binding.BWD_JFB)
+        assert rel(bj["dW"].cpu().numpy(), orc.backward(W, Cg, tau, dist, G, "jfb")["dW"]) < TOL_GRAD
+        bi = ctx.backward(Gd, binding.BWD_IMPLICIT, tol=0.0, max_iter=12, alpha=1.0)
+        ri = orc.backward(W, Cg, tau, dist, G, "implicit", tol=0.0, max_iter=12, alpha=1.0)
+        assert rel(bi["dW"].cpu().numpy(), ri["dW"]) < TOL_GRAD
+    finally:
+        ctx.set_path(binding.PATH_AUTO)
