@@ -7,7 +7,7 @@ paper_2312_07759_amd/workloads.py.  The HIP path is never imported or run.  The 
 runs take minutes (a forward solve of the 3x3x256x256 layer is ~100 s), which is why they are
 stored instead of being recomputed inside the GPU tests.
 
-  python tests/golden/make_golden.py C2 C3 C4 C5      (any subset; default: all)
+  python tests/golden/make_golden.py C2 C3 C4 P16 C5      (any subset; default: all)
 """
 from __future__ import annotations
 
@@ -85,7 +85,7 @@ def solved_layer(name, dist, out):
 
 
 def stepwise_layer(name, dist, out, steps):
-    """For the config that does not converge within its cap (k = 256): one evaluation of F and one
+    """For the configs that do not converge within their cap (k = 256; k = 16 with d = 4): one evaluation of F and one
     (dF/dC)^T pass at C0, the trajectory after `steps` evaluations, and the JFB gradient there."""
     p = wl.make_problem(name, dist)
     t0 = time.time()
@@ -136,14 +136,15 @@ def sweep(out):
 
 
 def main():
-    which = sys.argv[1:] or ["C2", "C3", "C4", "C5"]
+    which = sys.argv[1:] or ["C2", "C3", "C4", "P16", "C5"]
     for name in which:
         if name in ("C2", "C3"):
             for dist in (wl.DIST_L2, wl.DIST_SQL2):
                 solved_layer(name, dist, os.path.join(HERE, f"{name}_{wl.DIST_NAMES[dist]}.json"))
-        elif name == "C4":
+        elif name in ("C4", "P16"):
             for dist in (wl.DIST_L2, wl.DIST_SQL2):
-                stepwise_layer(name, dist, os.path.join(HERE, f"C4_{wl.DIST_NAMES[dist]}.json"), steps=12)
+                stepwise_layer(name, dist, os.path.join(HERE, f"{name}_{wl.DIST_NAMES[dist]}.json"),
+                               steps=12 if name == "C4" else 25)
         elif name == "C5":
             sweep(os.path.join(HERE, "C5_sweep.json"))
 

@@ -90,9 +90,10 @@ def test_full_size_solved_layers(ctx, name, dist):
 
 
 @pytest.mark.parametrize("dist", [wl.DIST_L2, wl.DIST_SQL2])
-def test_full_size_k256_stepwise(ctx, dist):
-    g = load(f"C4_{wl.DIST_NAMES[dist]}.json")
-    p = wl.make_problem("C4", dist)
+@pytest.mark.parametrize("name", ["C4", "P16"])
+def test_full_size_stepwise(ctx, name, dist):
+    g = load(f"{name}_{wl.DIST_NAMES[dist]}.json")
+    p = wl.make_problem(name, dist)
     W, C0, G = (torch.from_numpy(x).cuda() for x in (p.W, p.C0, p.G))
     Cp, n = ctx.step_F(W, C0, p.tau, dist)
     assert rel(Cp.cpu().numpy(), g["F_at_C0"]) < TOL_VAL
