@@ -85,11 +85,10 @@ idkm_status idkm_destroy(idkm_ctx* ctx);
 const char* idkm_last_error(const idkm_ctx* ctx);
 /* Select the scheduling path for subsequent calls (default IDKM_PATH_AUTO). */
 idkm_status idkm_set_path(idkm_ctx* ctx, idkm_path path);
-/* Shapes with d = 4 and 17 <= k <= 256 run the forward loop (Alg. 1) and the passes of the backward on the matrix
- * cores: the pass for v and the (dF/dC)^T passes (Eq. "backiter") for both energies, the last pass (dL/dW) for the
- * squared one.  enable = 0 sends them to the vector-ALU kernels that serve every other shape instead (diagnostics,
- * comparisons); the default is 1.  Takes effect from the next idkm_forward; a backward follows the setting in force
- * at its call. */
+/* Shapes with d = 4 and 17 <= k <= 256 run the forward loop (Alg. 1) and every pass of the backward (the pass for
+ * v, the (dF/dC)^T passes of Eq. "backiter", the last pass for dL/dW) on the matrix cores, for both energies.
+ * enable = 0 sends them to the vector-ALU kernels that serve every other shape instead (diagnostics, comparisons);
+ * the default is 1.  Takes effect from the next idkm_forward; a backward follows the setting in force at its call. */
 idkm_status idkm_set_matrix_cores(idkm_ctx* ctx, int32_t enable);
 /* Persistent path, k in {2,4,8,16}: a workgroup keeps its share of W (and of dL/dWq in the backward) in LDS when it
  * is at most `bytes` (default and maximum 147456).  A layer with larger shares (more than about 9.4 M weights) is

@@ -356,8 +356,7 @@ constexpr size_t LANE_BUF2_WORDS = (size_t)2 * (1024 + 512);       // k d + k
 
 
 // Can (m, k, d) run as one persistent launch with `tiles` resident tensors (1: W; 2: W and dL/dWq)?
-// matrix_ok: the matrix-core kernels may serve the call (with the plain norm only the (dF/dC)^T passes have a
-// matrix-core form: a JFB backward, which has none, keeps the 1024-thread kernel for its two passes there).
+// matrix_ok: the matrix-core kernels may serve the call (every pass of both energies has a matrix-core form).
 // dwq: the backward's upstream gradient (a layer too large for LDS is streamed from memory with 16-byte loads, which
 // W and dL/dWq must allow).
 bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp, bool matrix_ok = true, const void* dwq = nullptr) {
@@ -919,7 +918,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     PersistPlan pp;
     // the minimal-residual solve keeps its O(k d R) state in one workgroup's tail: stream path only
     const bool persistent = mode != IDKM_BWD_GMRES && ctx->path != IDKM_PATH_STREAM &&
-                            plan_persistent(ctx, true, &pp, mode != IDKM_BWD_JFB || ctx->dist == DIST_SQL2, dWq);
+                            plan_persistent(ctx, true, &pp, true, dWq);
     if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
         return fail(ctx, IDKM_ERR_UNSUPPORTED, mode == IDKM_BWD_GMRES
                         ? "IDKM_BWD_GMRES runs on the stream path only"

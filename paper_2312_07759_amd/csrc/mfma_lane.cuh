@@ -556,7 +556,7 @@ struct MfmaB3 {
     const float* hsb;
     const f32x4* hq;
     const f32x4* hc;  // entry 16 b: fac_j h_j (4 coordinates); entry TAB_STRIDE + 16 b: fac_j 2 (c_j - mu)
-    float mu_q;
+    float mu_q, mu_c;
 
     __device__ __forceinline__ void init(const float2* s_tab, const float* s_fac, const float* s_hsb, const f32x4* s_hq,
                                          const f32x4* s_hc, const float* s_mu) {
@@ -567,12 +567,15 @@ struct MfmaB3 {
         hq = s_hq + (lane & 15);
         hc = s_hc + (lane & 15);
         mu_q = s_mu[lane >> 4];
+        mu_c = s_mu[lane & 3];
     }
-    // s_hc[0][j] = f_j tau Hs_j, s_hc[1][j] = f_j 2 (c_j - mu), f_j the fold factor (1 if the pass does not fold);
+    // s_hc[0][j] = f_j tau Hs_j, s_hc[1][j] = f_j cfac (c_j - mu), f_j the fold factor (1 if the pass does not fold);
+    // cfac = 2 for the squared energy, s for the plain norm (d e / d w = 2 (w - c), resp. (w - c) s / e_scaled).
     // Hs = h / tau as everywhere.  Whole workgroup; the caller synchronises.
     template <int NT>
     static __device__ __forceinline__ void fill_output_tables(f32x4* s_hc, int k, const float* Hs, const float* Cf,
-                                                              const float* s_mu, const float* s_fac, bool fold, float tau) {
+                                                              const float* s_mu, const float* s_fac, bool fold, float tau,
+                                                              float cfac) {
         for (int j = threadIdx.x; j < TAB_STRIDE; j += NT) {
             f32x4 h = {0.f, 0.f, 0.f, 0.f}, c2 = {0.f, 0.f, 0.f, 0.f};
             if (j < k) {
@@ -580,7 +583,7 @@ struct MfmaB3 {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     h[r] = f * tau * Hs[j * 4 + r];
-                    c2[r] = f * 2.f * (Cf[j * 4 + r] - s_mu[r]);
+                    c2[r] = f * cfac * (Cf[j * 4 + r] - s_mu[r]);
                 }
             }
             s_hc[j] = h;
@@ -731,9 +734,135 @@ struct MfmaB3 {
         const int v = v0 + 4 * q + (j0 >> 2);
         if (v < vend) dW[(size_t)v * 4 + (j0 & 3)] = mine;
     }
+
+    // The same pass for the plain norm (s = log2(e)/tau): e_ij = sqrt(|x_ij|) in scaled units, the row is shifted by
+    // its minimum, delta_ij = (w_i - c_j) s / e_ij (zero where e_ij = 0 exactly), and sum_j kappa_ij / e_ij does not
+    // vanish, so the term in (w_i - mu) stays:
+    //   dL/dW_i = (1/S_i) [ sum_j p_ij h_j + s sum_j k_ij (c_j - mu) - s (w_i - mu) sum_j k_ij ],
+    //   k_ij = p_ij (z_ij - zbar_i) / e_ij.
+    __device__ __forceinline__ void step_l2(const float* s_w, const float* s_wn, int v0, int vend, float escale, float ag,
+                                            float* dW) {
+        const int lane = threadIdx.x & 63, j0 = lane & 15, q = lane >> 4;
+        asm volatile("" ::: "memory");
+        const float aw = (s_w[(v0 + j0) * 4 + q] - mu_q) * escale;
+        const f32x4 wn = *reinterpret_cast<const f32x4*>(&s_wn[v0 + 4 * q]);
+        float x[NB][4];
+        {
+            float cbv[NB], cn[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) cbv[b] = tab[16 * b].x;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) cn[b] = tab[16 * b].y;
+            f32x4 e[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, cbv[b], wn, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            // energies; a padding codeword is 1e15 away
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) x[b][r] = fast_sqrt(fabsf(e[b][r] + cn[b]));
+            }
+        }
+        float mn[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            mn[r] = x[0][r];
+#pragma unroll
+            for (int b = 1; b < NB; ++b) mn[r] = fminf(mn[r], x[b][r]);
+            mn[r] = row16_min(mn[r]);
+        }
+        // z_ij: h.(w - F) first, (G/tau).(c - mu) accumulated onto it
+        float z[NB][4];
+        {
+            float hv[NB], cbv[NB];
+            f32x4 e[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                hv[b] = hsb[16 * b];
+                cbv[b] = tab[16 * b].x;
+                e[b] = hq[16 * b];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(aw, hv[b], e[b], 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) e[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(ag, cbv[b], e[b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) z[b][r] = e[b][r];
+            }
+        }
+        float out[4][4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) out[r][c] = 0.f;
+        // weights p, row sums S and Z = sum p z, the term sum_j p h_j; then p / e in place of the energy and p z / e
+        // in place of z
+        float S[4] = {0.f, 0.f, 0.f, 0.f}, Z[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const f32x4 hj = hc[16 * b];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float e = x[b][r];
+                const float pw = fast_exp2(mn[r] - e);
+                const float ri = (e > 0.f) ? fast_rcp(e) : 0.f;
+                const float pz = pw * z[b][r];
+                S[r] += pw;
+                Z[r] += pz;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) out[r][c] = fmaf(pw, hj[c], out[r][c]);
+                x[b][r] = pw * ri;
+                z[b][r] = pz * ri;
+            }
+        }
+        float rS[4], nzb[4], K[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            rS[r] = fast_rcp(row16_sum(S[r]));
+            nzb[r] = -(row16_sum(Z[r]) * rS[r]);  // -zbar_i
+            K[r] = 0.f;
+        }
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const f32x4 cj = hc[TAB_STRIDE + 16 * b];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float kap = fmaf(nzb[r], x[b][r], z[b][r]);  // k S = (p z - zbar p) / e
+                K[r] += kap;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) out[r][c] = fmaf(kap, cj[c], out[r][c]);
+            }
+        }
+        // over the 16 lanes of the row, then lane 4 r + c keeps (r, c)
+        float mine = 0.f, Kmine = 0.f, rSmine = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float Ks = row16_sum(K[r]);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float t = row16_sum(out[r][c]);
+                if (j0 == 4 * r + c) {
+                    mine = t;
+                    Kmine = Ks;
+                    rSmine = rS[r];
+                }
+            }
+        }
+        const int v = v0 + 4 * q + (j0 >> 2);
+        if (v < vend) {
+            const float wc = (s_w[v * 4 + (j0 & 3)] - mu_c) * escale;
+            dW[(size_t)v * 4 + (j0 & 3)] = fmaf(-wc, Kmine, mine) * rSmine;
+        }
+    }
 };
 
-template <int KPL, int NT>
+template <int KPL, int DIST, int NT>
 __device__ __forceinline__ void mfma_b3_tile_pass(MfmaB3<KPL>& st, const float* s_w, const float* s_wn, const float* gG,
                                                   float* dW, int cnt, float escale, float inv_tau, bool fold) {
     constexpr int NW = NT / 64;
@@ -748,7 +877,9 @@ __device__ __forceinline__ void mfma_b3_tile_pass(MfmaB3<KPL>& st, const float* 
     float ag = (w0 < w1) ? fetch(w0) : 0.f;
     for (int v = w0; v < w1; v += 16) {
         const float ag_n = (v + 16 < w1) ? fetch(v + 16) : 0.f;
-        if (fold)
+        if constexpr (DIST == DIST_L2)
+            st.step_l2(s_w, s_wn, v, w1, escale, ag, dW);
+        else if (fold)
             st.template step<true>(s_w, s_wn, v, w1, escale, ag, dW);
         else
             st.template step<false>(s_w, s_wn, v, w1, escale, ag, dW);

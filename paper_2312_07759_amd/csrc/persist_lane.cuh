@@ -684,16 +684,17 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
     }
 
     // B3
-    if constexpr (MFMA && DIST == DIST_SQL2) {
+    if constexpr (MFMA) {
         // the output tables take the place of the per-wavefront partial sums, which no later pass needs
         f32x4* s_hc = reinterpret_cast<f32x4*>(&s_part[0][0]);
         static_assert(sizeof(s_part) >= 2 * TS * sizeof(f32x4), "output tables do not fit");
         MfmaB2<KPL>::template fill_cotangent<NT>(s_hsb, s_hq, k, s_Hs, s_Ff, s_mu, a.escale);
-        MfmaB3<KPL>::template fill_output_tables<NT>(s_hc, k, s_Hs, s_Cf, s_mu, s_fac0, fold, a.tau);
+        MfmaB3<KPL>::template fill_output_tables<NT>(s_hc, k, s_Hs, s_Cf, s_mu, s_fac0, fold, a.tau,
+                                                     DIST == DIST_SQL2 ? 2.f : a.escale);
         __syncthreads();
         MfmaB3<KPL> st;
         st.init(s_tab0, s_fac0, s_hsb, s_hq, s_hc, s_mu);
-        mfma_b3_tile_pass<KPL, NT>(st, s_tile, s_wn, s_gt, a.dW_out + base * D, cnt, a.escale, a.inv_tau, fold);
+        mfma_b3_tile_pass<KPL, DIST, NT>(st, s_tile, s_wn, s_gt, a.dW_out + base * D, cnt, a.escale, a.inv_tau, fold);
     } else {
         LaneWave<KPL, D, DIST, PASS_B3> st;
         st.init(k, s_Cf, s_Hs, s_Ff, a.escale);
