@@ -540,7 +540,7 @@ struct MfmaB2 {
     }
 };
 
-// The last pass of the backward (squared energy) on the matrix cores:
+// The last pass of the backward on the matrix cores (written out for the squared energy; step_l2 is the plain norm):
 //   dL/dW_i = sum_j a_ij h_j - (1/tau) sum_j (rho_ij + gamma_ij) delta_ij            (Eq. "grad", Alg. 2 backward step)
 // With z_ij = (G_i/tau).c_j + (h_j/tau).(w_i - F_j) (two chained 16x16x4 products), kappa_ij = a_ij (z_ij - zbar_i),
 // zbar_i = sum_j a_ij z_ij, and delta_ij = 2 (w_i - c_j), the second sum is -2 sum_j kappa_ij (c_j - mu) because
