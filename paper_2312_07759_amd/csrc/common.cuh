@@ -283,6 +283,13 @@ __device__ __forceinline__ float sum_sq_unfused(const float (&x)[D]) {
     }
     return key;
 }
+// x s - y with the product rounded on its own: when x s was rounded into y the result is exactly zero (a fused
+// multiply-add would leave the product's rounding residual, with a sign).
+__device__ __forceinline__ float scaled_minus_unfused(float x, float s, float y) {
+#pragma clang fp contract(off)
+    const float xs = x * s;
+    return xs - y;
+}
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ __forceinline__ float fast_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }

@@ -41,9 +41,42 @@ struct VecLoad<4> {
 // E-step for one vector against K uniform codewords (Eq. "aterms"): fills the
 // attention row a[K], the differences df = w - c and, for the plain norm with
 // D > 1 when derivatives are needed, ri = 1/||w - c|| (0 at coincidence).
+//
+// Scalar weights in the backward passes (D == 1, DERIV): scaled coordinates relative to the first codeword,
+// t_j = (w - c_0) s - (c_j - c_0) s with s = sqrt(log2(e)/tau) (squared energy) or log2(e)/tau (plain norm), so that
+// exp(-e_j/tau) = exp2(-t_j^2) resp. exp2(-|t_j|); the row is shifted by the smallest |t_j|.  Three operations fewer
+// per codeword than the general form.  df receives t_j and ri the factor that turns it into d e_j / d w for the squared
+// energy (2/s); for the plain norm only the sign of t_j is used, and t_j = 0 exactly where w = c_j (the two products
+// are rounded on their own).  The reference point keeps layers far from the origin free of cancellation.
 template <int K, int D, int DIST, bool DERIV>
-__device__ __forceinline__ void estep_small(const float (&w)[D], const float (&c)[K][D], float nscale, float (&a)[K],
-                                            float (&df)[K][D], float (&ri)[K]) {
+__device__ __forceinline__ void estep_small(const float (&w)[D], const float (&c)[K][D], float nscale, float escale,
+                                            float (&a)[K], float (&df)[K][D], float (&ri)[K]) {
+    if constexpr (D == 1 && DERIV) {
+        const float c0 = c[0][0];
+        const float wr = w[0] - c0;
+        float t[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) t[j] = scaled_minus_unfused(wr, escale, (c[j][0] - c0) * escale);  // (c_j - c_0) s is loop-invariant
+        float tmin = fabsf(t[0]);
+#pragma unroll
+        for (int j = 1; j < K; ++j) tmin = fminf(tmin, fabsf(t[j]));
+        const float qmin = tmin * tmin;
+        float S = 0.f;
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            a[j] = (DIST == DIST_SQL2) ? fast_exp2(fmaf(-t[j], t[j], qmin)) : fast_exp2(tmin - fabsf(t[j]));
+            S = (j == 0) ? a[0] : S + a[j];
+        }
+        const float rS = fast_rcp(S);
+        const float dfac = (DIST == DIST_SQL2) ? 2.f / escale : 0.f;  // loop-invariant
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            a[j] *= rS;
+            df[j][0] = t[j];
+            ri[j] = dfac;
+        }
+        return;
+    }
     float u[K];
 #pragma unroll
     for (int j = 0; j < K; ++j) {
@@ -88,9 +121,9 @@ __device__ __forceinline__ void estep_small(const float (&w)[D], const float (&c
 // delta_jr = d e_j / d w_r
 template <int K, int D, int DIST>
 __device__ __forceinline__ float delta_small(const float (&df)[K][D], const float (&ri)[K], int j, int r) {
-    if (DIST == DIST_SQL2) return 2.f * df[j][r];
-    if (D == 1) return (df[j][0] > 0.f) ? 1.f : ((df[j][0] < 0.f) ? -1.f : 0.f);
-    return df[j][r] * ri[j];
+    if (DIST == DIST_SQL2 && D > 1) return 2.f * df[j][r];
+    if (DIST == DIST_L2 && D == 1) return (df[j][0] > 0.f) ? 1.f : ((df[j][0] < 0.f) ? -1.f : 0.f);
+    return df[j][r] * ri[j];  // plain norm, D > 1: unit vector; squared energy, D == 1: df is scaled, ri = 2/s
 }
 
 // Everything one pass does for one weight vector i: E-step, then the pass's own
@@ -179,7 +212,7 @@ struct SmallItem {
 #pragma unroll
         for (int r = 0; r < D; ++r) gs[r] = USE_G ? g[r] * a.inv_tau : 0.f;
         float at[K], df[K][D], ri[K];
-        estep_small<K, D, DIST, BACK>(w, c, a.nscale, at, df, ri);
+        estep_small<K, D, DIST, BACK>(w, c, a.nscale, a.escale, at, df, ri);
 
         if (STATS) {
 #pragma unroll

@@ -540,11 +540,12 @@ def test_warm_start_and_temperature_schedule(ctx):
 
 # The widest shapes of the lane<->vector family (k d >= 32, d >= 2) take h_j . (w - F*_j) apart into h_j . (w - mu)
 # and a per-codeword constant in their (dF/dC)^T and last passes.  With a layer a hundred spreads away from the origin
-# the two parts would be large and nearly equal if mu were not the centre of the codebook.
+# the two parts would be large and nearly equal if mu were not the centre of the codebook.  The scalar shapes work in
+# scaled coordinates (w - c_0) s - (c_j - c_0) s in their backward passes, for the same reason relative to a codeword.
 @pytest.mark.parametrize("path", [binding.PATH_STREAM, binding.PATH_PERSISTENT], ids=["stream", "persistent"])
 @pytest.mark.parametrize("dist", DISTS)
-@pytest.mark.parametrize("k,d", [(16, 4), (8, 4), (16, 2)])
-def test_backward_of_a_wide_shape_far_from_the_origin(ctx, k, d, dist, path):
+@pytest.mark.parametrize("k,d", [(16, 4), (8, 4), (16, 2), (4, 1), (16, 1)])
+def test_backward_of_a_layer_far_from_the_origin(ctx, k, d, dist, path):
     rng = np.random.default_rng(770 + 16 * k + d)
     m = 20_011
     W = (5.0 + 0.05 * rng.standard_normal((m, d))).astype(np.float32)
@@ -565,3 +566,34 @@ def test_backward_of_a_wide_shape_far_from_the_origin(ctx, k, d, dist, path):
         assert rel(bi["dW"].cpu().numpy(), ri["dW"]) < TOL_GRAD
     finally:
         ctx.set_path(binding.PATH_AUTO)
+
+
+# Plain norm, scalar weights: d e / d w is the sign of w - c, and zero where the two coincide exactly.  The backward
+# passes work in scaled coordinates (w - c_0) s - (c_j - c_0) s; the two products have to be rounded on their own, or a
+# weight that equals a codeword would come out with the sign of a rounding residual.  Here a tenth (k = 4) to two
+# fifths (k = 16) of the weights sit exactly on codewords: a sign in place of the zero would move the result by 7-12 %.
+@pytest.mark.parametrize("k", [4, 16])
+def test_scalar_weights_that_coincide_with_codewords_plain_norm(ctx, k):
+    rng = np.random.default_rng(31)
+    m = 50_000
+    grid = np.linspace(-1, 1, 41).astype(np.float32)
+    W = rng.choice(grid, m).astype(np.float32).reshape(m, 1)
+    C = np.sort(rng.choice(grid, k, replace=False)).astype(np.float32).reshape(k, 1)
+    g = rng.standard_normal((k, 1)).astype(np.float32)
+    assert np.isin(W, C).mean() > 0.05
+    ctx.step_F(dev(W), dev(C), 0.2, wl.DIST_L2)
+    u = ctx.step_JCT(dev(g)).cpu().numpy()
+    assert rel(u, orc.vjp_F(C, W, 0.2, wl.DIST_L2, g)[0]) < TOL_GRAD
+    # the whole backward from this codebook (one evaluation of F moves it off the grid; the first pass, for v, and
+    # the last, for dW, still see it where the forward left it only through F*: compare at the GPU's own C*)
+    for path in (binding.PATH_STREAM, binding.PATH_PERSISTENT):
+        ctx.set_path(path)
+        try:
+            out = ctx.forward(dev(W), dev(C), 0.2, 0.0, 1, wl.DIST_L2)
+            Cg = out["C"].cpu().numpy()
+            G = rng.standard_normal((m, 1)).astype(np.float32)
+            bi = ctx.backward(dev(G), binding.BWD_IMPLICIT, tol=0.0, max_iter=6, alpha=1.0)
+            ri = orc.backward(W, Cg, 0.2, wl.DIST_L2, G, "implicit", tol=0.0, max_iter=6, alpha=1.0)
+            assert rel(bi["dW"].cpu().numpy(), ri["dW"]) < TOL_GRAD
+        finally:
+            ctx.set_path(binding.PATH_AUTO)
