@@ -297,7 +297,8 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
     // other vectors of the same lane, so vectors are taken in groups whose bodies the scheduler interleaves: in the
     // forward passes groups of UNR while they last, then groups of 4, then single vectors
     constexpr bool FWD_LIKE = (PASS == PASS_FWD || PASS == PASS_FIN);
-    // (for k = 8 and 16 the group size makes no measurable difference: 2 to 16 vectors are within 2 % of each other)
+    // (for k = 8 and 16 the group size makes no measurable difference: 2 to 16 vectors are within 2 % of each other;
+    // nor does it in the backward passes at k <= 4: 6, 9, 12 and 18 vectors are within 3 %)
     constexpr int UNR = SHARED ? (K <= 4 ? 4 : 2)
                                : (FWD_LIKE ? (K <= 4 ? 18 : (K == 8 ? 8 : 4)) : (K <= 4 ? 6 : (K == 8 ? 3 : 2)));
     auto one = [&](int it) {
@@ -805,9 +806,12 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     __syncthreads();
 
     while (!s_done) {
+        IDKM_STAMP(0);
         any_tile_pass<K, D, DIST, PASS_B2, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
+        IDKM_STAMP(1);
         ++seq;
         publish_partials<KD>(pa, seq, acc, xs);
+        IDKM_STAMP(2);
         const double alpha = s_alpha;
         if (pa.G == 1) {
             // a team of one has no exchange: its partial sums (xs.own) are the totals; the whole of g is updated
@@ -849,9 +853,11 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                     xs.bc[KD + r] = __float_as_uint((float)d2);
                 }
             }
+            IDKM_STAMP(3);
         }
         if (!gather_bcast<KD, WPR, KD>(pa, seq, NB, true, xs)) return;
         }
+        IDKM_STAMP(4);
         if (tid == 0) {
             // the same decision in every workgroup (same words, same order)
             double d2 = 0.0;
@@ -876,6 +882,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                 else
                     done = true;
             }
+            IDKM_STAMP(5);
             s_iters += 1;
             s_res = dn;
             if (conv) s_conv = 1;
