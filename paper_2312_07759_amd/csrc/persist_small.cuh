@@ -328,6 +328,7 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
 #pragma unroll UNR
         for (int it = threadIdx.x; it < cnt; it += PT) one(it);
     }
+    Item::finish(a, acc);
 }
 
 // The same pass for a layer that does not fit the chip's LDS: W (and dL/dWq) are read from memory in every pass, 16
@@ -411,6 +412,7 @@ __device__ __forceinline__ void tile_pass_global(const Args& a, const float* gw,
             Item::run(a, it, w, g, c, hs, ff, acc);
         }
     }
+    Item::finish(a, acc);
 }
 
 // A pass over the workgroup's share of the layer: its LDS tile (w, g: the tile; base, cnt: its place in the layer) or,

@@ -173,9 +173,60 @@ struct SmallItem {
         }
     }
 
+    // Scalar weights, (dF/dC)^T pass (the pass an implicit solve repeats): written out in scaled coordinates with ten
+    // instructions per codeword; for the squared energy the sums lack the constant factor 2/s of d e / d w, which
+    // finish() applies once per pass.
+    static constexpr bool SCALAR_B2 = (PASS == PASS_B2 && D == 1);
+
+    // Called once per pass by every caller of run(), after the last vector.
+    static __device__ __forceinline__ void finish(const Args& a, float (&acc)[NACC]) {
+        if constexpr (SCALAR_B2 && DIST == DIST_SQL2) {
+            const float f = 2.f / a.escale;
+#pragma unroll
+            for (int q = 0; q < NACC; ++q) acc[q] *= f;
+        }
+    }
+
     static __device__ __forceinline__ void run(const Args& a, int64_t i, const float (&w)[D], const float (&g)[D],
                                                const float (&c)[K][D], const float (&hs)[K][D],
                                                const float (&ff)[K][D], float (&acc)[NACC]) {
+        if constexpr (SCALAR_B2) {
+            // t_j = (w - c_0) s - (c_j - c_0) s (both products rounded on their own: exactly zero where w = c_j),
+            // p_j = exp2(-t_j^2 + min t^2) resp. exp2(-|t_j| + min |t|), S = sum p
+            const float sc = a.escale;
+            const float c0 = c[0][0];
+            const float wr = w[0] - c0;
+            float t[K];
+#pragma unroll
+            for (int j = 0; j < K; ++j) t[j] = scaled_minus_unfused(wr, sc, (c[j][0] - c0) * sc);  // loop-invariant product
+            float tmin = fabsf(t[0]);
+#pragma unroll
+            for (int j = 1; j < K; ++j) tmin = fminf(tmin, fabsf(t[j]));
+            const float qmin = tmin * tmin;
+            // q_j = (h_j/tau) (w - F_j) = hs_j (w - c_0) - hs_j (F_j - c_0); pq = sum p q
+            float p[K], q[K], S = 0.f, pq = 0.f;
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                p[j] = (DIST == DIST_SQL2) ? fast_exp2(fmaf(-t[j], t[j], qmin)) : fast_exp2(tmin - fabsf(t[j]));
+                S = (j == 0) ? p[0] : S + p[j];
+                q[j] = fmaf(hs[j][0], wr, -(hs[j][0] * (ff[j][0] - c0)));  // loop-invariant product
+                pq = fmaf(p[j], q[j], pq);
+            }
+            const float rS = fast_rcp(S);
+            const float nqb = -(pq * rS) * rS;  // -qbar / S
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                const float th = p[j] * fmaf(q[j], rS, nqb);  // a_j (q_j - qbar)
+                if (DIST == DIST_SQL2) {
+                    acc[j] = fmaf(th, t[j], acc[j]);  // times 2/s in finish()
+                } else {
+                    // sign(t_j), zero at t_j = 0: the median of (t_j 2^126, -1, 1) (an infinite product is fine)
+                    const float sg = __builtin_amdgcn_fmed3f(t[j] * 8.5070592e37f, -1.f, 1.f);
+                    acc[j] = fmaf(th, sg, acc[j]);
+                }
+            }
+            return;
+        }
         if (PASS == PASS_FWD && D == 1) {
             // Scalar weights, forward loop: work in scaled coordinates t_j = s w - s c_j with
             // s = sqrt(log2(e)/tau) (squared energy) or log2(e)/tau (plain norm), so that
@@ -375,6 +426,7 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
         }
         Item::run(a, i, w, g, c, hs, ff, acc);
     }
+    Item::finish(a, acc);
 
     if (PASS == PASS_B3) return;
 
