@@ -169,6 +169,15 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
                           float alpha, float* dW_out, idkm_info* info, void* hip_stream);
 
 /*
+ * The two O(k d) vectors of the last idkm_backward on this context (Eq. "grad"): v = dL/dC* with W fixed, and the
+ * g with which the call formed dL/dW -- the solution of (I - dF/dC*)^T g = v as far as the chosen mode took it
+ * (the iterate after the last pass of the averaged iteration of Sec. 4.2, the direct or Krylov solution, or v itself
+ * for IDKM_BWD_JFB).  v_out, g_out: HOST pointers to k d doubles each (row-major [k,d]), either may be NULL.
+ * Waits for hip_stream.  IDKM_ERR_NO_FORWARD if no backward has completed since the last forward.
+ */
+idkm_status idkm_get_cotangents(idkm_ctx* ctx, double* v_out, double* g_out, void* hip_stream);
+
+/*
  * Diagnostic: measures one of the ceilings a roofline of this path is drawn against, on the context's device.
  *   kind 0  full-rate lane operations per second (dependent-free v_fma_f32 chains, 8 wavefronts per SIMD)
  *   kind 1  exponentials per second (v_exp_f32 alone)

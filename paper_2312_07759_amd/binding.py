@@ -22,7 +22,7 @@ BWD_IMPLICIT, BWD_JFB, BWD_DENSE, BWD_GMRES = 0, 1, 2, 3
 PATH_AUTO, PATH_STREAM, PATH_PERSISTENT = 0, 1, 2
 
 EXPORTS = ["idkm_version", "idkm_limits", "idkm_status_string", "idkm_create", "idkm_destroy", "idkm_last_error",
-           "idkm_set_path", "idkm_set_matrix_cores", "idkm_set_tile_limit", "idkm_set_spin_limit", "idkm_set_gmres_basis", "idkm_advance_sequence", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT",
+           "idkm_set_path", "idkm_set_matrix_cores", "idkm_set_tile_limit", "idkm_set_spin_limit", "idkm_set_gmres_basis", "idkm_advance_sequence", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT", "idkm_get_cotangents",
            "idkm_calibrate", "idkm_code_bits", "idkm_code_words", "idkm_pack_codes", "idkm_unpack_quantize",
            "idkm_batch_create", "idkm_batch_destroy", "idkm_batch_last_error", "idkm_batch_launches",
            "idkm_batch_context", "idkm_batch_forward", "idkm_batch_backward"]
@@ -100,6 +100,8 @@ def load_library():
     lib.idkm_step_F.restype = C.c_int
     lib.idkm_step_JCT.argtypes = [vp, f32p, f32p, vp]
     lib.idkm_step_JCT.restype = C.c_int
+    lib.idkm_get_cotangents.argtypes = [vp, vp, vp, vp]
+    lib.idkm_get_cotangents.restype = C.c_int
     lib.idkm_calibrate.argtypes = [vp, C.c_int32, f32p, C.c_int64, C.POINTER(C.c_double), vp]
     lib.idkm_calibrate.restype = C.c_int
     lib.idkm_code_bits.argtypes = [C.c_int32]
@@ -245,6 +247,15 @@ class Context:
                                      C.byref(info), _stream())
         self._check(st)
         return dict(dW=dW, info=_info(info))
+
+    def get_cotangents(self, k, d):
+        """idkm_get_cotangents: (v, g) of the last backward as float64 numpy arrays [k,d]."""
+        import numpy as np
+        v = np.empty((k, d), dtype=np.float64)
+        g = np.empty((k, d), dtype=np.float64)
+        self._check(self._lib.idkm_get_cotangents(self._h, v.ctypes.data_as(C.c_void_p), g.ctypes.data_as(C.c_void_p),
+                                                  _stream()))
+        return v, g
 
     def calibrate(self, kind, buf=None):
         """idkm_calibrate: 0 lane-ops/s, 1 exponentials/s, 2 bytes/s of a streaming read of `buf` (float32 tensor),

@@ -1,6 +1,6 @@
 // Host-side lookup of kernel instantiations.
 #pragma once
-#include "common.cuh"
+#include "common.hpp"
 
 namespace idkm {
 

@@ -13,10 +13,10 @@
 #include <vector>
 
 #include "../../include/idkm.h"
-#include "common.cuh"
+#include "common.hpp"
 #include "dispatch.h"
-#include "persist_small.cuh"
-#include "persist_lane.cuh"
+#include "persist_small.hpp"
+#include "persist_lane.hpp"
 
 namespace idkm {
 KernelFn small_kernel_0(int, int, int);
@@ -176,6 +176,7 @@ struct idkm_ctx {
 #endif
     // forward state
     bool has_forward = false;
+    bool has_backward = false;  // a backward has been issued since the last forward: vd, gd hold its v and g
     const float* W = nullptr;
     int64_t m = 0;
     int d = 0, k = 0, dist = 0;
@@ -751,6 +752,7 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
     idkm_status st = check_common(ctx);
     if (st != IDKM_OK) return st;
     ctx->has_forward = false;
+    ctx->has_backward = false;
     st = validate_problem(ctx, W, m, d, C0, k, tau);
     if (st != IDKM_OK) return st;
     if (!C_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "C_out must be non-NULL");
@@ -863,6 +865,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     Args a = base_args(ctx);
     a.G = dWq;
     a.dW_out = dW_out;
+    ctx->has_backward = true;
 
     if (mode == IDKM_BWD_DENSE) {
         if (!g.small || ctx->k * ctx->d > DENSE_MAX_KD)
@@ -967,6 +970,19 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
         info->alpha = c.b_alpha;
         if (c.nonfinite) return fail(ctx, IDKM_ERR_NONFINITE, "the cotangent became non-finite");
     }
+    return IDKM_OK;
+}
+
+idkm_status idkm_get_cotangents(idkm_ctx* ctx, double* v_out, double* g_out, void* hip_stream) {
+    idkm_status st = check_common(ctx);
+    if (st != IDKM_OK) return st;
+    if (!ctx->has_forward || !ctx->has_backward)
+        return fail(ctx, IDKM_ERR_NO_FORWARD, "idkm_get_cotangents needs an idkm_backward after the last idkm_forward");
+    hipStream_t s = (hipStream_t)hip_stream;
+    const size_t bytes = (size_t)ctx->k * ctx->d * sizeof(double);
+    if (v_out) HIP_TRY(ctx, hipMemcpyAsync(v_out, ctx->vd, bytes, hipMemcpyDeviceToHost, s));
+    if (g_out) HIP_TRY(ctx, hipMemcpyAsync(g_out, ctx->gd, bytes, hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipStreamSynchronize(s));
     return IDKM_OK;
 }
 
@@ -1288,6 +1304,7 @@ idkm_status idkm_step_F(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, con
     idkm_status st = check_common(ctx);
     if (st != IDKM_OK) return st;
     ctx->has_forward = false;
+    ctx->has_backward = false;
     st = validate_problem(ctx, W, m, d, C, k, tau);
     if (st != IDKM_OK) return st;
     if (!Cplus_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "Cplus_out must be non-NULL");

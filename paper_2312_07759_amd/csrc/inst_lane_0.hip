@@ -1,6 +1,6 @@
 // Instantiations of the lane<->codeword kernels for energy variant 0.
 #include "dispatch.h"
-#include "lane_k.cuh"
+#include "lane_k.hpp"
 
 namespace idkm {
 

@@ -1,6 +1,6 @@
 // Instantiations of the stream-path matrix-core passes.
 #include "dispatch.h"
-#include "mfma_stream.cuh"
+#include "mfma_stream.hpp"
 
 namespace idkm {
 

@@ -1,6 +1,6 @@
 // Instantiations of the persistent (one launch per solve) kernels.
 #include "dispatch.h"
-#include "persist_small.cuh"
+#include "persist_small.hpp"
 
 namespace idkm {
 

@@ -1,6 +1,6 @@
 // Instantiations of the persistent kernels for layers larger than the chip's LDS (W streamed from memory).
 #include "dispatch.h"
-#include "persist_small.cuh"
+#include "persist_small.hpp"
 
 namespace idkm {
 

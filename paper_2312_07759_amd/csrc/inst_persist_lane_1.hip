@@ -1,6 +1,6 @@
 // Instantiations of the persistent lane<->codeword kernels for energy variant 1.
 #include "dispatch.h"
-#include "persist_lane.cuh"
+#include "persist_lane.hpp"
 
 namespace idkm {
 

@@ -1,6 +1,6 @@
 // Instantiations of the lane<->vector kernels for energy variant 1.
 #include "dispatch.h"
-#include "small_k.cuh"
+#include "small_k.hpp"
 
 namespace idkm {
 

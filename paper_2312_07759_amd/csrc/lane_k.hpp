@@ -3,8 +3,8 @@
 // weight vectors one at a time (broadcast from a lane with v_readlane), the row
 // softmax is a wavefront reduction, and the M-step sums stay in lane registers.
 #pragma once
-#include "common.cuh"
-#include "small_k.cuh"
+#include "common.hpp"
+#include "small_k.hpp"
 
 namespace idkm {
 

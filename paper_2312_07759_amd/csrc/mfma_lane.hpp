@@ -19,7 +19,7 @@
 // feeds register r straight into the second as the A operand of block l / 4, whose B operand is coordinate l % 4 of
 // vector 4 q + r.
 #pragma once
-#include "common.cuh"
+#include "common.hpp"
 
 namespace idkm {
 

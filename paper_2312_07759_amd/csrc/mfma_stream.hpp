@@ -1,11 +1,11 @@
 // Stream-path form of the matrix-core passes (d = 4, 17 <= k <= 256): one launch per pass, every workgroup copies its
-// chunk of W into LDS, runs the 16-vector steps of mfma_lane.cuh over it and leaves its partial sums in
+// chunk of W into LDS, runs the 16-vector steps of mfma_lane.hpp over it and leaves its partial sums in
 // a.partials[workgroup][.] (float64), which reduce_rows and the one-workgroup tail of the lane<->codeword family
 // then take as from lane_pass.  PASS_FWD and PASS_B2.
 #pragma once
-#include "common.cuh"
-#include "lane_k.cuh"
-#include "mfma_lane.cuh"
+#include "common.hpp"
+#include "lane_k.hpp"
+#include "mfma_lane.hpp"
 
 namespace idkm {
 

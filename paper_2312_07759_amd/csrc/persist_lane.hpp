@@ -7,12 +7,12 @@
 //          updates its codeword;
 //   hop 2  reducers store the float32 codeword (or h/tau) and a partial squared
 //          norm into buf2; every workgroup reads the k d + k words.
-// Waits are bounded exactly as in persist_small.cuh.
+// Waits are bounded exactly as in persist_small.hpp.
 #pragma once
-#include "common.cuh"
-#include "lane_k.cuh"
-#include "mfma_lane.cuh"
-#include "persist_small.cuh"
+#include "common.hpp"
+#include "lane_k.hpp"
+#include "mfma_lane.hpp"
+#include "persist_small.hpp"
 
 namespace idkm {
 
@@ -192,7 +192,7 @@ __device__ __forceinline__ void lane_tile_pass(const Args& a, LaneWave<KPL, D, D
 #define IDKM_LSTAMP(slot)
 #endif
 
-// Forward solve (Alg. 1) and the evaluation at C*.  MFMA: the loop's passes run on the matrix cores (mfma_lane.cuh;
+// Forward solve (Alg. 1) and the evaluation at C*.  MFMA: the loop's passes run on the matrix cores (mfma_lane.hpp;
 // d = 4), with NT = MT threads; the dynamic LDS then holds the tile padded by 16 zero vectors and,
 // behind it, -s^2 |w|^2 of every vector.
 template <int KPL, int D, int DIST, int NT = LT, bool MFMA = false>
@@ -721,7 +721,7 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
     }
 }
 
-// Launch forms: one team per grid, or one team per batched problem (see persist_small.cuh).
+// Launch forms: one team per grid, or one team per batched problem (see persist_small.hpp).
 template <int KPL, int D, int DIST>
 __global__ __launch_bounds__(LT) void persist_lane_fwd(const Args a, const PArgs pa_in) {
     PArgs pa = pa_in;

@@ -19,8 +19,8 @@
 // after spin_limit polls a workgroup raises Ctrl::abort_flag and leaves; the
 // others see the flag and leave too.  The grid must fit the device at once.
 #pragma once
-#include "common.cuh"
-#include "small_k.cuh"
+#include "common.hpp"
+#include "small_k.hpp"
 
 namespace idkm {
 

@@ -2,7 +2,7 @@
 // whole vectors, the K codewords are wave-uniform, and the K (D+1) partial sums
 // of the M-step live in the lane's registers.
 #pragma once
-#include "common.cuh"
+#include "common.hpp"
 
 namespace idkm {
 

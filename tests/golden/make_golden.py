@@ -7,7 +7,11 @@ paper_2312_07759_amd/workloads.py.  The HIP path is never imported or run.  The 
 runs take minutes (a forward solve of the 3x3x256x256 layer is ~100 s), which is why they are
 stored instead of being recomputed inside the GPU tests.
 
-  python tests/golden/make_golden.py C2 C3 C4 P16 C5      (any subset; default: all)
+  python tests/golden/make_golden.py C2 C3 C4 P16 C5 C4cap P16cap     (any subset; default: all)
+
+C4cap / P16cap run the configs that end at their iteration cap all the way to it (200 evaluations of F at
+k = 256 are about an hour and a half of numpy) and then take an averaged-iteration backward of a fixed number
+of passes; "C4cap:L2" or "C4cap:SQL2" runs one energy only, so that the two can run side by side.
 """
 from __future__ import annotations
 
@@ -79,6 +83,13 @@ def solved_layer(name, dist, out):
     rec["dW_jfb_norm"] = float(np.linalg.norm(jfb["dW"]))
     rec["dW_implicit_colsum"] = dense["dW"].sum(0).tolist()
     rec["G_colsum"] = G.astype(np.float64).sum(0).tolist()
+    # the averaged iteration of Sec. 4.2 held to a fixed number of passes (tol = 0): comparable pass by pass whether
+    # or not it would meet its stop rule; and the spectral radius of dF/dC*, which says whether it ever would
+    it40 = orc.backward(p.W, C, p.tau, dist, G, "implicit", tol=0.0, max_iter=40, alpha=1.0)
+    rec["implicit40"] = dict(iters=it40["iters"], alpha=it40["alpha"], residual=it40["residual"], g=it40["g"].tolist(),
+                             dW_rows=it40["dW"][idx].tolist(), dW_norm=float(np.linalg.norm(it40["dW"])),
+                             dW_absmax=float(np.abs(it40["dW"]).max()))
+    rec["rho"] = float(np.abs(np.linalg.eigvals(orc.jacobian_C(C, p.W, p.tau, dist))).max())
     rec["oracle_seconds"] = round(time.time() - t0, 1)
     dump(rec, out)
     print(name, dist, "iters", fw["iters"], "conv", fw["converged"], "%.0fs" % (time.time() - t0), flush=True)
@@ -114,10 +125,70 @@ def stepwise_layer(name, dist, out, steps):
     print(name, dist, "steps", steps, "%.0fs" % (time.time() - t0), flush=True)
 
 
+def capped_layer(name, dist, out, stages=(50, 100, 150, 200), bwd_passes=(10, 50)):
+    """The configs whose forward solve ends at its iteration cap: the codebook along the trajectory (every stage
+    continues the previous one, which Alg. 1 does anyway: its state is the codebook alone), the result at the cap,
+    and there JFB and the averaged iteration of Sec. 4.2 held to fixed pass counts (tol = 0)."""
+    p = wl.make_problem(name, dist)
+    assert stages[-1] == p.max_iter
+    t0 = time.time()
+    k, d = p.cfg.k, p.cfg.d
+    idx = np.unique(np.concatenate([sample_rows(p.cfg.m, 81, 2048), np.arange(p.cfg.m - 64, p.cfg.m),
+                                    np.arange(64)]))
+    rec = dict(note=NOTE, config=name, dist=dist, m=p.cfg.m, d=d, k=k, tau=p.tau, tol=p.tol, max_iter=p.max_iter,
+               stages=list(stages), C_at_stage=[], residual_at_stage=[], sample_rows=idx.tolist())
+    C = p.C0
+    done = 0
+    stopped = False
+    for s in stages:
+        fw = orc.soft_kmeans(p.W, C, p.tau, p.tol, s - done, dist)
+        C = fw["C"]
+        done += fw["iters"]
+        rec["C_at_stage"].append(C.tolist())
+        rec["residual_at_stage"].append(fw["residual"])
+        print(name, dist, "evaluations", done, "residual %.3e" % fw["residual"], "%.0fs" % (time.time() - t0),
+              flush=True)
+        if fw["converged"]:
+            stopped = True
+            break
+    rec.update(iters=done, converged=stopped, residual=rec["residual_at_stage"][-1], C=C.tolist())
+    Wq = orc.soft_quantize(p.W, C, p.tau, dist)
+    rec["Wq_rows"] = Wq[idx].tolist()
+    rec["Wq_norm"] = float(np.linalg.norm(Wq))
+    rec["Wq_colsum"] = Wq.sum(0).tolist()
+    del Wq
+    A = orc.attention(p.W, C, p.tau, dist)
+    Fv, n = orc.mstep(A, p.W, C)
+    del A
+    rec["n"] = n.tolist()
+    rec["F_at_C"] = Fv.tolist()
+    jfb = orc.backward(p.W, C, p.tau, dist, p.G, "jfb")
+    rec["v"] = jfb["v"].tolist()
+    rec["dW_jfb_rows"] = jfb["dW"][idx].tolist()
+    rec["dW_jfb_norm"] = float(np.linalg.norm(jfb["dW"]))
+    rec["dW_jfb_colsum"] = jfb["dW"].sum(0).tolist()
+    rec["dW_jfb_absmax"] = float(np.abs(jfb["dW"]).max())
+    del jfb
+    print(name, dist, "jfb done", "%.0fs" % (time.time() - t0), flush=True)
+    rec["implicit"] = []
+    for passes in bwd_passes:
+        imp = orc.backward(p.W, C, p.tau, dist, p.G, "implicit", tol=0.0, max_iter=passes, alpha=1.0)
+        rec["implicit"].append(dict(max_iter=passes, iters=imp["iters"], alpha=imp["alpha"], residual=imp["residual"],
+                                    g=imp["g"].tolist(), dW_rows=imp["dW"][idx].tolist(),
+                                    dW_norm=float(np.linalg.norm(imp["dW"])), dW_colsum=imp["dW"].sum(0).tolist(),
+                                    dW_absmax=float(np.abs(imp["dW"]).max())))
+        print(name, dist, "implicit", passes, "passes ->", imp["iters"], "alpha", imp["alpha"],
+              "%.0fs" % (time.time() - t0), flush=True)
+        del imp
+    rec["oracle_seconds"] = round(time.time() - t0, 1)
+    dump(rec, out)
+
+
 def sweep(out):
-    """A cross-section of the ResNet18 sweep: small, medium and 1x1 tensors at k = 2 and k = 4."""
+    """The ResNet18 sweep (Alg. 2's loop over layers): all 21 tensors at k = 2 and k = 4, both energies."""
     recs = []
-    for idx_t in (0, 1, 9, 14, 19):
+    t0 = time.time()
+    for idx_t in range(len(wl.RESNET18_TENSORS)):
         for k in (2, 4):
             for dist in (wl.DIST_L2, wl.DIST_SQL2):
                 cfg = wl.sweep_config(idx_t, k, dist)
@@ -127,16 +198,26 @@ def sweep(out):
                 rows = sample_rows(cfg.m, 80 + idx_t, 48)
                 dense = orc.backward(p.W, C, p.tau, dist, p.G, "dense")
                 jfb = orc.backward(p.W, C, p.tau, dist, p.G, "jfb")
+                it30 = orc.backward(p.W, C, p.tau, dist, p.G, "implicit", tol=0.0, max_iter=30, alpha=1.0)
+                A = orc.attention(p.W, C, p.tau, dist)
+                n = orc.mstep(A, p.W, C)[1]
+                del A
                 recs.append(dict(tensor=idx_t, k=k, dist=dist, m=cfg.m, tau=p.tau, iters=fw["iters"],
-                                 converged=fw["converged"], C=C.tolist(), sample_rows=rows.tolist(),
+                                 converged=fw["converged"], residual=fw["residual"], C=C.tolist(), n=n.tolist(),
+                                 sample_rows=rows.tolist(),
                                  Wq_rows=orc.soft_quantize(p.W[rows], C, p.tau, dist).tolist(),
-                                 dW_implicit_rows=dense["dW"][rows].tolist(), dW_jfb_rows=jfb["dW"][rows].tolist()))
-                print("C5", idx_t, k, dist, fw["iters"], fw["converged"], flush=True)
+                                 v=dense["v"].tolist(), g_dense=dense["g"].tolist(),
+                                 dW_implicit_rows=dense["dW"][rows].tolist(), dW_jfb_rows=jfb["dW"][rows].tolist(),
+                                 dW_implicit_norm=float(np.linalg.norm(dense["dW"])),
+                                 dW_jfb_norm=float(np.linalg.norm(jfb["dW"])),
+                                 implicit30=dict(iters=it30["iters"], alpha=it30["alpha"], g=it30["g"].tolist(),
+                                                 dW_rows=it30["dW"][rows].tolist(),
+                                                 dW_norm=float(np.linalg.norm(it30["dW"])))))
+                print("C5", idx_t, k, dist, fw["iters"], fw["converged"], "%.0fs" % (time.time() - t0), flush=True)
     dump(dict(note=NOTE, cases=recs), out)
 
-
 def main():
-    which = sys.argv[1:] or ["C2", "C3", "C4", "P16", "C5"]
+    which = sys.argv[1:] or ["C2", "C3", "C4", "P16", "C5", "C4cap", "P16cap"]
     for name in which:
         if name in ("C2", "C3"):
             for dist in (wl.DIST_L2, wl.DIST_SQL2):
@@ -147,6 +228,12 @@ def main():
                                steps=12 if name == "C4" else 25)
         elif name == "C5":
             sweep(os.path.join(HERE, "C5_sweep.json"))
+        elif name.split(":")[0] in ("C4cap", "P16cap"):
+            base = name.split(":")[0][:-3]
+            for dist in (wl.DIST_L2, wl.DIST_SQL2):
+                if ":" in name and wl.DIST_NAMES[dist] != name.split(":")[1]:
+                    continue
+                capped_layer(base, dist, os.path.join(HERE, f"{base}_{wl.DIST_NAMES[dist]}_cap.json"))
 
 
 if __name__ == "__main__":

@@ -174,9 +174,15 @@ def _forward_backward_case(ctx, cfg, m, dist, expect_path):
         assert bd["info"].converged and bd["info"].iters == 0
         assert rel(bd["dW"].cpu().numpy(), rd["dW"]) < TOL_GRAD, rel(bd["dW"].cpu().numpy(), rd["dW"])
     if kd <= 64:
-        # run to the stop rule and compare with the dense solve of the same linear system
-        bc = ctx.backward(Gd, binding.BWD_IMPLICIT, tol=1e-7, max_iter=5000, alpha=1.0)
-        if bc["info"].converged:
+        # Run to the stop rule and compare with the dense solve of the same linear system.  Whether the undamped
+        # iteration can meet its stop rule is decided by the oracle: the spectral radius of dF/dC* at this C*.  (The
+        # equal-pass comparison above holds either way.)
+        rho = float(np.abs(np.linalg.eigvals(orc.jacobian_C(Cg, p.W, p.tau, dist))).max())
+        if rho < 0.97:
+            # (float32 passes leave a noise floor of about 1e-6 ||g|| in the step norm, so the stop rule is asked for
+            # at 1e-5 ||v||; with rho < 0.97 the iterate is then within 1e-5 / (1 - rho) < 4e-4 of the solution)
+            bc = ctx.backward(Gd, binding.BWD_IMPLICIT, tol=1e-5, max_iter=5000, alpha=1.0)
+            assert bc["info"].converged, (bc["info"], rho)
             rd = orc.backward(p.W, Cg, p.tau, dist, G, "dense")
             assert rel(bc["dW"].cpu().numpy(), rd["dW"]) < TOL_GRAD
             # translation invariance of the layer: the implicit gradient sums to the upstream sum
@@ -373,11 +379,16 @@ def test_krylov_backward_solves_the_linear_system_of_the_implicit_gradient(ctx, 
     # the solution itself, read back through one raw (dF/dC)^T pass at g_ref: J^T g_ref = g_ref - v
     u = ctx.step_JCT(dev(ref["g"].astype(np.float32))).cpu().numpy()
     assert rel(u, ref["g"] - ref["v"]) < TOL_GRAD
-    # and the stream-path averaged iteration, where it converges, lands on the same dW
-    ctx.set_path(binding.PATH_STREAM)
-    it = ctx.backward(Gd, binding.BWD_IMPLICIT, tol=1e-7, max_iter=3000, alpha=1.0)
-    ctx.set_path(binding.PATH_AUTO)
-    if it["info"].converged:
+    # and the stream-path averaged iteration lands on the same dW wherever the oracle says it converges (spectral
+    # radius of dF/dC* below one; two of the cases are chosen to have it above one)
+    rho = float(np.abs(np.linalg.eigvals(orc.jacobian_C(Cg, W, tau, dist))).max())
+    if rho < 0.97:
+        ctx.set_path(binding.PATH_STREAM)
+        try:
+            it = ctx.backward(Gd, binding.BWD_IMPLICIT, tol=1e-5, max_iter=3000, alpha=1.0)
+        finally:
+            ctx.set_path(binding.PATH_AUTO)
+        assert it["info"].converged, (it["info"], rho)
         assert rel(r["dW"].cpu().numpy(), it["dW"].cpu().numpy()) < TOL_GRAD
 
 
