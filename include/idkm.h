@@ -269,6 +269,28 @@ idkm_status idkm_batch_backward(idkm_batch* b, const idkm_bwd_desc* layers, int3
                                 idkm_status* statuses, void* hip_stream);
 
 /*
+ * idkm_forward for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and error behaviour as idkm_forward, but there is no context: every
+ * byte the kernels need beyond the caller's tensors (the exchange words of the grid-wide sums, the O(k d) solver
+ * state, the block the kernel reports into -- about 530 KB) lies in one array in the library's device image, one
+ * copy per GPU, held until the process ends.  The call makes no hipMalloc / hipFree and no other allocating call.
+ *   device_id   the HIP device (0 .. 63) whose copy of the array is used; made current by the call.
+ *   Limits      k in {2, 4, 8, 16}, d in {1, 2, 4}, m d <= IDKM_NOALLOC_MAX_WEIGHTS (the whole layer is held in LDS, one
+ *               launch per solve); anything else returns IDKM_ERR_UNSUPPORTED and touches nothing.
+ *   info        host or NULL.  With NULL the solve is only enqueued on hip_stream and nothing waits; otherwise the
+ *               call copies the kernel's report back and waits for the stream.
+ * No state for idkm_backward is kept.  All calls on one GPU share that GPU's array, which keeps the previous call's
+ * contents (its words carry sequence numbers, so stale ones are never taken for new): calls that overlap on one GPU
+ * -- from several threads or on several streams -- race; the library serialises only its own host-side bookkeeping.
+ * idkm_noalloc_last_error gives the detail of the last failed call (process-wide; "" if none).
+ */
+#define IDKM_NOALLOC_MAX_WEIGHTS 9400000
+idkm_status idkm_forward_noalloc(int device_id, const float* W, int64_t m, int32_t d, const float* C0, int32_t k,
+                                 float tau, float tol, int32_t max_iter, idkm_dist dist, float* C_out, float* A_out,
+                                 float* Wq_out, int32_t* assign_out, idkm_info* info, void* hip_stream);
+const char* idkm_noalloc_last_error(void);
+
+/*
  * Single evaluations at a caller-supplied codebook C (device [k,d]), for testing one step in
  * isolation.  They overwrite the forward state of the context with (W, C, n = A^T 1, F(C, W)).
  *   idkm_step_F:   Cplus_out[k,d] = F(C, W)                         (Eq. "deepeqc"); n_out device [k] or NULL

@@ -22,7 +22,7 @@ BWD_IMPLICIT, BWD_JFB, BWD_DENSE, BWD_GMRES = 0, 1, 2, 3
 PATH_AUTO, PATH_STREAM, PATH_PERSISTENT = 0, 1, 2
 
 EXPORTS = ["idkm_version", "idkm_limits", "idkm_status_string", "idkm_create", "idkm_destroy", "idkm_last_error",
-           "idkm_set_path", "idkm_set_matrix_cores", "idkm_set_tile_limit", "idkm_set_spin_limit", "idkm_set_gmres_basis", "idkm_advance_sequence", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT", "idkm_get_cotangents",
+           "idkm_set_path", "idkm_set_matrix_cores", "idkm_set_tile_limit", "idkm_set_spin_limit", "idkm_set_gmres_basis", "idkm_advance_sequence", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT", "idkm_get_cotangents", "idkm_forward_noalloc", "idkm_noalloc_last_error",
            "idkm_calibrate", "idkm_code_bits", "idkm_code_words", "idkm_pack_codes", "idkm_unpack_quantize",
            "idkm_batch_create", "idkm_batch_destroy", "idkm_batch_last_error", "idkm_batch_launches",
            "idkm_batch_context", "idkm_batch_forward", "idkm_batch_backward"]
@@ -100,6 +100,11 @@ def load_library():
     lib.idkm_step_F.restype = C.c_int
     lib.idkm_step_JCT.argtypes = [vp, f32p, f32p, vp]
     lib.idkm_step_JCT.restype = C.c_int
+    lib.idkm_forward_noalloc.argtypes = [C.c_int, f32p, C.c_int64, C.c_int32, f32p, C.c_int32, C.c_float, C.c_float,
+                                         C.c_int32, C.c_int, f32p, f32p, f32p, i32p, C.POINTER(IdkmInfo), vp]
+    lib.idkm_forward_noalloc.restype = C.c_int
+    lib.idkm_noalloc_last_error.argtypes = []
+    lib.idkm_noalloc_last_error.restype = C.c_char_p
     lib.idkm_get_cotangents.argtypes = [vp, vp, vp, vp]
     lib.idkm_get_cotangents.restype = C.c_int
     lib.idkm_calibrate.argtypes = [vp, C.c_int32, f32p, C.c_int64, C.POINTER(C.c_double), vp]
@@ -312,6 +317,27 @@ class Context:
                                      _ptr(out, torch.float32, g.shape, "out"), _stream())
         self._check(st)
         return out
+
+
+def forward_noalloc(W, C0, tau, tol, max_iter, dist, out, device: int = 0, want_info: bool = True):
+    """idkm_forward_noalloc.  `out` holds the caller's preallocated device tensors: C [k,d] (required) and
+    optionally A [m,k], Wq [m,d], assign int32 [m].  Returns Info, or None when want_info is False (then the solve
+    is only enqueued on the current stream)."""
+    import torch
+    lib = load_library()
+    m, d = W.shape
+    k = C0.shape[0]
+    info = IdkmInfo()
+    st = lib.idkm_forward_noalloc(int(device), _ptr(W, torch.float32, (m, d), "W"), m, d,
+                                  _ptr(C0, torch.float32, (k, d), "C0"), k, float(tau), float(tol), int(max_iter),
+                                  int(dist), _ptr(out["C"], torch.float32, (k, d), "C_out"),
+                                  _ptr(out.get("A"), torch.float32, (m, k), "A_out"),
+                                  _ptr(out.get("Wq"), torch.float32, (m, d), "Wq_out"),
+                                  _ptr(out.get("assign"), torch.int32, (m,), "assign_out"),
+                                  C.byref(info) if want_info else None, _stream())
+    if st != IDKM_OK:
+        raise IdkmError(st, lib.idkm_noalloc_last_error().decode())
+    return _info(info) if want_info else None
 
 
 def code_bits(k: int) -> int:

@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <new>
 #include <algorithm>
 #include <string>
@@ -158,7 +159,9 @@ struct idkm_ctx {
     unsigned int seq_base = 0;
     unsigned long long* lane_xbuf = nullptr;  // exchange words of the lane<->codeword persistent kernels (lazy)
     unsigned int* abort_word = nullptr;  // device
-    PResult* h_res = nullptr;            // pinned host
+    PResult* h_res = nullptr;            // pinned host; device memory when res_on_device
+    bool res_on_device = false;          // the context of idkm_forward_noalloc: the kernel reports into device memory
+    PResult res_copy;                    // ... and the host reads this copy of it
     int last_empty = 0;                  // empty clusters seen by the last forward
     // a persistent launch whose result has not been collected yet (batched calls defer the wait)
     bool defer_wait = false;
@@ -479,7 +482,14 @@ idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PAr
     pa.per = pp.per;
     pa.abort_word = ctx->abort_word;
     pa.out = ctx->h_res;
-    std::memset(ctx->h_res, 0, sizeof(PResult));
+    if (ctx->res_on_device) {
+        static_assert(sizeof(PResult) % sizeof(unsigned long long) == 0, "PResult is cleared in 64-bit words");
+        hipLaunchKernelGGL(k_fill_u64, dim3(1), dim3(64), 0, s, reinterpret_cast<unsigned long long*>(ctx->h_res),
+                           sizeof(PResult) / sizeof(unsigned long long), 0ull);
+        HIP_TRY(ctx, hipGetLastError());
+    } else {
+        std::memset(ctx->h_res, 0, sizeof(PResult));
+    }
 #ifdef IDKM_TRACE
     pa.trace = ctx->trace;
 #endif
@@ -523,8 +533,10 @@ idkm_status finish_persistent(idkm_ctx* ctx, idkm_info* info) {
     const int kind = ctx->pending_kind;
     if (!kind) return IDKM_OK;
     ctx->pending_kind = 0;
+    if (ctx->res_on_device)
+        HIP_TRY(ctx, hipMemcpyAsync(&ctx->res_copy, ctx->h_res, sizeof(PResult), hipMemcpyDeviceToHost, ctx->pending_stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->pending_stream));
-    const PResult& c = *ctx->h_res;
+    const PResult& c = ctx->res_on_device ? ctx->res_copy : *ctx->h_res;
     if (c.done != ctx->pending_id) return fail(ctx, IDKM_ERR_DEVICE, "a grid-wide wait hit its limit");
     if (kind == 1) {
         int empty = 0, bad = c.nonfinite;
@@ -1353,6 +1365,140 @@ idkm_status idkm_step_JCT(idkm_ctx* ctx, const float* gvec, float* out, void* hi
     if (st != IDKM_OK) return st;
     hipLaunchKernelGGL(k_f64_to_f32, dim3(1), dim3(WG), 0, s, ctx->ud, out, ctx->k * ctx->d);
     HIP_TRY(ctx, hipGetLastError());
+    return IDKM_OK;
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------- the entry point that allocates nothing
+
+namespace {
+
+// Everything the persistent forward kernel needs beyond the caller's tensors: the exchange words of the grid-wide
+// sums, the O(k d) solver state it leaves behind, the abort word and the block it reports into.
+struct StaticScratch {
+    unsigned long long xbuf[XBUF_WORDS];
+    double Cd[64], Fd[64], nd[16];
+    float Cf[64], Ff[64];
+    unsigned int abort_word;
+    unsigned int pad_;
+    PResult res;
+};
+constexpr size_t STATIC_SCRATCH_BYTES = (sizeof(StaticScratch) + 255) / 256 * 256;
+constexpr int STATIC_MAX_DEVICES = 64;
+
+}  // namespace
+
+// One copy per GPU the library runs on, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the address the kernels get is the one that call returns for the current device.
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+
+struct StaticDevice {
+    bool ready = false;
+    idkm_ctx ctx;  // a host-side context whose device pointers all point into this device's copy of `scratch`
+};
+StaticDevice g_static[STATIC_MAX_DEVICES];
+std::mutex g_static_mutex;
+std::string g_static_err;
+
+}  // namespace
+
+extern "C" {
+
+const char* idkm_noalloc_last_error(void) { return g_static_err.c_str(); }
+
+idkm_status idkm_forward_noalloc(int device_id, const float* W, int64_t m, int32_t d, const float* C0, int32_t k,
+                                 float tau, float tol, int32_t max_iter, idkm_dist dist, float* C_out, float* A_out,
+                                 float* Wq_out, int32_t* assign_out, idkm_info* info, void* hip_stream) {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    g_static_err.clear();
+    auto bad = [&](idkm_status st, const std::string& msg) {
+        g_static_err = msg;
+        return st;
+    };
+    if (device_id < 0 || device_id >= STATIC_MAX_DEVICES) return bad(IDKM_ERR_INVALID_ARG, "device_id out of range");
+    if (hipSetDevice(device_id) != hipSuccess) {
+        (void)hipGetLastError();
+        return bad(IDKM_ERR_DEVICE, "hipSetDevice failed");
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    StaticDevice& sd = g_static[device_id];
+    idkm_ctx* ctx = &sd.ctx;
+    if (!sd.ready) {
+        // once per device, with that device current: the address of this device's copy of the array
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return bad(IDKM_ERR_DEVICE, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+        }
+        StaticScratch* sc = reinterpret_cast<StaticScratch*>(ptr);
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device_id) != hipSuccess || cus < 1) {
+            (void)hipGetLastError();
+            return bad(IDKM_ERR_DEVICE, "hipDeviceGetAttribute failed");
+        }
+        ctx->device = device_id;
+        ctx->num_cu = cus;
+        ctx->coop = true;  // plain launches of a grid that the occupancy query shows to be co-resident
+        ctx->xbuf = sc->xbuf;
+        ctx->xbuf_words = XBUF_WORDS;
+        ctx->Cd = sc->Cd;
+        ctx->Fd = sc->Fd;
+        ctx->nd = sc->nd;
+        ctx->Cf = sc->Cf;
+        ctx->Ff = sc->Ff;
+        ctx->abort_word = &sc->abort_word;
+        ctx->h_res = &sc->res;
+        ctx->res_on_device = true;
+        ctx->seq_base = 0;
+        // the stamps start from a cleared array (sequence number 0 is never used); a fill kernel, not a memset
+        hipLaunchKernelGGL(k_fill_u64, dim3(64), dim3(256), 0, s, reinterpret_cast<unsigned long long*>(ptr),
+                           STATIC_SCRATCH_BYTES / sizeof(unsigned long long), 0ull);
+        if (hipGetLastError() != hipSuccess) return bad(IDKM_ERR_DEVICE, "clearing the scratch array failed");
+        sd.ready = true;
+    }
+    ctx->err.clear();
+    ctx->pending_kind = 0;
+    idkm_status st = validate_problem(ctx, W, m, d, C0, k, tau);
+    if (st == IDKM_OK && !C_out) st = fail(ctx, IDKM_ERR_INVALID_ARG, "C_out must be non-NULL");
+    if (st == IDKM_OK && !(tol >= 0.f)) st = fail(ctx, IDKM_ERR_INVALID_ARG, "tol must be >= 0");
+    if (st == IDKM_OK && max_iter < 1) st = fail(ctx, IDKM_ERR_INVALID_ARG, "max_iter must be >= 1");
+    if (st == IDKM_OK && dist != IDKM_DIST_L2 && dist != IDKM_DIST_SQL2) st = fail(ctx, IDKM_ERR_INVALID_ARG, "unknown dist");
+    if (st != IDKM_OK) return bad(st, ctx->err);
+    const bool shape_ok = k >= 2 && k <= 16 && pow2(k) && (d == 1 || d == 2 || d == 4);
+    if (!shape_ok || m * d > IDKM_NOALLOC_MAX_WEIGHTS)
+        return bad(IDKM_ERR_UNSUPPORTED, "idkm_forward_noalloc serves k in {2,4,8,16}, d in {1,2,4} and m*d <= " +
+                                             std::to_string((long long)IDKM_NOALLOC_MAX_WEIGHTS) +
+                                             " (the layer is held in LDS)");
+    ctx->W = W;
+    ctx->m = m;
+    ctx->d = d;
+    ctx->k = k;
+    ctx->dist = (int)dist;
+    ctx->tau = tau;
+    ctx->path = IDKM_PATH_AUTO;
+    Args a = base_args(ctx);
+    a.C_out = C_out;
+    a.A_out = A_out;
+    a.Wq_out = Wq_out;
+    a.assign_out = assign_out;
+    PersistPlan pp;
+    if (!plan_persistent(ctx, false, &pp) || pp.lane || pp.lds == 0 || pp.lds > LDS_TILE_MAX)
+        return bad(IDKM_ERR_UNSUPPORTED, "idkm_forward_noalloc: the layer does not fit this device's LDS");
+    PArgs pa;
+    std::memset(&pa, 0, sizeof(pa));
+    pa.C0 = C0;
+    pa.tol = (double)tol;
+    pa.max_iter = (int)max_iter;
+    st = launch_persistent(ctx, pp, a, pa, (unsigned int)max_iter + 1u, s);
+    if (st != IDKM_OK) return bad(st, ctx->err);
+    if (!info) return IDKM_OK;  // enqueued; nothing waits
+    ctx->pending_kind = 1;
+    st = finish_persistent(ctx, info);
+    if (st != IDKM_OK) return bad(st, ctx->err);
     return IDKM_OK;
 }
 
