@@ -6,11 +6,15 @@ Two sources of expected values, both the CPU oracle's:
     averaged iteration of Sec. 4.2 held to a fixed number of passes;
   * the oracle run live on the WHOLE tensor at the GPU's own C*: everything that is one pass over W (Wq, hard
     assignments, the JFB gradient, the dense solve for k d <= 16), so every row is compared, tails included.
-The paper prints no worked example.  Every comparison is norm-wise AND element-wise:
+The paper prints no worked example.  Comparisons at the SAME codebook (the live ones, the codebooks themselves, the
+cotangents) are norm-wise AND element-wise:
   ||x - ref||_F <= tol ||ref||_F   and   max |x - ref| <= tol max |ref|,
-tol = 1e-4 for C*, Wq, F, n and 1e-3 for gradients and cotangents; hard assignments bit for bit.  The averaged
-iteration is compared at equal pass counts (tol = 0 on both sides), so nothing depends on whether it would converge.
-A missing fixture is a failure, not a skip.
+tol = 1e-4 for C*, Wq, F, n and 1e-3 for gradients and cotangents; hard assignments bit for bit.  Stored rows of Wq
+and dW belong to the ORACLE's C*, which differs from the GPU's by rounding: a row that lies between the two positions
+of a codeword or of a cell boundary changes by O(1) there (the plain norm's derivative is a sign), so those rows are
+held to the norm-wise bound only.  The averaged iteration is compared at equal pass counts (tol = 0 on both sides),
+so nothing depends on whether it would converge; where the float32 iteration reaches a step of exactly zero earlier
+(g no longer changes, further passes are no-ops) that is accepted.  A missing fixture is a failure, not a skip.
 """
 import json
 import os
@@ -49,6 +53,17 @@ def elem(x, ref):
 def check(x, ref, tol, what):
     r, e = rel(x, ref), elem(x, ref)
     assert r < tol and e < tol, f"{what}: norm-wise {r:.3e}, element-wise {e:.3e}, bound {tol:g}"
+
+
+def check_norm(x, ref, tol, what):
+    r = rel(x, ref)
+    assert r < tol, f"{what}: norm-wise {r:.3e}, bound {tol:g}"
+
+
+def same_passes(info, want_iters, want_alpha):
+    """The pass count and damping of an equal-pass run (tol = 0), or an exact fixed point of the float32 iteration."""
+    return (info.iters == want_iters and info.alpha == want_alpha and not info.converged) or \
+           (info.converged and info.residual == 0.0 and info.iters <= want_iters and info.alpha == want_alpha)
 
 
 def load(name):
@@ -108,16 +123,23 @@ def test_full_size_solved_layers(ctx, name, dist):
     bd = ctx.backward(G, binding.BWD_DENSE)
     assert bd["info"].converged and bd["info"].iters == 0
     check(bd["dW"].cpu().numpy(), rd["dW"], TOL_GRAD, f"{tag} dense dW (whole tensor)")
-    check(ctx.get_cotangents(k, d)[1], rd["g"], TOL_GRAD, f"{tag} g of the dense solve")
-    assert rel(bd["dW"].cpu().numpy()[idx], g["dW_implicit_rows"]) < TOL_GRAD
+    g_dense = ctx.get_cotangents(k, d)[1]
+    # the solve is held to its backward error, evaluated by the oracle: ||v + (dF/dC*)^T g - g|| <= 1e-3 ||v||; the
+    # forward error is bounded only where I - dF/dC* is well conditioned (at C2 with the squared energy it is not:
+    # condition number about 1e5 at the unconverged C*)
+    res = rj["v"] + orc.vjp_F(Cg, p.W, p.tau, dist, g_dense)[0] - g_dense
+    assert np.linalg.norm(res) < TOL_GRAD * np.linalg.norm(rj["v"]), (tag, np.linalg.norm(res), np.linalg.norm(rj["v"]))
+    if g["rho"] < 0.97:
+        check(g_dense, rd["g"], TOL_GRAD, f"{tag} g of the dense solve")
+    check_norm(bd["dW"].cpu().numpy()[idx], g["dW_implicit_rows"], TOL_GRAD, f"{tag} dense dW rows at the oracle's C*")
 
     # the averaged iteration at an equal pass count (no stop rule involved)
     r40 = g["implicit40"]
     b40 = ctx.backward(G, binding.BWD_IMPLICIT, tol=0.0, max_iter=40, alpha=1.0)
-    assert b40["info"].iters == r40["iters"] and b40["info"].alpha == r40["alpha"] and not b40["info"].converged
+    assert same_passes(b40["info"], r40["iters"], r40["alpha"]), (tag, b40["info"], r40["iters"], r40["alpha"])
     check(ctx.get_cotangents(k, d)[1], r40["g"], TOL_GRAD, f"{tag} g after 40 passes")
     d40 = b40["dW"].cpu().numpy()
-    check(d40[idx], r40["dW_rows"], TOL_GRAD, f"{tag} dW after 40 passes (sampled rows)")
+    check_norm(d40[idx], r40["dW_rows"], TOL_GRAD, f"{tag} dW after 40 passes (sampled rows)")
     assert abs(np.linalg.norm(d40.astype(np.float64)) / r40["dW_norm"] - 1) < TOL_GRAD
     assert np.abs(d40).max() <= r40["dW_absmax"] * (1 + 10 * TOL_GRAD)
 
@@ -181,23 +203,23 @@ def test_full_size_layers_that_end_at_their_iteration_cap(ctx, name, dist):
     check(Cg, g["C"], TOL_VAL, f"{tag} C at the cap")
     Wq = _whole_tensor_E_step(p, out, Cg, dist, tag)
     idx = np.array(g["sample_rows"])
-    check(Wq[idx], g["Wq_rows"], 10 * TOL_VAL, f"{tag} Wq rows at the oracle's C")
+    check_norm(Wq[idx], g["Wq_rows"], 10 * TOL_VAL, f"{tag} Wq rows at the oracle's C")
     assert abs(np.linalg.norm(Wq.astype(np.float64)) / g["Wq_norm"] - 1) < TOL_VAL
 
     bj = ctx.backward(G, binding.BWD_JFB)
     dj = bj["dW"].cpu().numpy()
     check(ctx.get_cotangents(k, d)[0], g["v"], TOL_GRAD, f"{tag} v")
-    check(dj[idx], g["dW_jfb_rows"], TOL_GRAD, f"{tag} JFB dW (sampled rows, first and last 64 rows)")
+    check_norm(dj[idx], g["dW_jfb_rows"], TOL_GRAD, f"{tag} JFB dW (sampled rows, first and last 64 rows)")
     assert abs(np.linalg.norm(dj.astype(np.float64)) / g["dW_jfb_norm"] - 1) < TOL_GRAD
     assert np.abs(dj).max() <= g["dW_jfb_absmax"] * (1 + 10 * TOL_GRAD)
     if k <= 16:
         check(dj, orc.backward(p.W, Cg, p.tau, dist, p.G, "jfb")["dW"], TOL_GRAD, f"{tag} JFB dW (whole tensor)")
     for r in g["implicit"]:
         bi = ctx.backward(G, binding.BWD_IMPLICIT, tol=0.0, max_iter=r["max_iter"], alpha=1.0)
-        assert bi["info"].iters == r["iters"] and bi["info"].alpha == r["alpha"], (tag, bi["info"], r["iters"], r["alpha"])
+        assert same_passes(bi["info"], r["iters"], r["alpha"]), (tag, bi["info"], r["iters"], r["alpha"])
         check(ctx.get_cotangents(k, d)[1], r["g"], TOL_GRAD, f"{tag} g after {r['max_iter']} passes")
         di = bi["dW"].cpu().numpy()
-        check(di[idx], r["dW_rows"], TOL_GRAD, f"{tag} dW after {r['max_iter']} passes (sampled rows)")
+        check_norm(di[idx], r["dW_rows"], TOL_GRAD, f"{tag} dW after {r['max_iter']} passes (sampled rows)")
         assert abs(np.linalg.norm(di.astype(np.float64)) / r["dW_norm"] - 1) < TOL_GRAD
         assert np.abs(di).max() <= r["dW_absmax"] * (1 + 10 * TOL_GRAD)
 
@@ -216,13 +238,13 @@ def sweep_gold():
 
 
 def _check_sweep_backwards(c, tag, rows, dj, dd, d30, i30, cot=None):
-    check(dj[rows], c["dW_jfb_rows"], TOL_GRAD, f"{tag} JFB dW rows")
+    check_norm(dj[rows], c["dW_jfb_rows"], TOL_GRAD, f"{tag} JFB dW rows")
     assert abs(np.linalg.norm(dj.astype(np.float64)) / c["dW_jfb_norm"] - 1) < TOL_GRAD, tag
-    check(dd[rows], c["dW_implicit_rows"], TOL_GRAD, f"{tag} dense dW rows")
+    check_norm(dd[rows], c["dW_implicit_rows"], TOL_GRAD, f"{tag} dense dW rows")
     assert abs(np.linalg.norm(dd.astype(np.float64)) / c["dW_implicit_norm"] - 1) < TOL_GRAD, tag
     r30 = c["implicit30"]
-    assert i30.iters == r30["iters"] and i30.alpha == r30["alpha"], (tag, i30, r30["iters"], r30["alpha"])
-    check(d30[rows], r30["dW_rows"], TOL_GRAD, f"{tag} dW rows after 30 passes")
+    assert same_passes(i30, r30["iters"], r30["alpha"]), (tag, i30, r30["iters"], r30["alpha"])
+    check_norm(d30[rows], r30["dW_rows"], TOL_GRAD, f"{tag} dW rows after 30 passes")
     assert abs(np.linalg.norm(d30.astype(np.float64)) / r30["dW_norm"] - 1) < TOL_GRAD, tag
     if cot is not None:
         check(cot["v"], c["v"], TOL_GRAD, f"{tag} v")
@@ -288,7 +310,9 @@ def test_resnet18_sweep_batched(sweep_gold, k, dist):
         # properties that hold at any size: convex combinations of the codebook, valid indices; the hard
         # assignments of every row against the float32 key at the batch's own C*
         assert Wq.min() >= Cg.min() - 1e-6 and Wq.max() <= Cg.max() + 1e-6, tag
-        assert np.array_equal(o["assign"].cpu().numpy(), orc.hard_assign_f32(p.W, Cg)), tag
+        _whole_tensor_E_step(p, o, Cg, dist, tag)
+        check(bj[t]["dW"].cpu().numpy(), orc.backward(p.W, Cg, p.tau, dist, p.G, "jfb")["dW"], TOL_GRAD,
+              f"{tag} JFB dW (whole tensor)")
         assert bd[t]["info"].converged, tag
         _check_sweep_backwards(c, tag, rows, bj[t]["dW"].cpu().numpy(), bd[t]["dW"].cpu().numpy(),
                                b30[t]["dW"].cpu().numpy(), b30[t]["info"])
