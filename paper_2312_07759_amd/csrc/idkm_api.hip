@@ -154,6 +154,7 @@ struct idkm_ctx {
     bool coop = false;
     bool coop_launch = false;  // IDKM_COOPERATIVE=1 launches the persistent kernels cooperatively
     int min_vec_per_thread = 4;  // vectors per thread before another workgroup is added (IDKM_MIN_VPT)
+    bool tree_exchange = true;   // two-level (die-local, then cross-die) exchange for full-device teams (IDKM_TREE=0: off)
     unsigned long long* xbuf = nullptr;  // exchange words: buf1 [2][PT][XLINE], then buf2 [2][XBCAST]
     size_t xbuf_words = 0;
     unsigned int seq_base = 0;
@@ -336,7 +337,8 @@ idkm_status launch_pass(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, hip
 }
 
 constexpr size_t XBUF1_WORDS = (size_t)2 * PT * XLINE;
-constexpr size_t XBUF_WORDS = XBUF1_WORDS + (size_t)2 * XBCAST;
+constexpr size_t XBUF3_WORDS = (size_t)2 * DIES * XLINE;  // two-level exchange: totals of the dies
+constexpr size_t XBUF_WORDS = XBUF1_WORDS + (size_t)2 * XBCAST + XBUF3_WORDS + DIES;
 constexpr size_t LDS_TILE_MAX = 144 * 1024;  // bytes of LDS a persistent workgroup may use for its tile
 
 struct PersistPlan {
@@ -476,6 +478,11 @@ idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PAr
     } else {
         pa.buf1 = ctx->xbuf;
         pa.buf2 = ctx->xbuf + XBUF1_WORDS;
+        pa.buf3 = pa.buf2 + (size_t)2 * XBCAST;
+        pa.tab = pa.buf3 + XBUF3_WORDS;
+        // a team that fills the device, one problem per launch: hop 1 stays inside each die (the explicit-Jacobian
+        // mode keeps the plain exchange, its one reduction ends in workgroup 0)
+        pa.tree = (ctx->tree_exchange && !ctx->sink && pp.grid >= TREE_MIN_G && pa.mode != BWD_DENSE) ? 1 : 0;
     }
     pa.seq_base = ctx->seq_base;
     pa.spin_limit = ctx->spin_limit;
@@ -539,6 +546,8 @@ idkm_status finish_persistent(idkm_ctx* ctx, idkm_info* info) {
     const PResult& c = ctx->res_on_device ? ctx->res_copy : *ctx->h_res;
     if (c.done != ctx->pending_id) return fail(ctx, IDKM_ERR_DEVICE, "a grid-wide wait hit its limit");
     if (kind == 1) {
+        for (int r = 0; r < c.nred && r < 16; ++r)
+            if (c.fin[r] != ctx->pending_id) return fail(ctx, IDKM_ERR_DEVICE, "a grid-wide wait hit its limit");
         int empty = 0, bad = c.nonfinite;
         for (int r = 0; r < 16; ++r) {
             empty += c.empty[r];
@@ -673,6 +682,7 @@ idkm_status idkm_create(idkm_ctx** out, int device_id) {
         c->coop = prop.cooperativeLaunch != 0;
     }
     if (const char* e = std::getenv("IDKM_COOPERATIVE")) c->coop_launch = (e[0] == '1');
+    if (const char* e = std::getenv("IDKM_TREE")) c->tree_exchange = (e[0] != '0');
     if (const char* e = std::getenv("IDKM_MIN_VPT")) {
         int v = std::atoi(e);
         if (v >= 1 && v <= 1024) c->min_vec_per_thread = v;

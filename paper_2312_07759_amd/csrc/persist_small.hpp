@@ -18,6 +18,18 @@
 // trip is needed; two buffers alternate by sequence parity.  Waits are bounded:
 // after spin_limit polls a workgroup raises Ctrl::abort_flag and leaves; the
 // others see the flag and leave too.  The grid must fit the device at once.
+//
+// Exchange of a full-device team (PArgs::tree; 64 or more workgroups, one problem per launch): the hardware hands
+// workgroup b to die b mod 8, and workgroups of one die share that die's L2.  A store that only has to reach the
+// L2 (workgroup scope) is seen by a device-scope load from the same die after about a third of a microsecond; a word
+// that crosses dies has to go through memory and takes more than twice as long.  So:
+//   hop 1  (inside a die)  workgroup b stores its partial sums with workgroup scope; workgroup b mod 8, the die's
+//          "leader", adds the up to 32 lines of its die in float64 in a fixed order;
+//   hop 2  (across dies)   the 8 leaders store their die's totals with device scope; EVERY workgroup reads those 8
+//          lines, adds them in the same fixed order and applies the O(k d) update itself, so that all hold the same
+//          new state and take the same stop decision without a third hop.
+// Every workgroup checks at the start of the launch that it runs on its leader's die (the die index is a hardware
+// register); one that does not stores with device scope instead, which is correct on any placement.
 #pragma once
 #include "common.hpp"
 #include "small_k.hpp"
@@ -27,6 +39,8 @@ namespace idkm {
 constexpr int PT = 256;      // threads per workgroup of the persistent kernels; also the largest grid
 constexpr int XLINE = 128;   // words reserved per workgroup in buf1 (K (D+1) <= 80, padded to a power of two)
 constexpr int XBCAST = 128;  // words reserved in buf2
+constexpr int DIES = 8;      // accelerator dies of the device (each with its own L2); workgroup b runs on die b mod 8
+constexpr int TREE_MIN_G = 64;  // smallest team that uses the two-level exchange
 constexpr int XDENSE = 32;   // the explicit-Jacobian mode is offered while its K D (K D + D + 1) sums fit this many words
 // Words between the lines of two workgroups in buf1 for a pass with NACC sums per workgroup: shapes of up to 32 sums
 // keep the short lines they were tuned with.
@@ -38,11 +52,17 @@ struct PResult {
     int iters, converged, nonfinite, halvings;
     double residual, alpha, vnorm;
     int empty[16], bad[16];  // per reducer, from the evaluation at C*
+    int nred;                // forward: reducers that report in fin[] (0: the workgroup that wrote `done` wrote everything)
+    unsigned int fin[16];    // forward: == launch id once reducer r has written its slice of the state
+    int pad_;
 };
 
 struct PArgs {
     unsigned long long* buf1;  // [2][PT][xline_of(NACC)] stamped partial sums, word (workgroup, accumulator)
     unsigned long long* buf2;  // [2][XBCAST] stamped broadcast values
+    unsigned long long* buf3;  // [2][DIES][XLINE] two-level exchange: stamped totals of each die
+    unsigned long long* tab;   // [DIES] two-level exchange: die index of each leader, stamped with the launch id
+    int tree;                  // two-level exchange (team of at least TREE_MIN_G workgroups, one problem per launch)
     unsigned int seq_base;     // sequence numbers seq_base+1 ... are used by this launch; seq_base+1 is its id
     unsigned int spin_limit;   // polls before a wait gives up
     int per;                   // vectors per workgroup tile
@@ -94,7 +114,23 @@ struct XShared {
     unsigned int bc[XBCAST];         // payloads of the broadcast words
     float own[XLINE];                // this workgroup's own partial sums (read back directly by a team of one)
     int abort;
+    // two-level exchange
+    int local;                       // this workgroup runs on its leader's die: its partial sums need only reach the L2
+    float stage[32 * NACC];          // leader: partial sums of its die's workgroups, [member][accumulator]
+    float stage2[DIES * NACC];       // totals of the dies, [die][accumulator]
+    double totd[NACC];               // grid totals
 };
+
+// Index of the accelerator die this wavefront runs on.
+__device__ __forceinline__ unsigned int die_id() {
+    unsigned int v;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(v));
+    return v & 0xfu;
+}
+// A stamped word that only a workgroup of the same die will read: it has to reach the die's L2, not memory.
+__device__ __forceinline__ void st_word_die(unsigned long long* p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
 
 // Row totals of accumulators [OFF, NACC) into xs.rpart, taken in power-of-two pieces, largest first (80 sums are a
 // piece of 64 and one of 16, not one of 128 padded with zeros: the exchange network costs about three instructions
@@ -140,7 +176,15 @@ __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int s
         const double s = (c4[0] + c4[1]) + (c4[2] + c4[3]);
         xs.own[tid] = (float)s;
         // a workgroup's words lie together: one store transaction per workgroup and pass
-        st_word(&pa.buf1[((size_t)(seq & 1u) * PT + pa.wg) * xline_of(NACC) + tid], pack_f(seq, (float)s));
+        unsigned long long* dst = &pa.buf1[((size_t)(seq & 1u) * PT + pa.wg) * xline_of(NACC) + tid];
+        if (!pa.tree)
+            st_word(dst, pack_f(seq, (float)s));
+        else if (pa.wg >= DIES) {  // (a leader reads its own sums from xs.own)
+            if (xs.local)
+                st_word_die(dst, pack_f(seq, (float)s));
+            else
+                st_word(dst, pack_f(seq, (float)s));
+        }
     }
     IDKM_SUB(3);
 }
@@ -262,6 +306,156 @@ __device__ __forceinline__ bool gather_bcast(const PArgs& pa, unsigned int seq, 
     }
     __syncthreads();
     return xs.abort == 0;
+}
+
+// ---------------------------------------------------------------- two-level exchange (PArgs::tree)
+
+// Start of a launch: the leaders publish the die they run on; every workgroup compares it with its own.
+// Leaves xs.local; returns false if the wait was abandoned.  Called by all threads; ends with a barrier.
+template <class XS>
+__device__ __forceinline__ bool tree_handshake(const PArgs& pa, XS& xs) {
+    if (threadIdx.x == 0) {
+        const unsigned int id = pa.seq_base + 1u, mine = die_id();
+        int local = 1;
+        if (pa.wg < DIES) {
+            st_word(&pa.tab[pa.wg], pack_u(id, mine));
+        } else {
+            unsigned long long w[1];
+            if (poll_words<1>(pa, pa.tab + (pa.wg % DIES), 0, id, w)) {
+                local = ((unsigned int)w[0] == mine) ? 1 : 0;
+            } else {
+                xs.abort = 1;
+                __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        xs.local = local;
+    }
+    __syncthreads();
+    return xs.abort == 0;
+}
+
+// hop 1, leader side (workgroups 0 .. DIES-1): totals of the partial sums of workgroups wg, wg + DIES, ... in
+// float64, members in increasing order (four interleaved chains), published as the die's line of buf3 and left in
+// xs.stage2 for this workgroup's own hop 2.  Returns false if the wait was abandoned (uniform over the workgroup).
+template <int NACC, class XS>
+__device__ __forceinline__ bool tree_die_totals(const PArgs& pa, unsigned int seq, XS& xs) {
+    constexpr int LINE = xline_of(NACC);
+    constexpr int NLD = (32 * NACC + PT - 1) / PT;  // loads per thread that cover 32 members
+    const int tid = threadIdx.x, x = pa.wg;
+    const int nmem = (pa.G - x + DIES - 1) / DIES;  // members of this die, the leader included; <= 32
+    const unsigned long long* line0 = pa.buf1 + ((size_t)(seq & 1u) * PT + x) * LINE;
+    unsigned long long w[NLD];
+    bool valid[NLD];
+#pragma unroll
+    for (int u = 0; u < NLD; ++u) {
+        const int f = tid + u * PT, mi = f / NACC;
+        valid[u] = mi >= 1 && mi < nmem;  // member 0 is this workgroup: its sums are in xs.own
+    }
+    bool aborted = false;
+    unsigned int spins = 0;
+    for (;;) {
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int f = tid + u * PT, mi = f / NACC, q = f - mi * NACC;
+            w[u] = valid[u] ? ld_word(line0 + (size_t)mi * DIES * LINE + q) : pack_f(seq, 0.f);
+        }
+        bool ok = true;
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) ok = ok && ((unsigned int)(w[u] >> 32) == seq);
+        if (ok) break;
+        ++spins;
+        if (spins > pa.spin_limit ||
+            ((spins & 31u) == 0u && __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u)) {
+            aborted = true;
+            break;
+        }
+    }
+    // (the barrier inside publish_partials lies before the stores to xs.own; this one orders them before the reads)
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < NLD; ++u) {
+        const int f = tid + u * PT, mi = f / NACC, q = f - mi * NACC;
+        if (f < 32 * NACC) xs.stage[f] = (mi == 0) ? xs.own[q] : __uint_as_float((unsigned int)w[u]);
+    }
+    if (aborted) {
+        xs.abort = 1;
+        __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (xs.abort) return false;
+    if (tid < NACC) {
+        double c4[4] = {0.0, 0.0, 0.0, 0.0};
+        int mi = 0;
+        for (; mi + 3 < nmem; mi += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) c4[u] += (double)xs.stage[(mi + u) * NACC + tid];
+        }
+        for (int u = 0; mi < nmem; ++mi, ++u) c4[u] += (double)xs.stage[mi * NACC + tid];
+        const float tot = (float)((c4[0] + c4[1]) + (c4[2] + c4[3]));
+        xs.stage2[x * NACC + tid] = tot;
+        st_word(&pa.buf3[((size_t)(seq & 1u) * DIES + x) * LINE + tid], pack_f(seq, tot));
+    }
+    return true;
+}
+
+// hop 2, every workgroup: waits for the totals of the DIES dies and adds them in float64 in a fixed order; the grid
+// totals are left in xs.totd.  Ends with a barrier.  Returns false if the wait was abandoned.
+template <int NACC, class XS>
+__device__ __forceinline__ bool tree_grid_totals(const PArgs& pa, unsigned int seq, XS& xs) {
+    constexpr int LINE = xline_of(NACC);
+    constexpr int NLD = (DIES * NACC + PT - 1) / PT;
+    const int tid = threadIdx.x;
+    const unsigned long long* base = pa.buf3 + (size_t)(seq & 1u) * DIES * LINE;
+    unsigned long long w[NLD];
+    bool valid[NLD];
+#pragma unroll
+    for (int u = 0; u < NLD; ++u) {
+        const int f = tid + u * PT, x = f / NACC;
+        valid[u] = f < DIES * NACC && x != pa.wg;  // a leader has left its own die's totals in xs.stage2 already
+    }
+    bool aborted = false;
+    unsigned int spins = 0;
+    for (;;) {
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int f = tid + u * PT, x = f / NACC, q = f - x * NACC;
+            w[u] = valid[u] ? ld_word(base + (size_t)x * LINE + q) : pack_f(seq, 0.f);
+        }
+        bool ok = true;
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) ok = ok && ((unsigned int)(w[u] >> 32) == seq);
+        if (ok) break;
+        ++spins;
+        if (spins > pa.spin_limit ||
+            ((spins & 31u) == 0u && __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u)) {
+            aborted = true;
+            break;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < NLD; ++u)
+        if (valid[u]) xs.stage2[tid + u * PT] = __uint_as_float((unsigned int)w[u]);
+    if (aborted) {
+        xs.abort = 1;
+        __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (xs.abort) return false;
+    if (tid < NACC) {
+        double t[DIES];
+#pragma unroll
+        for (int x = 0; x < DIES; ++x) t[x] = (double)xs.stage2[x * NACC + tid];
+        xs.totd[tid] = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+    }
+    __syncthreads();
+    return true;
+}
+
+// Both hops after publish_partials: grid totals of the NACC sums in xs.totd, in every workgroup.
+template <int NACC, class XS>
+__device__ __forceinline__ bool tree_totals(const PArgs& pa, unsigned int seq, XS& xs) {
+    if (pa.wg < DIES && !tree_die_totals<NACC>(pa, seq, xs)) return false;
+    return tree_grid_totals<NACC>(pa, seq, xs);
 }
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -478,8 +672,37 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     __syncthreads();
     const double tol = pa.tol;
     const int max_iter = pa.max_iter;
+    if (pa.tree && !tree_handshake(pa, xs)) return;
     // reducer r is workgroup r; with fewer than R workgroups the first ones take several slices in turn
     unsigned int seq = pa.seq_base;
+
+    // Centre update of the whole codebook (Alg. 1) and the stop test from grid totals every workgroup holds (a team
+    // of one, or the two-level exchange): tot(i) is total i of the K (D+1) sums.  Wavefront 0; lane 0 decides.
+    auto update_all = [&](auto tot) {
+        double df2 = 0.0;
+        if (tid < KD) {
+            const int j = tid / D, rr = tid - j * D;
+            const double n = tot(j * ACCW), sv = tot(j * ACCW + 1 + rr);
+            const double cold = s_Cd[tid];
+            double cnew = (n > 0.0) ? fast_div_d(sv, n) : cold;
+            if (!(n >= 0.0) || !(fabs(sv) <= 1.7e308) || !(fabs(cnew) <= 1.7e308)) cnew = __builtin_nan("");
+            s_Cd[tid] = cnew;
+            const float cn = (float)cnew;
+            const double df = (double)cn - (double)s_Cf[tid];
+            df2 = df * df;
+            s_Cf[tid] = cn;
+        }
+        const double r2 = first_lanes_sum_d_dpp<KD>(df2);
+        if (tid == 0) {
+            s_iters += 1;
+            s_res = r2;  // squared; the root is taken once, when the solve is over
+            const bool bad = !(r2 <= 1.7e308);
+            if (bad) s_bad = 1;
+            const bool conv = r2 < tol * tol;
+            s_conv = conv ? 1 : 0;
+            if (conv || bad || s_iters >= max_iter) s_done = 1;
+        }
+    };
 
     float acc[NACC];
     while (!s_done) {
@@ -493,31 +716,15 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
             // a team of one has no exchange: its partial sums (xs.own, the float32 words it would have published)
             // are the totals, and the whole codebook is updated here
             __syncthreads();
-            if (tid < 64) {
-                double df2 = 0.0;
-                if (tid < KD) {
-                    const int j = tid / D, rr = tid - j * D;
-                    const double n = (double)xs.own[j * ACCW], sv = (double)xs.own[j * ACCW + 1 + rr];
-                    const double cold = s_Cd[tid];
-                    double cnew = (n > 0.0) ? fast_div_d(sv, n) : cold;
-                    if (!(n >= 0.0) || !(fabs(sv) <= 1.7e308) || !(fabs(cnew) <= 1.7e308)) cnew = __builtin_nan("");
-                    s_Cd[tid] = cnew;
-                    const float cn = (float)cnew;
-                    const double df = (double)cn - (double)s_Cf[tid];
-                    df2 = df * df;
-                    s_Cf[tid] = cn;
-                }
-                const double r2 = first_lanes_sum_d_dpp<KD>(df2);
-                if (tid == 0) {
-                    s_iters += 1;
-                    s_res = r2;
-                    const bool bad = !(r2 <= 1.7e308);
-                    if (bad) s_bad = 1;
-                    const bool conv = r2 < tol * tol;
-                    s_conv = conv ? 1 : 0;
-                    if (conv || bad || s_iters >= max_iter) s_done = 1;
-                }
+            if (tid < 64) update_all([&](int i) { return (double)xs.own[i]; });
+        } else if (pa.tree) {
+            if (wg < DIES) {
+                if (!tree_die_totals<NACC>(pa, seq, xs)) return;
+                IDKM_STAMP(3);
             }
+            if (!tree_grid_totals<NACC>(pa, seq, xs)) return;
+            IDKM_STAMP(4);
+            if (tid < 64) update_all([&](int i) { return xs.totd[i]; });
         } else {
         for (int r = wg; r < R; r += pa.G) {
             if (!reduce_slice<NACC, WPR>(pa, seq, r * WPR, xs)) return;
@@ -589,6 +796,47 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     any_tile_pass<K, D, DIST, PASS_FIN, SHARED, GLOBALW>(a, pa, s_w, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
     ++seq;
     publish_partials<NACC>(pa, seq, acc, xs);
+    if (pa.tree) {
+        // only workgroup 0 needs these totals: it writes the state and, last, the word that says the launch ran to
+        // its end; the other leaders add up their die and leave, everybody else has left already
+        if (wg < DIES && !tree_die_totals<NACC>(pa, seq, xs)) return;
+        if (wg != 0) return;
+        if (!tree_grid_totals<NACC>(pa, seq, xs)) return;
+        {
+            if (tid < KD) {
+                const int j = tid / D, rr = tid - j * D;
+                const double n = xs.totd[j * ACCW], s = xs.totd[j * ACCW + 1 + rr];
+                const double cst = (double)s_Cf[tid];
+                const double f = (n > 0.0) ? fast_div_d(s, n) : cst;
+                a.Cd[tid] = cst;
+                a.Cf[tid] = s_Cf[tid];
+                a.Fd[tid] = f;
+                a.Ff[tid] = (float)f;
+                if (rr == 0) a.nd[j] = n;
+                if (a.C_out) a.C_out[tid] = s_Cf[tid];
+            }
+            if (tid == 0) {
+                int empty = 0, bad = 0;
+                for (int j = 0; j < K; ++j) {
+                    const double n = xs.totd[j * ACCW];
+                    if (!(n > 0.0)) empty++;
+                    if (!(n >= 0.0)) bad = 1;
+                    for (int rr = 0; rr < D; ++rr)
+                        if (!(fabs(xs.totd[j * ACCW + 1 + rr]) <= 1.7e308)) bad = 1;
+                }
+                PResult* o = pa.out;
+                o->empty[0] = empty;
+                o->bad[0] = bad;
+                o->nred = 0;
+                o->iters = s_iters;
+                o->residual = sqrt(s_res);
+                o->converged = s_conv;
+                o->nonfinite = s_bad;
+                o->done = pa.seq_base + 1u;
+            }
+        }
+        return;
+    }
     for (int r = wg; r < R; r += pa.G) {
         if (!reduce_slice<NACC, WPR>(pa, seq, r * WPR, xs)) return;
         if (tid < KPR * D) {
@@ -614,11 +862,15 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
             }
             pa.out->empty[r] = empty;
             pa.out->bad[r] = bad;
+            // this reducer's slice of the state is written: the host takes the launch as complete only when every
+            // reducer has said so (a reducer that gives up its wait in this last stage never does)
+            pa.out->fin[r] = pa.seq_base + 1u;
         }
         __syncthreads();
     }
     if (wg == pa.G - 1 && tid == 0) {
         PResult* o = pa.out;
+        o->nred = R;
         o->iters = s_iters;
         o->residual = sqrt(s_res);
         o->converged = s_conv;
@@ -689,6 +941,9 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         s_res = 0.0;
     }
     __syncthreads();
+    // (the explicit-Jacobian mode keeps the plain exchange: its one reduction is solved by workgroup 0)
+    const bool tree = pa.tree && mode != BWD_DENSE;
+    if (pa.tree && !tree_handshake(pa, xs)) return;
     unsigned int seq = pa.seq_base;
 
     float acc[KD];
@@ -769,6 +1024,23 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     any_tile_pass<K, D, DIST, PASS_B1, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
     ++seq;
     publish_partials<KD>(pa, seq, acc, xs);
+    if (tree) {
+        // every workgroup holds the whole of v and starts the solve at g = v itself
+        if (!tree_totals<KD>(pa, seq, xs)) return;
+        if (tid < 64) {
+            double v2 = 0.0;
+            if (tid < KD) {
+                const double v = xs.totd[tid];
+                s_v[tid] = v;
+                s_g[tid] = v;
+                v2 = v * v;
+                xs.bc[tid] = __float_as_uint((float)(v * s_rn[tid / D]));
+            }
+            v2 = first_lanes_sum_d_dpp<KD>(v2);
+            if (tid < R) xs.bc[KD + tid] = (tid == 0) ? __float_as_uint((float)v2) : 0u;
+        }
+        __syncthreads();
+    } else {
     for (int r = wg; r < R; r += pa.G) {
         if (!reduce_slice<KD, WPR>(pa, seq, r * WPR, xs)) return;
         if (tid < 64) {
@@ -791,7 +1063,8 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         }
     }
     }
-    if (!gather_bcast<KD, WPR, KD>(pa, seq, NB, !dense_done, xs)) return;
+    }
+    if (!(tree && !dense_done) && !gather_bcast<KD, WPR, KD>(pa, seq, NB, !dense_done, xs)) return;
     if (tid < KD) {
         s_Hs[tid] = __uint_as_float(xs.bc[tid]);
         s_Hv[tid] = s_Hs[tid];
@@ -815,15 +1088,21 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         publish_partials<KD>(pa, seq, acc, xs);
         IDKM_STAMP(2);
         const double alpha = s_alpha;
-        if (pa.G == 1) {
-            // a team of one has no exchange: its partial sums (xs.own) are the totals; the whole of g is updated
-            // here and the step norm goes where the decision below expects the reducers' parts
-            __syncthreads();
+        if (pa.G == 1 || tree) {
+            // a team of one has no exchange: its partial sums (xs.own) are the totals; with the two-level exchange
+            // every workgroup receives the totals (xs.totd).  Either way the whole of g is updated here and the step
+            // norm goes where the decision below expects the reducers' parts
+            if (tree) {
+                if (!tree_totals<KD>(pa, seq, xs)) return;
+            } else {
+                __syncthreads();
+            }
             if (tid < 64) {
                 double d2 = 0.0;
                 if (tid < KD) {
                     const double g = s_g[tid];
-                    const double gn = alpha * (s_v[tid] + (double)xs.own[tid]) + (1.0 - alpha) * g;
+                    const double u = tree ? xs.totd[tid] : (double)xs.own[tid];
+                    const double gn = alpha * (s_v[tid] + u) + (1.0 - alpha) * g;
                     const double df = gn - g;
                     d2 = df * df;
                     s_g[tid] = gn;
@@ -917,7 +1196,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
 
     // B3: dW = direct + (dF/dW)^T g
     any_tile_pass<K, D, DIST, PASS_B3, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, reinterpret_cast<float(&)[1]>(acc[0]));
-    if (dense_done) {
+    if (dense_done || tree) {
         if (wg == 0 && tid < KD) {
             a.gd[tid] = s_g[tid];
             a.vd[tid] = s_v[tid];
