@@ -117,7 +117,7 @@ struct XShared {
     // two-level exchange
     int local;                       // this workgroup runs on its leader's die: its partial sums need only reach the L2
     float stage[32 * NACC];          // leader: partial sums of its die's workgroups, [member][accumulator]
-    float stage2[DIES * NACC];       // totals of the dies, [die][accumulator]
+    float stage2[DIES * (NACC < 8 ? 8 : NACC)];  // totals of the dies, [die][accumulator] (lines of 8 slots when NACC <= 8)
     double totd[NACC];               // grid totals
 };
 
@@ -159,8 +159,16 @@ __device__ __forceinline__ void publish_rows(const float (&acc)[NACC], XS& xs, i
 
 // hop 1, sender side: workgroup partial of every accumulator into this workgroup's line.
 template <int NACC, class XS>
+__device__ __forceinline__ void publish_waves(const PArgs& pa, unsigned int seq, const float (&acc)[NACC], XS& xs);
+template <int NACC, class XS>
 __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int seq, const float (&acc)[NACC], XS& xs) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    if constexpr (NACC <= 8) {
+        if (pa.tree) {
+            publish_waves<NACC>(pa, seq, acc, xs);
+            return;
+        }
+    }
     IDKM_SUB(0);
     publish_rows<NACC, 0>(acc, xs, lane, tid >> 4);
     IDKM_SUB(1);
@@ -451,11 +459,132 @@ __device__ __forceinline__ bool tree_grid_totals(const PArgs& pa, unsigned int s
     return true;
 }
 
-// Both hops after publish_partials: grid totals of the NACC sums in xs.totd, in every workgroup.
+
+// ---------------------------------------------------------------- two-level exchange, up to 8 sums per workgroup
+
+// The shapes whose passes leave at most 8 sums per workgroup (k = 2 and k = 4 with scalar weights in the forward loop, k d <= 8
+// in the backward passes) take the two-level exchange without a detour through LDS on the sending side: every
+// WAVEFRONT reduces its lanes' sums to one value each (the halving network inside rows of 16 lanes, then two row
+// swaps) and stores its own 8 words; the leader adds 4 wavefronts x up to 32 workgroups, again across lanes, and hop
+// 2 runs inside wavefront 0 of every workgroup.  Slot p of a line holds accumulator slot_acc(p) (the order in which
+// the halving network leaves them in the lanes); unused slots carry zeros.
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+__host__ __device__ constexpr int slot_acc(int p) { return (p & 1) * 4 + ((p >> 1) & 1) * 2 + ((p >> 2) & 1); }
+// x + (the value of the lane 16 rows... ) : sum over the four lanes l % 16 + 16 r of a wavefront, in every lane.
+// v_permlane16_swap exchanges the odd rows of its first operand with the even rows of its second, v_permlane32_swap
+// the upper half of the first with the lower half of the second; adding the two results pairs every lane with its
+// partner, and both partners add the same two numbers (in either order: the same sum).
+__device__ __forceinline__ float cross_row_sum(float x) {
+    u32x2_t s = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(s[0]) + __uint_as_float(s[1]);
+    s = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(s[0]) + __uint_as_float(s[1]);
+}
+__device__ __forceinline__ double cross_row_sum_d(double x) {
+    u32x2_t lo = __builtin_amdgcn_permlane16_swap((unsigned)__double2loint(x), (unsigned)__double2loint(x), false, false);
+    u32x2_t hi = __builtin_amdgcn_permlane16_swap((unsigned)__double2hiint(x), (unsigned)__double2hiint(x), false, false);
+    x = __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+    lo = __builtin_amdgcn_permlane32_swap((unsigned)__double2loint(x), (unsigned)__double2loint(x), false, false);
+    hi = __builtin_amdgcn_permlane32_swap((unsigned)__double2hiint(x), (unsigned)__double2hiint(x), false, false);
+    return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+}
+// Sum over the eight lanes that share l % 8 (lanes l, l + 8, ..., l + 56), in every lane, float64, fixed order.
+__device__ __forceinline__ double sum_over_lane_bits_3_to_5(double x) {
+    x += dpp_d<0x128, 0xf>(x);  // row_ror:8
+    return cross_row_sum_d(x);
+}
+
+// hop 1, sender side: every wavefront stores the totals of its lanes' sums as 8 stamped words.
+template <int NACC, class XS>
+__device__ __forceinline__ void publish_waves(const PArgs& pa, unsigned int seq, const float (&acc)[NACC], XS& xs) {
+    static_assert(NACC <= 8, "one 8-word piece per wavefront");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = (q < NACC) ? acc[q] : 0.f;
+    row_sums<8>(v, lane);  // lane l of a row: the row's total of accumulator slot_acc(l % 8)
+    const float tot = cross_row_sum(v[0]);
+    if (lane < 8) {
+        xs.own[wave * 8 + lane] = tot;
+        if (pa.wg >= DIES) {  // (a leader reads its own sums from xs.own)
+            unsigned long long* dst = &pa.buf1[((size_t)(seq & 1u) * PT + pa.wg) * 32 + wave * 8 + lane];
+            if (xs.local)
+                st_word_die(dst, pack_f(seq, tot));
+            else
+                st_word(dst, pack_f(seq, tot));
+        }
+    }
+}
+
+// hop 1, leader side: thread t adds the four wavefront words of slot t % 8 of member t / 8; the members of a
+// wavefront are added across lanes, the four wavefronts through LDS.  Publishes the die's line and keeps its float32
+// totals in xs.stage2[die][slot].  Returns false if the wait was abandoned.
+template <class XS>
+__device__ __forceinline__ bool tree8_die_totals(const PArgs& pa, unsigned int seq, XS& xs) {
+    const int tid = threadIdx.x, x = pa.wg, p = tid & 7, mi = tid >> 3;
+    const int nmem = (pa.G - x + DIES - 1) / DIES;
+    const bool valid = mi >= 1 && mi < nmem;
+    const unsigned long long* src = pa.buf1 + ((size_t)(seq & 1u) * PT + x + (size_t)mi * DIES) * 32 + p;
+    unsigned long long w[4];
+    bool aborted = false;
+    if (valid) aborted = !poll_words<4>(pa, src, 8, seq, w);
+    __syncthreads();  // the wavefronts' stores to xs.own lie before this barrier
+    double s = 0.0;
+    if (valid)
+        s = ((double)__uint_as_float((unsigned int)w[0]) + (double)__uint_as_float((unsigned int)w[1])) +
+            ((double)__uint_as_float((unsigned int)w[2]) + (double)__uint_as_float((unsigned int)w[3]));
+    else if (mi == 0)
+        s = ((double)xs.own[p] + (double)xs.own[8 + p]) + ((double)xs.own[16 + p] + (double)xs.own[24 + p]);
+    s = sum_over_lane_bits_3_to_5(s);  // the eight members of this wavefront
+    if ((tid & 63) < 8) xs.red2[(tid >> 6) * 8 + p] = s;
+    if (aborted) {
+        xs.abort = 1;
+        __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (xs.abort) return false;
+    if (tid < 8) {
+        const float tot = (float)((xs.red2[tid] + xs.red2[8 + tid]) + (xs.red2[16 + tid] + xs.red2[24 + tid]));
+        xs.stage2[x * 8 + tid] = tot;
+        st_word(&pa.buf3[((size_t)(seq & 1u) * DIES + x) * 32 + tid], pack_f(seq, tot));
+    }
+    return true;
+}
+
+// hop 2 inside wavefront 0 (the other wavefronts go straight to the caller's barrier): lane 8 x + p waits for slot p
+// of die x; the eight dies are added across lanes; the grid totals go to xs.totd[accumulator].  A leader's own die
+// is read from xs.stage2.  On an abandoned wait xs.abort is set.  No barrier inside.
+template <int NACC, class XS>
+__device__ __forceinline__ void tree8_grid_totals_wave0(const PArgs& pa, unsigned int seq, XS& xs) {
+    const int lane = threadIdx.x, x = lane >> 3, p = lane & 7;
+    const unsigned long long* src = pa.buf3 + ((size_t)(seq & 1u) * DIES + x) * 32 + p;
+    unsigned long long w[1];
+    double s;
+    if (x == pa.wg) {
+        s = (double)xs.stage2[x * 8 + p];
+    } else if (poll_words<1>(pa, src, 0, seq, w)) {
+        s = (double)__uint_as_float((unsigned int)w[0]);
+    } else {
+        s = 0.0;
+        xs.abort = 1;
+        __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    s = sum_over_lane_bits_3_to_5(s);
+    if (lane < 8 && slot_acc(p) < NACC) xs.totd[slot_acc(p)] = s;
+}
+
+// Both hops after publish_partials: grid totals of the NACC sums in xs.totd, in every workgroup; ends with a barrier.
 template <int NACC, class XS>
 __device__ __forceinline__ bool tree_totals(const PArgs& pa, unsigned int seq, XS& xs) {
-    if (pa.wg < DIES && !tree_die_totals<NACC>(pa, seq, xs)) return false;
-    return tree_grid_totals<NACC>(pa, seq, xs);
+    if constexpr (NACC <= 8) {
+        if (pa.wg < DIES && !tree8_die_totals(pa, seq, xs)) return false;
+        if (threadIdx.x < 64) tree8_grid_totals_wave0<NACC>(pa, seq, xs);
+        __syncthreads();
+        return xs.abort == 0;
+    } else {
+        if (pa.wg < DIES && !tree_die_totals<NACC>(pa, seq, xs)) return false;
+        return tree_grid_totals<NACC>(pa, seq, xs);
+    }
 }
 
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -718,13 +847,26 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
             __syncthreads();
             if (tid < 64) update_all([&](int i) { return (double)xs.own[i]; });
         } else if (pa.tree) {
-            if (wg < DIES) {
-                if (!tree_die_totals<NACC>(pa, seq, xs)) return;
-                IDKM_STAMP(3);
+            if constexpr (NACC <= 8) {
+                // hop 2 and the update stay inside wavefront 0: no barrier between them
+                if (wg < DIES) {
+                    if (!tree8_die_totals(pa, seq, xs)) return;
+                    IDKM_STAMP(3);
+                }
+                if (tid < 64) {
+                    tree8_grid_totals_wave0<NACC>(pa, seq, xs);
+                    IDKM_STAMP(4);
+                    if (!xs.abort) update_all([&](int i) { return xs.totd[i]; });
+                }
+            } else {
+                if (wg < DIES) {
+                    if (!tree_die_totals<NACC>(pa, seq, xs)) return;
+                    IDKM_STAMP(3);
+                }
+                if (!tree_grid_totals<NACC>(pa, seq, xs)) return;
+                IDKM_STAMP(4);
+                if (tid < 64) update_all([&](int i) { return xs.totd[i]; });
             }
-            if (!tree_grid_totals<NACC>(pa, seq, xs)) return;
-            IDKM_STAMP(4);
-            if (tid < 64) update_all([&](int i) { return xs.totd[i]; });
         } else {
         for (int r = wg; r < R; r += pa.G) {
             if (!reduce_slice<NACC, WPR>(pa, seq, r * WPR, xs)) return;
@@ -799,9 +941,17 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     if (pa.tree) {
         // only workgroup 0 needs these totals: it writes the state and, last, the word that says the launch ran to
         // its end; the other leaders add up their die and leave, everybody else has left already
-        if (wg < DIES && !tree_die_totals<NACC>(pa, seq, xs)) return;
-        if (wg != 0) return;
-        if (!tree_grid_totals<NACC>(pa, seq, xs)) return;
+        if constexpr (NACC <= 8) {
+            if (wg < DIES && !tree8_die_totals(pa, seq, xs)) return;
+            if (wg != 0) return;
+            if (tid < 64) tree8_grid_totals_wave0<NACC>(pa, seq, xs);
+            __syncthreads();
+            if (xs.abort) return;
+        } else {
+            if (wg < DIES && !tree_die_totals<NACC>(pa, seq, xs)) return;
+            if (wg != 0) return;
+            if (!tree_grid_totals<NACC>(pa, seq, xs)) return;
+        }
         {
             if (tid < KD) {
                 const int j = tid / D, rr = tid - j * D;
