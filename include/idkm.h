@@ -54,7 +54,8 @@ typedef enum {
 
 /* How the device work is scheduled.  Results are identical up to rounding order. */
 typedef enum {
-    IDKM_PATH_AUTO = 0,      /* persistent when the problem fits on chip, else stream */
+    IDKM_PATH_AUTO = 0,      /* persistent when the problem fits on chip, else stream; also stream when a persistent
+                                attempt could not run to its end (see idkm_set_spin_limit) */
     IDKM_PATH_STREAM = 1,    /* one kernel launch per pass over W */
     IDKM_PATH_PERSISTENT = 2 /* one launch per solve, W held in LDS, one grid-wide exchange per pass */
 } idkm_path;
@@ -97,8 +98,10 @@ idkm_status idkm_set_matrix_cores(idkm_ctx* ctx, int32_t enable);
  * `bytes` send smaller layers that way (test support, comparisons). */
 idkm_status idkm_set_tile_limit(idkm_ctx* ctx, int64_t bytes);
 /* Bound of every device-side wait of the persistent kernels, in polls (default 2^20, about a second).  When a
- * wait expires all workgroups leave the kernel and the call returns IDKM_ERR_DEVICE; the context stays usable.
- * A limit of 0 makes the first unsuccessful poll give up (used to exercise that path). */
+ * wait expires all workgroups leave the kernel.  Under IDKM_PATH_AUTO the call is then answered by the stream path
+ * (a new launch from the host; idkm_info.path says IDKM_PATH_STREAM), and so is a call whose persistent grid would
+ * not be resident at once; under an explicit IDKM_PATH_PERSISTENT the call returns IDKM_ERR_DEVICE.  The context
+ * stays usable either way.  A limit of 0 makes the first unsuccessful poll give up (used to exercise that path). */
 idkm_status idkm_set_spin_limit(idkm_ctx* ctx, uint32_t polls);
 /* Test support.  The words that cross workgroups are stamped with 32-bit sequence numbers that the context counts up
  * over its lifetime (one per exchange of the persistent kernels, one per launch of the stream path); shortly before

@@ -381,6 +381,12 @@ class Batch:
             if st != IDKM_OK:
                 raise IdkmError(st, "idkm_set_path failed")
 
+    def context_set_spin_limit(self, i: int, polls: int):
+        """idkm_set_spin_limit on the i-th layer's context."""
+        st = self._lib.idkm_set_spin_limit(self._lib.idkm_batch_context(self._h, int(i)), int(polls))
+        if st != IDKM_OK:
+            raise IdkmError(st, "idkm_set_spin_limit failed")
+
     def _finish(self, st, statuses, strict):
         if st != IDKM_OK and strict:
             raise IdkmError(st, self._lib.idkm_batch_last_error(self._h).decode())

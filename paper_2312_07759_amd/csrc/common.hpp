@@ -785,6 +785,7 @@ __device__ __forceinline__ void tail_b2(const Args& a, const double* tot) {
                 restart = 1;
             } else {
                 c->b_done = 1;
+                if (!finite) c->nonfinite = 1;  // every damping factor tried ended in a non-finite step
             }
         }
         s_restart = restart;

@@ -67,6 +67,7 @@ __global__ void k_init_forward(Args a, const float* C0, double tol, int max_iter
 __global__ void k_init_backward(Args a, int mode, double tol, int max_iter, double alpha, int basis) {
     Ctrl* c = a.ctrl;
     c->abort_flag = 0;
+    c->nonfinite = 0;  // (a forward on the persistent path does not pass through k_init_forward)
     c->b_done = 0;
     c->b_iters = 0;
     c->b_converged = 0;
@@ -629,7 +630,7 @@ idkm_status run_until_done(idkm_ctx* ctx, const Geometry& g, int pass, Args& a, 
 
 extern "C" {
 
-int32_t idkm_version(void) { return 100; }
+int32_t idkm_version(void) { return 200; }
 
 void idkm_limits(idkm_limits_t* out) {
     if (!out) return;
@@ -811,9 +812,20 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
         pa.tol = (double)tol;
         pa.max_iter = (int)max_iter;
         st = launch_persistent(ctx, pp, a, pa, (unsigned int)max_iter + 1u, s);
-        if (st != IDKM_OK) return st;
-        ctx->pending_kind = 1;
-        return ctx->defer_wait ? IDKM_OK : finish_persistent(ctx, info);
+        if (st == IDKM_OK) {
+            ctx->pending_kind = 1;
+            if (ctx->defer_wait) return IDKM_OK;
+            st = finish_persistent(ctx, info);
+        }
+        // Under IDKM_PATH_AUTO a persistent attempt that could not run to its end -- the grid was not co-resident
+        // (other work occupies compute units) or a bounded wait expired -- is answered by the stream path, which
+        // depends on nothing but its own launches; an explicit IDKM_PATH_PERSISTENT reports the error.
+        if (st != IDKM_ERR_DEVICE || ctx->path != IDKM_PATH_AUTO) return st;
+        ctx->err.clear();
+        a.C_out = nullptr;
+        a.A_out = nullptr;
+        a.Wq_out = nullptr;
+        a.assign_out = nullptr;
     }
 
     hipLaunchKernelGGL(k_init_forward, dim3(1), dim3(WG), 0, s, a, C0, (double)tol, (int)max_iter);
@@ -904,9 +916,13 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
             pa.mode = (int)mode;
             pa.alpha = 1.0;
             st = launch_persistent(ctx, ppd, a, pa, 1u, s);
-            if (st != IDKM_OK) return st;
-            ctx->pending_kind = 2;
-            return ctx->defer_wait ? IDKM_OK : finish_persistent(ctx, info);
+            if (st == IDKM_OK) {
+                ctx->pending_kind = 2;
+                if (ctx->defer_wait) return IDKM_OK;
+                st = finish_persistent(ctx, info);
+            }
+            if (st != IDKM_ERR_DEVICE || ctx->path != IDKM_PATH_AUTO) return st;
+            ctx->err.clear();  // as in idkm_forward: the stream path answers instead
         }
         // otherwise two launches whatever the path: (v, dF/dC*) + direct solve, then the final pass
         const size_t nacc = (size_t)kd * kd + (size_t)kd * ctx->d + kd;
@@ -958,9 +974,13 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
             pa.mode = (int)mode;
             pa.alpha = (double)alpha;
             st = launch_persistent(ctx, pp, a, pa, (unsigned int)ex, s);
-            if (st != IDKM_OK) return st;
-            ctx->pending_kind = 2;
-            return ctx->defer_wait ? IDKM_OK : finish_persistent(ctx, info);
+            if (st == IDKM_OK) {
+                ctx->pending_kind = 2;
+                if (ctx->defer_wait) return IDKM_OK;
+                st = finish_persistent(ctx, info);
+            }
+            if (st != IDKM_ERR_DEVICE || ctx->path != IDKM_PATH_AUTO) return st;
+            ctx->err.clear();  // as in idkm_forward: the stream path answers instead
         }
     }
     hipLaunchKernelGGL(k_init_backward, dim3(1), dim3(1), 0, s, a, (int)mode, (double)tol, (int)max_iter, (double)alpha,
@@ -1297,7 +1317,28 @@ idkm_status idkm_batch_forward(idkm_batch* b, const idkm_fwd_desc* layers, int32
         c->sink = nullptr;
     }
     const idkm_status launched = batch_launch(b, (hipStream_t)hip_stream);
-    return batch_collect(b, launched, n, infos, statuses);
+    idkm_status first = batch_collect(b, launched, n, infos, statuses);
+    if (first != IDKM_OK) {
+        // layers whose persistent solve could not run to its end are solved again, one by one, on the stream path
+        // (contexts left at IDKM_PATH_AUTO only)
+        first = IDKM_OK;
+        for (int i = 0; i < n; ++i) {
+            idkm_ctx* c = b->ctx[i];
+            const idkm_fwd_desc& L = layers[i];
+            if (statuses[i] == IDKM_ERR_DEVICE && c->path == IDKM_PATH_AUTO) {
+                c->path = IDKM_PATH_STREAM;
+                statuses[i] = idkm_forward(c, L.W, L.m, L.d, L.C0, L.k, L.tau, L.tol, L.max_iter, (idkm_dist)L.dist, L.C_out,
+                                           L.A_out, L.Wq_out, L.assign_out, &infos[i], hip_stream);
+                c->path = IDKM_PATH_AUTO;
+            }
+            if (statuses[i] != IDKM_OK && first == IDKM_OK) {
+                first = statuses[i];
+                b->err = "layer " + std::to_string(i) + ": " + c->err;
+            }
+        }
+        if (first == IDKM_OK) b->err.clear();
+    }
+    return first;
 }
 
 idkm_status idkm_batch_backward(idkm_batch* b, const idkm_bwd_desc* layers, int32_t n, idkm_info* infos,
@@ -1318,7 +1359,26 @@ idkm_status idkm_batch_backward(idkm_batch* b, const idkm_bwd_desc* layers, int3
         c->sink = nullptr;
     }
     const idkm_status launched = batch_launch(b, (hipStream_t)hip_stream);
-    return batch_collect(b, launched, n, infos, statuses);
+    idkm_status first = batch_collect(b, launched, n, infos, statuses);
+    if (first != IDKM_OK) {
+        first = IDKM_OK;  // as in idkm_batch_forward
+        for (int i = 0; i < n; ++i) {
+            idkm_ctx* c = b->ctx[i];
+            const idkm_bwd_desc& L = layers[i];
+            if (statuses[i] == IDKM_ERR_DEVICE && c->path == IDKM_PATH_AUTO) {
+                c->path = IDKM_PATH_STREAM;
+                statuses[i] = idkm_backward(c, L.dWq, (idkm_bwd_mode)L.mode, L.tol, L.max_iter, L.alpha, L.dW_out, &infos[i],
+                                            hip_stream);
+                c->path = IDKM_PATH_AUTO;
+            }
+            if (statuses[i] != IDKM_OK && first == IDKM_OK) {
+                first = statuses[i];
+                b->err = "layer " + std::to_string(i) + ": " + c->err;
+            }
+        }
+        if (first == IDKM_OK) b->err.clear();
+    }
+    return first;
 }
 
 idkm_status idkm_step_F(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, const float* C, int32_t k, float tau,

@@ -649,10 +649,12 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
             }
             if (!done && !diverged && attempt >= max_iter) done = true;
             if (diverged) {
-                if (s_halv < 6)
+                if (s_halv < 6) {
                     restart = true;
-                else
+                } else {
                     done = true;
+                    if (!(dn <= 1.7e308)) s_bad = 1;  // every damping factor tried ended in a non-finite step
+                }
             }
             s_iters += 1;
             s_res = dn;

@@ -41,6 +41,14 @@ constexpr int XLINE = 128;   // words reserved per workgroup in buf1 (K (D+1) <=
 constexpr int XBCAST = 128;  // words reserved in buf2
 constexpr int DIES = 8;      // accelerator dies of the device (each with its own L2); workgroup b runs on die b mod 8
 constexpr int TREE_MIN_G = 64;  // smallest team that uses the two-level exchange
+#ifndef IDKM_HOP2_PIPE
+#define IDKM_HOP2_PIPE 1
+#endif
+#ifndef IDKM_HOP2_SLEEP
+#define IDKM_HOP2_SLEEP 5
+#endif
+constexpr int HOP2_PIPE = IDKM_HOP2_PIPE;    // loads in flight while waiting for the dies' totals
+constexpr int HOP2_SLEEP = IDKM_HOP2_SLEEP;  // s_sleep argument (units of 64 cycles) between their issue
 constexpr int XDENSE = 32;   // the explicit-Jacobian mode is offered while its K D (K D + D + 1) sums fit this many words
 // Words between the lines of two workgroups in buf1 for a pass with NACC sums per workgroup: shapes of up to 32 sums
 // keep the short lines they were tuned with.
@@ -214,6 +222,35 @@ __device__ __forceinline__ bool poll_words(const PArgs& pa, const unsigned long 
         ++spins;
         if (spins > pa.spin_limit ||
             ((spins & 31u) == 0u && __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u))
+            return false;
+    }
+}
+
+// Bounded wait for ONE stamped word with PIPE loads in flight, issued SLEEP x 64 cycles apart: a load that has to go
+// to memory returns after more than half a microsecond, so with one load at a time a word that lands just after a load
+// was issued is seen a whole round trip later; with staggered loads the next one is at most a fraction of that away.
+template <int PIPE, int SLEEP>
+__device__ __forceinline__ bool poll_word_staggered(const PArgs& pa, const unsigned long long* src, unsigned int seq,
+                                                    unsigned long long& out) {
+    unsigned long long w[PIPE];
+#pragma unroll
+    for (int i = 0; i < PIPE; ++i) {
+        w[i] = ld_word(src);
+        if (i + 1 < PIPE) __builtin_amdgcn_s_sleep(SLEEP);
+    }
+    unsigned int spins = 0;
+    for (;;) {
+#pragma unroll
+        for (int i = 0; i < PIPE; ++i) {
+            if ((unsigned int)(w[i] >> 32) == seq) {
+                out = w[i];
+                return true;
+            }
+            w[i] = ld_word(src);
+        }
+        spins += PIPE;
+        if (spins > pa.spin_limit ||
+            ((spins & 31u) < (unsigned)PIPE && __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u))
             return false;
     }
 }
@@ -562,7 +599,7 @@ __device__ __forceinline__ void tree8_grid_totals_wave0(const PArgs& pa, unsigne
     double s;
     if (x == pa.wg) {
         s = (double)xs.stage2[x * 8 + p];
-    } else if (poll_words<1>(pa, src, 0, seq, w)) {
+    } else if (HOP2_PIPE > 1 ? poll_word_staggered<HOP2_PIPE, HOP2_SLEEP>(pa, src, seq, w[0]) : poll_words<1>(pa, src, 0, seq, w)) {
         s = (double)__uint_as_float((unsigned int)w[0]);
     } else {
         s = 0.0;
@@ -1308,10 +1345,12 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
             }
             if (!done && !diverged && attempt >= max_iter) done = true;
             if (diverged) {
-                if (s_halv < 6)
+                if (s_halv < 6) {
                     restart = true;
-                else
+                } else {
                     done = true;
+                    if (!(dn <= 1.7e308)) s_bad = 1;  // every damping factor tried ended in a non-finite step
+                }
             }
             IDKM_STAMP(5);
             s_iters += 1;

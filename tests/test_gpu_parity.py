@@ -310,6 +310,65 @@ def test_an_expired_device_wait_is_reported_and_the_context_stays_usable(ctx):
         ctx.set_path(binding.PATH_AUTO)
 
 
+@pytest.mark.parametrize("kind", ["one call", "batched"])
+def test_an_expired_wait_is_answered_by_the_stream_path_under_auto(ctx, kind):
+    """A persistent solve that cannot run to its end (here: every device-side wait gives up at its first unsuccessful
+    poll; all kernels still exit normally) is solved again on the stream path when the path is AUTO."""
+    p = wl.make_problem("C3", wl.DIST_SQL2, m=300_007)   # 256 workgroups: the exchange has somebody to wait for
+    Wd, C0d, Gd = dev(p.W), dev(p.C0), dev(p.G)
+    ref = orc.soft_kmeans(p.W, p.C0, p.tau, p.tol, p.max_iter, wl.DIST_SQL2)
+    if kind == "one call":
+        ctx.set_spin_limit(0)
+        try:
+            out = ctx.forward(Wd, C0d, p.tau, p.tol, p.max_iter, wl.DIST_SQL2)
+            bj = ctx.backward(Gd, binding.BWD_JFB)
+            bi = ctx.backward(Gd, binding.BWD_IMPLICIT, tol=0.0, max_iter=20)
+        finally:
+            ctx.set_spin_limit(1 << 20)
+    else:
+        b = binding.Batch(2, 0)
+        try:
+            for i in range(2):
+                b.context_set_spin_limit(i, 0)
+            o2 = b.forward([(Wd, C0d), (Wd, C0d)], p.tau, p.tol, p.max_iter, wl.DIST_SQL2)
+            j2 = b.backward([Gd, Gd], binding.BWD_JFB)
+            i2 = b.backward([Gd, Gd], binding.BWD_IMPLICIT, tol=0.0, max_iter=20)
+            assert all(x["status"] == 0 for x in o2 + j2 + i2)
+            out, bj, bi = o2[1], j2[1], i2[1]
+        finally:
+            b.close()
+    assert out["info"].path == binding.PATH_STREAM and bj["info"].path == binding.PATH_STREAM
+    assert bi["info"].path == binding.PATH_STREAM and bi["info"].iters == 20
+    Cg = out["C"].cpu().numpy()
+    assert rel(Cg, ref["C"]) < TOL_VAL
+    assert rel(bj["dW"].cpu().numpy(), orc.backward(p.W, Cg, p.tau, wl.DIST_SQL2, p.G, "jfb")["dW"]) < TOL_GRAD
+    ri = orc.backward(p.W, Cg, p.tau, wl.DIST_SQL2, p.G, "implicit", tol=0.0, max_iter=20)
+    assert rel(bi["dW"].cpu().numpy(), ri["dW"]) < TOL_GRAD
+
+
+@pytest.mark.parametrize("path", ["stream", "persistent"])
+def test_a_cotangent_that_overflows_is_reported_as_non_finite(ctx, path):
+    """Upstream gradients so large that float32 overflows somewhere in the backward (in v, or only in the (dF/dC)^T
+    passes, for every damping factor the restart rule tries): the call must say so -- IDKM_ERR_NONFINITE -- and never
+    return IDKM_OK with a gradient that holds NaN or Inf."""
+    W, C0, _ = _case(20_011, 1, 4, seed=77)
+    ctx.set_path(binding.PATH_STREAM if path == "stream" else binding.PATH_PERSISTENT)
+    refused = 0
+    try:
+        ctx.forward(dev(W), dev(C0), 0.002, 1e-6, 50, wl.DIST_SQL2)
+        for scale in (1e28, 1e30, 1e32, 1e33, 1e34, 1e35, 1e36, 1e37):
+            G = (np.random.default_rng(5).standard_normal(W.shape) * scale).astype(np.float32)
+            try:
+                r = ctx.backward(dev(G), binding.BWD_IMPLICIT, tol=1e-6, max_iter=50, alpha=1.0)
+                assert torch.isfinite(r["dW"]).all(), (scale, r["info"])
+            except binding.IdkmError as e:
+                assert e.status == 4, (scale, e)
+                refused += 1
+    finally:
+        ctx.set_path(binding.PATH_AUTO)
+    assert refused >= 1
+
+
 def test_error_paths(ctx):
     d = wl.DIST_SQL2
     W = dev(np.zeros((8, 1), dtype=np.float32))
