@@ -957,15 +957,20 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     }
 
     PersistPlan pp;
-    // the minimal-residual solve keeps its O(k d R) state in one workgroup's tail: stream path only
-    const bool persistent = mode != IDKM_BWD_GMRES && ctx->path != IDKM_PATH_STREAM &&
-                            plan_persistent(ctx, true, &pp, true, dWq);
+    bool persistent = ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &pp, true, dWq);
+    // The minimal-residual solve keeps O(k d R) state.  Inside the persistent kernel every workgroup holds all of it,
+    // which takes a team where every workgroup receives the grid totals (one workgroup, or the two-level exchange of a
+    // full-device team) and k d <= 16; everything else runs it in the pass tail of the stream path.
+    if (persistent && mode == IDKM_BWD_GMRES)
+        persistent = !pp.lane && ctx->k * ctx->d <= 16 &&
+                     (pp.grid == 1 || (ctx->tree_exchange && !ctx->sink && pp.grid >= TREE_MIN_G));
     if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
         return fail(ctx, IDKM_ERR_UNSUPPORTED, mode == IDKM_BWD_GMRES
-                        ? "IDKM_BWD_GMRES runs on the stream path only"
+                        ? "IDKM_BWD_GMRES on the persistent path needs k in {2,4,8,16}, k*d <= 16 and a team of one or of at least 64 workgroups"
                         : "the persistent path needs k <= 512, d <= 4 and the tiles of W and dWq to fit in LDS");
     if (persistent) {
-        const uint64_t ex = 1ull + (mode == IDKM_BWD_IMPLICIT ? (uint64_t)max_iter * 7ull : 0ull);
+        const uint64_t ex = 1ull + (mode == IDKM_BWD_IMPLICIT ? (uint64_t)max_iter * 7ull
+                                                               : (mode == IDKM_BWD_GMRES ? (uint64_t)max_iter + 3ull : 0ull));
         if (ex < 0x7fffffffull) {
             PArgs pa;
             std::memset(&pa, 0, sizeof(pa));
@@ -973,6 +978,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
             pa.max_iter = (int)max_iter;
             pa.mode = (int)mode;
             pa.alpha = (double)alpha;
+            pa.gm_basis = ctx->gmres_basis;
             st = launch_persistent(ctx, pp, a, pa, (unsigned int)ex, s);
             if (st == IDKM_OK) {
                 ctx->pending_kind = 2;

@@ -71,6 +71,7 @@ struct PArgs {
     unsigned long long* buf3;  // [2][DIES][XLINE] two-level exchange: stamped totals of each die
     unsigned long long* tab;   // [DIES] two-level exchange: die index of each leader, stamped with the launch id
     int tree;                  // two-level exchange (team of at least TREE_MIN_G workgroups, one problem per launch)
+    int gm_basis;              // backward, BWD_GMRES: longest Krylov basis before a restart
     unsigned int seq_base;     // sequence numbers seq_base+1 ... are used by this launch; seq_base+1 is its id
     unsigned int spin_limit;   // polls before a wait gives up
     int per;                   // vectors per workgroup tile
@@ -128,6 +129,15 @@ struct XShared {
     float stage2[DIES * (NACC < 8 ? 8 : NACC)];  // totals of the dies, [die][accumulator] (lines of 8 slots when NACC <= 8)
     double totd[NACC];               // grid totals
 };
+
+// Between LDS accesses of ONE wavefront where a lane reads what another lane wrote: the hardware runs a wavefront's
+// LDS instructions in order, but the compiler reasons per thread (it may forward a thread's own earlier load past
+// another lane's store, or move accesses); this keeps its memory operations in program order.  No instruction issued
+// beyond a wait for the outstanding LDS operations.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
 
 // Index of the accelerator die this wavefront runs on.
 __device__ __forceinline__ unsigned int die_id() {
@@ -597,6 +607,7 @@ __device__ __forceinline__ void tree8_grid_totals_wave0(const PArgs& pa, unsigne
     const unsigned long long* src = pa.buf3 + ((size_t)(seq & 1u) * DIES + x) * 32 + p;
     unsigned long long w[1];
     double s;
+    wave_lds_sync();  // (a leader's lanes 0 .. 7 have just written its own die's totals)
     if (x == pa.wg) {
         s = (double)xs.stage2[x * 8 + p];
     } else if (HOP2_PIPE > 1 ? poll_word_staggered<HOP2_PIPE, HOP2_SLEEP>(pa, src, seq, w[0]) : poll_words<1>(pa, src, 0, seq, w)) {
@@ -608,6 +619,7 @@ __device__ __forceinline__ void tree8_grid_totals_wave0(const PArgs& pa, unsigne
     }
     s = sum_over_lane_bits_3_to_5(s);
     if (lane < 8 && slot_acc(p) < NACC) xs.totd[slot_acc(p)] = s;
+    wave_lds_sync();  // the caller's lanes read one another's totals
 }
 
 // Both hops after publish_partials: grid totals of the NACC sums in xs.totd, in every workgroup; ends with a barrier.
@@ -1066,6 +1078,176 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     }
 }
 
+// State of the minimal-residual (restarted GMRES) solve of (I - dF/dC*)^T g = v inside the persistent backward: every
+// workgroup of a team that receives the grid totals (a team of one, or the two-level exchange) keeps the whole of it
+// and takes every step itself, in float64, so that all workgroups hold the same iterate.  N = k d <= 16 unknowns.
+template <int N>
+struct GmState {
+    double Q[N + 1][N];   // orthonormal basis, row i = q_i
+    double H[N][N + 1];   // Hessenberg columns, rotated in place to triangular
+    double cs[N], sn[N], sv[N + 1], y[N], p[N + 1], w[N];
+    int phase, j, R, stall;
+    double beta;
+};
+
+// One step of that solve in wavefront 0 (all 64 lanes call it; lanes idx < N own element idx).  u(idx) = the grid
+// total of this pass: (dF/dC)^T applied to the vector the pass was run with -- basis vector q_j in phase 0, the
+// iterate g in phase 1.  Same steps, stop rule and counting as the stream path's pass tail: classical Gram-Schmidt
+// twice, Givens update of the least-squares problem, at the end of a cycle g += Q y and one pass for the true
+// residual r = v + (dF/dC)^T g - g, whose norm is held to tol ||v||.  Leaves the next pass's vector in hnext (lanes
+// < N; times 1/(tau n) and rounded to float32 by the caller) and returns 1 if the solve is over, else 0.
+// Lane 0 writes the result fields through the references.
+template <int N, class U>
+__device__ __forceinline__ int gmres_step(GmState<N>& gm, U u, const double* s_v, double* s_g, double tol, double vnorm,
+                                         int max_iter, int& s_iters, int& s_conv, int& s_bad, double& s_res,
+                                         double& hnext) {
+    const int lane = threadIdx.x;
+    wave_lds_sync();
+    const int R = __builtin_amdgcn_readfirstlane(gm.R);
+    const int phase = __builtin_amdgcn_readfirstlane(gm.phase);
+    int over = 0;
+    hnext = 0.0;
+    if (phase == 0) {
+        const int j = __builtin_amdgcn_readfirstlane(gm.j);
+        if (lane < N) gm.w[lane] = gm.Q[j][lane] - u(lane);
+        wave_lds_sync();
+        for (int round = 0; round < 2; ++round) {
+            // lane i <= j: h_i = q_i . w (its own row, element by element); then lane idx: w -= sum_i h_i q_i
+            if (lane <= j && lane < N + 1) {
+                double pr = 0.0;
+                for (int idx = 0; idx < N; ++idx) pr += gm.Q[lane][idx] * gm.w[idx];
+                gm.p[lane] = pr;
+                gm.H[j][lane] = round ? gm.H[j][lane] + pr : pr;
+            }
+            wave_lds_sync();
+            if (lane < N) {
+                double x = gm.w[lane];
+                for (int i = 0; i <= j; ++i) x -= gm.p[i] * gm.Q[i][lane];
+                gm.w[lane] = x;
+            }
+            wave_lds_sync();
+        }
+        int next = 0;  // 0 next basis vector, 1 cycle over: apply to g, 3 done
+        int nj_new = 0;
+        double scale = 0.0;
+        if (lane == 0) {
+            double w2 = 0.0;
+            for (int idx = 0; idx < N; ++idx) w2 += gm.w[idx] * gm.w[idx];
+            const double hn = sqrt(w2);
+            double* hcol = gm.H[j];
+            for (int i = 0; i < j; ++i) {
+                const double t0 = gm.cs[i] * hcol[i] + gm.sn[i] * hcol[i + 1];
+                hcol[i + 1] = -gm.sn[i] * hcol[i] + gm.cs[i] * hcol[i + 1];
+                hcol[i] = t0;
+            }
+            const double hj = hcol[j];
+            const double rr = sqrt(hj * hj + hn * hn);
+            const double cj = rr > 0.0 ? hj / rr : 1.0, sj = rr > 0.0 ? hn / rr : 0.0;
+            gm.cs[j] = cj;
+            gm.sn[j] = sj;
+            hcol[j] = rr;
+            gm.sv[j + 1] = -sj * gm.sv[j];
+            gm.sv[j] = cj * gm.sv[j];
+            const double est = fabs(gm.sv[j + 1]);
+            s_iters += 1;
+            s_res = est * est;
+            const bool finite = (w2 <= 1.7e308) && (rr <= 1.7e308);
+            const bool vanished = !(hn > 1e-14 * rr);
+            const bool last = (j + 1 >= R) || (s_iters + 1 >= max_iter);
+            if (!finite) {
+                s_bad = 1;
+                next = 3;
+            } else if (vanished || last || est <= 0.5 * tol * vnorm) {
+                const int nj = (rr > 0.0) ? j + 1 : j;
+                for (int i = nj - 1; i >= 0; --i) {
+                    double t0 = gm.sv[i];
+                    for (int l = i + 1; l < nj; ++l) t0 -= gm.H[l][i] * gm.y[l];
+                    gm.y[i] = t0 / gm.H[i][i];
+                }
+                gm.j = nj;
+                nj_new = nj;
+                next = 1;
+            } else {
+                gm.j = j + 1;
+                scale = 1.0 / hn;
+            }
+        }
+        wave_lds_sync();
+        // (what lane 0 decided travels in registers: the other lanes must not take their own stale view of gm.j)
+        next = __builtin_amdgcn_readfirstlane(next);
+        nj_new = __builtin_amdgcn_readfirstlane(nj_new);
+        scale = __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(scale)),
+                                 __builtin_amdgcn_readfirstlane(__double2loint(scale)));
+        if (next == 0) {
+            if (lane < N) {
+                const double q = gm.w[lane] * scale;
+                gm.Q[j + 1][lane] = q;
+                hnext = q;
+            }
+        } else if (next == 1) {
+            const int nj = nj_new;
+            if (lane < N) {
+                double g = s_g[lane];
+                for (int i = 0; i < nj; ++i) g += gm.y[i] * gm.Q[i][lane];
+                s_g[lane] = g;
+                hnext = g;
+            }
+            if (lane == 0) gm.phase = 1;
+        } else {
+            over = 1;
+        }
+        return over;
+    }
+    // phase 1: true residual at g
+    double r = 0.0;
+    if (lane < N) {
+        r = s_v[lane] + u(lane) - s_g[lane];
+        gm.Q[0][lane] = r;
+    }
+    wave_lds_sync();
+    int next = 2;  // 2 new cycle from the residual, 3 done
+    double scale = 0.0;
+    if (lane == 0) {
+        double r2 = 0.0;
+        for (int idx = 0; idx < N; ++idx) r2 += gm.Q[0][idx] * gm.Q[0][idx];
+        const double beta = sqrt(r2);
+        s_iters += 1;
+        s_res = r2;
+        if (!(r2 <= 1.7e308)) {
+            s_bad = 1;
+            next = 3;
+        } else if (beta <= tol * vnorm) {
+            s_conv = 1;
+            next = 3;
+        } else {
+            gm.stall = (beta > 0.95 * gm.beta) ? gm.stall + 1 : 0;
+            if (gm.stall >= 2 || s_iters + 2 > max_iter) next = 3;
+        }
+        if (next == 2) {
+            gm.beta = beta;
+            gm.phase = 0;
+            gm.j = 0;
+            gm.sv[0] = beta;
+            scale = 1.0 / beta;
+        }
+    }
+    wave_lds_sync();
+    next = __builtin_amdgcn_readfirstlane(next);
+    scale = __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(scale)),
+                             __builtin_amdgcn_readfirstlane(__double2loint(scale)));
+    if (next == 2) {
+        if (lane < N) {
+            const double q = r * scale;
+            gm.Q[0][lane] = q;
+            hnext = q;
+        }
+        return 0;
+    }
+    // done: the caller keeps h(g)/tau from the end of the cycle for the final pass
+    if (lane < N) hnext = s_g[lane];
+    return 1;
+}
+
 // Backward (Alg. 2 per-layer steps): v, the averaged fixed-point iteration of
 // Sec. 4.2 for g (skipped for JFB), and dW, in one launch.
 template <int K, int D, int DIST, bool SHARED, bool GLOBALW = false>
@@ -1086,6 +1268,9 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     __shared__ float s_Cf[KD], s_Hs[KD], s_Hv[KD], s_Ff[KD];
     __shared__ int s_done, s_iters, s_conv, s_attempt, s_grow, s_halv, s_bad, s_restart;
     __shared__ double s_alpha, s_prev, s_vnorm, s_res;
+    // minimal-residual solve (BWD_GMRES): offered for k d <= 16 to teams in which every workgroup receives the totals
+    constexpr bool HAS_GMRES = KD <= 16;
+    __shared__ GmState<HAS_GMRES ? KD : 1> gm;
 
     const int tid = threadIdx.x, wg = pa.wg;
     const int64_t base = (int64_t)wg * pa.per;
@@ -1266,6 +1451,39 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         }
     }
     __syncthreads();
+    if constexpr (HAS_GMRES) {
+        if (mode == BWD_GMRES && !s_done) {
+            // from g = 0: the first residual is v itself, the first basis vector v / ||v||  (every workgroup holds v)
+            if (tid < 64) {
+                double v2 = 0.0;
+                if (tid < KD) v2 = s_v[tid] * s_v[tid];
+                v2 = first_lanes_sum_d_dpp<KD>(v2);
+                v2 = __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(v2)),
+                                      __builtin_amdgcn_readfirstlane(__double2loint(v2)));
+                const double vn = sqrt(v2), inv = v2 > 0.0 ? 1.0 / vn : 0.0;
+                if (tid < KD) {
+                    const double q = s_v[tid] * inv;
+                    gm.Q[0][tid] = q;
+                    s_g[tid] = 0.0;
+                    s_Hs[tid] = (float)(q * s_rn[tid / D]);
+                }
+                if (tid == 0) {
+                    s_vnorm = v2;  // (the float64 norm of the float64 v, not the sum of float32 parts)
+                    gm.phase = 0;
+                    gm.j = 0;
+                    gm.stall = 0;
+                    gm.beta = vn;
+                    gm.sv[0] = vn;
+                    gm.R = pa.gm_basis < KD ? (pa.gm_basis < 1 ? 1 : pa.gm_basis) : KD;
+                    if (v2 == 0.0) {  // v = 0: g = 0 is the solution
+                        s_conv = 1;
+                        s_done = 1;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
 
     while (!s_done) {
         IDKM_STAMP(0);
@@ -1275,6 +1493,31 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         publish_partials<KD>(pa, seq, acc, xs);
         IDKM_STAMP(2);
         const double alpha = s_alpha;
+        if constexpr (HAS_GMRES) {
+            if (mode == BWD_GMRES) {
+                // (offered only where every workgroup receives the totals: a team of one, or the two-level exchange)
+                if (tree) {
+                    if (!tree_totals<KD>(pa, seq, xs)) return;
+                } else {
+                    __syncthreads();
+                }
+                if (tid < 64) {
+                    double hn;
+                    const double vn = sqrt(s_vnorm);
+                    int over;
+                    if (tree)
+                        over = gmres_step<KD>(gm, [&](int i) { return xs.totd[i]; }, s_v, s_g, tol, vn, max_iter, s_iters,
+                                              s_conv, s_bad, s_res, hn);
+                    else
+                        over = gmres_step<KD>(gm, [&](int i) { return (double)xs.own[i]; }, s_v, s_g, tol, vn, max_iter,
+                                              s_iters, s_conv, s_bad, s_res, hn);
+                    if (tid < KD) s_Hs[tid] = (float)(hn * s_rn[tid / D]);
+                    if (tid == 0 && over) s_done = 1;
+                }
+                __syncthreads();
+                continue;
+            }
+        }
         if (pa.G == 1 || tree) {
             // a team of one has no exchange: its partial sums (xs.own) are the totals; with the two-level exchange
             // every workgroup receives the totals (xs.totd).  Either way the whole of g is updated here and the step

@@ -140,7 +140,20 @@ def capped_layer(name, dist, out, stages=(50, 100, 150, 200), bwd_passes=(10, 50
     C = p.C0
     done = 0
     stopped = False
+    # the forward trajectory takes most of an hour at k = 256: every finished stage is kept beside the output (a file
+    # git ignores), so that an interrupted run continues from its last stage instead of starting over
+    ckpt = out + ".ckpt.json"
+    if os.path.exists(ckpt):
+        with open(ckpt) as f:
+            ck = json.load(f)
+        if ck["stages"] == list(stages) and ck["tau"] == p.tau and ck["m"] == p.cfg.m:
+            rec["C_at_stage"], rec["residual_at_stage"] = ck["C_at_stage"], ck["residual_at_stage"]
+            done = stages[len(rec["C_at_stage"]) - 1]
+            C = np.array(rec["C_at_stage"][-1], dtype=np.float64)
+            print(name, dist, "continuing after", done, "evaluations", flush=True)
     for s in stages:
+        if s <= done:
+            continue
         fw = orc.soft_kmeans(p.W, C, p.tau, p.tol, s - done, dist)
         C = fw["C"]
         done += fw["iters"]
@@ -151,6 +164,9 @@ def capped_layer(name, dist, out, stages=(50, 100, 150, 200), bwd_passes=(10, 50
         if fw["converged"]:
             stopped = True
             break
+        with open(ckpt, "w") as f:  # full precision: the next stage starts from these numbers
+            json.dump(dict(stages=list(stages), tau=p.tau, m=p.cfg.m, C_at_stage=rec["C_at_stage"],
+                           residual_at_stage=rec["residual_at_stage"]), f)
     rec.update(iters=done, converged=stopped, residual=rec["residual_at_stage"][-1], C=C.tolist())
     Wq = orc.soft_quantize(p.W, C, p.tau, dist)
     rec["Wq_rows"] = Wq[idx].tolist()

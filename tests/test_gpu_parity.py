@@ -451,6 +451,46 @@ def test_krylov_backward_solves_the_linear_system_of_the_implicit_gradient(ctx, 
         assert rel(r["dW"].cpu().numpy(), it["dW"].cpu().numpy()) < TOL_GRAD
 
 
+@pytest.mark.parametrize("dist", DISTS)
+@pytest.mark.parametrize("cfg,m", [("C1", None), ("C3", 300_007), ("C2", 100_003)], ids=["C1", "C3@300k", "C2@100k"])
+def test_krylov_backward_inside_the_persistent_kernel(ctx, cfg, m, dist):
+    """k d <= 16 with a team of one workgroup (C1) or a full-device team (two-level exchange): the whole minimal-residual
+    solve runs in one launch.  Held to the oracle's dense solve and to the stream path's pass count."""
+    p = wl.make_problem(cfg, dist, m=m)
+    Wd, C0d = dev(p.W), dev(p.C0)
+    out = ctx.forward(Wd, C0d, p.tau, p.tol, p.max_iter, dist)
+    Cg = out["C"].cpu().numpy()
+    G = p.G if p.G is not None else (2.0 * (orc.soft_quantize(p.W, Cg, p.tau, dist) - p.T)).astype(np.float32)
+    Gd = dev(G)
+    ref = orc.backward(p.W, Cg, p.tau, dist, G, "dense")
+    res = {}
+    for path in (binding.PATH_STREAM, binding.PATH_PERSISTENT):
+        ctx.set_path(path)
+        try:
+            r = ctx.backward(Gd, binding.BWD_GMRES, tol=1e-5, max_iter=200)
+        finally:
+            ctx.set_path(binding.PATH_AUTO)
+        assert r["info"].path == path
+        res[path] = (r["info"], r["dW"].cpu().numpy(), ctx.get_cotangents(p.cfg.k, p.cfg.d)[1])
+    (si, sdW, sg), (pi, pdW, pg) = res[binding.PATH_STREAM], res[binding.PATH_PERSISTENT]
+    kd = p.cfg.k * p.cfg.d
+    rho = float(np.abs(np.linalg.eigvals(orc.jacobian_C(Cg, p.W, p.tau, dist))).max())
+    if rho < 0.97:
+        # well conditioned: one exact cycle (+ the pass for the true residual) on either path
+        assert pi.converged and si.converged and abs(pi.iters - si.iters) <= 2, (si, pi)
+        assert pi.iters <= 2 * (kd + 1)
+    # (otherwise -- C2 with the squared energy, condition number about 1e5 -- the float32 operator decides after how
+    #  many restarts the true residual passes the test; both paths are held to the backward error below)
+    # backward error of the returned g, evaluated by the oracle: || v + (dF/dC*)^T g - g || <= 1e-3 || v ||
+    rr = ref["v"] + orc.vjp_F(Cg, p.W, p.tau, dist, pg)[0] - pg
+    assert np.linalg.norm(rr) < TOL_GRAD * np.linalg.norm(ref["v"]), (np.linalg.norm(rr), np.linalg.norm(ref["v"]), pi)
+    assert rel(pdW, sdW) < TOL_GRAD
+    if rho < 0.97:  # well conditioned: the solution itself
+        assert rel(pg, ref["g"]) < TOL_GRAD and rel(pdW, ref["dW"]) < TOL_GRAD
+    ra = ctx.backward(Gd, binding.BWD_GMRES, tol=1e-5, max_iter=200)      # AUTO takes the persistent form here
+    assert ra["info"].path == binding.PATH_PERSISTENT
+
+
 def test_krylov_backward_on_the_persistent_path_is_refused(ctx):
     W, C0, G = _case(5_000, 1, 4, seed=1)
     ctx.forward(dev(W), dev(C0), 0.05, 1e-6, 30, wl.DIST_SQL2)
