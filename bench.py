@@ -41,6 +41,14 @@ def fwd_lane_ops_per_vector(k: int, d: int, dist: int) -> int:
     return k * (3 * d + 5) + TRANS_COST * trans
 
 
+def bwd_lane_ops_per_vector(k: int, d: int, dist: int) -> int:
+    """Algorithmic lane-cycles of one (dF/dC)^T pass per weight vector: about k (5d+9) full-rate operations (the
+    E-step of the forward evaluation plus beta, its row mean, gamma and the k d accumulations) and the same k+1
+    transcendentals, each at two issue slots."""
+    trans = k + 1 + (k if (dist == 0 and d > 1) else 0)
+    return k * (5 * d + 9) + TRANS_COST * trans
+
+
 def matrix_core_lane_cycles_per_vector(k: int, dist: int) -> int:
     """The same count for the shapes whose forward loop runs on the matrix cores (d = 4, 17 <= k <= 256, persistent
     path): per (vector, codeword) pair 8 float32 multiply-adds on the matrix cores (4 of the energy product, 4 of
@@ -85,29 +93,47 @@ def measure_gmres(ctx, binding, torch, np, G, reps, tol, max_iter):
 def measure(ctx, binding, torch, np, p, dist, W, C0, G, reps, bwd_tol, bwd_max_iter):
     """Median event times (ms) of forward, implicit backward and JFB backward over `reps` runs."""
     recs = []
+    kern = {"fwd": [], "bwd": [], "jfb": []}
+
+    def kernel_ms(key):
+        # the launch itself, bracketed by events the library records on this stream right around it (persistent path)
+        try:
+            kern[key].append(ctx.last_kernel_ms())
+        except binding.IdkmError:
+            pass
+
     # outputs are allocated once, as a training loop would keep them
     fo = {"C": torch.empty_like(C0), "Wq": torch.empty_like(W)}
     dW = torch.empty_like(G)
+    ctx.set_kernel_timing(True)
     for _ in range(reps):
         e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         e[0].record()
         f = ctx.forward(W, C0, p.tau, p.tol, p.max_iter, dist, want_A=False, want_Wq=True, out=fo)
         e[1].record()
+        kernel_ms("fwd")
         b = ctx.backward(G, binding.BWD_IMPLICIT, tol=bwd_tol, max_iter=bwd_max_iter, alpha=1.0, out=dW)
         e[2].record()
+        kernel_ms("bwd")
         ctx.backward(G, binding.BWD_JFB, out=dW)
         e[3].record()
+        kernel_ms("jfb")
         recs.append((e, f["info"], b["info"]))
     torch.cuda.synchronize()
+    ctx.set_kernel_timing(False)
     fwd = float(np.median([e[0].elapsed_time(e[1]) for e, _, _ in recs]))
     bwd = float(np.median([e[1].elapsed_time(e[2]) for e, _, _ in recs]))
     jfb = float(np.median([e[2].elapsed_time(e[3]) for e, _, _ in recs]))
+    measure.kernel_ms = {k: (float(np.median(v)) if len(v) == reps else None) for k, v in kern.items()}
     return fwd, bwd, jfb, recs[-1][1], recs[-1][2]
 
 
-def roofline_of(cfg, dist, fwd_ms, finfo):
+def roofline_of(cfg, dist, fwd_ms, finfo, kernel_ms=None):
+    """fwd_ms: event time of the whole idkm_forward call; kernel_ms: event time of its one persistent launch (None on
+    the stream path, where a solve is many launches and the call is what can be timed)."""
     evals = finfo.iters + 1  # + the evaluation at C*
-    per_eval = fwd_ms * 1e-3 / evals
+    call_per_eval = fwd_ms * 1e-3 / evals
+    per_eval = (kernel_ms if kernel_ms else fwd_ms) * 1e-3 / evals
     valu_ops = fwd_lane_ops_per_vector(cfg.k, cfg.d, dist)
     matrix = cfg.d == 4 and 17 <= cfg.k <= 256 and finfo.path == 2
     ops = matrix_core_lane_cycles_per_vector(cfg.k, dist) if matrix else valu_ops
@@ -119,6 +145,9 @@ def roofline_of(cfg, dist, fwd_ms, finfo):
         "traffic": None, "lane_ops_per_vector": ops,
         "evaluations_per_launch": evals if finfo.path == 2 else 1, "avg_eval_us": per_eval * 1e6,
         "hbm_effective_GBps": hbm / 1e9, "hbm_effective_frac": hbm / PEAK_HBM,
+        "timed": ("the forward solve's one kernel launch, HIP events recorded by the library on the launch stream right "
+                  "before and after it" if kernel_ms else "the whole idkm_forward call (one launch per pass)"),
+        "kernel_ms": kernel_ms, "call_ms": fwd_ms, "frac_over_the_call": ops * cfg.m / call_per_eval / PEAK_LANE_OPS,
     }
     if matrix:
         out["note"] = ("forward loop on the matrix cores: a float32 matrix multiply-add counts as half a lane-cycle "
@@ -204,12 +233,35 @@ def main() -> int:
     del big
     dense_ms = measure_dense(ctx, binding, torch, np, G, 5)
     gm_ms, gm_info = measure_gmres(ctx, binding, torch, np, G, 5, args.bwd_tol, args.bwd_max_iter)
-    roofline = roofline_of(cfg, dist, fwd_ms, finfo)
+    kms = dict(measure.kernel_ms)
+    roofline = roofline_of(cfg, dist, fwd_ms, finfo, kms.get("fwd"))
+    # the (dF/dC)^T passes of the implicit backward (Eq. "backiter"): the JFB call is the same launch without them
+    # (one pass for v, one for dL/dW), so their time is the difference of the two calls
+    roofline_backward = None
+    if binfo.iters > 0:
+        bops = bwd_lane_ops_per_vector(cfg.k, cfg.d, dist)
+        use_kernel = bool(kms.get("bwd") and kms.get("jfb"))
+        b_ms, j_ms = (kms["bwd"], kms["jfb"]) if use_kernel else (bwd_ms, jfb_ms)
+        per_pass = max(b_ms - j_ms, 1e-9) * 1e-3 / binfo.iters
+        roofline_backward = {
+            "bound": "alu", "kernel": "implicit backward: (dF/dC)^T passes of the averaged iteration (E-step recomputed in every pass)",
+            "achieved": bops * cfg.m / per_pass / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
+            "frac": bops * cfg.m / per_pass / PEAK_LANE_OPS, "lane_ops_per_vector": bops, "passes": binfo.iters,
+            "us_per_pass": per_pass * 1e6, "implicit_ms": b_ms, "jfb_ms": j_ms,
+            "timed": "kernel launches (library-recorded events)" if use_kernel else "whole calls",
+            "note": "time per pass = (implicit launch - JFB launch) / passes; lane-ops per vector = k (5d+9) + 2 (k+1)"}
+        if cfg.d == 4 and 17 <= cfg.k <= 256 and binfo.path == 2:
+            roofline_backward["note"] += ("; this shape runs the passes on the matrix cores, so the fraction is against "
+                                          "the vector-ALU count and can exceed what the vector ALU alone could reach")
     mfma_rate, mfma_mixed, mfma4_rate = ctx.calibrate(6), ctx.calibrate(7), ctx.calibrate(8)
+    mfma_mixed_4w, mfma_mixed_8w, mfma_rate_4w = ctx.calibrate(9), ctx.calibrate(10), ctx.calibrate(11)
     roofline["ceilings"] = {"fma_Tlane_ops": fma_rate / 1e12, "exp_T_per_s": exp_rate / 1e12,
                             "mfma_f32_16x16x4_Tmac_per_s": mfma_rate / 1e12,
                             "mfma_f32_16x16x4_Tmac_per_s_with_8_fma_each": mfma_mixed / 1e12,
                             "mfma_f32_4x4x1_Tmac_per_s": mfma4_rate / 1e12,
+                            "mfma_f32_16x16x4_Tmac_per_s_4_waves_per_simd": mfma_rate_4w / 1e12,
+                            "mfma_f32_16x16x4_Tmac_per_s_with_8_fma_each_4_waves_per_simd": mfma_mixed_4w / 1e12,
+                            "mfma_f32_16x16x4_Tmac_per_s_with_8_fma_each_8_waves_per_simd": mfma_mixed_8w / 1e12,
                             "slots_per_transcendental": fma_rate / exp_rate, "stream_read_GBps": read_rate / 1e9,
                             "frac_of_measured_fma_rate": roofline["achieved"] * 1e12 / fma_rate,
                             "note": "idkm_calibrate on this device: v_fma_f32 chains, v_exp_f32 chains, float32 matrix "
@@ -220,8 +272,12 @@ def main() -> int:
     if finfo.path == 2 and os.path.exists(tpath):
         with open(tpath) as f:
             t = json.load(f)
+        lib_version = int(binding.load_library().idkm_version())
         roofline["traffic"] = {"fetch_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
-                               "algorithmic_bytes": 8 * cfg.m * cfg.d, "per": t["per"], "source": t["source"]}
+                               "algorithmic_bytes": 8 * cfg.m * cfg.d, "per": t["per"], "source": t["source"],
+                               "measured_with_library_version": t.get("library_version"),
+                               "measured_at_commit": t.get("commit"),
+                               "stale": t.get("library_version") != lib_version}
 
     others = None
     if not args.no_others:
@@ -232,7 +288,7 @@ def main() -> int:
             q, W, C0, G = load(name, dd)
             measure(ctx, binding, torch, np, q, dd, W, C0, G, 1, args.bwd_tol, 300)
             f_ms, b_ms, j_ms, fi, bi = measure(ctx, binding, torch, np, q, dd, W, C0, G, 3, args.bwd_tol, 300)
-            r = roofline_of(q.cfg, dd, f_ms, fi)
+            r = roofline_of(q.cfg, dd, f_ms, fi, measure.kernel_ms.get("fwd"))
             d_ms = measure_dense(ctx, binding, torch, np, G, 3)
             g_ms, gi = measure_gmres(ctx, binding, torch, np, G, 2, args.bwd_tol, 300)
             others.append({"dense_ms": None if d_ms is None else round(d_ms, 4), "workload": name, "dist": wl.DIST_NAMES[dd], "m": q.cfg.m, "d": q.cfg.d, "k": q.cfg.k,
@@ -303,6 +359,7 @@ def main() -> int:
                            "fwd_iters_per_s": round(tot["fwd_iters"] / (bt["fwd_ms"] * 1e-3), 1)})
 
     cpu = None
+    cpu_all = None
     if not args.no_cpu_baseline:
         from oracle import idkm_oracle as orc
         limiter = None
@@ -323,9 +380,61 @@ def main() -> int:
                 break
         if limiter is not None:
             limiter.unregister() if hasattr(limiter, "unregister") else None
+        cpu_model = "unknown"
+        try:
+            with open("/proc/cpuinfo") as f:
+                for line in f:
+                    if line.startswith("model name"):
+                        cpu_model = line.split(":", 1)[1].strip()
+                        break
+        except OSError:  # pragma: no cover
+            pass
         cpu = {"value": n_eval / el, "unit": "iters/s", "cores": 1, "kind": "oracle",
                "sample": f"{n_eval} evaluations of F (float64 numpy oracle, BLAS pinned to one thread) on the full "
-                         f"{cfg.name} tensor, m={cfg.m}, k={cfg.k}, d={cfg.d}"}
+                         f"{cfg.name} tensor, m={cfg.m}, k={cfg.k}, d={cfg.d}",
+               "cpu_model": cpu_model, "host_cores_visible": os.cpu_count()}
+        # all host cores: the numpy oracle is single-threaded by nature, so the cores are filled with independent
+        # copies of the same evaluation (as the layers of a network would be), one process each, none touching the GPU
+        import subprocess
+        workers = max(1, min(16, os.cpu_count() or 1))
+        code = ("import sys,time,numpy as np\n"
+                "sys.path.insert(0, %r)\n"
+                "from oracle import idkm_oracle as orc\n"
+                "from paper_2312_07759_amd import workloads as wl\n"
+                "p = wl.make_problem(%r, %d)\n"
+                "C = p.C0.astype(np.float64); W = p.W.astype(np.float64)\n"
+                "print('ready', flush=True); sys.stdin.readline()\n"
+                "t0 = time.perf_counter(); n = 0\n"
+                "while True:\n"
+                "    C = orc.F(C, W, p.tau, %d); n += 1\n"
+                "    if time.perf_counter() - t0 > 8.0 or n >= 40: break\n"
+                "print(n, time.perf_counter() - t0, flush=True)\n") % (ROOT, cfg.name, dist, dist)
+        env = dict(os.environ, OMP_NUM_THREADS="1", OPENBLAS_NUM_THREADS="1", MKL_NUM_THREADS="1",
+                   HIP_VISIBLE_DEVICES="", ROCR_VISIBLE_DEVICES="")
+        procs = [subprocess.Popen([sys.executable, "-c", code], stdin=subprocess.PIPE, stdout=subprocess.PIPE, text=True,
+                                  env=env) for _ in range(workers)]
+        try:
+            for q in procs:  # every worker has drawn its inputs before any of them starts the clock
+                q.stdout.readline()
+            for q in procs:
+                q.stdin.write("go\n")
+                q.stdin.flush()
+            done = [q.stdout.readline().split() for q in procs]
+            total = sum(int(x[0]) for x in done)
+            longest = max(float(x[1]) for x in done)
+            cpu_all = {"value": total / longest, "unit": "iters/s", "cores": workers, "kind": "oracle",
+                       "sample": f"{workers} processes side by side, each {done[0][0]} evaluations of F on the full {cfg.name} "
+                                 f"tensor (the numpy oracle is single-threaded; independent copies fill the cores)",
+                       "cpu_model": cpu_model}
+        except Exception as e:  # pragma: no cover
+            cpu_all = {"error": repr(e)}
+        finally:
+            for q in procs:
+                try:
+                    q.stdin.close()
+                    q.wait(timeout=60)
+                except Exception:  # pragma: no cover
+                    q.kill()
 
     out = {
         "metric": "soft-k-means forward iters/s (implicit-backward and JFB ms per layer alongside)",
@@ -340,10 +449,14 @@ def main() -> int:
                               "tol": args.bwd_tol},
         "jfb_backward": {"ms": jfb_ms},
         "gmres_backward": {"ms": gm_ms, "passes": gm_info.iters, "converged": gm_info.converged, "tol": args.bwd_tol,
-                           "note": "restarted GMRES on (I - dF/dC*)^T g = v, one pass over W per basis vector (stream path)"},
+                           "path": {1: "stream", 2: "persistent"}.get(gm_info.path),
+                           "note": "restarted GMRES on (I - dF/dC*)^T g = v, one pass over W per basis vector"},
         "dense_backward": {"ms": dense_ms, "note": "explicit k d x k d Jacobian in one pass + direct solve (2 passes over W)"},
         "roofline": roofline,
+        "roofline_backward": roofline_backward,
         "cpu_baseline": cpu,
+        "cpu_baseline_all_cores": cpu_all,
+        "library_version": int(binding.load_library().idkm_version()),
         "others": others,
     }
     print(json.dumps(out))

@@ -103,6 +103,13 @@ idkm_status idkm_set_tile_limit(idkm_ctx* ctx, int64_t bytes);
  * not be resident at once; under an explicit IDKM_PATH_PERSISTENT the call returns IDKM_ERR_DEVICE.  The context
  * stays usable either way.  A limit of 0 makes the first unsuccessful poll give up (used to exercise that path). */
 idkm_status idkm_set_spin_limit(idkm_ctx* ctx, uint32_t polls);
+/* Measurement support.  With enable != 0 the library records a HIP event on the caller's stream immediately before
+ * and immediately after every launch of a persistent kernel (one launch = one whole solve); idkm_last_kernel_ms then
+ * waits for the second event and gives the time between the two -- the duration of that launch as the stream saw it,
+ * without the host-side work of the call around it.  IDKM_ERR_INVALID_ARG if timing is off or the last call did not
+ * launch a persistent kernel (stream path, batched calls).  ms_out: host. */
+idkm_status idkm_set_kernel_timing(idkm_ctx* ctx, int32_t enable);
+idkm_status idkm_last_kernel_ms(idkm_ctx* ctx, float* ms_out);
 /* Test support.  The words that cross workgroups are stamped with 32-bit sequence numbers that the context counts up
  * over its lifetime (one per exchange of the persistent kernels, one per launch of the stream path); shortly before
  * they would wrap the library clears its exchange buffers and starts over.  This call advances both counters by n
@@ -193,6 +200,8 @@ idkm_status idkm_get_cotangents(idkm_ctx* ctx, double* v_out, double* g_out, voi
  *   kind 7  the same count with 8 independent v_fma_f32 issued after every matrix instruction (equal to kind 6 if
  *           matrix and vector instructions overlapped; they do not on gfx950: about half)
  *   kind 8  float32 multiply-adds per second of v_mfma_f32_4x4x1_f32 (16 blocks per instruction)
+ *   kind 9, 10  kind 7 with 4 and with 8 wavefronts per SIMD (does vector work of OTHER wavefronts fill the cycles a
+ *           matrix instruction holds the pipeline?); kind 11  kind 6 with 4 wavefronts per SIMD
  * Waits for completion; *result (host) receives the rate.  Nothing on the method's path calls this.
  */
 idkm_status idkm_calibrate(idkm_ctx* ctx, int32_t kind, const float* buf, int64_t n_floats, double* result,

@@ -22,7 +22,7 @@ BWD_IMPLICIT, BWD_JFB, BWD_DENSE, BWD_GMRES = 0, 1, 2, 3
 PATH_AUTO, PATH_STREAM, PATH_PERSISTENT = 0, 1, 2
 
 EXPORTS = ["idkm_version", "idkm_limits", "idkm_status_string", "idkm_create", "idkm_destroy", "idkm_last_error",
-           "idkm_set_path", "idkm_set_matrix_cores", "idkm_set_tile_limit", "idkm_set_spin_limit", "idkm_set_gmres_basis", "idkm_advance_sequence", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT", "idkm_get_cotangents", "idkm_forward_noalloc", "idkm_noalloc_last_error",
+           "idkm_set_path", "idkm_set_matrix_cores", "idkm_set_tile_limit", "idkm_set_spin_limit", "idkm_set_kernel_timing", "idkm_last_kernel_ms", "idkm_set_gmres_basis", "idkm_advance_sequence", "idkm_forward", "idkm_backward", "idkm_step_F", "idkm_step_JCT", "idkm_get_cotangents", "idkm_forward_noalloc", "idkm_noalloc_last_error",
            "idkm_calibrate", "idkm_code_bits", "idkm_code_words", "idkm_pack_codes", "idkm_unpack_quantize",
            "idkm_batch_create", "idkm_batch_destroy", "idkm_batch_last_error", "idkm_batch_launches",
            "idkm_batch_context", "idkm_batch_forward", "idkm_batch_backward"]
@@ -87,6 +87,10 @@ def load_library():
     lib.idkm_set_matrix_cores.restype = C.c_int
     lib.idkm_set_spin_limit.argtypes = [vp, C.c_uint32]
     lib.idkm_set_spin_limit.restype = C.c_int
+    lib.idkm_set_kernel_timing.argtypes = [vp, C.c_int32]
+    lib.idkm_set_kernel_timing.restype = C.c_int
+    lib.idkm_last_kernel_ms.argtypes = [vp, C.POINTER(C.c_float)]
+    lib.idkm_last_kernel_ms.restype = C.c_int
     lib.idkm_advance_sequence.argtypes = [vp, C.c_uint32, vp]
     lib.idkm_advance_sequence.restype = C.c_int
     lib.idkm_set_gmres_basis.argtypes = [vp, C.c_int32]
@@ -208,6 +212,15 @@ class Context:
 
     def set_gmres_basis(self, basis: int):
         self._check(self._lib.idkm_set_gmres_basis(self._h, int(basis)))
+
+    def set_kernel_timing(self, enable: bool):
+        self._check(self._lib.idkm_set_kernel_timing(self._h, 1 if enable else 0))
+
+    def last_kernel_ms(self) -> float:
+        """idkm_last_kernel_ms: event time of the last persistent launch (needs set_kernel_timing(True))."""
+        ms = C.c_float()
+        self._check(self._lib.idkm_last_kernel_ms(self._h, C.byref(ms)))
+        return float(ms.value)
 
     def set_spin_limit(self, polls: int):
         self._check(self._lib.idkm_set_spin_limit(self._h, int(polls)))

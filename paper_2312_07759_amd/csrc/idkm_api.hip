@@ -156,6 +156,10 @@ struct idkm_ctx {
     bool coop_launch = false;  // IDKM_COOPERATIVE=1 launches the persistent kernels cooperatively
     int min_vec_per_thread = 4;  // vectors per thread before another workgroup is added (IDKM_MIN_VPT)
     bool tree_exchange = true;   // two-level (die-local, then cross-die) exchange for full-device teams (IDKM_TREE=0: off)
+    // idkm_set_kernel_timing: events recorded on the caller's stream right before and after a persistent launch
+    bool timing = false;
+    bool timed = false;          // ev0 / ev1 bracket the last persistent launch
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
     unsigned long long* xbuf = nullptr;  // exchange words: buf1 [2][PT][XLINE], then buf2 [2][XBCAST]
     size_t xbuf_words = 0;
     unsigned int seq_base = 0;
@@ -521,6 +525,7 @@ idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PAr
     }
     if ((int64_t)checked.second * ctx->num_cu < pp.grid)
         return fail(ctx, IDKM_ERR_DEVICE, "persistent grid would not be co-resident");
+    if (ctx->timing) HIP_TRY(ctx, hipEventRecord(ctx->ev0, s));
     if (ctx->coop_launch) {
         void* args[] = {(void*)&a, (void*)&pa};
         HIP_TRY(ctx, hipLaunchCooperativeKernel((const void*)pp.fn, dim3(pp.grid), dim3(pp.threads), args, pp.lds, s));
@@ -528,6 +533,10 @@ idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PAr
         // plain launch: the grid fits the device (checked above), every wait in the kernel is bounded
         hipLaunchKernelGGL(pp.fn, dim3(pp.grid), dim3(pp.threads), pp.lds, s, a, pa);
         HIP_TRY(ctx, hipGetLastError());
+    }
+    if (ctx->timing) {
+        HIP_TRY(ctx, hipEventRecord(ctx->ev1, s));
+        ctx->timed = true;
     }
     ctx->pending_id = ctx->seq_base + 1u;
     ctx->pending_stream = s;
@@ -713,6 +722,8 @@ idkm_status idkm_destroy(idkm_ctx* c) {
     void* dev[] = {c->ctrl, c->Cd, c->Fd, c->gd, c->vd, c->ud, c->nd, c->Cf, c->Ff, c->Hs, c->stage, c->tot, c->partials, c->kry, c->tickets, c->xbuf, c->lane_xbuf, c->abort_word};
     for (void* p : dev)
         if (p) (void)hipFree(p);
+    if (c->ev0) (void)hipEventDestroy(c->ev0);
+    if (c->ev1) (void)hipEventDestroy(c->ev1);
     if (c->h_ctrl) (void)hipHostFree(c->h_ctrl);
     if (c->h_res) (void)hipHostFree(c->h_res);
     delete c;
@@ -763,6 +774,29 @@ idkm_status idkm_advance_sequence(idkm_ctx* ctx, uint32_t n, void* hip_stream) {
     return IDKM_OK;
 }
 
+idkm_status idkm_set_kernel_timing(idkm_ctx* ctx, int32_t enable) {
+    idkm_status st = check_common(ctx);
+    if (st != IDKM_OK) return st;
+    if (enable && !ctx->ev0) {
+        HIP_TRY(ctx, hipEventCreate(&ctx->ev0));
+        HIP_TRY(ctx, hipEventCreate(&ctx->ev1));
+    }
+    ctx->timing = enable != 0;
+    ctx->timed = false;
+    return IDKM_OK;
+}
+
+idkm_status idkm_last_kernel_ms(idkm_ctx* ctx, float* ms_out) {
+    idkm_status st = check_common(ctx);
+    if (st != IDKM_OK) return st;
+    if (!ms_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "ms_out must be non-NULL");
+    if (!ctx->timing || !ctx->timed)
+        return fail(ctx, IDKM_ERR_INVALID_ARG, "no timed persistent launch: enable idkm_set_kernel_timing and make a call on the persistent path first");
+    HIP_TRY(ctx, hipEventSynchronize(ctx->ev1));
+    HIP_TRY(ctx, hipEventElapsedTime(ms_out, ctx->ev0, ctx->ev1));
+    return IDKM_OK;
+}
+
 idkm_status idkm_set_spin_limit(idkm_ctx* ctx, uint32_t polls) {
     if (!ctx) return IDKM_ERR_INVALID_ARG;
     ctx->spin_limit = polls;
@@ -776,6 +810,7 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
     if (st != IDKM_OK) return st;
     ctx->has_forward = false;
     ctx->has_backward = false;
+    ctx->timed = false;
     st = validate_problem(ctx, W, m, d, C0, k, tau);
     if (st != IDKM_OK) return st;
     if (!C_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "C_out must be non-NULL");
@@ -866,6 +901,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
                           float alpha, float* dW_out, idkm_info* info, void* hip_stream) {
     idkm_status st = check_common(ctx);
     if (st != IDKM_OK) return st;
+    ctx->timed = false;
     if (!ctx->has_forward) return fail(ctx, IDKM_ERR_NO_FORWARD, "idkm_backward needs a successful idkm_forward first");
     if (!dWq || !dW_out) return fail(ctx, IDKM_ERR_INVALID_ARG, "dWq and dW_out must be non-NULL");
     if (mode != IDKM_BWD_IMPLICIT && mode != IDKM_BWD_JFB && mode != IDKM_BWD_DENSE && mode != IDKM_BWD_GMRES)
@@ -1038,7 +1074,7 @@ idkm_status idkm_calibrate(idkm_ctx* ctx, int32_t kind, const float* buf, int64_
                            void* hip_stream) {
     idkm_status st = check_common(ctx);
     if (st != IDKM_OK) return st;
-    if (!result || kind < 0 || kind > 8) return fail(ctx, IDKM_ERR_INVALID_ARG, "kind must be 0 .. 8 and result non-NULL");
+    if (!result || kind < 0 || kind > 11) return fail(ctx, IDKM_ERR_INVALID_ARG, "kind must be 0 .. 11 and result non-NULL");
     if (kind == 2 && (!buf || n_floats < 4 || (reinterpret_cast<uintptr_t>(buf) & 15u) != 0))
         return fail(ctx, IDKM_ERR_INVALID_ARG, "the streaming read needs a 16-byte aligned buffer");
     hipStream_t s = (hipStream_t)hip_stream;
@@ -1054,6 +1090,12 @@ idkm_status idkm_calibrate(idkm_ctx* ctx, int32_t kind, const float* buf, int64_
         if (kind == 0) {
             launch_cal_fma(sink, grid, iters, s);
             work = (double)grid * 256.0 * iters * 16.0;  // lane operations
+        } else if (kind >= 9) {
+            // the matrix / vector mix (and the matrix instruction alone) with more wavefronts per SIMD: can the vector
+            // work of other wavefronts run while a matrix instruction holds the pipeline?
+            const int wgs = ctx->num_cu * (kind == 10 ? 4 : 2);  // 512 threads each: 4 or 8 wavefronts per SIMD
+            launch_cal_mfma(sink, wgs, iters, kind == 11 ? 0 : 1, s);
+            work = (double)wgs * 8.0 * iters * 8.0 * 1024.0;  // multiply-adds
         } else if (kind >= 6) {
             // one workgroup of 512 threads per compute unit: two wavefronts per SIMD, as in the kernel that uses them
             launch_cal_mfma(sink, ctx->num_cu, iters, kind - 6, s);
