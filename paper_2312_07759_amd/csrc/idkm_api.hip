@@ -156,6 +156,7 @@ struct idkm_ctx {
     bool coop_launch = false;  // IDKM_COOPERATIVE=1 launches the persistent kernels cooperatively
     int min_vec_per_thread = 4;  // vectors per thread before another workgroup is added (IDKM_MIN_VPT)
     bool tree_exchange = true;   // two-level (die-local, then cross-die) exchange for full-device teams (IDKM_TREE=0: off)
+    bool tree_remote = false;    // IDKM_TREE=2: hop 1 with device-scope stores, as for workgroups that are not on their leader's die
     // idkm_set_kernel_timing: events recorded on the caller's stream right before and after a persistent launch
     bool timing = false;
     bool timed = false;          // ev0 / ev1 bracket the last persistent launch
@@ -487,7 +488,7 @@ idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PAr
         pa.tab = pa.buf3 + XBUF3_WORDS;
         // a team that fills the device, one problem per launch: hop 1 stays inside each die (the explicit-Jacobian
         // mode keeps the plain exchange, its one reduction ends in workgroup 0)
-        pa.tree = (ctx->tree_exchange && !ctx->sink && pp.grid >= TREE_MIN_G && pa.mode != BWD_DENSE) ? 1 : 0;
+        pa.tree = (ctx->tree_exchange && !ctx->sink && pp.grid >= TREE_MIN_G && pa.mode != BWD_DENSE) ? (ctx->tree_remote ? 2 : 1) : 0;
     }
     pa.seq_base = ctx->seq_base;
     pa.spin_limit = ctx->spin_limit;
@@ -692,7 +693,10 @@ idkm_status idkm_create(idkm_ctx** out, int device_id) {
         c->coop = prop.cooperativeLaunch != 0;
     }
     if (const char* e = std::getenv("IDKM_COOPERATIVE")) c->coop_launch = (e[0] == '1');
-    if (const char* e = std::getenv("IDKM_TREE")) c->tree_exchange = (e[0] != '0');
+    if (const char* e = std::getenv("IDKM_TREE")) {
+        c->tree_exchange = (e[0] != '0');
+        c->tree_remote = (e[0] == '2');
+    }
     if (const char* e = std::getenv("IDKM_MIN_VPT")) {
         int v = std::atoi(e);
         if (v >= 1 && v <= 1024) c->min_vec_per_thread = v;

@@ -70,7 +70,8 @@ struct PArgs {
     unsigned long long* buf2;  // [2][XBCAST] stamped broadcast values
     unsigned long long* buf3;  // [2][DIES][XLINE] two-level exchange: stamped totals of each die
     unsigned long long* tab;   // [DIES] two-level exchange: die index of each leader, stamped with the launch id
-    int tree;                  // two-level exchange (team of at least TREE_MIN_G workgroups, one problem per launch)
+    int tree;                  // two-level exchange (team of at least TREE_MIN_G workgroups, one problem per launch);
+                               // 2: the same with every store at device scope (test support)
     int gm_basis;              // backward, BWD_GMRES: longest Krylov basis before a restart
     unsigned int seq_base;     // sequence numbers seq_base+1 ... are used by this launch; seq_base+1 is its id
     unsigned int spin_limit;   // polls before a wait gives up
@@ -383,6 +384,7 @@ __device__ __forceinline__ bool tree_handshake(const PArgs& pa, XS& xs) {
                 __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
+        if (pa.tree == 2) local = 0;  // test support: behave as if no workgroup ran on its leader's die
         xs.local = local;
     }
     __syncthreads();

@@ -209,6 +209,37 @@ def test_damped_solve_agrees_with_the_undamped_one(ctx, dist):
     assert abs(ro["iters"] - b["info"].iters) <= 2 + 0.02 * ro["iters"]
 
 
+@pytest.mark.parametrize("setting", ["0", "2"])
+@pytest.mark.parametrize("cfg,m", [("C3", 300_007), ("C3", 70_001), ("C2", 100_003), ("P16", 80_011)],
+                         ids=["C3@300k", "C3@70k", "C2@100k", "P16@80k"])
+def test_forms_of_the_grid_exchange_agree(ctx, cfg, m, setting, monkeypatch):
+    """Teams of 64 or more workgroups exchange their sums in two levels (inside a die through its L2, then across dies).
+    IDKM_TREE=0 (read when a context is created) keeps the one-level exchange; IDKM_TREE=2 takes the two levels with
+    every store at device scope, the form a workgroup falls back to when it does not run on its leader's die.  Same
+    sums in a different order: the solves agree to rounding, and each form is held to the oracle."""
+    dist = wl.DIST_SQL2
+    p = wl.make_problem(cfg, dist, m=m)      # 256, 69, 98 and 79 workgroups: full and partly filled dies
+    Wd, C0d, Gd = dev(p.W), dev(p.C0), dev(p.G)
+    monkeypatch.setenv("IDKM_TREE", setting)
+    other = binding.Context(0)
+    monkeypatch.delenv("IDKM_TREE")
+    try:
+        res = []
+        for c in (ctx, other):
+            o = c.forward(Wd, C0d, p.tau, p.tol, p.max_iter, dist)
+            b = c.backward(Gd, binding.BWD_IMPLICIT, tol=0.0, max_iter=25)
+            assert o["info"].path == binding.PATH_PERSISTENT and b["info"].iters == 25
+            res.append((o["C"].cpu().numpy(), o["Wq"].cpu().numpy(), o["info"].iters, b["dW"].cpu().numpy()))
+    finally:
+        other.close()
+    assert abs(res[0][2] - res[1][2]) <= 1
+    assert rel(res[1][0], res[0][0]) < 1e-5 and rel(res[1][1], res[0][1]) < 1e-5 and rel(res[1][3], res[0][3]) < 1e-4
+    ref = orc.soft_kmeans(p.W, p.C0, p.tau, 0.0, res[1][2], dist)
+    assert rel(res[1][0], ref["C"]) < TOL_VAL
+    ri = orc.backward(p.W, res[1][0], p.tau, dist, p.G, "implicit", tol=0.0, max_iter=25)
+    assert rel(res[1][3], ri["dW"]) < TOL_GRAD
+
+
 def test_results_are_bitwise_reproducible(ctx):
     p = wl.make_problem("C3", wl.DIST_SQL2, m=200_001)
     Wd, C0d, Gd = dev(p.W), dev(p.C0), dev(p.G)
