@@ -286,7 +286,7 @@ idkm_status idkm_batch_backward(idkm_batch* b, const idkm_bwd_desc* layers, int3
  * idkm_forward for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same arguments, results and error behaviour as idkm_forward, but there is no context: every
  * byte the kernels need beyond the caller's tensors (the exchange words of the grid-wide sums, the O(k d) solver
- * state, the block the kernel reports into -- about 530 KB) lies in one array in the library's device image, one
+ * state, the block the kernel reports into -- about 545 KB) lies in one array in the library's device image, one
  * copy per GPU, held until the process ends.  The call makes no hipMalloc / hipFree and no other allocating call.
  *   device_id   the HIP device (0 .. 63) whose copy of the array is used; made current by the call.
  *   Limits      k in {2, 4, 8, 16}, d in {1, 2, 4}, m d <= IDKM_NOALLOC_MAX_WEIGHTS (the whole layer is held in LDS, one

@@ -400,6 +400,34 @@ def test_a_cotangent_that_overflows_is_reported_as_non_finite(ctx, path):
     assert refused >= 1
 
 
+def test_cotangents_and_kernel_timing_accessors(ctx):
+    p = wl.make_problem("C1", wl.DIST_SQL2)
+    Wd, C0d = dev(p.W), dev(p.C0)
+    fresh = binding.Context(0)
+    try:
+        fresh.forward(Wd, C0d, p.tau, p.tol, p.max_iter, wl.DIST_SQL2)
+        with pytest.raises(binding.IdkmError) as e:      # no backward since this forward
+            fresh.get_cotangents(4, 1)
+        assert e.value.status == 5
+        with pytest.raises(binding.IdkmError) as e:      # timing is off
+            fresh.last_kernel_ms()
+        assert e.value.status == 1
+        fresh.set_kernel_timing(True)
+        fresh.forward(Wd, C0d, p.tau, p.tol, p.max_iter, wl.DIST_SQL2)
+        t = fresh.last_kernel_ms()
+        assert 0.0 < t < 50.0
+        fresh.set_path(binding.PATH_STREAM)
+        fresh.forward(Wd, C0d, p.tau, p.tol, p.max_iter, wl.DIST_SQL2)
+        with pytest.raises(binding.IdkmError):            # the stream path is many launches: nothing to report
+            fresh.last_kernel_ms()
+        G = dev(np.ones_like(p.W))
+        fresh.backward(G, binding.BWD_JFB)
+        v, g = fresh.get_cotangents(4, 1)
+        assert np.array_equal(v, g) and np.isfinite(v).all() and np.abs(v).max() > 0
+    finally:
+        fresh.close()
+
+
 def test_error_paths(ctx):
     d = wl.DIST_SQL2
     W = dev(np.zeros((8, 1), dtype=np.float32))
