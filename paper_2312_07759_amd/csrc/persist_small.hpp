@@ -828,9 +828,16 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
     // forward passes groups of UNR while they last, then groups of 4, then single vectors
     constexpr bool FWD_LIKE = (PASS == PASS_FWD || PASS == PASS_FIN);
     // (for k = 8 and 16 the group size makes no measurable difference: 2 to 16 vectors are within 2 % of each other;
-    // nor does it in the backward passes at k <= 4: 6, 9, 12 and 18 vectors are within 3 %)
+    // in the backward passes at k <= 4, 4 / 6 / 9 / 12 vectors give 6.53 / 6.34 / 6.30 / 6.24 us per pass at C3; in the forward
+    // loop 9 / 12 / 18 / 36 give 4.79 / 4.79 / 4.71 / 4.65 us per evaluation)
+#ifndef IDKM_FWD_UNR
+#define IDKM_FWD_UNR 18
+#endif
+#ifndef IDKM_BWD_UNR
+#define IDKM_BWD_UNR 12
+#endif
     constexpr int UNR = SHARED ? (K <= 4 ? 4 : 2)
-                               : (FWD_LIKE ? (K <= 4 ? 18 : (K == 8 ? 8 : 4)) : (K <= 4 ? 6 : (K == 8 ? 3 : 2)));
+                               : (FWD_LIKE ? (K <= 4 ? IDKM_FWD_UNR : (K == 8 ? 8 : 4)) : (K <= 4 ? IDKM_BWD_UNR : (K == 8 ? 3 : 2)));
     auto one = [&](int it) {
         float w[D], g[D];
 #pragma unroll
@@ -842,6 +849,13 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
     };
     if constexpr (FWD_LIKE) {
         int it = threadIdx.x;
+        if constexpr (UNR >= 18) {
+            // a tile of 2 UNR or more vectors per lane: one straight block of 2 UNR bodies first (C3: the whole tile)
+            for (; it + (2 * UNR - 1) * PT < cnt; it += 2 * UNR * PT) {
+#pragma unroll
+                for (int u = 0; u < 2 * UNR; ++u) one(it + u * PT);
+            }
+        }
         for (; it + (UNR - 1) * PT < cnt; it += UNR * PT) {
 #pragma unroll
             for (int u = 0; u < UNR; ++u) one(it + u * PT);

@@ -80,3 +80,53 @@ def test_forward_and_backward_on_both_paths(ctx, k, d, m, tau, seed, dist):
         finally:
             ctx.set_path(binding.PATH_AUTO)
     assert tried >= 1
+
+
+def _team_cases():
+    """Layers large enough for teams of 64 to 256 workgroups (the two-level grid exchange), ragged sizes."""
+    rng = np.random.default_rng(20231208)
+    out = []
+    for k in (2, 4, 8, 16):
+        for d in (1, 2, 4):
+            m = int(rng.integers(64 * 1024 + 1, 300_000))
+            out.append((k, d, m, float(rng.choice([0.05, 0.15, 0.5])), int(rng.integers(0, 1 << 30))))
+    out.append((4, 1, 64 * 1024 - 1023, 0.1, 7))   # exactly 64 workgroups
+    out.append((4, 1, 65 * 1024 + 5, 0.1, 8))      # 66 workgroups: dies with 9 and with 8 members
+    out.append((2, 2, 255 * 1024 + 3, 0.1, 9))     # 256 workgroups, the last one nearly empty
+    return out
+
+
+TEAM_CASES = _team_cases()
+
+
+@pytest.mark.parametrize("dist", [wl.DIST_L2, wl.DIST_SQL2])
+@pytest.mark.parametrize("k,d,m,tau,seed", TEAM_CASES, ids=[f"k{c[0]}d{c[1]}m{c[2]}" for c in TEAM_CASES])
+def test_full_device_teams_on_the_persistent_path(ctx, k, d, m, tau, seed, dist):
+    W, C0, G = wl.random_problem(m, d, k, seed=seed, std=0.5, spread=1.5)
+    W, G = W.astype(np.float32), G.astype(np.float32)
+    C0 = (C0 + 0.01 * np.random.default_rng(seed + 1).standard_normal(C0.shape)).astype(np.float32)
+    Wd, Cd, Gd = dev(W), dev(C0), dev(G)
+    iters = 8
+    ref = orc.soft_kmeans(W, C0, tau, 0.0, iters, dist)
+    out = ctx.forward(Wd, Cd, tau, 0.0, iters, dist, want_assign=True)
+    assert out["info"].iters == iters and out["info"].path == binding.PATH_PERSISTENT
+    Cg = out["C"].cpu().numpy()
+    assert rel(Cg, ref["C"]) < TOL_VAL, rel(Cg, ref["C"])
+    assert rel(out["Wq"].cpu().numpy(), orc.soft_quantize(W, Cg, tau, dist)) < TOL_VAL
+    assert np.array_equal(out["assign"].cpu().numpy(), orc.hard_assign_f32(W, Cg))
+    bj = ctx.backward(Gd, binding.BWD_JFB)
+    rj = orc.backward(W, Cg, tau, dist, G, "jfb")
+    assert rel(bj["dW"].cpu().numpy(), rj["dW"]) < TOL_GRAD
+    v, g = ctx.get_cotangents(k, d)
+    assert rel(v, rj["v"]) < TOL_GRAD
+    bi = ctx.backward(Gd, binding.BWD_IMPLICIT, tol=0.0, max_iter=6, alpha=1.0)
+    ri = orc.backward(W, Cg, tau, dist, G, "implicit", tol=0.0, max_iter=6, alpha=1.0)
+    if not (bi["info"].converged or ri["converged"]):
+        assert bi["info"].iters == ri["iters"] and bi["info"].alpha == ri["alpha"]
+    assert rel(bi["dW"].cpu().numpy(), ri["dW"]) < TOL_GRAD, rel(bi["dW"].cpu().numpy(), ri["dW"])
+    if k * d <= 16:
+        bg = ctx.backward(Gd, binding.BWD_GMRES, tol=1e-5, max_iter=60)
+        assert bg["info"].path == binding.PATH_PERSISTENT
+        gg = ctx.get_cotangents(k, d)[1]
+        res = rj["v"] + orc.vjp_F(Cg, W, tau, dist, gg)[0] - gg
+        assert np.linalg.norm(res) < TOL_GRAD * np.linalg.norm(rj["v"]), (bg["info"], np.linalg.norm(res), np.linalg.norm(rj["v"]))
