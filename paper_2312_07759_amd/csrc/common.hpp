@@ -268,6 +268,26 @@ __device__ __forceinline__ double fast_div_d(double s, double n) {
     return s * r;
 }
 
+// sqrt(x) and 1/x for the O(k d) float64 steps that sit on the critical path of a pass (one lane, every workgroup
+// waiting): float32 seed refined by Newton steps in float64 instead of the IEEE sequences (several hundred cycles each).
+// Outside the range a float32 seed covers they fall back to the exact routines.  Relative error below 1e-15.
+__device__ __forceinline__ double fast_sqrt_d(double x) {
+    if (!(x > 1e-30 && x < 1e30)) return sqrt(x);
+    double r = (double)__builtin_amdgcn_rsqf((float)x);  // ~1e-7
+    r = r * (1.5 - 0.5 * x * r * r);                     // ~1e-14
+    r = r * (1.5 - 0.5 * x * r * r);
+    const double s = x * r;
+    return s + 0.5 * r * (x - s * s);                    // one correction of the root itself
+}
+__device__ __forceinline__ double fast_rcp_d(double x) {
+    const double ax = fabs(x);
+    if (!(ax > 1e-30 && ax < 1e30)) return 1.0 / x;
+    double r = (double)__builtin_amdgcn_rcpf((float)x);
+    r = r * (2.0 - x * r);
+    r = r * (2.0 - x * r);
+    return r;
+}
+
 // Sum of squares with every multiplication and addition rounded on its own, in index order.  This is the float32 key
 // of the hard assignment for d > 1 and has to be the same number in every kernel and in a checker that emulates it;
 // the compiler's default would fuse the additions into multiply-adds (and the rounded-operation intrinsics are plain

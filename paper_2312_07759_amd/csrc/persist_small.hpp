@@ -1305,7 +1305,7 @@ __device__ __forceinline__ int gmres_step(GmState<N>& gm, U u, const double* s_v
         if (lane == 0) {
             double w2 = 0.0;
             for (int idx = 0; idx < N; ++idx) w2 += gm.w[idx] * gm.w[idx];
-            const double hn = sqrt(w2);
+            const double hn = fast_sqrt_d(w2);
             double* hcol = gm.H[j];
             for (int i = 0; i < j; ++i) {
                 const double t0 = gm.cs[i] * hcol[i] + gm.sn[i] * hcol[i + 1];
@@ -1313,8 +1313,9 @@ __device__ __forceinline__ int gmres_step(GmState<N>& gm, U u, const double* s_v
                 hcol[i] = t0;
             }
             const double hj = hcol[j];
-            const double rr = sqrt(hj * hj + hn * hn);
-            const double cj = rr > 0.0 ? hj / rr : 1.0, sj = rr > 0.0 ? hn / rr : 0.0;
+            const double rr = fast_sqrt_d(hj * hj + hn * hn);
+            const double irr = rr > 0.0 ? fast_rcp_d(rr) : 0.0;
+            const double cj = rr > 0.0 ? hj * irr : 1.0, sj = hn * irr;
             gm.cs[j] = cj;
             gm.sn[j] = sj;
             hcol[j] = rr;
@@ -1334,14 +1335,14 @@ __device__ __forceinline__ int gmres_step(GmState<N>& gm, U u, const double* s_v
                 for (int i = nj - 1; i >= 0; --i) {
                     double t0 = gm.sv[i];
                     for (int l = i + 1; l < nj; ++l) t0 -= gm.H[l][i] * gm.y[l];
-                    gm.y[i] = t0 / gm.H[i][i];
+                    gm.y[i] = t0 * fast_rcp_d(gm.H[i][i]);
                 }
                 gm.j = nj;
                 nj_new = nj;
                 next = 1;
             } else {
                 gm.j = j + 1;
-                scale = 1.0 / hn;
+                scale = fast_rcp_d(hn);
             }
         }
         wave_lds_sync();
@@ -1382,7 +1383,7 @@ __device__ __forceinline__ int gmres_step(GmState<N>& gm, U u, const double* s_v
     if (lane == 0) {
         double r2 = 0.0;
         for (int idx = 0; idx < N; ++idx) r2 += gm.Q[0][idx] * gm.Q[0][idx];
-        const double beta = sqrt(r2);
+        const double beta = fast_sqrt_d(r2);
         s_iters += 1;
         s_res = r2;
         if (!(r2 <= 1.7e308)) {
@@ -1400,7 +1401,7 @@ __device__ __forceinline__ int gmres_step(GmState<N>& gm, U u, const double* s_v
             gm.phase = 0;
             gm.j = 0;
             gm.sv[0] = beta;
-            scale = 1.0 / beta;
+            scale = fast_rcp_d(beta);
         }
     }
     wave_lds_sync();
@@ -1675,7 +1676,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                 }
                 if (tid < 64) {
                     double hn;
-                    const double vn = sqrt(s_vnorm);
+                    const double vn = fast_sqrt_d(s_vnorm);
                     int over;
                     if (tree)
                         over = gmres_step<KD>(gm, [&](int i) { return xs.totd[i]; }, s_v, s_g, tol, vn, max_iter, s_iters,
