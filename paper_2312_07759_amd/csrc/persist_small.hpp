@@ -122,7 +122,7 @@ struct BatchItem {
 // Shared scratch of the exchange.
 template <int NACC>
 struct XShared {
-    float rpart[pow2_at_least(NACC)][PT / 16];  // partial sums of every row of 16 lanes, [accumulator][row]
+    float rpart[pow2_at_least(NACC)][PT / 64];  // partial sums of every wavefront, [accumulator][wavefront]
     double red2[PT];                 // reducer: per-thread sums (thread t: word t mod WPR, workgroups t/WPR + k PT/WPR)
     double tot[8];                   // reducer: totals of its slice
     unsigned int bc[XBCAST];         // payloads of the broadcast words
@@ -155,6 +155,25 @@ __device__ __forceinline__ void st_word_die(unsigned long long* p, unsigned long
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+// Sum over the four lanes l % 16 + 16 r of a wavefront (one lane of each row of 16), in every lane.
+// v_permlane16_swap exchanges the odd rows of its first operand with the even rows of its second, v_permlane32_swap
+// the upper half of the first with the lower half of the second; adding the two results pairs every lane with its
+// partner, and both partners add the same two numbers (in either order: the same sum).
+__device__ __forceinline__ float cross_row_sum(float x) {
+    u32x2_t s = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(s[0]) + __uint_as_float(s[1]);
+    s = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(s[0]) + __uint_as_float(s[1]);
+}
+__device__ __forceinline__ double cross_row_sum_d(double x) {
+    u32x2_t lo = __builtin_amdgcn_permlane16_swap((unsigned)__double2loint(x), (unsigned)__double2loint(x), false, false);
+    u32x2_t hi = __builtin_amdgcn_permlane16_swap((unsigned)__double2hiint(x), (unsigned)__double2hiint(x), false, false);
+    x = __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+    lo = __builtin_amdgcn_permlane32_swap((unsigned)__double2loint(x), (unsigned)__double2loint(x), false, false);
+    hi = __builtin_amdgcn_permlane32_swap((unsigned)__double2hiint(x), (unsigned)__double2hiint(x), false, false);
+    return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+}
 // Row totals of accumulators [OFF, NACC) into xs.rpart, taken in power-of-two pieces, largest first (80 sums are a
 // piece of 64 and one of 16, not one of 128 padded with zeros: the exchange network costs about three instructions
 // per value it starts with).
@@ -164,20 +183,24 @@ constexpr int pow2_at_most(int n) {
     return p;
 }
 template <int NACC, int OFF, class XS>
-__device__ __forceinline__ void publish_rows(const float (&acc)[NACC], XS& xs, int lane, int row) {
+__device__ __forceinline__ void publish_rows(const float (&acc)[NACC], XS& xs, int lane, int wave) {
     constexpr int NP = pow2_at_most(NACC - OFF);
     float v[NP];
 #pragma unroll
     for (int q = 0; q < NP; ++q) v[q] = (OFF + q < NACC) ? acc[OFF + q] : 0.f;
     row_sums<NP>(v, lane);
-    if (row_sum_owner<NP>(lane & 15)) {
+    // the four rows of the wavefront in registers (two row swaps per value), so that LDS only sees one value per
+    // wavefront and accumulator
+#pragma unroll
+    for (int i = 0; i < row_sum_live(NP); ++i) v[i] = cross_row_sum(v[i]);
+    if (lane < 16 && row_sum_owner<NP>(lane)) {
 #pragma unroll
         for (int i = 0; i < row_sum_live(NP); ++i) {
-            const int q = OFF + row_sum_index<NP>(lane & 15, i);
-            if (q < NACC) xs.rpart[q][row] = v[i];
+            const int q = OFF + row_sum_index<NP>(lane, i);
+            if (q < NACC) xs.rpart[q][wave] = v[i];
         }
     }
-    if constexpr (OFF + NP < NACC) publish_rows<NACC, OFF + NP>(acc, xs, lane, row);
+    if constexpr (OFF + NP < NACC) publish_rows<NACC, OFF + NP>(acc, xs, lane, wave);
 }
 
 // hop 1, sender side: workgroup partial of every accumulator into this workgroup's line.
@@ -198,18 +221,14 @@ __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int s
         }
     }
     IDKM_SUB(0);
-    publish_rows<NACC, 0>(acc, xs, lane, tid >> 4);
+    publish_rows<NACC, 0>(acc, xs, lane, tid >> 6);
     IDKM_SUB(1);
     __syncthreads();
     IDKM_SUB(2);
     if (tid < NACC) {
-        // the 16 rows in float64, four chains of four and then the chains: a fixed order with a short dependency
-        double c4[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            c4[u] = ((double)xs.rpart[tid][4 * u] + (double)xs.rpart[tid][4 * u + 1]) +
-                    ((double)xs.rpart[tid][4 * u + 2] + (double)xs.rpart[tid][4 * u + 3]);
-        const double s = (c4[0] + c4[1]) + (c4[2] + c4[3]);
+        // the four wavefronts in float64, a fixed order
+        const double s = ((double)xs.rpart[tid][0] + (double)xs.rpart[tid][1]) +
+                         ((double)xs.rpart[tid][2] + (double)xs.rpart[tid][3]);
         xs.own[tid] = (float)s;
         // a workgroup's words lie together: one store transaction per workgroup and pass
         unsigned long long* dst = &pa.buf1[((size_t)(seq & 1u) * PT + pa.wg) * xline_of(NACC) + tid];
@@ -526,26 +545,7 @@ __device__ __forceinline__ bool tree_grid_totals(const PArgs& pa, unsigned int s
 // swaps) and stores its own 8 words; the leader adds 4 wavefronts x up to 32 workgroups, again across lanes, and hop
 // 2 runs inside wavefront 0 of every workgroup.  Slot p of a line holds accumulator slot_acc(p) (the order in which
 // the halving network leaves them in the lanes); unused slots carry zeros.
-typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 __host__ __device__ constexpr int slot_acc(int p) { return (p & 1) * 4 + ((p >> 1) & 1) * 2 + ((p >> 2) & 1); }
-// x + (the value of the lane 16 rows... ) : sum over the four lanes l % 16 + 16 r of a wavefront, in every lane.
-// v_permlane16_swap exchanges the odd rows of its first operand with the even rows of its second, v_permlane32_swap
-// the upper half of the first with the lower half of the second; adding the two results pairs every lane with its
-// partner, and both partners add the same two numbers (in either order: the same sum).
-__device__ __forceinline__ float cross_row_sum(float x) {
-    u32x2_t s = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    x = __uint_as_float(s[0]) + __uint_as_float(s[1]);
-    s = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(s[0]) + __uint_as_float(s[1]);
-}
-__device__ __forceinline__ double cross_row_sum_d(double x) {
-    u32x2_t lo = __builtin_amdgcn_permlane16_swap((unsigned)__double2loint(x), (unsigned)__double2loint(x), false, false);
-    u32x2_t hi = __builtin_amdgcn_permlane16_swap((unsigned)__double2hiint(x), (unsigned)__double2hiint(x), false, false);
-    x = __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
-    lo = __builtin_amdgcn_permlane32_swap((unsigned)__double2loint(x), (unsigned)__double2loint(x), false, false);
-    hi = __builtin_amdgcn_permlane32_swap((unsigned)__double2hiint(x), (unsigned)__double2hiint(x), false, false);
-    return __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
-}
 // Sum over the eight lanes that share l % 8 (lanes l, l + 8, ..., l + 56), in every lane, float64, fixed order.
 __device__ __forceinline__ double sum_over_lane_bits_3_to_5(double x) {
     x += dpp_d<0x128, 0xf>(x);  // row_ror:8
