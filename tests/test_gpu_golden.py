@@ -208,12 +208,26 @@ def test_full_size_layers_that_end_at_their_iteration_cap(ctx, name, dist):
 
     bj = ctx.backward(G, binding.BWD_JFB)
     dj = bj["dW"].cpu().numpy()
-    check(ctx.get_cotangents(k, d)[0], g["v"], TOL_GRAD, f"{tag} v")
+    v_gpu = ctx.get_cotangents(k, d)[0]
+    check_norm(v_gpu, g["v"], TOL_GRAD, f"{tag} v at the oracle's C")
     check_norm(dj[idx], g["dW_jfb_rows"], TOL_GRAD, f"{tag} JFB dW (sampled rows, first and last 64 rows)")
     assert abs(np.linalg.norm(dj.astype(np.float64)) / g["dW_jfb_norm"] - 1) < TOL_GRAD
     assert np.abs(dj).max() <= g["dW_jfb_absmax"] * (1 + 10 * TOL_GRAD)
-    if k <= 16:
-        check(dj, orc.backward(p.W, Cg, p.tau, dist, p.G, "jfb")["dW"], TOL_GRAD, f"{tag} JFB dW (whole tensor)")
+    # every row, and v, against the oracle at the GPU's own C (two passes of numpy over the m x k matrices)
+    rj = orc.backward(p.W, Cg, p.tau, dist, p.G, "jfb")
+    check(v_gpu, rj["v"], TOL_GRAD, f"{tag} v")
+    check(dj, rj["dW"], TOL_GRAD, f"{tag} JFB dW (whole tensor)")
+    # The stored backward results belong to the ORACLE's codebook at the cap.  Along an unconverged trajectory the GPU's
+    # codebook differs from it by about 1e-5, and with the plain norm (whose derivative is a sign) that alone moves v by
+    # 9e-4 and the iterate after 10 passes by 1.3e-3.  So the backward is run from the oracle's codebook (rounded to
+    # float32: 6e-8), handed over through idkm_step_F, which leaves (W, C, n, F(C, W)) as the forward state.
+    Co = np.array(g["C"], dtype=np.float32)
+    Fo, no = ctx.step_F(W, dev(Co), p.tau, dist)
+    check(Fo.cpu().numpy(), g["F_at_C"], TOL_VAL, f"{tag} F at the oracle's C")
+    check(no.cpu().numpy(), g["n"], TOL_VAL, f"{tag} n at the oracle's C")
+    bo = ctx.backward(G, binding.BWD_JFB)
+    check(ctx.get_cotangents(k, d)[0], g["v"], TOL_GRAD, f"{tag} v from the oracle's C")
+    check_norm(bo["dW"].cpu().numpy()[idx], g["dW_jfb_rows"], TOL_GRAD, f"{tag} JFB dW rows from the oracle's C")
     for r in g["implicit"]:
         bi = ctx.backward(G, binding.BWD_IMPLICIT, tol=0.0, max_iter=r["max_iter"], alpha=1.0)
         assert same_passes(bi["info"], r["iters"], r["alpha"]), (tag, bi["info"], r["iters"], r["alpha"])
