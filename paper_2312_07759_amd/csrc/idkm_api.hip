@@ -177,7 +177,7 @@ struct idkm_ctx {
     hipStream_t pending_stream = nullptr;
     std::vector<Deferred>* sink = nullptr;  // set by a batched call: persistent launches are handed over, not issued
     std::map<const void*, std::pair<size_t, int>> checked;  // kernel -> (largest LDS size set, blocks per CU at that size)
-    std::map<const void*, size_t> static_lds;               // matrix-core kernels: bytes of static LDS
+    std::map<const void*, size_t> static_lds;               // bytes of static LDS of the kernels whose dynamic LDS is sized against it
     unsigned int spin_limit = 1u << 20;
     bool use_matrix = true;           // d = 4, 17 <= k <= 256: matrix-core kernels where they exist
     size_t tile_limit = 144 * 1024;   // largest tile of W (and dL/dWq) a persistent workgroup of the lane<->vector family keeps in LDS
@@ -998,15 +998,33 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
 
     PersistPlan pp;
     bool persistent = ctx->path != IDKM_PATH_STREAM && plan_persistent(ctx, true, &pp, true, dWq);
-    // The minimal-residual solve keeps O(k d R) state.  Inside the persistent kernel every workgroup holds all of it,
-    // which takes a team where every workgroup receives the grid totals (one workgroup, or the two-level exchange of a
-    // full-device team) and k d <= 16; everything else runs it in the pass tail of the stream path.
-    if (persistent && mode == IDKM_BWD_GMRES)
-        persistent = !pp.lane && ctx->k * ctx->d <= 16 &&
+    // The minimal-residual solve keeps O(k d R) state.  Inside the persistent kernel every workgroup holds all of it
+    // (in LDS, behind its tiles), which takes a team where every workgroup receives the grid totals (one workgroup, or
+    // the two-level exchange of a full-device team), k d <= 64 and room for the state beside the tiles; everything
+    // else runs it in the pass tail of the stream path.
+    unsigned int gm_off = 0;
+    if (persistent && mode == IDKM_BWD_GMRES) {
+        const int kd = ctx->k * ctx->d;
+        persistent = !pp.lane && kd <= 64 &&
                      (pp.grid == 1 || (ctx->tree_exchange && !ctx->sink && pp.grid >= TREE_MIN_G));
+        if (persistent) {
+            size_t& fixed = ctx->static_lds[(const void*)pp.fn];
+            if (fixed == 0) {
+                hipFuncAttributes at;
+                fixed = (hipFuncGetAttributes(&at, (const void*)pp.fn) == hipSuccess) ? at.sharedSizeBytes : LDS_PER_CU;
+                (void)hipGetLastError();
+            }
+            gm_off = (unsigned int)((pp.lds + 15) / 16 * 16);
+            const size_t lds = gm_off + gm_state_bytes(kd, gm_basis_length(ctx->gmres_basis, kd));
+            if (fixed + lds <= LDS_PER_CU)
+                pp.lds = lds;
+            else
+                persistent = false;
+        }
+    }
     if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
         return fail(ctx, IDKM_ERR_UNSUPPORTED, mode == IDKM_BWD_GMRES
-                        ? "IDKM_BWD_GMRES on the persistent path needs k in {2,4,8,16}, k*d <= 16 and a team of one or of at least 64 workgroups"
+                        ? "IDKM_BWD_GMRES on the persistent path needs k in {2,4,8,16}, k*d <= 64, a team of one or of at least 64 workgroups and room in LDS for its basis beside the tiles"
                         : "the persistent path needs k <= 512, d <= 4 and the tiles of W and dWq to fit in LDS");
     if (persistent) {
         const uint64_t ex = 1ull + (mode == IDKM_BWD_IMPLICIT ? (uint64_t)max_iter * 7ull
@@ -1019,6 +1037,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
             pa.mode = (int)mode;
             pa.alpha = (double)alpha;
             pa.gm_basis = ctx->gmres_basis;
+            pa.gm_off = gm_off;
             st = launch_persistent(ctx, pp, a, pa, (unsigned int)ex, s);
             if (st == IDKM_OK) {
                 ctx->pending_kind = 2;

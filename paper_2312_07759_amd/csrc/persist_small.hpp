@@ -77,6 +77,7 @@ struct PArgs {
     int tree;                  // two-level exchange (team of at least TREE_MIN_G workgroups, one problem per launch);
                                // 2: the same with every store at device scope (test support)
     int gm_basis;              // backward, BWD_GMRES: longest Krylov basis before a restart
+    unsigned int gm_off;       // backward, BWD_GMRES: byte offset of the solve's state in the dynamic LDS (a multiple of 16)
     unsigned int seq_base;     // sequence numbers seq_base+1 ... are used by this launch; seq_base+1 is its id
     unsigned int spin_limit;   // polls before a wait gives up
     int per;                   // vectors per workgroup tile
@@ -130,7 +131,6 @@ struct XShared {
     int abort;
     // two-level exchange
     int local;                       // this workgroup runs on its leader's die: its partial sums need only reach the L2
-    float stage[32 * NACC];          // leader: partial sums of its die's workgroups, [member][accumulator]
     float stage2[DIES * (NACC <= 8 ? 8 : (NACC <= 16 ? 16 : (NACC <= 32 ? 32 : NACC)))];  // totals of the dies, [die][slot]
     double totd[NACC];               // grid totals
 };
@@ -420,33 +420,36 @@ __device__ __forceinline__ bool tree_handshake(const PArgs& pa, XS& xs) {
 }
 
 // hop 1, leader side (workgroups 0 .. DIES-1): totals of the partial sums of workgroups wg, wg + DIES, ... in
-// float64, members in increasing order (four interleaved chains), published as the die's line of buf3 and left in
-// xs.stage2 for this workgroup's own hop 2.  Returns false if the wait was abandoned (uniform over the workgroup).
+// float64, published as the die's line of buf3 and left in xs.stage2 for this workgroup's own hop 2.  Thread t takes
+// accumulator t % NACC of members t / NACC, t / NACC + PARTS, ... and adds them in registers in increasing order (two
+// interleaved chains); the PARTS groups are added through LDS, again in a fixed order.  Returns false if the wait was
+// abandoned (uniform over the workgroup).
 template <int NACC, class XS>
 __device__ __forceinline__ bool tree_die_totals(const PArgs& pa, unsigned int seq, XS& xs) {
     constexpr int LINE = xline_of(NACC);
-    constexpr int NLD = (32 * NACC + PT - 1) / PT;  // loads per thread that cover 32 members
-    const int tid = threadIdx.x, x = pa.wg;
+    constexpr int PARTS = PT / NACC;                 // member groups
+    constexpr int MPT = (32 + PARTS - 1) / PARTS;    // members per thread
+    static_assert(PARTS >= 1, "one thread per accumulator at least");
+    const int tid = threadIdx.x, x = pa.wg, q = tid % NACC, part = tid / NACC;
+    const bool live = part < PARTS;
     const int nmem = (pa.G - x + DIES - 1) / DIES;  // members of this die, the leader included; <= 32
-    const unsigned long long* line0 = pa.buf1 + ((size_t)(seq & 1u) * PT + x) * LINE;
-    unsigned long long w[NLD];
-    bool valid[NLD];
+    const unsigned long long* line0 = pa.buf1 + ((size_t)(seq & 1u) * PT + x) * LINE + q;
+    unsigned long long w[MPT];
+    bool valid[MPT];
 #pragma unroll
-    for (int u = 0; u < NLD; ++u) {
-        const int f = tid + u * PT, mi = f / NACC;
-        valid[u] = mi >= 1 && mi < nmem;  // member 0 is this workgroup: its sums are in xs.own
+    for (int u = 0; u < MPT; ++u) {
+        const int mi = part + PARTS * u;
+        valid[u] = live && mi >= 1 && mi < nmem;  // member 0 is this workgroup: its sums are in xs.own
     }
     bool aborted = false;
     unsigned int spins = 0;
     for (;;) {
 #pragma unroll
-        for (int u = 0; u < NLD; ++u) {
-            const int f = tid + u * PT, mi = f / NACC, q = f - mi * NACC;
-            w[u] = valid[u] ? ld_word(line0 + (size_t)mi * DIES * LINE + q) : pack_f(seq, 0.f);
-        }
+        for (int u = 0; u < MPT; ++u)
+            w[u] = valid[u] ? ld_word(line0 + (size_t)(part + PARTS * u) * DIES * LINE) : pack_f(seq, 0.f);
         bool ok = true;
 #pragma unroll
-        for (int u = 0; u < NLD; ++u) ok = ok && ((unsigned int)(w[u] >> 32) == seq);
+        for (int u = 0; u < MPT; ++u) ok = ok && ((unsigned int)(w[u] >> 32) == seq);
         if (ok) break;
         ++spins;
         if (spins > pa.spin_limit ||
@@ -455,12 +458,12 @@ __device__ __forceinline__ bool tree_die_totals(const PArgs& pa, unsigned int se
             break;
         }
     }
-    // (the barrier inside publish_partials lies before the stores to xs.own; this one orders them before the reads)
-    __syncthreads();
+    if (live) {
+        // (thread q < NACC wrote xs.own[q] itself in publish_partials; members that do not exist carry zeros)
+        double c2[2] = {tid < NACC ? (double)xs.own[q] : 0.0, 0.0};
 #pragma unroll
-    for (int u = 0; u < NLD; ++u) {
-        const int f = tid + u * PT, mi = f / NACC, q = f - mi * NACC;
-        if (f < 32 * NACC) xs.stage[f] = (mi == 0) ? xs.own[q] : __uint_as_float((unsigned int)w[u]);
+        for (int u = 0; u < MPT; ++u) c2[u & 1] += (double)__uint_as_float((unsigned int)w[u]);
+        xs.red2[part * NACC + q] = c2[0] + c2[1];
     }
     if (aborted) {
         xs.abort = 1;
@@ -469,14 +472,10 @@ __device__ __forceinline__ bool tree_die_totals(const PArgs& pa, unsigned int se
     __syncthreads();
     if (xs.abort) return false;
     if (tid < NACC) {
-        double c4[4] = {0.0, 0.0, 0.0, 0.0};
-        int mi = 0;
-        for (; mi + 3 < nmem; mi += 4) {
+        double c2[2] = {0.0, 0.0};
 #pragma unroll
-            for (int u = 0; u < 4; ++u) c4[u] += (double)xs.stage[(mi + u) * NACC + tid];
-        }
-        for (int u = 0; mi < nmem; ++mi, ++u) c4[u] += (double)xs.stage[mi * NACC + tid];
-        const float tot = (float)((c4[0] + c4[1]) + (c4[2] + c4[3]));
+        for (int g = 0; g < PARTS; ++g) c2[g & 1] += xs.red2[g * NACC + tid];
+        const float tot = (float)(c2[0] + c2[1]);
         xs.stage2[x * NACC + tid] = tot;
         st_word(&pa.buf3[((size_t)(seq & 1u) * DIES + x) * LINE + tid], pack_f(seq, tot));
     }
@@ -1252,14 +1251,39 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
 
 // State of the minimal-residual (restarted GMRES) solve of (I - dF/dC*)^T g = v inside the persistent backward: every
 // workgroup of a team that receives the grid totals (a team of one, or the two-level exchange) keeps the whole of it
-// and takes every step itself, in float64, so that all workgroups hold the same iterate.  N = k d <= 16 unknowns.
+// and takes every step itself, in float64, so that all workgroups hold the same iterate.  N = k d <= 64 unknowns, a
+// basis of R <= N vectors; the arrays lie in the launch's dynamic LDS behind the tiles (at k d = 64, R = 64 they are
+// 67 KB, which only calls of this mode pay for).
+__host__ __device__ constexpr size_t gm_state_doubles(int n, int r) {
+    // Q, H, cs, sn, sv, y, p, w, beta
+    return (size_t)(r + 1) * (n + 1) + (size_t)r * (r + 1) + r + r + (r + 1) + r + (r + 1) + n + 1;
+}
+__host__ __device__ constexpr size_t gm_state_bytes(int n, int r) { return gm_state_doubles(n, r) * sizeof(double) + 16; }
+__host__ __device__ constexpr int gm_basis_length(int asked, int n) { return asked < n ? (asked < 1 ? 1 : asked) : n; }
+
 template <int N>
-struct GmState {
-    double Q[N + 1][N];   // orthonormal basis, row i = q_i
-    double H[N][N + 1];   // Hessenberg columns, rotated in place to triangular
-    double cs[N], sn[N], sv[N + 1], y[N], p[N + 1], w[N];
-    int phase, j, R, stall;
-    double beta;
+struct GmView {
+    static constexpr int QS = N + 1;  // row stride of Q: lanes that read one row each then fall on different LDS banks
+    double* Q;    // [R + 1][QS] orthonormal basis, row i = q_i
+    double* H;    // [R][R + 1] Hessenberg columns, rotated in place to triangular
+    double *cs, *sn, *sv, *y, *p, *w, *beta;
+    int* ctl;     // phase, j, stall
+    int R, HS;
+    __device__ __forceinline__ void bind(void* mem, int r) {
+        R = r;
+        HS = r + 1;
+        double* d = reinterpret_cast<double*>(mem);
+        Q = d;   d += (size_t)(r + 1) * QS;
+        H = d;   d += (size_t)r * (r + 1);
+        cs = d;  d += r;
+        sn = d;  d += r;
+        sv = d;  d += r + 1;
+        y = d;   d += r;
+        p = d;   d += r + 1;
+        w = d;   d += N;
+        beta = d; d += 1;
+        ctl = reinterpret_cast<int*>(d);
+    }
 };
 
 // One step of that solve in wavefront 0 (all 64 lanes call it; lanes idx < N own element idx).  u(idx) = the grid
@@ -1270,58 +1294,67 @@ struct GmState {
 // < N; times 1/(tau n) and rounded to float32 by the caller) and returns 1 if the solve is over, else 0.
 // Lane 0 writes the result fields through the references.
 template <int N, class U>
-__device__ __forceinline__ int gmres_step(GmState<N>& gm, U u, const double* s_v, double* s_g, double tol, double vnorm,
+__device__ __forceinline__ int gmres_step(const GmView<N>& gm, U u, const double* s_v, double* s_g, double tol, double vnorm,
                                          int max_iter, int& s_iters, int& s_conv, int& s_bad, double& s_res,
                                          double& hnext) {
+    static_assert(N <= 64, "one lane per unknown and per basis vector");
+    constexpr int QS = GmView<N>::QS;
     const int lane = threadIdx.x;
     wave_lds_sync();
-    const int R = __builtin_amdgcn_readfirstlane(gm.R);
-    const int phase = __builtin_amdgcn_readfirstlane(gm.phase);
+    const int R = gm.R, HS = gm.HS;
+    const int phase = __builtin_amdgcn_readfirstlane(gm.ctl[0]);
     int over = 0;
     hnext = 0.0;
     if (phase == 0) {
-        const int j = __builtin_amdgcn_readfirstlane(gm.j);
-        if (lane < N) gm.w[lane] = gm.Q[j][lane] - u(lane);
+        const int j = __builtin_amdgcn_readfirstlane(gm.ctl[1]);
+        double* hcol = gm.H + (size_t)j * HS;
+        if (lane < N) gm.w[lane] = gm.Q[j * QS + lane] - u(lane);
         wave_lds_sync();
+        double x = 0.0;
         for (int round = 0; round < 2; ++round) {
             // lane i <= j: h_i = q_i . w (its own row, element by element); then lane idx: w -= sum_i h_i q_i
-            if (lane <= j && lane < N + 1) {
+            if (lane <= j) {
+                const double* row = gm.Q + lane * QS;
                 double pr = 0.0;
-                for (int idx = 0; idx < N; ++idx) pr += gm.Q[lane][idx] * gm.w[idx];
+#pragma unroll 8
+                for (int idx = 0; idx < N; ++idx) pr += row[idx] * gm.w[idx];
                 gm.p[lane] = pr;
-                gm.H[j][lane] = round ? gm.H[j][lane] + pr : pr;
+                hcol[lane] = round ? hcol[lane] + pr : pr;
             }
             wave_lds_sync();
             if (lane < N) {
-                double x = gm.w[lane];
-                for (int i = 0; i <= j; ++i) x -= gm.p[i] * gm.Q[i][lane];
+                x = gm.w[lane];
+#pragma unroll 4
+                for (int i = 0; i <= j; ++i) x -= gm.p[i] * gm.Q[i * QS + lane];
                 gm.w[lane] = x;
             }
             wave_lds_sync();
         }
+        // |w|^2 across the lanes (valid in lane 0)
+        const double w2 = first_lanes_sum_d_dpp<N>(lane < N ? x * x : 0.0);
         int next = 0;  // 0 next basis vector, 1 cycle over: apply to g, 3 done
         int nj_new = 0;
         double scale = 0.0;
         if (lane == 0) {
-            double w2 = 0.0;
-            for (int idx = 0; idx < N; ++idx) w2 += gm.w[idx] * gm.w[idx];
             const double hn = fast_sqrt_d(w2);
-            double* hcol = gm.H[j];
+            // the earlier rotations on the new column; the running element stays in a register
+            double hi = hcol[0];
             for (int i = 0; i < j; ++i) {
-                const double t0 = gm.cs[i] * hcol[i] + gm.sn[i] * hcol[i + 1];
-                hcol[i + 1] = -gm.sn[i] * hcol[i] + gm.cs[i] * hcol[i + 1];
-                hcol[i] = t0;
+                const double h1 = hcol[i + 1], c = gm.cs[i], sn = gm.sn[i];
+                hcol[i] = c * hi + sn * h1;
+                hi = -sn * hi + c * h1;
             }
-            const double hj = hcol[j];
+            const double hj = hi;
             const double rr = fast_sqrt_d(hj * hj + hn * hn);
             const double irr = rr > 0.0 ? fast_rcp_d(rr) : 0.0;
             const double cj = rr > 0.0 ? hj * irr : 1.0, sj = hn * irr;
             gm.cs[j] = cj;
             gm.sn[j] = sj;
             hcol[j] = rr;
-            gm.sv[j + 1] = -sj * gm.sv[j];
-            gm.sv[j] = cj * gm.sv[j];
-            const double est = fabs(gm.sv[j + 1]);
+            const double svj = gm.sv[j];
+            gm.sv[j + 1] = -sj * svj;
+            gm.sv[j] = cj * svj;
+            const double est = fabs(sj * svj);
             s_iters += 1;
             s_res = est * est;
             const bool finite = (w2 <= 1.7e308) && (rr <= 1.7e308);
@@ -1331,41 +1364,47 @@ __device__ __forceinline__ int gmres_step(GmState<N>& gm, U u, const double* s_v
                 s_bad = 1;
                 next = 3;
             } else if (vanished || last || est <= 0.5 * tol * vnorm) {
-                const int nj = (rr > 0.0) ? j + 1 : j;
-                for (int i = nj - 1; i >= 0; --i) {
-                    double t0 = gm.sv[i];
-                    for (int l = i + 1; l < nj; ++l) t0 -= gm.H[l][i] * gm.y[l];
-                    gm.y[i] = t0 * fast_rcp_d(gm.H[i][i]);
-                }
-                gm.j = nj;
-                nj_new = nj;
+                nj_new = (rr > 0.0) ? j + 1 : j;
+                gm.ctl[1] = nj_new;
                 next = 1;
             } else {
-                gm.j = j + 1;
+                gm.ctl[1] = j + 1;
                 scale = fast_rcp_d(hn);
             }
         }
         wave_lds_sync();
-        // (what lane 0 decided travels in registers: the other lanes must not take their own stale view of gm.j)
+        // (what lane 0 decided travels in registers: the other lanes must not take their own stale view of the state)
         next = __builtin_amdgcn_readfirstlane(next);
         nj_new = __builtin_amdgcn_readfirstlane(nj_new);
         scale = __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(scale)),
                                  __builtin_amdgcn_readfirstlane(__double2loint(scale)));
         if (next == 0) {
             if (lane < N) {
-                const double q = gm.w[lane] * scale;
-                gm.Q[j + 1][lane] = q;
+                const double q = x * scale;
+                gm.Q[(j + 1) * QS + lane] = q;
                 hnext = q;
             }
         } else if (next == 1) {
             const int nj = nj_new;
+            // back substitution of the triangular system, one unknown per step: lane l holds the running right-hand
+            // side of row l; y_i is taken from lane i and leaves every row above it
+            double t = (lane < nj) ? gm.sv[lane] : 0.0;
+            for (int i = nj - 1; i >= 0; --i) {
+                const double ti = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(t), i),
+                                                   __builtin_amdgcn_readlane(__double2loint(t), i));
+                const double yi = ti * fast_rcp_d(gm.H[(size_t)i * HS + i]);
+                if (lane < i) t -= gm.H[(size_t)i * HS + lane] * yi;
+                if (lane == i) gm.y[i] = yi;
+            }
+            wave_lds_sync();
             if (lane < N) {
                 double g = s_g[lane];
-                for (int i = 0; i < nj; ++i) g += gm.y[i] * gm.Q[i][lane];
+#pragma unroll 4
+                for (int i = 0; i < nj; ++i) g += gm.y[i] * gm.Q[i * QS + lane];
                 s_g[lane] = g;
                 hnext = g;
             }
-            if (lane == 0) gm.phase = 1;
+            if (lane == 0) gm.ctl[0] = 1;
         } else {
             over = 1;
         }
@@ -1373,16 +1412,11 @@ __device__ __forceinline__ int gmres_step(GmState<N>& gm, U u, const double* s_v
     }
     // phase 1: true residual at g
     double r = 0.0;
-    if (lane < N) {
-        r = s_v[lane] + u(lane) - s_g[lane];
-        gm.Q[0][lane] = r;
-    }
-    wave_lds_sync();
+    if (lane < N) r = s_v[lane] + u(lane) - s_g[lane];
+    const double r2 = first_lanes_sum_d_dpp<N>(r * r);
     int next = 2;  // 2 new cycle from the residual, 3 done
     double scale = 0.0;
     if (lane == 0) {
-        double r2 = 0.0;
-        for (int idx = 0; idx < N; ++idx) r2 += gm.Q[0][idx] * gm.Q[0][idx];
         const double beta = fast_sqrt_d(r2);
         s_iters += 1;
         s_res = r2;
@@ -1393,13 +1427,13 @@ __device__ __forceinline__ int gmres_step(GmState<N>& gm, U u, const double* s_v
             s_conv = 1;
             next = 3;
         } else {
-            gm.stall = (beta > 0.95 * gm.beta) ? gm.stall + 1 : 0;
-            if (gm.stall >= 2 || s_iters + 2 > max_iter) next = 3;
+            gm.ctl[2] = (beta > 0.95 * gm.beta[0]) ? gm.ctl[2] + 1 : 0;
+            if (gm.ctl[2] >= 2 || s_iters + 2 > max_iter) next = 3;
         }
         if (next == 2) {
-            gm.beta = beta;
-            gm.phase = 0;
-            gm.j = 0;
+            gm.beta[0] = beta;
+            gm.ctl[0] = 0;
+            gm.ctl[1] = 0;
             gm.sv[0] = beta;
             scale = fast_rcp_d(beta);
         }
@@ -1411,7 +1445,7 @@ __device__ __forceinline__ int gmres_step(GmState<N>& gm, U u, const double* s_v
     if (next == 2) {
         if (lane < N) {
             const double q = r * scale;
-            gm.Q[0][lane] = q;
+            gm.Q[lane] = q;
             hnext = q;
         }
         return 0;
@@ -1441,9 +1475,11 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     __shared__ float s_Cf[KD], s_Hs[KD], s_Hv[KD], s_Ff[KD];
     __shared__ int s_done, s_iters, s_conv, s_attempt, s_grow, s_halv, s_bad, s_restart;
     __shared__ double s_alpha, s_prev, s_vnorm, s_res;
-    // minimal-residual solve (BWD_GMRES): offered for k d <= 16 to teams in which every workgroup receives the totals
-    constexpr bool HAS_GMRES = KD <= 16;
-    __shared__ GmState<HAS_GMRES ? KD : 1> gm;
+    // minimal-residual solve (BWD_GMRES): offered to teams in which every workgroup receives the totals; its state lies
+    // in the dynamic LDS at pa.gm_off (behind the tiles), only in launches of that mode
+    extern __shared__ double s_dyn_d[];
+    GmView<KD> gm;
+    gm.bind(reinterpret_cast<char*>(s_dyn_d) + pa.gm_off, gm_basis_length(pa.gm_basis, KD));
 
     const int tid = threadIdx.x, wg = pa.wg;
     const int64_t base = (int64_t)wg * pa.per;
@@ -1624,7 +1660,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         }
     }
     __syncthreads();
-    if constexpr (HAS_GMRES) {
+    {
         if (mode == BWD_GMRES && !s_done) {
             // from g = 0: the first residual is v itself, the first basis vector v / ||v||  (every workgroup holds v)
             if (tid < 64) {
@@ -1636,18 +1672,17 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                 const double vn = sqrt(v2), inv = v2 > 0.0 ? 1.0 / vn : 0.0;
                 if (tid < KD) {
                     const double q = s_v[tid] * inv;
-                    gm.Q[0][tid] = q;
+                    gm.Q[tid] = q;
                     s_g[tid] = 0.0;
                     s_Hs[tid] = (float)(q * s_rn[tid / D]);
                 }
                 if (tid == 0) {
                     s_vnorm = v2;  // (the float64 norm of the float64 v, not the sum of float32 parts)
-                    gm.phase = 0;
-                    gm.j = 0;
-                    gm.stall = 0;
-                    gm.beta = vn;
+                    gm.ctl[0] = 0;
+                    gm.ctl[1] = 0;
+                    gm.ctl[2] = 0;
+                    gm.beta[0] = vn;
                     gm.sv[0] = vn;
-                    gm.R = pa.gm_basis < KD ? (pa.gm_basis < 1 ? 1 : pa.gm_basis) : KD;
                     if (v2 == 0.0) {  // v = 0: g = 0 is the solution
                         s_conv = 1;
                         s_done = 1;
@@ -1666,7 +1701,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         publish_partials<KD>(pa, seq, acc, xs);
         IDKM_STAMP(2);
         const double alpha = s_alpha;
-        if constexpr (HAS_GMRES) {
+        {
             if (mode == BWD_GMRES) {
                 // (offered only where every workgroup receives the totals: a team of one, or the two-level exchange)
                 if (tree) {

@@ -124,8 +124,8 @@ def test_full_device_teams_on_the_persistent_path(ctx, k, d, m, tau, seed, dist)
     if not (bi["info"].converged or ri["converged"]):
         assert bi["info"].iters == ri["iters"] and bi["info"].alpha == ri["alpha"]
     assert rel(bi["dW"].cpu().numpy(), ri["dW"]) < TOL_GRAD, rel(bi["dW"].cpu().numpy(), ri["dW"])
-    if k * d <= 16:
-        bg = ctx.backward(Gd, binding.BWD_GMRES, tol=1e-5, max_iter=60)
+    if k * d <= 64:      # (every case: the minimal-residual solve inside the persistent kernel, basis of up to k d vectors)
+        bg = ctx.backward(Gd, binding.BWD_GMRES, tol=1e-5, max_iter=200)
         assert bg["info"].path == binding.PATH_PERSISTENT
         gg = ctx.get_cotangents(k, d)[1]
         res = rj["v"] + orc.vjp_F(Cg, W, tau, dist, gg)[0] - gg
