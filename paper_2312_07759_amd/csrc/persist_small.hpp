@@ -1025,6 +1025,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     // reducer r is workgroup r; with fewer than R workgroups the first ones take several slices in turn
     unsigned int seq = pa.seq_base;
 
+    int r_iters = 0;
     // Centre update of the whole codebook (Alg. 1) and the stop test from grid totals every workgroup holds (a team
     // of one, or the two-level exchange): tot(i) is total i of the K (D+1) sums.  Wavefront 0; lane 0 decides.
     auto update_all = [&](auto tot) {
@@ -1042,14 +1043,15 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
             s_Cf[tid] = cn;
         }
         const double r2 = first_lanes_sum_d_dpp<KD>(df2);
+        r_iters += 1;  // (wavefront 0 counts in a register: nothing on this path waits for an LDS read of the state)
         if (tid == 0) {
-            s_iters += 1;
+            s_iters = r_iters;
             s_res = r2;  // squared; the root is taken once, when the solve is over
             const bool bad = !(r2 <= 1.7e308);
             if (bad) s_bad = 1;
             const bool conv = r2 < tol * tol;
             s_conv = conv ? 1 : 0;
-            if (conv || bad || s_iters >= max_iter) s_done = 1;
+            if (conv || bad || r_iters >= max_iter) s_done = 1;
         }
     };
 
@@ -1693,6 +1695,18 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         }
     }
 
+    // Where every workgroup receives the totals (a team of one, the two-level exchange) wavefront 0 keeps the state of
+    // the averaged iteration in registers -- its own element of g, v and 1/(tau n), the damping factor, the counters of
+    // the restart rule -- and every lane takes the same decision from the same step norm: between the arrival of the
+    // totals and the next pass there is then one barrier and no read of that state from LDS.
+    double r_g = 0.0, r_v = 0.0, r_rn = 0.0, r_alpha = pa.alpha, r_prev = __builtin_inf();
+    const double vnorm2 = s_vnorm;
+    int r_grow = 0, r_attempt = 0, r_halv = 0, r_iters = 0;
+    if (tid < KD) {
+        r_g = s_g[tid];
+        r_v = s_v[tid];
+        r_rn = s_rn[tid / D];
+    }
     while (!s_done) {
         IDKM_STAMP(0);
         any_tile_pass<K, D, DIST, PASS_B2, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
@@ -1700,7 +1714,6 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         ++seq;
         publish_partials<KD>(pa, seq, acc, xs);
         IDKM_STAMP(2);
-        const double alpha = s_alpha;
         {
             if (mode == BWD_GMRES) {
                 // (offered only where every workgroup receives the totals: a team of one, or the two-level exchange)
@@ -1728,29 +1741,90 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         }
         if (pa.G == 1 || tree) {
             // a team of one has no exchange: its partial sums (xs.own) are the totals; with the two-level exchange
-            // every workgroup receives the totals (xs.totd).  Either way the whole of g is updated here and the step
-            // norm goes where the decision below expects the reducers' parts
+            // every workgroup receives the totals (xs.totd).  Either way the whole of g is updated here
+            bool wave0_abort = false;
             if (tree) {
-                if (!tree_totals<KD>(pa, seq, xs)) return;
+                if constexpr (KD <= 8) {
+                    // (hop 2 inside wavefront 0, no barrier before the update)
+                    if (wg < DIES && !tree8_die_totals(pa, seq, xs)) return;
+                    if (tid < 64) {
+                        tree8_grid_totals_wave0<KD>(pa, seq, xs);
+                        wave0_abort = xs.abort != 0;
+                    }
+                } else {
+                    if (!tree_totals<KD>(pa, seq, xs)) return;
+                }
             } else {
                 __syncthreads();
             }
-            if (tid < 64) {
-                double d2 = 0.0;
+            IDKM_STAMP(4);
+            if (tid < 64 && !wave0_abort) {
+                double d2 = 0.0, gn = 0.0;
                 if (tid < KD) {
-                    const double g = s_g[tid];
                     const double u = tree ? xs.totd[tid] : (double)xs.own[tid];
-                    const double gn = alpha * (s_v[tid] + u) + (1.0 - alpha) * g;
-                    const double df = gn - g;
+                    gn = r_alpha * (r_v + u) + (1.0 - r_alpha) * r_g;
+                    const double df = gn - r_g;
                     d2 = df * df;
-                    s_g[tid] = gn;
-                    xs.bc[tid] = __float_as_uint((float)(gn * s_rn[tid / D]));
                 }
                 d2 = first_lanes_sum_d_dpp<KD>(d2);
-                if (tid < R) xs.bc[KD + tid] = (tid == 0) ? __float_as_uint((float)d2) : 0u;
+                // the squared step norm as every lane sees it (rounded to float32 like the word the plain exchange
+                // broadcasts, so that all forms of the exchange take the same decisions)
+                const double dn = (double)__uint_as_float((unsigned int)__builtin_amdgcn_readfirstlane((int)__float_as_uint((float)d2)));
+                bool restart = false, done = false, conv = false, diverged = false, bad = false;
+                int grow = r_grow;
+                const int attempt = r_attempt + 1;
+                if (!(dn <= 1.7e308)) {
+                    diverged = true;
+                } else if (dn <= tol * tol * vnorm2) {
+                    conv = true;
+                    done = true;
+                } else {
+                    grow = (dn > r_prev) ? grow + 1 : 0;
+                    if (grow >= 5) diverged = true;
+                }
+                if (!done && !diverged && attempt >= max_iter) done = true;
+                if (diverged) {
+                    if (r_halv < 6) {
+                        restart = true;
+                    } else {
+                        done = true;
+                        if (!(dn <= 1.7e308)) bad = true;  // every damping factor tried ended in a non-finite step
+                    }
+                }
+                r_iters += 1;
+                if (restart) {
+                    // back to g = v with the halved alpha
+                    r_alpha *= 0.5;
+                    r_halv += 1;
+                    r_attempt = 0;
+                    r_grow = 0;
+                    r_prev = __builtin_inf();
+                    r_g = r_v;
+                } else {
+                    r_attempt = attempt;
+                    r_grow = grow;
+                    if (!diverged && !conv) r_prev = dn;
+                    r_g = gn;
+                }
+                if (tid < KD) {
+                    s_g[tid] = r_g;
+                    s_Hs[tid] = restart ? s_Hv[tid] : (float)(gn * r_rn);
+                }
+                if (tid == 0) {  // (stores only)
+                    s_iters = r_iters;
+                    s_res = dn;
+                    s_alpha = r_alpha;
+                    if (conv) s_conv = 1;
+                    if (bad) s_bad = 1;
+                    if (done) s_done = 1;
+                }
             }
             __syncthreads();
-        } else {
+            if (xs.abort) return;
+            continue;
+        }
+        const double alpha = s_alpha;
+        {
         for (int r = wg; r < R; r += pa.G) {
             if (!reduce_slice<KD, WPR>(pa, seq, r * WPR, xs)) return;
             if (tid < 64) {
