@@ -42,9 +42,11 @@ constexpr int XBCAST = 128;  // words reserved in buf2
 constexpr int DIES = 8;      // accelerator dies of the device (each with its own L2); workgroup b runs on die b mod 8
 constexpr int TREE_MIN_G = 64;  // smallest team that uses the two-level exchange
 // Two-level exchange: passes with up to this many sums per workgroup publish per WAVEFRONT (no LDS stage on the sending
-// side).  Measured at k = 16, d = 1: with 32 sums the leader's 16 loads per thread cost more than the senders save (forward
-// 5.45 -> 5.87 us per evaluation), with 16 sums it is a small gain ((dF/dC)^T pass 6.37 -> 6.28 us).
-constexpr int WAVE_WORDS_MAX = 16;
+// side, hop 2 inside wavefront 0).  With more sums the leader's loads per thread cost more than the senders save:
+// measured with 9 .. 16 sums (one 16-word piece per wavefront) against the workgroup-level form below, forward at
+// k = 8, d = 1 7.55 against 7.05 us per evaluation, k = 4, d = 2 5.35 against 4.80, (dF/dC)^T pass at k = 16, d = 1
+// 6.26 against 5.86; with 32 sums 5.87 against 5.45.
+constexpr int WAVE_WORDS_MAX = 8;
 #ifndef IDKM_HOP2_PIPE
 #define IDKM_HOP2_PIPE 1
 #endif
@@ -131,7 +133,7 @@ struct XShared {
     int abort;
     // two-level exchange
     int local;                       // this workgroup runs on its leader's die: its partial sums need only reach the L2
-    float stage2[DIES * (NACC <= 8 ? 8 : (NACC <= 16 ? 16 : (NACC <= 32 ? 32 : NACC)))];  // totals of the dies, [die][slot]
+    float stage2[DIES * (NACC <= 8 ? 8 : NACC)];  // totals of the dies, [die][slot]
     double totd[NACC];               // grid totals
 };
 
@@ -207,16 +209,11 @@ __device__ __forceinline__ void publish_rows(const float (&acc)[NACC], XS& xs, i
 template <int NACC, class XS>
 __device__ __forceinline__ void publish_waves(const PArgs& pa, unsigned int seq, const float (&acc)[NACC], XS& xs);
 template <int NACC, class XS>
-__device__ __forceinline__ void publish_waves_n(const PArgs& pa, unsigned int seq, const float (&acc)[NACC], XS& xs);
-template <int NACC, class XS>
 __device__ __forceinline__ void publish_partials(const PArgs& pa, unsigned int seq, const float (&acc)[NACC], XS& xs) {
     const int tid = threadIdx.x, lane = tid & 63;
     if constexpr (NACC <= WAVE_WORDS_MAX) {
         if (pa.tree) {
-            if constexpr (NACC <= 8)
-                publish_waves<NACC>(pa, seq, acc, xs);
-            else
-                publish_waves_n<NACC>(pa, seq, acc, xs);
+            publish_waves<NACC>(pa, seq, acc, xs);
             return;
         }
     }
@@ -632,161 +629,14 @@ __device__ __forceinline__ void tree8_grid_totals_wave0(const PArgs& pa, unsigne
     wave_lds_sync();  // the caller's lanes read one another's totals
 }
 
-// ---------------------------------------------------------------- two-level exchange, 9 .. 32 sums per workgroup
-
-// The same scheme with 16 or 32 slots per wavefront (k = 8 and k = 16 with scalar weights, k d <= 32 in the backward
-// passes): after the halving network a lane of a row holds NP / 16 totals, slot (l % 16) (NP / 16) + i being
-// accumulator row_sum_index<NP>(l % 16, i).  A workgroup's line is 4 NP words; hop 2 goes through LDS (8 NP words do
-// not fit one wavefront).
-constexpr int wave_slots(int nacc) { return nacc <= 8 ? 8 : (nacc <= 16 ? 16 : 32); }
-template <int NP>
-__host__ __device__ constexpr int slot_acc_n(int slot) {
-    constexpr int LIVE = NP / 16;
-    const int l = slot / LIVE, i = slot % LIVE;
-    int idx = i, half = NP / 2;
-    for (int s = 0; s < 4; ++s) {
-        if (half >= 1) idx += ((l >> s) & 1) * half;
-        half /= 2;
-    }
-    return idx;
-}
-
-template <int NACC, class XS>
-__device__ __forceinline__ void publish_waves_n(const PArgs& pa, unsigned int seq, const float (&acc)[NACC], XS& xs) {
-    constexpr int NP = wave_slots(NACC), LIVE = NP / 16;
-    static_assert(NACC > 8 && NACC <= 32, "16 or 32 slots per wavefront");
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    float v[NP];
-#pragma unroll
-    for (int q = 0; q < NP; ++q) v[q] = (q < NACC) ? acc[q] : 0.f;
-    row_sums<NP>(v, lane);
-#pragma unroll
-    for (int i = 0; i < LIVE; ++i) v[i] = cross_row_sum(v[i]);
-    if (lane < 16) {
-        unsigned long long* dst = &pa.buf1[((size_t)(seq & 1u) * PT + pa.wg) * XLINE + wave * NP + lane * LIVE];
-#pragma unroll
-        for (int i = 0; i < LIVE; ++i) {
-            xs.own[wave * NP + lane * LIVE + i] = v[i];
-            if (pa.wg >= DIES) {  // (a leader reads its own sums from xs.own)
-                if (xs.local)
-                    st_word_die(dst + i, pack_f(seq, v[i]));
-                else
-                    st_word(dst + i, pack_f(seq, v[i]));
-            }
-        }
-    }
-}
-
-// hop 1, leader side: thread t takes slot t % NP of members t / NP, t / NP + PT / NP, ... (all four wavefront words of
-// each), adds them in float64; the member groups of a wavefront are added across lanes, the four wavefronts through LDS.
-template <int NP, class XS>
-__device__ __forceinline__ bool treeN_die_totals(const PArgs& pa, unsigned int seq, XS& xs) {
-    constexpr int NG = PT / NP;   // member groups: 16 or 8
-    constexpr int MPT = 32 / NG;  // members per thread: 2 or 4
-    const int tid = threadIdx.x, x = pa.wg, p = tid % NP, mg = tid / NP;
-    const int nmem = (pa.G - x + DIES - 1) / DIES;
-    const unsigned long long* line0 = pa.buf1 + ((size_t)(seq & 1u) * PT + x) * XLINE + p;
-    unsigned long long w[MPT * 4];
-    bool valid[MPT];
-#pragma unroll
-    for (int u = 0; u < MPT; ++u) {
-        const int mi = mg + NG * u;
-        valid[u] = mi >= 1 && mi < nmem;
-    }
-    bool aborted = false;
-    unsigned int spins = 0;
-    for (;;) {
-#pragma unroll
-        for (int u = 0; u < MPT; ++u)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                w[u * 4 + q] = valid[u] ? ld_word(line0 + (size_t)(mg + NG * u) * DIES * XLINE + q * NP) : pack_f(seq, 0.f);
-        bool ok = true;
-#pragma unroll
-        for (int q = 0; q < MPT * 4; ++q) ok = ok && ((unsigned int)(w[q] >> 32) == seq);
-        if (ok) break;
-        ++spins;
-        if (spins > pa.spin_limit ||
-            ((spins & 31u) == 0u && __hip_atomic_load(pa.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == pa.seq_base + 1u)) {
-            aborted = true;
-            break;
-        }
-    }
-    __syncthreads();  // the wavefronts' stores to xs.own lie before this barrier
-    double s = 0.0;
-#pragma unroll
-    for (int u = 0; u < MPT; ++u) {
-        double m4;
-        if (mg + NG * u == 0)
-            m4 = ((double)xs.own[p] + (double)xs.own[NP + p]) + ((double)xs.own[2 * NP + p] + (double)xs.own[3 * NP + p]);
-        else
-            m4 = ((double)__uint_as_float((unsigned int)w[u * 4]) + (double)__uint_as_float((unsigned int)w[u * 4 + 1])) +
-                 ((double)__uint_as_float((unsigned int)w[u * 4 + 2]) + (double)__uint_as_float((unsigned int)w[u * 4 + 3]));
-        s += m4;  // (members that do not exist carry zeros)
-    }
-    // the 64 / NP member groups of this wavefront
-    if constexpr (NP == 16) {
-        s = cross_row_sum_d(s);
-    } else {
-        u32x2_t lo = __builtin_amdgcn_permlane32_swap((unsigned)__double2loint(s), (unsigned)__double2loint(s), false, false);
-        u32x2_t hi = __builtin_amdgcn_permlane32_swap((unsigned)__double2hiint(s), (unsigned)__double2hiint(s), false, false);
-        s = __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
-    }
-    if ((tid & 63) < NP) xs.red2[(tid >> 6) * NP + p] = s;
-    if (aborted) {
-        xs.abort = 1;
-        __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    if (xs.abort) return false;
-    if (tid < NP) {
-        const float tot = (float)((xs.red2[tid] + xs.red2[NP + tid]) + (xs.red2[2 * NP + tid] + xs.red2[3 * NP + tid]));
-        xs.stage2[x * NP + tid] = tot;
-        st_word(&pa.buf3[((size_t)(seq & 1u) * DIES + x) * XLINE + tid], pack_f(seq, tot));
-    }
-    return true;
-}
-
-// hop 2: thread t < 8 NP waits for slot t % NP of die t / NP; the eight dies are added by NP threads in float64; the
-// grid totals go to xs.totd[accumulator].  Ends with a barrier.
-template <int NACC, int NP, class XS>
-__device__ __forceinline__ bool treeN_grid_totals(const PArgs& pa, unsigned int seq, XS& xs) {
-    const int tid = threadIdx.x, x = tid / NP, p = tid % NP;
-    bool aborted = false;
-    if (tid < DIES * NP && x != pa.wg) {  // (a leader has left its own die's totals in xs.stage2)
-        unsigned long long w[1];
-        if (poll_words<1>(pa, pa.buf3 + ((size_t)(seq & 1u) * DIES + x) * XLINE + p, 0, seq, w))
-            xs.stage2[tid] = __uint_as_float((unsigned int)w[0]);
-        else
-            aborted = true;
-    }
-    if (aborted) {
-        xs.abort = 1;
-        __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    if (xs.abort) return false;
-    if (tid < NP && slot_acc_n<NP>(tid) < NACC) {
-        double t[DIES];
-#pragma unroll
-        for (int y = 0; y < DIES; ++y) t[y] = (double)xs.stage2[y * NP + tid];
-        xs.totd[slot_acc_n<NP>(tid)] = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
-    }
-    __syncthreads();
-    return true;
-}
-
 // Both hops after publish_partials: grid totals of the NACC sums in xs.totd, in every workgroup; ends with a barrier.
 template <int NACC, class XS>
 __device__ __forceinline__ bool tree_totals(const PArgs& pa, unsigned int seq, XS& xs) {
-    if constexpr (NACC <= 8) {
+    if constexpr (NACC <= WAVE_WORDS_MAX) {
         if (pa.wg < DIES && !tree8_die_totals(pa, seq, xs)) return false;
         if (threadIdx.x < 64) tree8_grid_totals_wave0<NACC>(pa, seq, xs);
         __syncthreads();
         return xs.abort == 0;
-    } else if constexpr (NACC <= WAVE_WORDS_MAX) {
-        if (pa.wg < DIES && !treeN_die_totals<wave_slots(NACC)>(pa, seq, xs)) return false;
-        return treeN_grid_totals<NACC, wave_slots(NACC)>(pa, seq, xs);
     } else {
         if (pa.wg < DIES && !tree_die_totals<NACC>(pa, seq, xs)) return false;
         return tree_grid_totals<NACC>(pa, seq, xs);
@@ -1069,7 +919,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
             __syncthreads();
             if (tid < 64) update_all([&](int i) { return (double)xs.own[i]; });
         } else if (pa.tree) {
-            if constexpr (NACC <= 8) {
+            if constexpr (NACC <= WAVE_WORDS_MAX) {
                 // hop 2 and the update stay inside wavefront 0: no barrier between them
                 if (wg < DIES) {
                     if (!tree8_die_totals(pa, seq, xs)) return;
@@ -1159,16 +1009,12 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     if (pa.tree) {
         // only workgroup 0 needs these totals: it writes the state and, last, the word that says the launch ran to
         // its end; the other leaders add up their die and leave, everybody else has left already
-        if constexpr (NACC <= 8) {
+        if constexpr (NACC <= WAVE_WORDS_MAX) {
             if (wg < DIES && !tree8_die_totals(pa, seq, xs)) return;
             if (wg != 0) return;
             if (tid < 64) tree8_grid_totals_wave0<NACC>(pa, seq, xs);
             __syncthreads();
             if (xs.abort) return;
-        } else if constexpr (NACC <= WAVE_WORDS_MAX) {
-            if (wg < DIES && !treeN_die_totals<wave_slots(NACC)>(pa, seq, xs)) return;
-            if (wg != 0) return;
-            if (!treeN_grid_totals<NACC, wave_slots(NACC)>(pa, seq, xs)) return;
         } else {
             if (wg < DIES && !tree_die_totals<NACC>(pa, seq, xs)) return;
             if (wg != 0) return;
@@ -1744,7 +1590,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
             // every workgroup receives the totals (xs.totd).  Either way the whole of g is updated here
             bool wave0_abort = false;
             if (tree) {
-                if constexpr (KD <= 8) {
+                if constexpr (KD <= WAVE_WORDS_MAX) {
                     // (hop 2 inside wavefront 0, no barrier before the update)
                     if (wg < DIES && !tree8_die_totals(pa, seq, xs)) return;
                     if (tid < 64) {
