@@ -662,7 +662,24 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
             hs[j][r] = Item::USE_H ? s_Hs[j * D + r] : 0.f;
             ff[j][r] = Item::USE_F ? s_Ff[j * D + r] : 0.f;
         }
-    Item::prepare(c, hs, ff);
+    if constexpr (Item::FWD_DOT) {
+        // the per-codeword operands of the product form: from the caller's LDS table where it keeps one (fwd_dot_tables:
+        // formed once per evaluation by wavefront 0), else formed here by every lane
+        if (s_Hs) {
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+#pragma unroll
+                for (int r = 0; r < D; ++r) hs[j][r] = s_Hs[j * D + r];
+                ff[j][0] = s_Hs[K * D + j];
+            }
+#pragma unroll
+            for (int r = 0; r < D; ++r) ff[r][1] = s_Hs[K * D + K + r];
+        } else {
+            Item::prepare(a, c, hs, ff);
+        }
+    } else {
+        Item::prepare(a, c, hs, ff);
+    }
     if constexpr (Item::FOLD_HF) {
         // the codebook is the same for all lanes: as scalar registers it leaves the vector registers to h and the sums
 #pragma unroll
@@ -744,7 +761,7 @@ __device__ __forceinline__ void tile_pass_global(const Args& a, const float* gw,
             hs[j][r] = Item::USE_H ? s_Hs[j * D + r] : 0.f;
             ff[j][r] = Item::USE_F ? s_Ff[j * D + r] : 0.f;
         }
-    Item::prepare(c, hs, ff);
+    Item::prepare(a, c, hs, ff);
 #pragma unroll
     for (int q = 0; q < Item::NACC; ++q) acc[q] = 0.f;
     constexpr int VPL = 4 / D;                // vectors per 16-byte load
@@ -829,6 +846,32 @@ constexpr int cw_per_reducer(int K, int D) {
     return p > K ? K : p;
 }
 
+// Operands of the product form of the forward loop (SmallItem::FWD_DOT), formed once per evaluation by wavefront 0
+// (all 64 lanes call; lane j d + r < k d passes component r of codeword j, the other lanes zero) instead of by every lane
+// at the start of its pass:  tab[j d + r] = 2 s^2 (c_jr - mu_r), tab[k d + j] = -s^2 |c_j - mu|^2, tab[k d + k + r] = mu_r,
+// mu the mean codeword.  The sums over codewords and over components run across the lanes.
+template <int K, int D>
+__device__ __forceinline__ void fwd_dot_tables(float c, float s2, float* tab) {
+    static_assert(D == 2 || D == 4, "lane layout j d + r with d a divisor of 4");
+    const int lane = threadIdx.x;
+    // mu_r: over the lanes with the same lane % d
+    float m = c;
+    if (D == 2) m += dpp_f<0x4E, 0xf>(0.f, m);  // quad_perm [2,3,0,1]
+    m += dpp_f<0x124, 0xf>(0.f, m);              // row_ror:4
+    m += dpp_f<0x128, 0xf>(0.f, m);              // row_ror:8
+    m = cross_row_sum(m) * (1.f / K);
+    const float dc = c - m;
+    // |c_j - mu|^2: over the d lanes of codeword j
+    float q = dc * dc;
+    q += dpp_f<0xB1, 0xf>(0.f, q);               // quad_perm [1,0,3,2]
+    if (D == 4) q += dpp_f<0x4E, 0xf>(0.f, q);
+    if (lane < K * D) {
+        tab[lane] = 2.f * s2 * dc;
+        if (lane % D == 0) tab[K * D + lane / D] = -s2 * q;
+        if (lane < D) tab[K * D + K + lane] = m;
+    }
+}
+
 // Forward solve (Alg. 1) and the evaluation at C*, in one launch.
 // GLOBALW: the layer does not fit the chip's LDS; every pass reads the workgroup's share of W from memory.
 template <int K, int D, int DIST, bool SHARED, bool GLOBALW = false>
@@ -847,6 +890,11 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     __shared__ float s_Cf[KD];
     __shared__ int s_done, s_iters, s_conv, s_bad;
     __shared__ double s_res;
+    // product form of the loop's E-step: its per-codeword operands, kept up to date by wavefront 0
+    // (worth it from k d = 32 on: below, what a lane saves at the start of its pass is less than wavefront 0 adds to the
+    // path every workgroup waits on: k = 4, d = 2 4.38 -> 4.64 us per evaluation with the table, k = 16, d = 4 8.65 -> 8.39)
+    constexpr bool DOT = SmallItem<K, D, DIST, PASS_FWD>::FWD_DOT && !GLOBALW && K * D >= 32;
+    __shared__ float s_tab[DOT ? KD + K + D : 1];
 
     const int tid = threadIdx.x, wg = pa.wg;
     const int64_t base = (int64_t)wg * pa.per;
@@ -867,6 +915,9 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
         s_conv = 0;
         s_bad = 0;
         s_res = 0.0;
+    }
+    if constexpr (DOT) {
+        if (tid < 64) fwd_dot_tables<K, D>(tid < KD ? pa.C0[tid] : 0.f, -a.nscale, s_tab);
     }
     __syncthreads();
     const double tol = pa.tol;
@@ -908,7 +959,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     float acc[NACC];
     while (!s_done) {
         IDKM_STAMP(0);
-        any_tile_pass<K, D, DIST, PASS_FWD, SHARED, GLOBALW>(a, pa, s_w, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc);
+        any_tile_pass<K, D, DIST, PASS_FWD, SHARED, GLOBALW>(a, pa, s_w, nullptr, base, cnt, s_Cf, DOT ? s_tab : nullptr, nullptr, acc);
         IDKM_STAMP(1);
         ++seq;
         publish_partials<NACC>(pa, seq, acc, xs);
@@ -995,6 +1046,12 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
                 if (conv || bad || s_iters >= max_iter) s_done = 1;
             }
         }
+        }
+        if constexpr (DOT) {
+            if (tid < 64) {  // (wavefront 0 has just written the new codebook)
+                wave_lds_sync();
+                fwd_dot_tables<K, D>(tid < KD ? s_Cf[tid] : 0.f, -a.nscale, s_tab);
+            }
         }
         __syncthreads();
         IDKM_SUB(10);

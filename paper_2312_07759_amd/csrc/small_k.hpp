@@ -149,8 +149,44 @@ struct SmallItem {
     // subtractions per vector instead of d per codeword.
     static constexpr bool FOLD_HF = ((PASS == PASS_B2 || PASS == PASS_B3) && D >= 2 && K * D >= 32);
 
+    // Forward loop, squared energy, d >= 2: the exponent of a weight of the row softmax (Eq. "aterms") is taken as a
+    // product.  With s^2 = log2(e)/tau and a reference point mu (the mean codeword; the energy does not change when w
+    // and c move together),  -s^2 |w - c_j|^2 = -s^2 |w - mu|^2 + 2 s^2 (c_j - mu).(w - mu) - s^2 |c_j - mu|^2 :  the
+    // first term is the same for every codeword and drops out of the row, the rest is d multiply-adds per codeword
+    // (2 d + 1 operations for differences, squares and scale) at the price of d subtractions per vector.  The row is
+    // shifted by its largest exponent, and the normalisation is folded into the multiply-adds of the M-step (Eq.
+    // "centers").  prepare() leaves 2 s^2 (c_j - mu) in hs[j][.], -s^2 |c_j - mu|^2 in ff[j][0] and mu_r in ff[r][1]
+    // (this pass uses neither h nor F*).  The rounding error of an exponent is a few float32 ulps of
+    // s^2 |c - mu| |w - mu|, i.e. of the exponents themselves; the closest-codeword key of the last pass is not formed
+    // this way.
+    static constexpr bool FWD_DOT = (PASS == PASS_FWD && DIST == DIST_SQL2 && D >= 2 && K >= D);
+
     // Called once per pass by every caller of run(), after it has loaded the tables into registers.
-    static __device__ __forceinline__ void prepare(const float (&c)[K][D], const float (&hs)[K][D], float (&ff)[K][D]) {
+    static __device__ __forceinline__ void prepare(const Args& a, const float (&c)[K][D], float (&hs)[K][D], float (&ff)[K][D]) {
+        if constexpr (FWD_DOT) {
+            const float s2 = -a.nscale;
+            float mu[D];
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                float s = 0.f;
+#pragma unroll
+                for (int j = 0; j < K; ++j) s += c[j][r];
+                mu[r] = s * (1.f / K);
+            }
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                float q = 0.f;
+#pragma unroll
+                for (int r = 0; r < D; ++r) {
+                    const float dc = c[j][r] - mu[r];
+                    hs[j][r] = 2.f * s2 * dc;
+                    q = fmaf(dc, dc, q);
+                }
+                ff[j][0] = -s2 * q;
+            }
+#pragma unroll
+            for (int r = 0; r < D; ++r) ff[r][1] = mu[r];
+        }
         if constexpr (FOLD_HF) {
             static_assert(K >= D, "mu is kept in ff[0..D)[1]");
             float mu[D];
@@ -256,6 +292,39 @@ struct SmallItem {
             for (int j = 0; j < K; ++j) {
                 acc[j * ACCW] = fmaf(p[j], rS, acc[j * ACCW]);
                 acc[j * ACCW + 1] = fmaf(p[j], rw, acc[j * ACCW + 1]);
+            }
+            return;
+        }
+        if constexpr (FWD_DOT) {
+            float wm[D];
+#pragma unroll
+            for (int r = 0; r < D; ++r) wm[r] = w[r] - ff[r][1];
+            float l[K];
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                float x = fmaf(wm[0], hs[j][0], ff[j][0]);
+#pragma unroll
+                for (int r = 1; r < D; ++r) x = fmaf(wm[r], hs[j][r], x);
+                l[j] = x;
+            }
+            float lmax = l[0];
+#pragma unroll
+            for (int j = 1; j < K; ++j) lmax = fmaxf(lmax, l[j]);
+            float p[K], S = 0.f;
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                p[j] = fast_exp2(l[j] - lmax);
+                S = (j == 0) ? p[0] : S + p[j];
+            }
+            const float rS = fast_rcp(S);
+            float rw[D];
+#pragma unroll
+            for (int r = 0; r < D; ++r) rw[r] = rS * w[r];
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                acc[j * ACCW] = fmaf(p[j], rS, acc[j * ACCW]);
+#pragma unroll
+                for (int r = 0; r < D; ++r) acc[j * ACCW + 1 + r] = fmaf(p[j], rw[r], acc[j * ACCW + 1 + r]);
             }
             return;
         }
@@ -404,7 +473,7 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
             hs[j][r] = Item::USE_H ? a.Hs[j * D + r] : 0.f;
             ff[j][r] = Item::USE_F ? a.Ff[j * D + r] : 0.f;
         }
-    Item::prepare(c, hs, ff);
+    Item::prepare(a, c, hs, ff);
 
     float acc[NACC];
 #pragma unroll
