@@ -651,9 +651,9 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 template <int K, int D, int DIST, int PASS, bool SHARED>
 __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const float* s_g, int64_t base, int cnt,
                                           const float* s_Cf, const float* s_Hs, const float* s_Ff,
-                                          float (&acc)[SmallItem<K, D, DIST, PASS>::NACC]) {
+                                          float (&acc)[SmallItem<K, D, DIST, PASS>::NREG]) {
     using Item = SmallItem<K, D, DIST, PASS>;
-    float c[K][D], hs[K][D], ff[K][D];
+    float c[K][D], hs[K][D], ff[K][D + 1];
 #pragma unroll
     for (int j = 0; j < K; ++j)
 #pragma unroll
@@ -680,7 +680,7 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
     } else {
         Item::prepare(a, c, hs, ff);
     }
-    if constexpr (Item::FOLD_HF) {
+    if constexpr (Item::FOLD_HF || (Item::B2_DOT && K * D >= 32)) {
         // the codebook is the same for all lanes: as scalar registers it leaves the vector registers to h and the sums
 #pragma unroll
         for (int j = 0; j < K; ++j)
@@ -688,7 +688,7 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
             for (int r = 0; r < D; ++r) c[j][r] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, c[j][r])));
     }
 #pragma unroll
-    for (int q = 0; q < Item::NACC; ++q) acc[q] = 0.f;
+    for (int q = 0; q < Item::NREG; ++q) acc[q] = 0.f;
     // one wavefront per SIMD: the latencies of a vector's chain (LDS load, exponentials, reciprocal) are hidden by
     // other vectors of the same lane, so vectors are taken in groups whose bodies the scheduler interleaves: in the
     // forward passes groups of UNR while they last, then groups of 4, then single vectors
@@ -738,7 +738,7 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
 #pragma unroll UNR
         for (int it = threadIdx.x; it < cnt; it += PT) one(it);
     }
-    Item::finish(a, acc);
+    Item::finish(a, c, acc);
 }
 
 // The same pass for a layer that does not fit the chip's LDS: W (and dL/dWq) are read from memory in every pass, 16
@@ -750,9 +750,9 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
 template <int K, int D, int DIST, int PASS>
 __device__ __forceinline__ void tile_pass_global(const Args& a, const float* gw, const float* gg, int wg, int G,
                                                  const float* s_Cf, const float* s_Hs, const float* s_Ff,
-                                                 float (&acc)[SmallItem<K, D, DIST, PASS>::NACC]) {
+                                                 float (&acc)[SmallItem<K, D, DIST, PASS>::NREG]) {
     using Item = SmallItem<K, D, DIST, PASS>;
-    float c[K][D], hs[K][D], ff[K][D];
+    float c[K][D], hs[K][D], ff[K][D + 1];
 #pragma unroll
     for (int j = 0; j < K; ++j)
 #pragma unroll
@@ -763,7 +763,7 @@ __device__ __forceinline__ void tile_pass_global(const Args& a, const float* gw,
         }
     Item::prepare(a, c, hs, ff);
 #pragma unroll
-    for (int q = 0; q < Item::NACC; ++q) acc[q] = 0.f;
+    for (int q = 0; q < Item::NREG; ++q) acc[q] = 0.f;
     constexpr int VPL = 4 / D;                // vectors per 16-byte load
     constexpr int NLD = Item::USE_G ? 4 : 8;  // loads in flight per lane and operand
     const int64_t ngroups = a.m / VPL;        // whole 16-byte groups of the layer
@@ -822,7 +822,7 @@ __device__ __forceinline__ void tile_pass_global(const Args& a, const float* gw,
             Item::run(a, it, w, g, c, hs, ff, acc);
         }
     }
-    Item::finish(a, acc);
+    Item::finish(a, c, acc);
 }
 
 // A pass over the workgroup's share of the layer: its LDS tile (w, g: the tile; base, cnt: its place in the layer) or,
@@ -830,7 +830,7 @@ __device__ __forceinline__ void tile_pass_global(const Args& a, const float* gw,
 template <int K, int D, int DIST, int PASS, bool SHARED, bool GLOBALW>
 __device__ __forceinline__ void any_tile_pass(const Args& a, const PArgs& pa, const float* w, const float* g,
                                               int64_t base, int cnt, const float* s_Cf, const float* s_Hs,
-                                              const float* s_Ff, float (&acc)[SmallItem<K, D, DIST, PASS>::NACC]) {
+                                              const float* s_Ff, float (&acc)[SmallItem<K, D, DIST, PASS>::NREG]) {
     if constexpr (GLOBALW)
         tile_pass_global<K, D, DIST, PASS>(a, w, g, pa.wg, pa.G, s_Cf, s_Hs, s_Ff, acc);
     else
@@ -1432,7 +1432,8 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     if (pa.tree && !tree_handshake(pa, xs)) return;
     unsigned int seq = pa.seq_base;
 
-    float acc[KD];
+    float accr[SmallItem<K, D, DIST, PASS_B2>::NREG];            // (the (dF/dC)^T pass may keep more sums in registers than it publishes)
+    float(&acc)[KD] = reinterpret_cast<float(&)[KD]>(accr);
     bool dense_done = false;
     if constexpr (HAS_DENSE) {
         if (mode == BWD_DENSE) {
@@ -1612,7 +1613,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     }
     while (!s_done) {
         IDKM_STAMP(0);
-        any_tile_pass<K, D, DIST, PASS_B2, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, acc);
+        any_tile_pass<K, D, DIST, PASS_B2, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, accr);
         IDKM_STAMP(1);
         ++seq;
         publish_partials<KD>(pa, seq, acc, xs);

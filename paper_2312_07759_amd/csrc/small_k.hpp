@@ -141,13 +141,24 @@ struct SmallItem {
     // dense backward: T[KD][KD], U[KD][D], V[KD]
     static constexpr int NACC = (PASS == PASS_B3) ? 1 : (PASS == PASS_BJ ? KD * KD + KD * D + KD : K * ACCW);
 
+    // (dF/dC)^T pass, squared energy, d >= 2 (the pass an implicit solve repeats): in coordinates relative to the mean
+    // codeword mu, wm = w - mu and cm_j = c_j - mu, the exponents of the row are products as in the forward loop
+    // (FWD_DOT below), l_j = 2 s^2 cm_j.wm - s^2 |cm_j|^2, and  sum_i theta_ij (w_i - c_j)  is accumulated as
+    // sum_i theta_ij wm_i  -  cm_j sum_i theta_ij :  k more sums per lane (registers [K D, K D + K)), folded in by
+    // finish(), instead of d subtractions per (vector, codeword) pair; 2 d + 6 operations per pair and 10 per vector
+    // instead of 5 d + 9 and 2.  prepare() leaves cm in c, h_j.(F*_j - mu) in ff[j][0], mu_r in ff[r][1] and
+    // -s^2 |cm_j|^2 in ff[j][D].
+    static constexpr bool B2_DOT = (PASS == PASS_B2 && DIST == DIST_SQL2 && D >= 2 && K >= D);
+    // accumulators a lane keeps in registers; the first NACC of them are the pass's partial sums after finish()
+    static constexpr int NREG = NACC + (B2_DOT ? K : 0);
+
     // k d >= 32 with d >= 2, (dF/dC)^T pass and last pass: codebook, h and F* (up to 192 values) plus the sums and a
     // vector's own state do not fit 256 registers, and what the compiler moves to the accumulation registers costs a
     // vector-ALU move per use.  There h_j . (w - F*_j) is taken as h_j . (w - mu) - h_j . (F*_j - mu), mu the mean
     // codeword (so that layers far from the origin lose nothing to cancellation): prepare() leaves the k products in
     // ff[j][0] and mu_r in ff[r][1] (the other values of F* are not used again) and run() expects them there; d
     // subtractions per vector instead of d per codeword.
-    static constexpr bool FOLD_HF = ((PASS == PASS_B2 || PASS == PASS_B3) && D >= 2 && K * D >= 32);
+    static constexpr bool FOLD_HF = ((PASS == PASS_B2 || PASS == PASS_B3) && D >= 2 && K * D >= 32) && !B2_DOT;
 
     // Forward loop, squared energy, d >= 2: the exponent of a weight of the row softmax (Eq. "aterms") is taken as a
     // product.  With s^2 = log2(e)/tau and a reference point mu (the mean codeword; the energy does not change when w
@@ -162,7 +173,32 @@ struct SmallItem {
     static constexpr bool FWD_DOT = (PASS == PASS_FWD && DIST == DIST_SQL2 && D >= 2 && K >= D);
 
     // Called once per pass by every caller of run(), after it has loaded the tables into registers.
-    static __device__ __forceinline__ void prepare(const Args& a, const float (&c)[K][D], float (&hs)[K][D], float (&ff)[K][D]) {
+    static __device__ __forceinline__ void prepare(const Args& a, float (&c)[K][D], float (&hs)[K][D], float (&ff)[K][D + 1]) {
+        if constexpr (B2_DOT) {
+            const float s2 = -a.nscale;
+            float mu[D];
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                float s = 0.f;
+#pragma unroll
+                for (int j = 0; j < K; ++j) s += c[j][r];
+                mu[r] = s * (1.f / K);
+            }
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                float q = 0.f, hf = 0.f;
+#pragma unroll
+                for (int r = 0; r < D; ++r) {
+                    hf = fmaf(hs[j][r], ff[j][r] - mu[r], hf);
+                    c[j][r] -= mu[r];
+                    q = fmaf(c[j][r], c[j][r], q);
+                }
+                ff[j][0] = hf;
+                ff[j][D] = -s2 * q;
+            }
+#pragma unroll
+            for (int r = 0; r < D; ++r) ff[r][1] = mu[r];
+        }
         if constexpr (FWD_DOT) {
             const float s2 = -a.nscale;
             float mu[D];
@@ -215,17 +251,63 @@ struct SmallItem {
     static constexpr bool SCALAR_B2 = (PASS == PASS_B2 && D == 1);
 
     // Called once per pass by every caller of run(), after the last vector.
-    static __device__ __forceinline__ void finish(const Args& a, float (&acc)[NACC]) {
+    static __device__ __forceinline__ void finish(const Args& a, const float (&c)[K][D], float (&acc)[NREG]) {
+        if constexpr (B2_DOT) {
+            // d e / d w = 2 (w - c) = 2 (wm - cm)
+#pragma unroll
+            for (int j = 0; j < K; ++j)
+#pragma unroll
+                for (int r = 0; r < D; ++r) acc[j * D + r] = 2.f * fmaf(-c[j][r], acc[KD + j], acc[j * D + r]);
+        }
         if constexpr (SCALAR_B2 && DIST == DIST_SQL2) {
             const float f = 2.f / a.escale;
 #pragma unroll
             for (int q = 0; q < NACC; ++q) acc[q] *= f;
         }
+        (void)c;
     }
 
     static __device__ __forceinline__ void run(const Args& a, int64_t i, const float (&w)[D], const float (&g)[D],
                                                const float (&c)[K][D], const float (&hs)[K][D],
-                                               const float (&ff)[K][D], float (&acc)[NACC]) {
+                                               const float (&ff)[K][D + 1], float (&acc)[NREG]) {
+        if constexpr (B2_DOT) {
+            const float two_s2 = -2.f * a.nscale;
+            float wm[D];
+#pragma unroll
+            for (int r = 0; r < D; ++r) wm[r] = w[r] - ff[r][1];
+            float l[K], q[K];
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                float dot = wm[0] * c[j][0], qq = fmaf(hs[j][0], wm[0], -ff[j][0]);
+#pragma unroll
+                for (int r = 1; r < D; ++r) {
+                    dot = fmaf(wm[r], c[j][r], dot);
+                    qq = fmaf(hs[j][r], wm[r], qq);
+                }
+                l[j] = fmaf(dot, two_s2, ff[j][D]);
+                q[j] = qq;  // (h_j/tau) . (w - F*_j)
+            }
+            float lmax = l[0];
+#pragma unroll
+            for (int j = 1; j < K; ++j) lmax = fmaxf(lmax, l[j]);
+            float p[K], S = 0.f, pq = 0.f;
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                p[j] = fast_exp2(l[j] - lmax);
+                S = (j == 0) ? p[0] : S + p[j];
+                pq = fmaf(p[j], q[j], pq);
+            }
+            const float rS = fast_rcp(S);
+            const float nqb = -(pq * rS) * rS;  // -qbar / S
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                const float th = p[j] * fmaf(q[j], rS, nqb);  // a_j (q_j - qbar)
+                acc[KD + j] += th;
+#pragma unroll
+                for (int r = 0; r < D; ++r) acc[j * D + r] = fmaf(th, wm[r], acc[j * D + r]);
+            }
+            return;
+        }
         if constexpr (SCALAR_B2) {
             // t_j = (w - c_0) s - (c_j - c_0) s (both products rounded on their own: exactly zero where w = c_j),
             // p_j = exp2(-t_j^2 + min t^2) resp. exp2(-|t_j| + min |t|), S = sum p
@@ -464,7 +546,7 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
     if (PASS == PASS_B2 && a.ctrl->b_done) return;
     const unsigned int seq = a.ctrl->launch_seq + 1u;  // stamp of this launch's partial sums
 
-    float c[K][D], hs[K][D], ff[K][D];
+    float c[K][D], hs[K][D], ff[K][D + 1];
 #pragma unroll
     for (int j = 0; j < K; ++j)
 #pragma unroll
@@ -475,9 +557,9 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
         }
     Item::prepare(a, c, hs, ff);
 
-    float acc[NACC];
+    float acc[Item::NREG];
 #pragma unroll
-    for (int q = 0; q < NACC; ++q) acc[q] = 0.f;
+    for (int q = 0; q < Item::NREG; ++q) acc[q] = 0.f;
 
     const int64_t base = (int64_t)blockIdx.x * a.vec_per_wg;
     int64_t end = base + a.vec_per_wg;
@@ -495,7 +577,7 @@ __global__ __launch_bounds__(WG) void small_pass(const Args a) {
         }
         Item::run(a, i, w, g, c, hs, ff, acc);
     }
-    Item::finish(a, acc);
+    Item::finish(a, c, acc);
 
     if (PASS == PASS_B3) return;
 
