@@ -648,10 +648,12 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 // One pass over the workgroup's LDS tile.
 // SHARED: the workgroup shares its SIMDs with other teams' workgroups (batched launches); the hardware then
 // interleaves wavefronts, and short groups keep the registers low enough for four or five workgroups per compute unit.
+// s_tab: the caller's LDS table of the product forms' per-codeword operands (fwd_dot_tables), or null: then every lane
+// forms them itself in prepare().
 template <int K, int D, int DIST, int PASS, bool SHARED>
 __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const float* s_g, int64_t base, int cnt,
                                           const float* s_Cf, const float* s_Hs, const float* s_Ff,
-                                          float (&acc)[SmallItem<K, D, DIST, PASS>::NREG]) {
+                                          float (&acc)[SmallItem<K, D, DIST, PASS>::NREG], const float* s_tab = nullptr) {
     using Item = SmallItem<K, D, DIST, PASS>;
     float c[K][D], hs[K][D], ff[K][D + 1];
 #pragma unroll
@@ -662,18 +664,24 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
             hs[j][r] = Item::USE_H ? s_Hs[j * D + r] : 0.f;
             ff[j][r] = Item::USE_F ? s_Ff[j * D + r] : 0.f;
         }
-    if constexpr (Item::FWD_DOT) {
-        // the per-codeword operands of the product form: from the caller's LDS table where it keeps one (fwd_dot_tables:
-        // formed once per evaluation by wavefront 0), else formed here by every lane
-        if (s_Hs) {
+    if constexpr (Item::FWD_DOT || Item::B2_DOT) {
+        // the per-codeword operands of the product form: from the caller's LDS table where it keeps one (formed once per
+        // evaluation by wavefront 0), else formed here by every lane
+        if (s_tab) {
 #pragma unroll
             for (int j = 0; j < K; ++j) {
 #pragma unroll
-                for (int r = 0; r < D; ++r) hs[j][r] = s_Hs[j * D + r];
-                ff[j][0] = s_Hs[K * D + j];
+                for (int r = 0; r < D; ++r) {
+                    if (Item::FWD_DOT)
+                        hs[j][r] = s_tab[j * D + r];
+                    else
+                        c[j][r] = s_tab[j * D + r];
+                }
+                ff[j][Item::FWD_DOT ? 0 : D] = s_tab[K * D + j];
+                if (Item::B2_DOT) ff[j][0] = s_tab[K * D + K + D + j];
             }
 #pragma unroll
-            for (int r = 0; r < D; ++r) ff[r][1] = s_Hs[K * D + K + r];
+            for (int r = 0; r < D; ++r) ff[r][1] = s_tab[K * D + K + r];
         } else {
             Item::prepare(a, c, hs, ff);
         }
@@ -830,11 +838,12 @@ __device__ __forceinline__ void tile_pass_global(const Args& a, const float* gw,
 template <int K, int D, int DIST, int PASS, bool SHARED, bool GLOBALW>
 __device__ __forceinline__ void any_tile_pass(const Args& a, const PArgs& pa, const float* w, const float* g,
                                               int64_t base, int cnt, const float* s_Cf, const float* s_Hs,
-                                              const float* s_Ff, float (&acc)[SmallItem<K, D, DIST, PASS>::NREG]) {
+                                              const float* s_Ff, float (&acc)[SmallItem<K, D, DIST, PASS>::NREG],
+                                              const float* s_tab = nullptr) {
     if constexpr (GLOBALW)
         tile_pass_global<K, D, DIST, PASS>(a, w, g, pa.wg, pa.G, s_Cf, s_Hs, s_Ff, acc);
     else
-        tile_pass<K, D, DIST, PASS, SHARED>(a, w, g, base, cnt, s_Cf, s_Hs, s_Ff, acc);
+        tile_pass<K, D, DIST, PASS, SHARED>(a, w, g, base, cnt, s_Cf, s_Hs, s_Ff, acc, s_tab);
 }
 
 // Codewords per reducer: as many as fit 8 words of (n_j, s_j) per workgroup.
@@ -848,10 +857,10 @@ constexpr int cw_per_reducer(int K, int D) {
 
 // Operands of the product form of the forward loop (SmallItem::FWD_DOT), formed once per evaluation by wavefront 0
 // (all 64 lanes call; lane j d + r < k d passes component r of codeword j, the other lanes zero) instead of by every lane
-// at the start of its pass:  tab[j d + r] = 2 s^2 (c_jr - mu_r), tab[k d + j] = -s^2 |c_j - mu|^2, tab[k d + k + r] = mu_r,
+// at the start of its pass:  tab[j d + r] = ascale (c_jr - mu_r) (ascale = 2 s^2), tab[k d + j] = -s^2 |c_j - mu|^2, tab[k d + k + r] = mu_r,
 // mu the mean codeword.  The sums over codewords and over components run across the lanes.
 template <int K, int D>
-__device__ __forceinline__ void fwd_dot_tables(float c, float s2, float* tab) {
+__device__ __forceinline__ float fwd_dot_tables(float c, float s2, float* tab, float ascale) {
     static_assert(D == 2 || D == 4, "lane layout j d + r with d a divisor of 4");
     const int lane = threadIdx.x;
     // mu_r: over the lanes with the same lane % d
@@ -866,10 +875,20 @@ __device__ __forceinline__ void fwd_dot_tables(float c, float s2, float* tab) {
     q += dpp_f<0xB1, 0xf>(0.f, q);               // quad_perm [1,0,3,2]
     if (D == 4) q += dpp_f<0x4E, 0xf>(0.f, q);
     if (lane < K * D) {
-        tab[lane] = 2.f * s2 * dc;
+        tab[lane] = ascale * dc;
         if (lane % D == 0) tab[K * D + lane / D] = -s2 * q;
         if (lane < D) tab[K * D + K + lane] = m;
     }
+    return m;  // mu_r of this lane's component
+}
+// The backward's table keeps c_j - mu itself (ascale = 1) and, behind mu, h_j . (F*_j - mu) / tau of the current h:
+// lane j d + r passes h_jr / tau times (F*_jr - mu_r); the d lanes of a codeword are added across lanes.
+template <int K, int D>
+__device__ __forceinline__ void bwd_dot_hf(float hfm, float* tab) {
+    const int lane = threadIdx.x;
+    hfm += dpp_f<0xB1, 0xf>(0.f, hfm);              // quad_perm [1,0,3,2]
+    if (D == 4) hfm += dpp_f<0x4E, 0xf>(0.f, hfm);  // quad_perm [2,3,0,1]
+    if (lane < K * D && lane % D == 0) tab[K * D + K + D + lane / D] = hfm;
 }
 
 // Forward solve (Alg. 1) and the evaluation at C*, in one launch.
@@ -917,7 +936,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
         s_res = 0.0;
     }
     if constexpr (DOT) {
-        if (tid < 64) fwd_dot_tables<K, D>(tid < KD ? pa.C0[tid] : 0.f, -a.nscale, s_tab);
+        if (tid < 64) fwd_dot_tables<K, D>(tid < KD ? pa.C0[tid] : 0.f, -a.nscale, s_tab, -2.f * a.nscale);
     }
     __syncthreads();
     const double tol = pa.tol;
@@ -959,7 +978,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     float acc[NACC];
     while (!s_done) {
         IDKM_STAMP(0);
-        any_tile_pass<K, D, DIST, PASS_FWD, SHARED, GLOBALW>(a, pa, s_w, nullptr, base, cnt, s_Cf, DOT ? s_tab : nullptr, nullptr, acc);
+        any_tile_pass<K, D, DIST, PASS_FWD, SHARED, GLOBALW>(a, pa, s_w, nullptr, base, cnt, s_Cf, nullptr, nullptr, acc, DOT ? s_tab : nullptr);
         IDKM_STAMP(1);
         ++seq;
         publish_partials<NACC>(pa, seq, acc, xs);
@@ -1050,7 +1069,7 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
         if constexpr (DOT) {
             if (tid < 64) {  // (wavefront 0 has just written the new codebook)
                 wave_lds_sync();
-                fwd_dot_tables<K, D>(tid < KD ? s_Cf[tid] : 0.f, -a.nscale, s_tab);
+                fwd_dot_tables<K, D>(tid < KD ? s_Cf[tid] : 0.f, -a.nscale, s_tab, -2.f * a.nscale);
             }
         }
         __syncthreads();
@@ -1378,6 +1397,11 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     __shared__ XShared<HAS_DENSE ? NBJ : KD> xs;
     __shared__ double s_v[KD], s_g[KD], s_rn[K];  // a reducer's own slice is the live one; s_rn = 1/(tau n)
     __shared__ float s_Cf[KD], s_Hs[KD], s_Hv[KD], s_Ff[KD];
+    // product form of the (dF/dC)^T pass: its per-codeword operands (c_j - mu, -s^2 |c_j - mu|^2, mu, h_j . (F*_j - mu) / tau),
+    // formed by wavefront 0 -- the first three once per launch, the last whenever h changes -- from k d = 32 on (below,
+    // every lane forms them itself at the start of its pass)
+    constexpr bool BTAB = SmallItem<K, D, DIST, PASS_B2>::B2_DOT && !GLOBALW && KD >= 32;
+    __shared__ float s_tabB[BTAB ? KD + K + D + K : 1];
     __shared__ int s_done, s_iters, s_conv, s_attempt, s_grow, s_halv, s_bad, s_restart;
     __shared__ double s_alpha, s_prev, s_vnorm, s_res;
     // minimal-residual solve (BWD_GMRES): offered to teams in which every workgroup receives the totals; its state lies
@@ -1404,6 +1428,18 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         s_Hs[tid] = 0.f;
         s_Hv[tid] = 0.f;
     }
+    float r_fm = 0.f;  // lane j d + r < k d of wavefront 0: F*_jr - mu_r
+    if constexpr (BTAB) {
+        if (tid < 64) {
+            const float mu = fwd_dot_tables<K, D>(tid < KD ? a.Cf[tid] : 0.f, -a.nscale, s_tabB, 1.f);
+            if (tid < KD) r_fm = a.Ff[tid] - mu;
+        }
+    }
+    // every change of h/tau goes through here (lanes < k d of wavefront 0, all of them together)
+    auto set_h = [&](float h) {
+        s_Hs[tid] = h;
+        if constexpr (BTAB) bwd_dot_hf<K, D>(h * r_fm, s_tabB);
+    };
     if (tid < K) {
         const double n = a.nd[tid];
         s_rn[tid] = (n > 0.0) ? (double)a.inv_tau / n : 0.0;  // zero for an empty cluster
@@ -1553,8 +1589,8 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     }
     if (!(tree && !dense_done) && !gather_bcast<KD, WPR, KD>(pa, seq, NB, !dense_done, xs)) return;
     if (tid < KD) {
-        s_Hs[tid] = __uint_as_float(xs.bc[tid]);
-        s_Hv[tid] = s_Hs[tid];
+        set_h(__uint_as_float(xs.bc[tid]));
+        s_Hv[tid] = __uint_as_float(xs.bc[tid]);
     }
     if (tid == 0) {
         double v2 = 0.0;
@@ -1580,7 +1616,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                     const double q = s_v[tid] * inv;
                     gm.Q[tid] = q;
                     s_g[tid] = 0.0;
-                    s_Hs[tid] = (float)(q * s_rn[tid / D]);
+                    set_h((float)(q * s_rn[tid / D]));
                 }
                 if (tid == 0) {
                     s_vnorm = v2;  // (the float64 norm of the float64 v, not the sum of float32 parts)
@@ -1613,7 +1649,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     }
     while (!s_done) {
         IDKM_STAMP(0);
-        any_tile_pass<K, D, DIST, PASS_B2, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, accr);
+        any_tile_pass<K, D, DIST, PASS_B2, SHARED, GLOBALW>(a, pa, s_w, s_gt, base, cnt, s_Cf, s_Hs, s_Ff, accr, BTAB ? s_tabB : nullptr);
         IDKM_STAMP(1);
         ++seq;
         publish_partials<KD>(pa, seq, acc, xs);
@@ -1636,7 +1672,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                     else
                         over = gmres_step<KD>(gm, [&](int i) { return (double)xs.own[i]; }, s_v, s_g, tol, vn, max_iter,
                                               s_iters, s_conv, s_bad, s_res, hn);
-                    if (tid < KD) s_Hs[tid] = (float)(hn * s_rn[tid / D]);
+                    if (tid < KD) set_h((float)(hn * s_rn[tid / D]));
                     if (tid == 0 && over) s_done = 1;
                 }
                 __syncthreads();
@@ -1712,7 +1748,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
                 }
                 if (tid < KD) {
                     s_g[tid] = r_g;
-                    s_Hs[tid] = restart ? s_Hv[tid] : (float)(gn * r_rn);
+                    set_h(restart ? s_Hv[tid] : (float)(gn * r_rn));
                 }
                 if (tid == 0) {  // (stores only)
                     s_iters = r_iters;
@@ -1803,11 +1839,11 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
         if (s_restart) {
             // back to g = v with the halved alpha: every workgroup kept h(v)/tau, reducers reset their slice
             if (tid < KD) {
-                s_Hs[tid] = s_Hv[tid];
+                set_h(s_Hv[tid]);
                 s_g[tid] = s_v[tid];
             }
         } else if (tid < KD) {
-            s_Hs[tid] = __uint_as_float(xs.bc[tid]);
+            set_h(__uint_as_float(xs.bc[tid]));
         }
         __syncthreads();
     }
