@@ -942,4 +942,52 @@ __device__ __forceinline__ void grid_tail(const Args& a, unsigned int seq) {
     if (PASS == PASS_BJ) tail_bj(a, s_tot);
 }
 
+// Copy of n floats from memory into LDS by a workgroup of NT threads, with up to eight loads of a thread in flight (16-byte
+// loads where the source allows): a loop that waits for each load before it issues the next is bound by the memory
+// latency -- 36 round trips for the 36 KB tile of a 2.4 M-weight layer, 9 us of a 184 us solve.
+template <int NT>
+__device__ __forceinline__ void load_tile(float* dst, const float* __restrict__ src, int n) {
+    const int tid = threadIdx.x;
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    if ((reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
+        const int n4 = n >> 2;
+        const f4* s4 = reinterpret_cast<const f4*>(src);
+        int i = tid;
+        for (; i + 7 * NT < n4; i += 8 * NT) {
+            f4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = s4[i + u * NT];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) dst[4 * (i + u * NT) + e] = v[u][e];
+            }
+        }
+        for (; i + NT < n4; i += 2 * NT) {
+            const f4 v0 = s4[i], v1 = s4[i + NT];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                dst[4 * i + e] = v0[e];
+                dst[4 * (i + NT) + e] = v1[e];
+            }
+        }
+        for (; i < n4; i += NT) {
+            const f4 v0 = s4[i];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[4 * i + e] = v0[e];
+        }
+        for (int k = (n4 << 2) + tid; k < n; k += NT) dst[k] = src[k];
+        return;
+    }
+    int i = tid;
+    for (; i + 7 * NT < n; i += 8 * NT) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[i + u * NT];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) dst[i + u * NT] = v[u];
+    }
+    for (; i < n; i += NT) dst[i] = src[i];
+}
+
 }  // namespace idkm

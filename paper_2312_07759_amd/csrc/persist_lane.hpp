@@ -216,7 +216,7 @@ __device__ __forceinline__ void persist_lane_fwd_body(const Args& a, const PArgs
     const int64_t base = (int64_t)wg * pa.per;
     int cnt = 0;
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
-    for (int i = tid; i < cnt * D; i += NT) s_tile[i] = a.W[base * D + i];
+    load_tile<NT>(s_tile, a.W + base * D, cnt * D);
     for (int i = tid; i < kd; i += NT) {
         const float c0 = pa.C0[i];
         s_Cd[i] = (double)c0;
@@ -455,10 +455,8 @@ __device__ __forceinline__ void persist_lane_bwd_body(const Args& a, const PArgs
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
     float* s_w = s_tile;
     const float* s_gt = MFMA ? a.G + base * D : s_tile + (size_t)pa.per * D;
-    for (int i = tid; i < cnt * D; i += NT) {
-        s_w[i] = a.W[base * D + i];
-        if (!MFMA) s_tile[(size_t)pa.per * D + i] = a.G[base * D + i];
-    }
+    load_tile<NT>(s_w, a.W + base * D, cnt * D);
+    if (!MFMA) load_tile<NT>(s_tile + (size_t)pa.per * D, a.G + base * D, cnt * D);
     for (int i = tid; i < kd; i += NT) {
         s_Cf[i] = a.Cf[i];
         s_Ff[i] = a.Ff[i];

@@ -393,14 +393,16 @@ __device__ __forceinline__ bool gather_bcast(const PArgs& pa, unsigned int seq, 
 
 // Start of a launch: the leaders publish the die they run on; every workgroup compares it with its own.
 // Leaves xs.local; returns false if the wait was abandoned.  Called by all threads; ends with a barrier.
+// (the leaders say where they run before they load their tile -- tree_announce -- so that nobody waits for that word)
+__device__ __forceinline__ void tree_announce(const PArgs& pa) {
+    if (pa.tree && threadIdx.x == 0 && pa.wg < DIES) st_word(&pa.tab[pa.wg], pack_u(pa.seq_base + 1u, die_id()));
+}
 template <class XS>
 __device__ __forceinline__ bool tree_handshake(const PArgs& pa, XS& xs) {
     if (threadIdx.x == 0) {
         const unsigned int id = pa.seq_base + 1u, mine = die_id();
         int local = 1;
-        if (pa.wg < DIES) {
-            st_word(&pa.tab[pa.wg], pack_u(id, mine));
-        } else {
+        if (pa.wg >= DIES) {
             unsigned long long w[1];
             if (poll_words<1>(pa, pa.tab + (pa.wg % DIES), 0, id, w)) {
                 local = ((unsigned int)w[0] == mine) ? 1 : 0;
@@ -919,8 +921,9 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     const int64_t base = (int64_t)wg * pa.per;
     int cnt = 0;
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
+    tree_announce(pa);
     if (!GLOBALW)
-        for (int i = tid; i < cnt * D; i += PT) s_tile[i] = a.W[base * D + i];
+        load_tile<PT>(s_tile, a.W + base * D, cnt * D);
     const float* s_w = GLOBALW ? a.W : s_tile;
     if (tid < KD) {
         const float c0 = pa.C0[tid];
@@ -1416,11 +1419,10 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
     if (base < a.m) cnt = (a.m - base < pa.per) ? (int)(a.m - base) : pa.per;
     const float* s_w = GLOBALW ? a.W : s_tile;
     const float* s_gt = GLOBALW ? a.G : s_tile + (size_t)pa.per * D;
+    tree_announce(pa);
     if (!GLOBALW) {
-        for (int i = tid; i < cnt * D; i += PT) {
-            s_tile[i] = a.W[base * D + i];
-            s_tile[(size_t)pa.per * D + i] = a.G[base * D + i];
-        }
+        load_tile<PT>(s_tile, a.W + base * D, cnt * D);
+        load_tile<PT>(s_tile + (size_t)pa.per * D, a.G + base * D, cnt * D);
     }
     if (tid < KD) {
         s_Cf[tid] = a.Cf[tid];
