@@ -714,7 +714,7 @@ def test_warm_start_and_temperature_schedule(ctx):
 # scaled coordinates (w - c_0) s - (c_j - c_0) s in their backward passes, for the same reason relative to a codeword.
 @pytest.mark.parametrize("path", [binding.PATH_STREAM, binding.PATH_PERSISTENT], ids=["stream", "persistent"])
 @pytest.mark.parametrize("dist", DISTS)
-@pytest.mark.parametrize("k,d", [(16, 4), (8, 4), (16, 2), (4, 1), (16, 1)])
+@pytest.mark.parametrize("k,d", [(16, 4), (8, 4), (16, 2), (4, 2), (2, 2), (4, 4), (4, 1), (16, 1)])
 def test_backward_of_a_layer_far_from_the_origin(ctx, k, d, dist, path):
     rng = np.random.default_rng(770 + 16 * k + d)
     m = 20_011
@@ -734,6 +734,36 @@ def test_backward_of_a_layer_far_from_the_origin(ctx, k, d, dist, path):
         bi = ctx.backward(Gd, binding.BWD_IMPLICIT, tol=0.0, max_iter=12, alpha=1.0)
         ri = orc.backward(W, Cg, tau, dist, G, "implicit", tol=0.0, max_iter=12, alpha=1.0)
         assert rel(bi["dW"].cpu().numpy(), ri["dW"]) < TOL_GRAD
+    finally:
+        ctx.set_path(binding.PATH_AUTO)
+
+
+# Squared energy, d >= 2: the forward loop and the (dF/dC)^T pass take the exponents of the row softmax as products about
+# the mean codeword; their rounding error is a few float32 ulps of s^2 |c - mu| |w - mu|, s^2 = log2(e)/tau.  The lower
+# the temperature against the spread of the codebook, the larger that is: here s^2 |c - mu|^2 runs from about 250 to
+# 6000 (rows from soft to nearly hard).
+@pytest.mark.parametrize("path", [binding.PATH_STREAM, binding.PATH_PERSISTENT], ids=["stream", "persistent"])
+@pytest.mark.parametrize("tau", [0.05, 0.01, 0.002])
+@pytest.mark.parametrize("k,d", [(16, 4), (4, 2), (8, 2)])
+def test_product_form_of_the_exponents_from_soft_to_nearly_hard_rows(ctx, k, d, tau, path):
+    W, C0, G = wl.random_problem(30_011, d, k, seed=900 + k + d, std=0.5, spread=1.5)
+    W, G = W.astype(np.float32), G.astype(np.float32)
+    C0 = (C0 + 0.05 * np.random.default_rng(5).standard_normal(C0.shape)).astype(np.float32)
+    dist = wl.DIST_SQL2
+    ctx.set_path(path)
+    try:
+        out = ctx.forward(dev(W), dev(C0), tau, 0.0, 6, dist)
+        Cg = out["C"].cpu().numpy()
+        ref = orc.soft_kmeans(W, C0, tau, 0.0, 6, dist)
+        assert rel(Cg, ref["C"]) < TOL_VAL, rel(Cg, ref["C"])
+        assert np.abs(Cg - ref["C"]).max() < TOL_VAL * np.abs(ref["C"]).max()
+        bi = ctx.backward(dev(G), binding.BWD_IMPLICIT, tol=0.0, max_iter=8, alpha=1.0)
+        ri = orc.backward(W, Cg, tau, dist, G, "implicit", tol=0.0, max_iter=8, alpha=1.0)
+        if not (bi["info"].converged or ri["converged"]):
+            assert bi["info"].iters == ri["iters"] and bi["info"].alpha == ri["alpha"]
+        assert rel(bi["dW"].cpu().numpy(), ri["dW"]) < TOL_GRAD, rel(bi["dW"].cpu().numpy(), ri["dW"])
+        v, g = ctx.get_cotangents(k, d)
+        assert rel(g, ri["g"]) < TOL_GRAD, rel(g, ri["g"])
     finally:
         ctx.set_path(binding.PATH_AUTO)
 
