@@ -743,6 +743,23 @@ __device__ __forceinline__ void tile_pass(const Args& a, const float* s_w, const
             }
         }
         for (; it < cnt; it += PT) one(it);
+    } else if constexpr (PASS == PASS_B2 && K <= 4 && D == 1 && !SHARED) {
+        // the pass an implicit solve repeats, scalar weights: straight blocks of 36 vectors per lane while they last (C3:
+        // the whole tile), then of UNR, of 4, and single vectors (6.29 -> 6.06 us per pass at C3 against blocks of 12)
+        int it = threadIdx.x;
+        for (; it + 35 * PT < cnt; it += 36 * PT) {
+#pragma unroll
+            for (int u = 0; u < 36; ++u) one(it + u * PT);
+        }
+        for (; it + (UNR - 1) * PT < cnt; it += UNR * PT) {
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) one(it + u * PT);
+        }
+        for (; it + 3 * PT < cnt; it += 4 * PT) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) one(it + u * PT);
+        }
+        for (; it < cnt; it += PT) one(it);
     } else {
         // the backward passes carry more state per vector; a plainly unrolled loop schedules them better (measured)
 #pragma unroll UNR
