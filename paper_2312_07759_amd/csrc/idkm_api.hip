@@ -1024,7 +1024,7 @@ idkm_status idkm_backward(idkm_ctx* ctx, const float* dWq, idkm_bwd_mode mode, f
     }
     if (ctx->path == IDKM_PATH_PERSISTENT && !persistent)
         return fail(ctx, IDKM_ERR_UNSUPPORTED, mode == IDKM_BWD_GMRES
-                        ? "IDKM_BWD_GMRES on the persistent path needs k in {2,4,8,16}, k*d <= 64, a team of one or of at least 64 workgroups and room in LDS for its basis beside the tiles"
+                        ? "IDKM_BWD_GMRES on the persistent path needs k in {2,4,8,16}, k*d <= 64, a team of one or of at least 8 workgroups and room in LDS for its basis beside the tiles"
                         : "the persistent path needs k <= 512, d <= 4 and the tiles of W and dWq to fit in LDS");
     if (persistent) {
         const uint64_t ex = 1ull + (mode == IDKM_BWD_IMPLICIT ? (uint64_t)max_iter * 7ull

@@ -40,7 +40,9 @@ constexpr int PT = 256;      // threads per workgroup of the persistent kernels;
 constexpr int XLINE = 128;   // words reserved per workgroup in buf1 (K (D+1) <= 80, padded to a power of two)
 constexpr int XBCAST = 128;  // words reserved in buf2
 constexpr int DIES = 8;      // accelerator dies of the device (each with its own L2); workgroup b runs on die b mod 8
-constexpr int TREE_MIN_G = 64;  // smallest team that uses the two-level exchange
+// smallest team that uses the two-level exchange: every die has its leader from DIES workgroups on, and already there it beats
+// the one-level form (k = 4, d = 1, per evaluation: 8 workgroups 2.80 -> 2.33 us, 36 workgroups 3.01 -> 2.57, 59 workgroups 3.29 -> 2.86)
+constexpr int TREE_MIN_G = DIES;
 // Two-level exchange: passes with up to this many sums per workgroup publish per WAVEFRONT (no LDS stage on the sending
 // side, hop 2 inside wavefront 0).  With more sums the leader's loads per thread cost more than the senders save:
 // measured with 9 .. 16 sums (one 16-word piece per wavefront) against the workgroup-level form below, forward at

@@ -210,15 +210,15 @@ def test_damped_solve_agrees_with_the_undamped_one(ctx, dist):
 
 
 @pytest.mark.parametrize("setting", ["0", "2"])
-@pytest.mark.parametrize("cfg,m", [("C3", 300_007), ("C3", 70_001), ("C2", 100_003), ("P16", 80_011)],
-                         ids=["C3@300k", "C3@70k", "C2@100k", "P16@80k"])
+@pytest.mark.parametrize("cfg,m", [("C3", 300_007), ("C3", 70_001), ("C2", 100_003), ("P16", 80_011), ("C3", 8_003), ("C2", 21_001)],
+                         ids=["C3@300k", "C3@70k", "C2@100k", "P16@80k", "C3@8k", "C2@21k"])
 def test_forms_of_the_grid_exchange_agree(ctx, cfg, m, setting, monkeypatch):
-    """Teams of 64 or more workgroups exchange their sums in two levels (inside a die through its L2, then across dies).
+    """Teams of 8 or more workgroups exchange their sums in two levels (inside a die through its L2, then across dies).
     IDKM_TREE=0 (read when a context is created) keeps the one-level exchange; IDKM_TREE=2 takes the two levels with
     every store at device scope, the form a workgroup falls back to when it does not run on its leader's die.  Same
     sums in a different order: the solves agree to rounding, and each form is held to the oracle."""
     dist = wl.DIST_SQL2
-    p = wl.make_problem(cfg, dist, m=m)      # 256, 69, 98 and 79 workgroups: full and partly filled dies
+    p = wl.make_problem(cfg, dist, m=m)      # 256, 69, 98, 79, 8 and 21 workgroups: full and partly filled dies
     Wd, C0d, Gd = dev(p.W), dev(p.C0), dev(p.G)
     monkeypatch.setenv("IDKM_TREE", setting)
     other = binding.Context(0)
