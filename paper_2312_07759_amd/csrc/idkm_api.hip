@@ -486,9 +486,11 @@ idkm_status launch_persistent(idkm_ctx* ctx, const PersistPlan& pp, Args& a, PAr
         pa.buf2 = ctx->xbuf + XBUF1_WORDS;
         pa.buf3 = pa.buf2 + (size_t)2 * XBCAST;
         pa.tab = pa.buf3 + XBUF3_WORDS;
-        // a team that fills the device, one problem per launch: hop 1 stays inside each die (the explicit-Jacobian
-        // mode keeps the plain exchange, its one reduction ends in workgroup 0)
-        pa.tree = (ctx->tree_exchange && !ctx->sink && pp.grid >= TREE_MIN_G && pa.mode != BWD_DENSE) ? (ctx->tree_remote ? 2 : 1) : 0;
+        // teams of DIES workgroups or more: hop 1 stays inside each die (the explicit-Jacobian mode keeps the plain
+        // exchange, its one reduction ends in workgroup 0).  Also inside a batched launch: a team's workgroups are
+        // consecutive in the grid, so its first DIES lie on DIES different dies and member i shares its die with member
+        // i mod DIES wherever the team starts (checked by every workgroup at the start of the launch, as always)
+        pa.tree = (ctx->tree_exchange && pp.grid >= TREE_MIN_G && pa.mode != BWD_DENSE) ? (ctx->tree_remote ? 2 : 1) : 0;
     }
     pa.seq_base = ctx->seq_base;
     pa.spin_limit = ctx->spin_limit;
