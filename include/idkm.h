@@ -166,7 +166,7 @@ idkm_status idkm_forward(idkm_ctx* ctx, const float* W, int64_t m, int32_t d, co
  *   test <= tol ||v||_F; otherwise a new cycle starts from that residual.  info.iters counts all these passes
  *   (at most max_iter + 1), info.residual is the last true residual, alpha is ignored; two cycles in a row that
  *   leave more than 95 % of the residual end the solve with converged = 0.  With k d <= 64 the first cycle is exact up to
- *   rounding.  With k in {2,4,8,16}, k d <= 64 and a layer of at most 4096 or at least 7169 vectors (a team of one or of at least 8 workgroups) whose tiles leave
+ *   rounding.  With k in {2,4,8,16}, k d <= 64 and a layer whose tiles leave
  *   room on chip for the Krylov state (about 8 (R + 1)(k d + R + 1) bytes for a basis of R = min(k d, basis) vectors: 67 KB
  *   at k d = 64) the whole solve runs inside the persistent kernel (every workgroup keeps that state and takes the
  *   same steps); otherwise one launch per pass on the stream path (there IDKM_PATH_PERSISTENT gives

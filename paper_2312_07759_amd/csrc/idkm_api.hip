@@ -434,6 +434,8 @@ bool plan_persistent(idkm_ctx* ctx, bool bwd, PersistPlan* pp, bool matrix_ok = 
     // it needs no exchange through memory
     if (m <= (int64_t)16 * PT) g = 1;
     if (g < 1) g = 1;
+    // (a team of 2 to 7 workgroups would take the one-level exchange; 8 smaller workgroups take the two-level one)
+    if (ctx->tree_exchange && g > 1 && g < DIES) g = DIES;
     if (g > ctx->num_cu) g = ctx->num_cu;
     if (g > PT) g = PT;  // a reducer reads one workgroup per thread
     int64_t per = (m + g - 1) / g;

@@ -552,7 +552,8 @@ def test_krylov_backward_inside_the_persistent_kernel(ctx, cfg, m, dist):
 
 
 def test_krylov_backward_on_the_persistent_path_is_refused(ctx):
-    W, C0, G = _case(5_000, 1, 4, seed=1)
+    # (k = 3: the lane<->codeword family, whose persistent kernels do not hold the minimal-residual solve)
+    W, C0, G = _case(5_000, 1, 3, seed=1)
     ctx.forward(dev(W), dev(C0), 0.05, 1e-6, 30, wl.DIST_SQL2)
     ctx.set_path(binding.PATH_PERSISTENT)
     with pytest.raises(binding.IdkmError) as e:

@@ -94,6 +94,7 @@ def _team_cases():
     out.append((4, 1, 65 * 1024 + 5, 0.1, 8))      # 66 workgroups: dies with 9 and with 8 members
     out.append((2, 2, 255 * 1024 + 3, 0.1, 9))     # 256 workgroups, the last one nearly empty
     out.append((4, 1, 7 * 1024 + 1, 0.1, 10))      # 8 workgroups: the smallest team of the two-level exchange, one per die
+    out.append((8, 2, 4_099, 0.1, 14))             # just above one workgroup's share: 8 workgroups of 513 vectors
     out.append((4, 1, 9 * 1024 + 5, 0.1, 11))      # 10 workgroups: dies with two members and with one
     out.append((16, 4, 20 * 1024 + 3, 0.15, 12))   # 21 workgroups, 80 sums per workgroup
     out.append((2, 2, 36 * 1024 + 7, 0.1, 13))     # 37 workgroups
