@@ -633,6 +633,38 @@ __device__ __forceinline__ void tree8_grid_totals_wave0(const PArgs& pa, unsigne
     wave_lds_sync();  // the caller's lanes read one another's totals
 }
 
+// The same hop for the loops (forward evaluations, (dF/dC)^T passes): the totals stay in registers -- every lane l
+// returns the grid total of slot l % 8, i.e. of accumulator slot_acc(l % 8) -- and an abandoned wait is reported by the
+// return value (the same in all lanes), so that nothing between the arrival of the totals and the update waits for LDS.
+// All 64 lanes of wavefront 0 call it.
+template <class XS>
+__device__ __forceinline__ bool tree8_grid_totals_regs(const PArgs& pa, unsigned int seq, XS& xs, double& total) {
+    const int lane = threadIdx.x, x = lane >> 3, p = lane & 7;
+    const unsigned long long* src = pa.buf3 + ((size_t)(seq & 1u) * DIES + x) * 32 + p;
+    unsigned long long w[1];
+    double s;
+    bool failed = false;
+    wave_lds_sync();  // (a leader's lanes 0 .. 7 have just written its own die's totals)
+    if (x == pa.wg) {
+        s = (double)xs.stage2[x * 8 + p];
+    } else if (HOP2_PIPE > 1 ? poll_word_staggered<HOP2_PIPE, HOP2_SLEEP>(pa, src, seq, w[0]) : poll_words<1>(pa, src, 0, seq, w)) {
+        s = (double)__uint_as_float((unsigned int)w[0]);
+    } else {
+        s = 0.0;
+        failed = true;
+        xs.abort = 1;
+        __hip_atomic_store(pa.abort_word, pa.seq_base + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    total = sum_over_lane_bits_3_to_5(s);
+    return __builtin_amdgcn_ballot_w64(failed) == 0ull;
+}
+// Total of accumulator a (a < 8, any value per lane) from the registers tree8_grid_totals_regs left: all 64 lanes call it.
+__device__ __forceinline__ double tree8_total_of(double total, int a) {
+    const int src = slot_acc(a & 7) << 2;
+    return __hiloint2double(__builtin_amdgcn_ds_bpermute(src, __double2hiint(total)),
+                            __builtin_amdgcn_ds_bpermute(src, __double2loint(total)));
+}
+
 // Both hops after publish_partials: grid totals of the NACC sums in xs.totd, in every workgroup; ends with a barrier.
 template <int NACC, class XS>
 __device__ __forceinline__ bool tree_totals(const PArgs& pa, unsigned int seq, XS& xs) {
@@ -970,18 +1002,25 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
     int r_iters = 0;
     // Centre update of the whole codebook (Alg. 1) and the stop test from grid totals every workgroup holds (a team
     // of one, or the two-level exchange): tot(i) is total i of the K (D+1) sums.  Wavefront 0; lane 0 decides.
-    auto update_all = [&](auto tot) {
+    // (lanes < k d of wavefront 0 keep their component of the codebook in registers too: float64 master and float32 copy)
+    double r_cd = 0.0;
+    float r_cf = 0.f;
+    if (tid < KD) {
+        r_cf = pa.C0[tid];
+        r_cd = (double)r_cf;
+    }
+    // n, sv: mass of this lane's codeword and the sum of its component (lanes < k d; all 64 lanes of wavefront 0 call)
+    auto update_vals = [&](double n, double sv) {
         double df2 = 0.0;
         if (tid < KD) {
-            const int j = tid / D, rr = tid - j * D;
-            const double n = tot(j * ACCW), sv = tot(j * ACCW + 1 + rr);
-            const double cold = s_Cd[tid];
-            double cnew = (n > 0.0) ? fast_div_d(sv, n) : cold;
+            double cnew = (n > 0.0) ? fast_div_d(sv, n) : r_cd;
             if (!(n >= 0.0) || !(fabs(sv) <= 1.7e308) || !(fabs(cnew) <= 1.7e308)) cnew = __builtin_nan("");
+            r_cd = cnew;
             s_Cd[tid] = cnew;
             const float cn = (float)cnew;
-            const double df = (double)cn - (double)s_Cf[tid];
+            const double df = (double)cn - (double)r_cf;
             df2 = df * df;
+            r_cf = cn;
             s_Cf[tid] = cn;
         }
         const double r2 = first_lanes_sum_d_dpp<KD>(df2);
@@ -995,6 +1034,15 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
             s_conv = conv ? 1 : 0;
             if (conv || bad || r_iters >= max_iter) s_done = 1;
         }
+    };
+    auto update_all = [&](auto tot) {
+        double n = 0.0, sv = 0.0;
+        if (tid < KD) {
+            const int j = tid / D, rr = tid - j * D;
+            n = tot(j * ACCW);
+            sv = tot(j * ACCW + 1 + rr);
+        }
+        update_vals(n, sv);
     };
 
     float acc[NACC];
@@ -1018,9 +1066,12 @@ __device__ __forceinline__ void persist_fwd_body(const Args& a, const PArgs& pa)
                     IDKM_STAMP(3);
                 }
                 if (tid < 64) {
-                    tree8_grid_totals_wave0<NACC>(pa, seq, xs);
+                    double total;
+                    const bool ok = tree8_grid_totals_regs(pa, seq, xs, total);
                     IDKM_STAMP(4);
-                    if (!xs.abort) update_all([&](int i) { return xs.totd[i]; });
+                    const int jj = (tid < KD) ? tid / D : 0, rr = (tid < KD) ? tid - jj * D : 0;
+                    const double n = tree8_total_of(total, jj * ACCW), sv = tree8_total_of(total, jj * ACCW + 1 + rr);
+                    if (ok) update_vals(n, sv);
                 }
             } else {
                 if (!tree_totals<NACC>(pa, seq, xs)) return;
@@ -1704,13 +1755,17 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
             // a team of one has no exchange: its partial sums (xs.own) are the totals; with the two-level exchange
             // every workgroup receives the totals (xs.totd).  Either way the whole of g is updated here
             bool wave0_abort = false;
+            double u_reg = 0.0;   // (total of this lane's component where hop 2 leaves the totals in registers)
+            bool in_regs = false;
             if (tree) {
                 if constexpr (KD <= WAVE_WORDS_MAX) {
-                    // (hop 2 inside wavefront 0, no barrier before the update)
+                    // (hop 2 inside wavefront 0, no barrier and no LDS round trip before the update)
                     if (wg < DIES && !tree8_die_totals(pa, seq, xs)) return;
                     if (tid < 64) {
-                        tree8_grid_totals_wave0<KD>(pa, seq, xs);
-                        wave0_abort = xs.abort != 0;
+                        double total;
+                        wave0_abort = !tree8_grid_totals_regs(pa, seq, xs, total);
+                        u_reg = tree8_total_of(total, tid < KD ? tid : 0);
+                        in_regs = true;
                     }
                 } else {
                     if (!tree_totals<KD>(pa, seq, xs)) return;
@@ -1722,7 +1777,7 @@ __device__ __forceinline__ void persist_bwd_body(const Args& a, const PArgs& pa)
             if (tid < 64 && !wave0_abort) {
                 double d2 = 0.0, gn = 0.0;
                 if (tid < KD) {
-                    const double u = tree ? xs.totd[tid] : (double)xs.own[tid];
+                    const double u = in_regs ? u_reg : (tree ? xs.totd[tid] : (double)xs.own[tid]);
                     gn = r_alpha * (r_v + u) + (1.0 - r_alpha) * r_g;
                     const double df = gn - r_g;
                     d2 = df * df;
